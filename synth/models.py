@@ -1,0 +1,92 @@
+"""Model shapes and (holder -> reader) layout pairings of the five workloads.
+
+Shapes are public Llama-3-8B / 70B-like and DeepSeek-MoE-like dimensions; they
+stand in for the proprietary 9B-1T production models of the paper's Table 3.
+A layout here is only a tuple of parallel sizes / ranks; what a rank *holds*
+under such a layout is worked out independently by the oracle and by the
+library's planner.
+"""
+
+MiB = 1 << 20
+
+
+def layout(tp_size=1, tp_rank=0, ep_size=1, ep_rank=0, experts_stacked=0, f32_store="f32"):
+    """One worker's place in a model-parallel group.
+
+    f32_store: dtype in which this side keeps tensors whose model dtype is
+    fp32 ("f32" keeps them, "bf16" narrows them: the inference-ready format).
+    """
+    assert f32_store in ("f32", "bf16")
+    return dict(tp_size=tp_size, tp_rank=tp_rank, ep_size=ep_size, ep_rank=ep_rank,
+                experts_stacked=experts_stacked, f32_store=f32_store)
+
+
+def _dense(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, tied):
+    return dict(kind="dense", n_layers=n_layers, hidden=hidden, n_q_heads=n_q_heads,
+                n_kv_heads=n_kv_heads, head_dim=head_dim, ffn=ffn, vocab=vocab,
+                tied_embeddings=tied, n_experts=0, n_shared_experts=0, expert_ffn=0,
+                weight_dtype="bf16", norm_dtype="f32")
+
+
+MODELS = {
+    # config 1: tiny Llama-style, tied embeddings
+    "tiny": _dense(2, 256, 4, 2, 64, 1024, 1000, 1),
+    # config 2: 8B-shaped dense
+    "dense8b": _dense(32, 4096, 32, 8, 128, 14336, 128256, 0),
+    # config 3: 70B-shaped dense
+    "dense70b": _dense(80, 8192, 64, 8, 128, 28672, 128256, 0),
+    # config 4: MoE-shaped, 64 routed + 2 shared experts per layer
+    "moe": dict(kind="moe", n_layers=24, hidden=2048, n_q_heads=16, n_kv_heads=16, head_dim=128,
+                ffn=0, vocab=102400, tied_embeddings=0, n_experts=64, n_shared_experts=2,
+                expert_ffn=1408, weight_dtype="bf16", norm_dtype="f32"),
+    # reduced shapes of the same families, for CPU tests and quick GPU parity
+    "dense_small": _dense(3, 512, 8, 4, 64, 1536, 4096, 0),
+    "moe_small": dict(kind="moe", n_layers=2, hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64,
+                      ffn=0, vocab=2048, tied_embeddings=0, n_experts=16, n_shared_experts=2,
+                      expert_ffn=176, weight_dtype="bf16", norm_dtype="f32"),
+}
+
+WORKLOADS = {
+    # tiny Llama, both TP=2 holders -> one TP=1 reader, 1 MiB chunks
+    "cfg1_tiny_tp2_to_tp1": dict(
+        model="tiny", seed=1, chunk_bytes=1 * MiB,
+        holders=[layout(2, 0), layout(2, 1)],
+        reader=layout(1, 0, f32_store="bf16")),
+    # 8B, TP=1 holder -> TP=4 rank-0 reader, 64 MiB chunks
+    "cfg2_8b_tp1_to_tp4": dict(
+        model="dense8b", seed=2, chunk_bytes=64 * MiB,
+        holders=[layout(1, 0)],
+        reader=layout(4, 0, f32_store="bf16")),
+    # 70B, TP=8 holders 0 and 1 -> TP=4 rank-0 reader, 256 MiB chunks
+    "cfg3_70b_tp8_to_tp4": dict(
+        model="dense70b", seed=3, chunk_bytes=256 * MiB,
+        holders=[layout(8, 0), layout(8, 1)],
+        reader=layout(4, 0, f32_store="bf16")),
+    # MoE, EP=8 rank-0 holder (per-expert tensors, TP=1 attention) -> TP=2 rank-0
+    # reader with stacked experts, 4 MiB chunks
+    "cfg4_moe_ep8_to_tp2": dict(
+        model="moe", seed=4, chunk_bytes=4 * MiB,
+        holders=[layout(1, 0, ep_size=8, ep_rank=0)],
+        reader=layout(2, 0, experts_stacked=1, f32_store="bf16")),
+    # reduced variants
+    "small_dense_tp1_to_tp4": dict(
+        model="dense_small", seed=12, chunk_bytes=1 * MiB,
+        holders=[layout(1, 0)],
+        reader=layout(4, 0, f32_store="bf16")),
+    "small_dense_tp4_to_tp2": dict(
+        model="dense_small", seed=13, chunk_bytes=256 * 1024,
+        holders=[layout(4, 2), layout(4, 3)],
+        reader=layout(2, 1, f32_store="bf16")),
+    "small_moe_ep4_to_tp2": dict(
+        model="moe_small", seed=14, chunk_bytes=128 * 1024,
+        holders=[layout(1, 0, ep_size=4, ep_rank=1)],
+        reader=layout(2, 1, experts_stacked=1, f32_store="bf16")),
+}
+
+
+def workload(name):
+    w = dict(WORKLOADS[name])
+    w["name"] = name
+    w["model_name"] = w["model"]
+    w["model"] = dict(MODELS[w["model"]])
+    return w
