@@ -1,0 +1,256 @@
+/* th.h - C ABI of the GPU-resident reshard path of Reference-Oriented Storage
+ * weight transfer (TensorHub).
+ *
+ * Where this sits in the paper.  A reader materialises weight version v "into
+ * the handle's registered tensors" from a replica held by other workers
+ * (Sec. 3.1 replicate, Sec. 4.2 Registration / Replicate); before transfer the
+ * weights are "resharded and converted to inference-ready format" (Sec. 2.1,
+ * step 4); the transfer engine copies tensor data slice by slice into staging
+ * buffers (Sec. 4.3.2, RDMA Copy) and compacts small tensors into contiguous
+ * buffers that the receiver unpacks into their slices (Sec. 4.3.2, Tiny-Tensor
+ * Optimization); a reader may consume the prefix of tensors that has arrived
+ * (Sec. 4.3.3, progress counter).  The paper stops there: it gives no layout
+ * math and no wire format.  This library defines both (standard tensor- /
+ * expert-parallel shard shapes, a tensor-ordered wire stream cut into chunks)
+ * and runs the two data-moving steps on the GPU:
+ *
+ *   th_pack    holder side: gather what one reader needs out of the holder's
+ *              registered tensors into contiguous wire chunks (narrowing fp32 to
+ *              bf16 on the way if the reader stores bf16);
+ *   th_unpack  reader side: scatter received chunks into the reader's
+ *              registered tensors, which are sharded differently.
+ *
+ * Conventions
+ *   - All functions return th_status (0 = ok, negative = error) unless they
+ *     return a size; they never abort, throw or print.  th_last_error() gives
+ *     the message of the calling thread's last failure.
+ *   - "host"/"device" in a parameter comment says where the pointed-to memory
+ *     lives.  The caller owns every tensor and every wire chunk; the library
+ *     owns the plan and the small device tables that belong to it.
+ *   - A plan is immutable after creation and is bound to the HIP device that
+ *     was current when it was created.  th_pack / th_unpack on one plan may be
+ *     issued from several threads and on several streams.
+ *   - Mutability contract (Sec. 3.2): while a th_pack that was enqueued has not
+ *     completed on its stream, the caller must not write the source tensors;
+ *     the same holds for wire chunks during th_unpack.  Destination bytes that
+ *     the plan does not cover are never written.
+ *
+ * Wire format (one plan = one holder -> one reader)
+ *   The stream is, for each of the holder's registered tensors in registration
+ *   order, the elements of that tensor the reader needs, in the tensor's
+ *   row-major order, already in the reader's dtype.  Each tensor's run starts
+ *   at the next 16-byte boundary; gap bytes are zero; tensors that contribute
+ *   nothing occupy nothing.  Chunk c is stream bytes [c*CB, min((c+1)*CB, total)).
+ *   Chunks are self-contained: any subset can be packed or unpacked, in any
+ *   order, which is what lets a reader consume a prefix.
+ */
+#ifndef TENSORHUB_RESHARD_TH_H
+#define TENSORHUB_RESHARD_TH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct th_plan th_plan; /* opaque; created and destroyed by the library */
+
+typedef enum { TH_BF16 = 1, TH_F32 = 2 } th_dtype;
+
+typedef enum {
+    TH_OK = 0,
+    TH_ERR_ARG = -1,          /* null pointer, bad enum, negative size, misaligned pointer ... */
+    TH_ERR_INDIVISIBLE = -2,  /* a dimension does not split evenly over the parallel size */
+    TH_ERR_UNSUPPORTED = -3,  /* e.g. more tensor-parallel ranks than KV heads, bf16 -> fp32 */
+    TH_ERR_RANGE = -4,        /* chunk / tensor index or a segment outside its tensor */
+    TH_ERR_NOMEM = -5,
+    TH_ERR_HIP = -6           /* a HIP runtime call failed; message has the HIP error string */
+} th_status;
+
+enum { TH_MODEL_DENSE = 1, TH_MODEL_MOE = 2 };
+
+/* th_plan_create* flags */
+enum {
+    TH_FLAG_HOST_ONLY = 1u << 0,  /* build the manifest only; no device tables, pack/unpack refuse */
+    TH_FLAG_PTRS_ALIGNED16 = 1u << 1 /* th_plan_create_from_segments: caller promises that every
+                                        tensor base pointer is 16-byte aligned (model plans always
+                                        require it) */
+};
+
+/* Shape of the model whose weights are transferred (Sec. 2.1: what is resharded).
+ * Every weight is a logical row-major matrix W[out, in].  Registration order on
+ * every rank: embed_tokens; per layer: input_norm, qkv_proj, o_proj,
+ * post_attn_norm, then gate_up_proj, down_proj (dense) or router, experts
+ * 0..: w13, w2, shared experts 0..: w13, w2 (MoE); final_norm; lm_head unless
+ * tied. */
+typedef struct th_model_desc {
+    int kind;        /* TH_MODEL_DENSE or TH_MODEL_MOE */
+    int n_layers, hidden, n_q_heads, n_kv_heads, head_dim;
+    int ffn;         /* dense FFN width (SwiGLU, fused gate_up); ignored for MoE */
+    int vocab;
+    int tied_embeddings; /* nonzero: no lm_head tensor */
+    int n_experts, n_shared_experts, expert_ffn; /* MoE only */
+    int weight_dtype; /* th_dtype of matrices */
+    int norm_dtype;   /* th_dtype of normalisation weights at the model level */
+} th_model_desc;
+
+/* One worker's place in a model-parallel group (Sec. 4.1: one shard per worker).
+ *   tensor parallel: column-parallel qkv_proj / gate_up_proj / w13 / lm_head and
+ *   vocab-parallel embed_tokens split rows, row-parallel o_proj / down_proj / w2
+ *   split columns, norms and router are replicated.  Fused QKV is [Q heads | K
+ *   heads | V heads] globally and [Q_r; K_r; V_r] locally with contiguous head
+ *   ranges (needs tp_size | n_kv_heads); fused gate_up is [gate | up] globally
+ *   and [gate_r; up_r] locally.
+ *   expert parallel: rank p keeps routed experts [p*E/P, (p+1)*E/P) whole.
+ *   experts_stacked: the rank's routed experts live in one tensor per layer and
+ *   kind ("layers.L.experts.w13" [E_local, 2F/T, H], ".w2" [E_local, H, F/T])
+ *   instead of one tensor per expert.
+ *   f32_store: th_dtype in which this side keeps tensors whose model dtype is
+ *   fp32 (TH_BF16 on the reader side = narrow on the wire, round-to-nearest-even).
+ * Replicated data is sent by one holder only: tensor-parallel rank
+ * floor(d*S/D) for reader rank d of D and S holder ranks, same rule for
+ * expert-parallel ranks and tensors that are not routed experts. */
+typedef struct th_layout {
+    int tp_size, tp_rank, ep_size, ep_rank;
+    int experts_stacked;
+    int f32_store;
+} th_layout;
+
+/* Build the plan for holder layout `src` -> reader layout `dst` (all host
+ * pointers).  chunk_bytes: wire chunk size CB, a positive multiple of 16.
+ * On success *out receives the plan; unless TH_FLAG_HOST_ONLY is set the
+ * plan's device tables are allocated and uploaded on the current device
+ * (synchronous).  Errors: TH_ERR_ARG, TH_ERR_INDIVISIBLE, TH_ERR_UNSUPPORTED,
+ * TH_ERR_NOMEM, TH_ERR_HIP. */
+int th_plan_create(const th_model_desc* model, const th_layout* src, const th_layout* dst,
+                   size_t chunk_bytes, unsigned flags, th_plan** out);
+
+/* A caller-defined segment: nrows rows of row_len elements; row r starts at
+ * element src_elem_off + r*src_row_stride of source tensor src_tensor and at
+ * dst_elem_off + r*dst_row_stride of destination tensor dst_tensor.  Offsets
+ * and strides are in elements of the respective dtype. */
+typedef struct th_segment {
+    uint32_t src_tensor, dst_tensor;
+    uint64_t src_elem_off, dst_elem_off;
+    uint64_t src_row_stride, dst_row_stride;
+    uint64_t nrows, row_len;
+    uint8_t src_dtype, dst_dtype; /* th_dtype; wire dtype = dst_dtype */
+    uint8_t reserved[6];
+} th_segment;
+
+/* Build a plan from explicit segments given in wire order (host array of n).
+ * On the wire each segment is dense, row after row; a segment whose source
+ * tensor differs from the previous segment's starts at the next 16-byte
+ * boundary.  src_tensor_elems / dst_tensor_elems (host arrays of n_src / n_dst)
+ * give each tensor's element count; every segment is bounds-checked against
+ * them (TH_ERR_RANGE).  A tensor has one dtype: segments that disagree on a
+ * tensor's dtype are rejected.  Overlapping destination segments are the
+ * caller's responsibility. */
+int th_plan_create_from_segments(const th_segment* segs, size_t n,
+                                 const uint64_t* src_tensor_elems, uint32_t n_src,
+                                 const uint64_t* dst_tensor_elems, uint32_t n_dst,
+                                 size_t chunk_bytes, unsigned flags, th_plan** out);
+
+/* Enqueue the gather of chunks [chunk_first, chunk_first + chunk_count) on
+ * hip_stream (a hipStream_t, NULL = the default stream) and return without
+ * synchronising.
+ *   src_ptrs   host array of n_src device pointers, indexed by the plan's source
+ *              tensor ids (the holder's registered tensors); n_src must equal
+ *              th_plan_num_tensors(plan, 0).  Pointers must be aligned to the
+ *              element size, and to 16 bytes for model plans / ALIGNED16 plans.
+ *   wire_ptrs  host array of chunk_count device pointers; wire_ptrs[i] receives
+ *              chunk chunk_first+i, must be 16-byte aligned and hold at least
+ *              th_plan_chunk_bytes(plan, chunk_first+i) bytes.  Every byte of the
+ *              chunk is written (payload and zero gaps).
+ * The host arrays are read before the call returns.  Pointer tables are kept on
+ * the device and re-uploaded only when their contents change.
+ * Errors (synchronous): TH_ERR_ARG, TH_ERR_RANGE, TH_ERR_HIP.  Device-side
+ * faults surface at the caller's next synchronisation. */
+int th_pack(const th_plan* plan, const void* const* src_ptrs, uint32_t n_src,
+            void* const* wire_ptrs, uint32_t chunk_first, uint32_t chunk_count, void* hip_stream);
+
+/* Enqueue the scatter of chunks [chunk_first, chunk_first + chunk_count) into
+ * the reader's registered tensors.  wire_ptrs as for th_pack (read-only here);
+ * dst_ptrs: host array of n_dst device pointers indexed by destination tensor
+ * id, n_dst == th_plan_num_tensors(plan, 1), same alignment rules.  Only the
+ * elements the plan covers are written. */
+int th_unpack(const th_plan* plan, const void* const* wire_ptrs, uint32_t chunk_first,
+              uint32_t chunk_count, void* const* dst_ptrs, uint32_t n_dst, void* hip_stream);
+
+/* Free the plan and its device tables.  NULL is accepted.  The caller must
+ * have synchronised every stream that still runs work of this plan. */
+int th_plan_destroy(th_plan* plan);
+
+/* ---- read-only queries (host) ------------------------------------------------------------- */
+
+uint32_t th_plan_num_chunks(const th_plan* plan);
+size_t th_plan_chunk_bytes(const th_plan* plan, uint32_t chunk); /* 0 if out of range */
+size_t th_plan_wire_bytes(const th_plan* plan);    /* stream length: payload + alignment gaps */
+size_t th_plan_payload_bytes(const th_plan* plan); /* element bytes on the wire */
+size_t th_plan_src_read_bytes(const th_plan* plan); /* element bytes th_pack reads from the holder */
+
+/* side: 0 = source (holder) tensors, 1 = destination (reader) tensors */
+uint32_t th_plan_num_tensors(const th_plan* plan, int side);
+/* name is copied (truncated to cap-1 chars, always terminated) when name != NULL;
+ * rows*cols = element count (explicit-segment plans report rows = 1). */
+int th_plan_tensor_info(const th_plan* plan, int side, uint32_t id, char* name, size_t cap,
+                        uint64_t* rows, uint64_t* cols, int* dtype);
+
+/* The manifest.  A run is one rectangle of one source tensor cut so that it
+ * lies inside one wire chunk: `nrows` rows of `row_len` elements.  Byte offsets
+ * are relative to the tensor base / chunk base; strides in bytes. */
+typedef struct th_run {
+    uint32_t src_tensor, dst_tensor, chunk, reserved;
+    uint64_t src_byte_off, src_byte_stride;
+    uint64_t dst_byte_off, dst_byte_stride;
+    uint64_t chunk_byte_off, wire_byte_stride;
+    uint64_t nrows, row_len;
+    uint8_t src_dtype, dst_dtype;
+    uint8_t pad_bytes; /* zero bytes that follow the run's last element on the wire */
+    uint8_t reserved2[5];
+} th_run;
+size_t th_plan_num_runs(const th_plan* plan);
+int th_plan_get_run(const th_plan* plan, size_t i, th_run* out);
+
+/* The device work list, for inspection.  side 0 = th_pack's tiles, 1 =
+ * th_unpack's.  Tiles are ordered by chunk; each is one workgroup's share: a
+ * sub-rectangle of a run, described as a copy from (src_buf, src_byte_off) to
+ * (dst_buf, dst_byte_off).  For side 0 src_buf is a source tensor id and
+ * dst_buf a chunk index; for side 1 src_buf is a chunk index and dst_buf a
+ * destination tensor id.  ncols is in elements of width `elem_bytes_dst` on the
+ * destination and `elem_bytes_src` on the source. */
+typedef struct th_tile_info {
+    uint32_t src_buf, dst_buf;
+    uint64_t src_byte_off, src_byte_stride;
+    uint64_t dst_byte_off, dst_byte_stride;
+    uint64_t nrows, ncols;
+    uint8_t elem_bytes_src, elem_bytes_dst;
+    uint8_t kind;      /* 0 = 16-byte vector path, 1 = any-alignment path */
+    uint8_t pad_bytes; /* zero bytes written after the tile's last element (pack side) */
+    uint8_t reserved[4];
+} th_tile_info;
+size_t th_plan_num_tiles(const th_plan* plan, int side);
+int th_plan_get_tile(const th_plan* plan, int side, size_t i, th_tile_info* out);
+/* first tile of `chunk` on `side`; chunk == num_chunks gives the tile count */
+size_t th_plan_chunk_first_tile(const th_plan* plan, int side, uint32_t chunk);
+
+/* Process-wide tuning knobs, read when a plan is created.  Returns TH_ERR_ARG
+ * for an unknown key or an out-of-range value. */
+enum {
+    TH_CFG_TILE_BYTES = 1 /* destination bytes per tile (one workgroup's share);
+                             multiple of 4096 in [4096, 1048576 - 4096]; default 65536 */
+};
+int th_config_set(int key, uint64_t value);
+uint64_t th_config_get(int key);
+
+/* Message of the calling thread's most recent error ("" if none); static storage. */
+const char* th_last_error(void);
+
+/* Library version, e.g. "0.1". */
+const char* th_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TENSORHUB_RESHARD_TH_H */

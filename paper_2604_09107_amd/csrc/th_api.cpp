@@ -1,0 +1,448 @@
+// The C ABI declared in th.h: plan objects, device tables, pointer-table cache, queries.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "th_internal.hpp"
+
+namespace th {
+
+namespace {
+thread_local char g_err[512] = "";
+std::mutex g_cfg_mu;
+Tuning g_tuning;
+}  // namespace
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+}
+
+Tuning current_tuning() {
+    std::lock_guard<std::mutex> lk(g_cfg_mu);
+    return g_tuning;
+}
+
+namespace {
+
+int hip_fail(hipError_t e, const char* what) {
+    set_error("%s: %s", what, hipGetErrorString(e));
+    return TH_ERR_HIP;
+}
+
+// A pointer table that lives on the device, with the host copy it was uploaded from and an
+// event marking the last kernel that reads it.
+struct PtrSlot {
+    std::vector<uintptr_t> host;
+    void** dev = nullptr;
+    size_t cap = 0;  // entries allocated on the device
+    hipEvent_t used = nullptr;
+    bool recorded = false;
+    uint64_t stamp = 0;
+};
+
+// Small cache of uploaded pointer tables: callers usually pass the same registered
+// tensors and the same wire buffers version after version (tensors are registered once
+// and reused, Sec. 4.2), so steady-state calls upload nothing.
+struct PtrCache {
+    static constexpr size_t kSlots = 8;
+    std::vector<PtrSlot> slots;
+    uint64_t clock = 0;
+
+    // Returns the slot holding exactly `key` (uploading it if new), or nullptr on error.
+    PtrSlot* get(const std::vector<uintptr_t>& key, bool& fresh) {
+        fresh = false;
+        for (PtrSlot& s : slots)
+            if (s.host == key) {
+                s.stamp = ++clock;
+                return &s;
+            }
+        PtrSlot* s;
+        if (slots.size() < kSlots) {
+            slots.emplace_back();
+            s = &slots.back();
+        } else {
+            s = &slots[0];
+            for (PtrSlot& c : slots)
+                if (c.stamp < s->stamp) s = &c;
+            // a kernel that was handed this table may still be running
+            if (s->recorded) {
+                hipError_t e = hipEventSynchronize(s->used);
+                if (e != hipSuccess) {
+                    hip_fail(e, "hipEventSynchronize");
+                    return nullptr;
+                }
+            }
+        }
+        if (!s->used) {
+            hipError_t e = hipEventCreateWithFlags(&s->used, hipEventDisableTiming);
+            if (e != hipSuccess) {
+                hip_fail(e, "hipEventCreate");
+                return nullptr;
+            }
+        }
+        const size_t n = key.size() ? key.size() : 1;
+        if (s->cap < n) {
+            if (s->dev) (void)hipFree(s->dev);
+            s->dev = nullptr;
+            s->cap = 0;
+            hipError_t e = hipMalloc(reinterpret_cast<void**>(&s->dev), n * sizeof(void*));
+            if (e != hipSuccess) {
+                s->host.clear();
+                hip_fail(e, "hipMalloc(pointer table)");
+                return nullptr;
+            }
+            s->cap = n;
+        }
+        if (!key.empty()) {
+            hipError_t e = hipMemcpy(s->dev, key.data(), key.size() * sizeof(void*), hipMemcpyHostToDevice);
+            if (e != hipSuccess) {
+                s->host.clear();
+                hip_fail(e, "hipMemcpy(pointer table)");
+                return nullptr;
+            }
+        }
+        s->host = key;
+        s->recorded = false;
+        s->stamp = ++clock;
+        fresh = true;
+        return s;
+    }
+
+    void release() {
+        for (PtrSlot& s : slots) {
+            if (s.dev) (void)hipFree(s.dev);
+            if (s.used) (void)hipEventDestroy(s.used);
+        }
+        slots.clear();
+    }
+};
+
+}  // namespace
+}  // namespace th
+
+struct th_plan {
+    th::Manifest m;
+    bool host_only = false;
+    int device = -1;
+    th::Tile* d_tiles[2] = {nullptr, nullptr};
+    // guarded by mu: pointer-table caches (tensor side per direction, wire side per direction)
+    mutable std::mutex mu;
+    mutable th::PtrCache tensor_cache[2], wire_cache[2];
+};
+
+namespace th {
+namespace {
+
+int upload_tables(th_plan* p) {
+    hipError_t e = hipGetDevice(&p->device);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    for (int side = 0; side < 2; ++side) {
+        const std::vector<Tile>& t = p->m.tiles[side];
+        if (t.empty()) continue;
+        e = hipMalloc(reinterpret_cast<void**>(&p->d_tiles[side]), t.size() * sizeof(Tile));
+        if (e != hipSuccess) return hip_fail(e, "hipMalloc(tile table)");
+        e = hipMemcpy(p->d_tiles[side], t.data(), t.size() * sizeof(Tile), hipMemcpyHostToDevice);
+        if (e != hipSuccess) return hip_fail(e, "hipMemcpy(tile table)");
+    }
+    return TH_OK;
+}
+
+int finish_plan(th_plan* p, size_t chunk_bytes, unsigned flags, bool aligned16, th_plan** out) {
+    int rc = finish_manifest(p->m, chunk_bytes, aligned16, current_tuning());
+    if (rc == TH_OK) {
+        p->host_only = (flags & TH_FLAG_HOST_ONLY) != 0;
+        if (!p->host_only) rc = upload_tables(p);
+    }
+    if (rc != TH_OK) {
+        th_plan_destroy(p);
+        return rc;
+    }
+    *out = p;
+    return TH_OK;
+}
+
+// Shared body of th_pack / th_unpack.  side 0: tensors are the source, wire the destination.
+int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_t n_tensors,
+             const void* const* wire_ptrs, uint32_t chunk_first, uint32_t chunk_count, void* stream) {
+    if (!p) {
+        set_error("plan is NULL");
+        return TH_ERR_ARG;
+    }
+    if (p->host_only) {
+        set_error("plan was created with TH_FLAG_HOST_ONLY");
+        return TH_ERR_ARG;
+    }
+    const Manifest& m = p->m;
+    if (n_tensors != m.tensors[side].size()) {
+        set_error("%u tensor pointers given, plan has %zu %s tensors", n_tensors, m.tensors[side].size(),
+                  side ? "destination" : "source");
+        return TH_ERR_ARG;
+    }
+    if ((uint64_t)chunk_first + chunk_count > m.n_chunks) {
+        set_error("chunk range [%u, %u+%u) outside the plan's %u chunks", chunk_first, chunk_first, chunk_count,
+                  m.n_chunks);
+        return TH_ERR_RANGE;
+    }
+    if (chunk_count == 0) return TH_OK;
+    if (!wire_ptrs || (n_tensors && !tensor_ptrs)) {
+        set_error("null pointer array");
+        return TH_ERR_ARG;
+    }
+    const uint64_t tile0 = m.chunk_tile0[side][chunk_first];
+    const uint64_t ntiles = m.chunk_tile0[side][chunk_first + chunk_count] - tile0;
+    if (ntiles == 0) return TH_OK;
+
+    std::vector<uintptr_t> tkey(n_tensors), wkey((size_t)chunk_count + 1);
+    for (uint32_t i = 0; i < n_tensors; ++i) tkey[i] = reinterpret_cast<uintptr_t>(tensor_ptrs[i]);
+    wkey[0] = chunk_first;  // entry 0 of the uploaded table is skipped by the kernel's indexing
+    for (uint32_t i = 0; i < chunk_count; ++i) wkey[i + 1] = reinterpret_cast<uintptr_t>(wire_ptrs[i]);
+
+    std::lock_guard<std::mutex> lk(p->mu);
+    bool fresh = false;
+    PtrSlot* ts = p->tensor_cache[side].get(tkey, fresh);
+    if (!ts) return TH_ERR_HIP;
+    if (fresh) {
+        // validate once per distinct table
+        for (uint32_t i = 0; i < n_tensors; ++i) {
+            const TensorInfo& t = m.tensors[side][i];
+            if (!t.used) continue;
+            const uintptr_t a = tkey[i];
+            const uintptr_t need = t.need16 ? 16 : esize(t.dtype);
+            if (a == 0 || a % need) {
+                ts->host.clear();  // do not keep a rejected table
+                set_error("%s tensor %u (%s): pointer %p is %s", side ? "destination" : "source", i,
+                          t.name.c_str(), (void*)a, a ? "misaligned" : "NULL");
+                return TH_ERR_ARG;
+            }
+        }
+    }
+    PtrSlot* ws = p->wire_cache[side].get(wkey, fresh);
+    if (!ws) return TH_ERR_HIP;
+    if (fresh) {
+        for (uint32_t i = 0; i < chunk_count; ++i)
+            if (wkey[i + 1] == 0 || wkey[i + 1] % 16) {
+                ws->host.clear();
+                set_error("wire pointer %u is NULL or not 16-byte aligned", i);
+                return TH_ERR_ARG;
+            }
+    }
+    const void* const* wire_tab = reinterpret_cast<const void* const*>(ws->dev + 1);
+    const void* const* tens_tab = reinterpret_cast<const void* const*>(ts->dev);
+    int rc;
+    if (side == 0)
+        rc = launch_tiles(true, p->d_tiles[0], tile0, ntiles, tens_tab, const_cast<void* const*>(wire_tab),
+                          chunk_first, stream);
+    else
+        rc = launch_tiles(false, p->d_tiles[1], tile0, ntiles, wire_tab, const_cast<void* const*>(tens_tab),
+                          chunk_first, stream);
+    if (rc != TH_OK) return rc;
+    for (PtrSlot* s : {ts, ws}) {
+        hipError_t e = hipEventRecord(s->used, static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return hip_fail(e, "hipEventRecord");
+        s->recorded = true;
+    }
+    return TH_OK;
+}
+
+}  // namespace
+}  // namespace th
+
+using namespace th;
+
+extern "C" {
+
+int th_plan_create(const th_model_desc* model, const th_layout* src, const th_layout* dst, size_t chunk_bytes,
+                   unsigned flags, th_plan** out) {
+    if (!model || !src || !dst || !out) {
+        set_error("null argument");
+        return TH_ERR_ARG;
+    }
+    *out = nullptr;
+    th_plan* p = new (std::nothrow) th_plan;
+    if (!p) {
+        set_error("out of memory");
+        return TH_ERR_NOMEM;
+    }
+    try {
+        int rc = build_model_segments(*model, *src, *dst, p->m);
+        if (rc != TH_OK) {
+            delete p;
+            return rc;
+        }
+        return finish_plan(p, chunk_bytes, flags, /*aligned16=*/true, out);
+    } catch (const std::bad_alloc&) {
+        delete p;
+        set_error("out of memory");
+        return TH_ERR_NOMEM;
+    }
+}
+
+int th_plan_create_from_segments(const th_segment* segs, size_t n, const uint64_t* src_tensor_elems,
+                                 uint32_t n_src, const uint64_t* dst_tensor_elems, uint32_t n_dst,
+                                 size_t chunk_bytes, unsigned flags, th_plan** out) {
+    if (!out) {
+        set_error("null argument");
+        return TH_ERR_ARG;
+    }
+    *out = nullptr;
+    th_plan* p = new (std::nothrow) th_plan;
+    if (!p) {
+        set_error("out of memory");
+        return TH_ERR_NOMEM;
+    }
+    try {
+        int rc = segments_from_user(segs, n, src_tensor_elems, n_src, dst_tensor_elems, n_dst, p->m);
+        if (rc != TH_OK) {
+            delete p;
+            return rc;
+        }
+        return finish_plan(p, chunk_bytes, flags, (flags & TH_FLAG_PTRS_ALIGNED16) != 0, out);
+    } catch (const std::bad_alloc&) {
+        delete p;
+        set_error("out of memory");
+        return TH_ERR_NOMEM;
+    }
+}
+
+int th_pack(const th_plan* plan, const void* const* src_ptrs, uint32_t n_src, void* const* wire_ptrs,
+            uint32_t chunk_first, uint32_t chunk_count, void* hip_stream) {
+    return run_side(plan, 0, src_ptrs, n_src, const_cast<const void* const*>(wire_ptrs), chunk_first,
+                    chunk_count, hip_stream);
+}
+
+int th_unpack(const th_plan* plan, const void* const* wire_ptrs, uint32_t chunk_first, uint32_t chunk_count,
+              void* const* dst_ptrs, uint32_t n_dst, void* hip_stream) {
+    return run_side(plan, 1, const_cast<const void* const*>(dst_ptrs), n_dst, wire_ptrs, chunk_first,
+                    chunk_count, hip_stream);
+}
+
+int th_plan_destroy(th_plan* p) {
+    if (!p) return TH_OK;
+    for (int side = 0; side < 2; ++side) {
+        if (p->d_tiles[side]) (void)hipFree(p->d_tiles[side]);
+        p->tensor_cache[side].release();
+        p->wire_cache[side].release();
+    }
+    delete p;
+    return TH_OK;
+}
+
+uint32_t th_plan_num_chunks(const th_plan* p) { return p ? p->m.n_chunks : 0; }
+
+size_t th_plan_chunk_bytes(const th_plan* p, uint32_t c) {
+    if (!p || c >= p->m.n_chunks) return 0;
+    const uint64_t lo = (uint64_t)c * p->m.chunk_bytes;
+    return (size_t)std::min<uint64_t>(p->m.chunk_bytes, p->m.wire_bytes - lo);
+}
+
+size_t th_plan_wire_bytes(const th_plan* p) { return p ? p->m.wire_bytes : 0; }
+size_t th_plan_payload_bytes(const th_plan* p) { return p ? p->m.payload_bytes : 0; }
+size_t th_plan_src_read_bytes(const th_plan* p) { return p ? p->m.src_read_bytes : 0; }
+
+uint32_t th_plan_num_tensors(const th_plan* p, int side) {
+    return (p && (side == 0 || side == 1)) ? (uint32_t)p->m.tensors[side].size() : 0;
+}
+
+int th_plan_tensor_info(const th_plan* p, int side, uint32_t id, char* name, size_t cap, uint64_t* rows,
+                        uint64_t* cols, int* dtype) {
+    if (!p || (side != 0 && side != 1)) {
+        set_error("bad plan or side");
+        return TH_ERR_ARG;
+    }
+    if (id >= p->m.tensors[side].size()) {
+        set_error("tensor id %u out of range", id);
+        return TH_ERR_RANGE;
+    }
+    const TensorInfo& t = p->m.tensors[side][id];
+    if (name && cap) {
+        std::strncpy(name, t.name.c_str(), cap - 1);
+        name[cap - 1] = 0;
+    }
+    if (rows) *rows = t.rows;
+    if (cols) *cols = t.cols;
+    if (dtype) *dtype = t.dtype;
+    return TH_OK;
+}
+
+size_t th_plan_num_runs(const th_plan* p) { return p ? p->m.runs.size() : 0; }
+
+int th_plan_get_run(const th_plan* p, size_t i, th_run* out) {
+    if (!p || !out) {
+        set_error("null argument");
+        return TH_ERR_ARG;
+    }
+    if (i >= p->m.runs.size()) {
+        set_error("run index out of range");
+        return TH_ERR_RANGE;
+    }
+    *out = p->m.runs[i];
+    return TH_OK;
+}
+
+size_t th_plan_num_tiles(const th_plan* p, int side) {
+    return (p && (side == 0 || side == 1)) ? p->m.tiles[side].size() : 0;
+}
+
+int th_plan_get_tile(const th_plan* p, int side, size_t i, th_tile_info* out) {
+    if (!p || !out || (side != 0 && side != 1)) {
+        set_error("bad argument");
+        return TH_ERR_ARG;
+    }
+    if (i >= p->m.tiles[side].size()) {
+        set_error("tile index out of range");
+        return TH_ERR_RANGE;
+    }
+    const Tile& t = p->m.tiles[side][i];
+    std::memset(out, 0, sizeof *out);
+    out->src_buf = t.src_buf;
+    out->dst_buf = t.dst_buf;
+    out->src_byte_off = t.src_off;
+    out->src_byte_stride = t.src_stride;
+    out->dst_byte_off = t.dst_off;
+    out->dst_byte_stride = t.dst_stride;
+    out->nrows = t.nrows;
+    const bool vec = (t.flags & TILE_KIND_MASK) == TILE_KIND_VEC;
+    out->elem_bytes_src = (t.flags & TILE_SRC_F32) ? 4 : 2;
+    out->elem_bytes_dst = (t.flags & TILE_DST_F32) ? 4 : 2;
+    out->ncols = vec ? (uint64_t)t.ncols * 16 / out->elem_bytes_dst : t.ncols;
+    out->kind = vec ? 0 : 1;
+    out->pad_bytes = (uint8_t)((t.flags & TILE_PAD_MASK) >> TILE_PAD_SHIFT);
+    return TH_OK;
+}
+
+size_t th_plan_chunk_first_tile(const th_plan* p, int side, uint32_t chunk) {
+    if (!p || (side != 0 && side != 1) || chunk > p->m.n_chunks) return 0;
+    return (size_t)p->m.chunk_tile0[side][chunk];
+}
+
+int th_config_set(int key, uint64_t value) {
+    std::lock_guard<std::mutex> lk(g_cfg_mu);
+    switch (key) {
+        case TH_CFG_TILE_BYTES:
+            if (value < 4096 || value > 1048576 - 4096 || value % 4096) {
+                set_error("tile bytes must be a multiple of 4096 in [4096, 1044480]");
+                return TH_ERR_ARG;
+            }
+            g_tuning.tile_bytes = value;
+            return TH_OK;
+    }
+    set_error("unknown configuration key %d", key);
+    return TH_ERR_ARG;
+}
+
+uint64_t th_config_get(int key) {
+    std::lock_guard<std::mutex> lk(g_cfg_mu);
+    return key == TH_CFG_TILE_BYTES ? g_tuning.tile_bytes : 0;
+}
+
+const char* th_last_error(void) { return g_err; }
+const char* th_version(void) { return "0.1"; }
+
+}  // extern "C"

@@ -1,0 +1,101 @@
+// Internal structures shared by the host planner, the C ABI and the kernels.
+#pragma once
+
+#include <cstdint>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "th.h"
+
+namespace th {
+
+// ---- host side -----------------------------------------------------------------------------
+
+// One registered tensor of a rank (holder or reader side of a plan).
+struct TensorInfo {
+    std::string name;
+    int dtype = 0;  // th_dtype
+    uint64_t rows = 0, cols = 0;
+    bool used = false;    // some run reads or writes it
+    bool need16 = false;  // some tile addresses it with 16-byte vector accesses
+};
+
+// A rectangle of one source tensor that the reader needs, with its place on the
+// wire and in the reader's tensor.  Offsets / strides in elements, wire in bytes.
+struct Segment {
+    uint32_t src_tensor = 0, dst_tensor = 0;
+    uint64_t src_off = 0, src_stride = 0;
+    uint64_t dst_off = 0, dst_stride = 0;
+    uint64_t nrows = 0, row_len = 0;
+    uint64_t wire_off = 0, wire_stride = 0;  // bytes
+    uint8_t src_dtype = 0, dst_dtype = 0;
+    uint8_t pad_after = 0;  // zero bytes after the segment's last element (wire alignment gap)
+};
+
+// 64-byte device record: one workgroup's share of a pack or unpack launch.
+// Self-contained so that a workgroup needs a single (scalar) fetch to know its job.
+struct alignas(64) Tile {
+    uint64_t src_off;     // bytes from the base pointer of src_buf
+    uint64_t dst_off;     // bytes from the base pointer of dst_buf
+    uint64_t src_stride;  // bytes between consecutive rows
+    uint64_t dst_stride;
+    uint32_t src_buf;  // pack: source tensor id; unpack: chunk index
+    uint32_t dst_buf;  // pack: chunk index;      unpack: destination tensor id
+    uint32_t nrows;
+    uint32_t ncols;  // KIND_VEC: 16-byte vectors per row; KIND_ANY: elements per row
+    uint32_t flags;  // see below
+    uint32_t magic;  // KIND_VEC with nrows > 1: floor(2^32 / ncols) + 1
+    uint32_t reserved[2];
+};
+static_assert(sizeof(Tile) == 64, "tile record is one 64-byte line");
+
+enum : uint32_t {
+    TILE_KIND_MASK = 0x3,
+    TILE_KIND_VEC = 0,   // every address and the row length are multiples of 16 bytes, no conversion
+    TILE_KIND_ANY = 1,   // element-aligned addresses, optional fp32 -> bf16 narrowing
+    TILE_SRC_F32 = 1u << 2,
+    TILE_DST_F32 = 1u << 3,
+    TILE_LG_LANES_SHIFT = 8,  // KIND_ANY: log2 of the threads that share one row (0..8)
+    TILE_LG_LANES_MASK = 0xF << TILE_LG_LANES_SHIFT,
+    TILE_PAD_SHIFT = 16,  // zero bytes (0..14) to write after the tile's last element
+    TILE_PAD_MASK = 0xF << TILE_PAD_SHIFT,
+};
+
+constexpr int kBlockThreads = 256;
+
+struct Manifest {
+    std::vector<TensorInfo> tensors[2];  // 0 = source side, 1 = destination side
+    std::vector<Segment> segments;       // wire order
+    std::vector<th_run> runs;            // segments cut at chunk boundaries, wire order
+    std::vector<Tile> tiles[2];          // 0 = pack, 1 = unpack; ordered by chunk
+    std::vector<uint64_t> chunk_tile0[2];  // first tile of each chunk (+ total at the end)
+    uint64_t chunk_bytes = 0, wire_bytes = 0, payload_bytes = 0, src_read_bytes = 0;
+    uint32_t n_chunks = 0;
+};
+
+struct Tuning {
+    uint64_t tile_bytes = 65536;
+};
+Tuning current_tuning();
+
+void set_error(const char* fmt, ...);
+
+// th_layouts.cpp: registered tensors of both ranks and the rectangles that move between them.
+int build_model_segments(const th_model_desc& model, const th_layout& src, const th_layout& dst,
+                         Manifest& m);
+// th_planner.cpp
+int segments_from_user(const th_segment* segs, size_t n, const uint64_t* src_elems, uint32_t n_src,
+                       const uint64_t* dst_elems, uint32_t n_dst, Manifest& m);
+int finish_manifest(Manifest& m, uint64_t chunk_bytes, bool ptrs_aligned16, const Tuning& tune);
+
+inline unsigned esize(int dtype) { return dtype == TH_F32 ? 4u : 2u; }
+
+// ---- device side (th_kernels.hip) ------------------------------------------------------------
+// Launches one kernel over tiles [tile0, tile0 + ntiles) of `tiles` (device pointer).
+// wire_first: chunk index that entry 0 of the wire pointer table stands for.
+int launch_tiles(bool is_pack, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
+                 const void* const* src_table, void* const* dst_table, uint32_t wire_first,
+                 void* stream);
+
+}  // namespace th

@@ -1,0 +1,267 @@
+// Host planner: turns wire-ordered segments into the chunk manifest (runs) and the
+// device work list (tiles).  Integer arithmetic only.
+#include <algorithm>
+#include <cstring>
+
+#include "th_internal.hpp"
+
+namespace th {
+namespace {
+
+typedef unsigned __int128 u128;
+
+uint64_t seg_wire_end(const Segment& g) {
+    return g.wire_off + (g.nrows - 1) * g.wire_stride + g.row_len * esize(g.dst_dtype);
+}
+
+unsigned ceil_log2(uint64_t v) {
+    unsigned l = 0;
+    while ((1ull << l) < v) ++l;
+    return l;
+}
+
+struct Side {  // one end of a copy, in bytes
+    uint32_t buf;
+    uint64_t off, stride;
+    unsigned es;
+};
+
+// Append the tiles of one run, seen as a copy S -> D of nrows x ncols elements.
+void tile_run(std::vector<Tile>& out, Side S, Side D, uint64_t nrows, uint64_t ncols, unsigned pad,
+              bool bases_aligned16, uint64_t tile_bytes, bool& used_vec) {
+    // rows that follow each other without a gap on both ends are one long row
+    if (nrows > 1 && S.stride == ncols * S.es && D.stride == ncols * D.es) {
+        ncols *= nrows;
+        nrows = 1;
+    }
+    const bool vec = bases_aligned16 && pad == 0 && S.es == D.es && S.off % 16 == 0 && D.off % 16 == 0 &&
+                     (ncols * D.es) % 16 == 0 && (nrows == 1 || (S.stride % 16 == 0 && D.stride % 16 == 0));
+    used_vec = vec;
+    uint32_t flags = vec ? TILE_KIND_VEC : TILE_KIND_ANY;
+    if (S.es == 4) flags |= TILE_SRC_F32;
+    if (D.es == 4) flags |= TILE_DST_F32;
+    const uint64_t unit_d = vec ? 16 : D.es, unit_s = vec ? 16 : S.es;  // bytes per column unit
+    const uint64_t units = ncols * D.es / unit_d;                        // column units per row
+    const uint64_t row_bytes = ncols * D.es;
+
+    auto emit = [&](uint64_t r0, uint64_t nr, uint64_t u0, uint64_t nu, bool last) {
+        Tile t;
+        std::memset(&t, 0, sizeof t);
+        t.src_off = S.off + r0 * S.stride + u0 * unit_s;
+        t.dst_off = D.off + r0 * D.stride + u0 * unit_d;
+        t.src_stride = S.stride;
+        t.dst_stride = D.stride;
+        t.src_buf = S.buf;
+        t.dst_buf = D.buf;
+        t.nrows = (uint32_t)nr;
+        t.ncols = (uint32_t)nu;
+        t.flags = flags;
+        if (vec) {
+            t.magic = nr > 1 ? (uint32_t)((1ull << 32) / nu) + 1 : 0;
+        } else {
+            const uint64_t slots = (nu * D.es + 15) / 16 + 1;  // 16-byte destination slots a row can touch
+            t.flags |= std::min(8u, ceil_log2(slots)) << TILE_LG_LANES_SHIFT;
+        }
+        if (last && pad) t.flags |= (uint32_t)pad << TILE_PAD_SHIFT;
+        out.push_back(t);
+    };
+
+    if (nrows == 1 || row_bytes >= tile_bytes) {
+        // long rows: each row is cut into equal column pieces of at most one tile
+        const uint64_t k = (row_bytes + tile_bytes - 1) / tile_bytes;
+        uint64_t per = (units + k - 1) / k;
+        if (!vec) per = (per + 7) / 8 * 8;
+        for (uint64_t r = 0; r < nrows; ++r)
+            for (uint64_t u = 0; u < units; u += per)
+                emit(r, 1, u, std::min(per, units - u), r + 1 == nrows && u + per >= units);
+    } else {
+        // short rows: several whole rows per tile, evenly
+        const uint64_t fit = std::max<uint64_t>(1, tile_bytes / row_bytes);
+        const uint64_t nt = (nrows + fit - 1) / fit;
+        const uint64_t per = (nrows + nt - 1) / nt;
+        for (uint64_t r = 0; r < nrows; r += per)
+            emit(r, std::min(per, nrows - r), 0, units, r + per >= nrows);
+    }
+}
+
+}  // namespace
+
+int segments_from_user(const th_segment* segs, size_t n, const uint64_t* src_elems, uint32_t n_src,
+                       const uint64_t* dst_elems, uint32_t n_dst, Manifest& m) {
+    if ((n && !segs) || (n_src && !src_elems) || (n_dst && !dst_elems)) {
+        set_error("null segment or tensor-size array");
+        return TH_ERR_ARG;
+    }
+    for (int side = 0; side < 2; ++side) {
+        const uint32_t cnt = side ? n_dst : n_src;
+        m.tensors[side].resize(cnt);
+        for (uint32_t i = 0; i < cnt; ++i) {
+            TensorInfo& t = m.tensors[side][i];
+            t.name = (side ? "dst." : "src.") + std::to_string(i);
+            t.rows = 1;
+            t.cols = side ? dst_elems[i] : src_elems[i];
+            t.dtype = 0;
+        }
+    }
+    uint64_t wire = 0;
+    int64_t prev_tensor = -1;
+    for (size_t k = 0; k < n; ++k) {
+        const th_segment& u = segs[k];
+        if (u.src_tensor >= n_src || u.dst_tensor >= n_dst) {
+            set_error("segment %zu: tensor id out of range", k);
+            return TH_ERR_RANGE;
+        }
+        if ((u.src_dtype != TH_BF16 && u.src_dtype != TH_F32) || (u.dst_dtype != TH_BF16 && u.dst_dtype != TH_F32)) {
+            set_error("segment %zu: bad dtype", k);
+            return TH_ERR_ARG;
+        }
+        if (u.src_dtype == TH_BF16 && u.dst_dtype == TH_F32) {
+            set_error("segment %zu: bf16 -> fp32 widening is not supported", k);
+            return TH_ERR_UNSUPPORTED;
+        }
+        TensorInfo& st = m.tensors[0][u.src_tensor];
+        TensorInfo& dt = m.tensors[1][u.dst_tensor];
+        if ((st.dtype && st.dtype != u.src_dtype) || (dt.dtype && dt.dtype != u.dst_dtype)) {
+            set_error("segment %zu: a tensor is used with two dtypes", k);
+            return TH_ERR_ARG;
+        }
+        st.dtype = u.src_dtype;
+        dt.dtype = u.dst_dtype;
+        if (u.nrows == 0 || u.row_len == 0) continue;
+        if (u.nrows > 1 && u.dst_row_stride < u.row_len) {
+            set_error("segment %zu: destination rows overlap (stride < row length)", k);
+            return TH_ERR_ARG;
+        }
+        const u128 s_last = (u128)u.src_elem_off + (u128)(u.nrows - 1) * u.src_row_stride + u.row_len;
+        const u128 d_last = (u128)u.dst_elem_off + (u128)(u.nrows - 1) * u.dst_row_stride + u.row_len;
+        if (s_last > st.cols || d_last > dt.cols) {
+            set_error("segment %zu reaches outside its %s tensor", k, s_last > st.cols ? "source" : "destination");
+            return TH_ERR_RANGE;
+        }
+        if ((u128)u.nrows * u.row_len > ((u128)1 << 60)) {
+            set_error("segment %zu is too large", k);
+            return TH_ERR_RANGE;
+        }
+        if ((int64_t)u.src_tensor != prev_tensor) {
+            const uint64_t aligned = (wire + 15) / 16 * 16;
+            if (!m.segments.empty()) m.segments.back().pad_after = (uint8_t)(aligned - wire);
+            wire = aligned;
+            prev_tensor = u.src_tensor;
+        }
+        Segment g;
+        g.src_tensor = u.src_tensor;
+        g.dst_tensor = u.dst_tensor;
+        g.src_off = u.src_elem_off;
+        g.src_stride = u.src_row_stride;
+        g.dst_off = u.dst_elem_off;
+        g.dst_stride = u.dst_row_stride;
+        g.nrows = u.nrows;
+        g.row_len = u.row_len;
+        g.src_dtype = u.src_dtype;
+        g.dst_dtype = u.dst_dtype;
+        g.wire_off = wire;
+        g.wire_stride = u.row_len * esize(u.dst_dtype);
+        m.segments.push_back(g);
+        wire += u.nrows * u.row_len * esize(u.dst_dtype);
+    }
+    return TH_OK;
+}
+
+int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning& tune) {
+    if (CB == 0 || CB % 16) {
+        set_error("chunk_bytes must be a positive multiple of 16");
+        return TH_ERR_ARG;
+    }
+    m.chunk_bytes = CB;
+    m.wire_bytes = m.payload_bytes = m.src_read_bytes = 0;
+    for (const Segment& g : m.segments) {
+        m.wire_bytes = std::max(m.wire_bytes, seg_wire_end(g));
+        m.payload_bytes += g.nrows * g.row_len * esize(g.dst_dtype);
+        m.src_read_bytes += g.nrows * g.row_len * esize(g.src_dtype);
+    }
+    const uint64_t nchunks = (m.wire_bytes + CB - 1) / CB;
+    if (nchunks > 0x7FFFFFFFull) {
+        set_error("too many chunks");
+        return TH_ERR_RANGE;
+    }
+    m.n_chunks = (uint32_t)nchunks;
+
+    // ---- runs: every segment cut so that each piece lies inside one chunk ----
+    for (const Segment& g : m.segments) {
+        const unsigned es_s = esize(g.src_dtype), es_w = esize(g.dst_dtype);
+        const uint64_t row_bytes = g.row_len * es_w;
+        auto emit = [&](uint64_t r0, uint64_t nr, uint64_t c0, uint64_t nc, uint64_t wire_pos) {
+            th_run r;
+            std::memset(&r, 0, sizeof r);
+            r.src_tensor = g.src_tensor;
+            r.dst_tensor = g.dst_tensor;
+            r.chunk = (uint32_t)(wire_pos / CB);
+            r.src_byte_off = (g.src_off + r0 * g.src_stride + c0) * es_s;
+            r.src_byte_stride = g.src_stride * es_s;
+            r.dst_byte_off = (g.dst_off + r0 * g.dst_stride + c0) * es_w;
+            r.dst_byte_stride = g.dst_stride * es_w;
+            r.chunk_byte_off = wire_pos % CB;
+            r.wire_byte_stride = g.wire_stride;
+            r.nrows = nr;
+            r.row_len = nc;
+            r.src_dtype = g.src_dtype;
+            r.dst_dtype = g.dst_dtype;
+            if (r0 + nr == g.nrows && c0 + nc == g.row_len) r.pad_bytes = g.pad_after;
+            m.runs.push_back(r);
+        };
+        uint64_t r = 0;
+        while (r < g.nrows) {
+            const uint64_t start = g.wire_off + r * g.wire_stride;
+            const uint64_t lim = (start / CB + 1) * CB;
+            if (start + row_bytes <= lim) {
+                // this row and maybe more rows end inside the chunk
+                const uint64_t cnt = std::min(g.nrows - r, (lim - row_bytes - start) / g.wire_stride + 1);
+                emit(r, cnt, 0, g.row_len, start);
+                r += cnt;
+            } else {
+                // the row crosses one or more chunk boundaries: cut it by columns
+                uint64_t col = 0;
+                while (col < g.row_len) {
+                    const uint64_t pos = start + col * es_w;
+                    const uint64_t room = ((pos / CB + 1) * CB - pos) / es_w;
+                    const uint64_t nc = std::min(g.row_len - col, room);
+                    emit(r, 1, col, nc, pos);
+                    col += nc;
+                }
+                r += 1;
+            }
+        }
+    }
+
+    // ---- tiles, one list per direction, grouped by chunk ----
+    for (int side = 0; side < 2; ++side) {
+        std::vector<Tile>& tiles = m.tiles[side];
+        for (const th_run& r : m.runs) {
+            const unsigned es_s = esize(r.src_dtype), es_w = esize(r.dst_dtype);
+            Side S, D;
+            if (side == 0) {
+                S = Side{r.src_tensor, r.src_byte_off, r.src_byte_stride, es_s};
+                D = Side{r.chunk, r.chunk_byte_off, r.wire_byte_stride, es_w};
+            } else {
+                S = Side{r.chunk, r.chunk_byte_off, r.wire_byte_stride, es_w};
+                D = Side{r.dst_tensor, r.dst_byte_off, r.dst_byte_stride, es_w};
+            }
+            bool vec = false;
+            tile_run(tiles, S, D, r.nrows, r.row_len, side == 0 ? r.pad_bytes : 0, ptrs_aligned16,
+                     tune.tile_bytes, vec);
+            TensorInfo& t = side == 0 ? m.tensors[0][r.src_tensor] : m.tensors[1][r.dst_tensor];
+            t.used = true;
+            t.need16 = t.need16 || vec;
+        }
+        auto chunk_of = [side](const Tile& t) { return side == 0 ? t.dst_buf : t.src_buf; };
+        std::stable_sort(tiles.begin(), tiles.end(),
+                         [&](const Tile& a, const Tile& b) { return chunk_of(a) < chunk_of(b); });
+        std::vector<uint64_t>& first = m.chunk_tile0[side];
+        first.assign((size_t)m.n_chunks + 1, 0);
+        for (const Tile& t : tiles) first[chunk_of(t) + 1]++;
+        for (size_t c = 0; c < m.n_chunks; ++c) first[c + 1] += first[c];
+    }
+    return TH_OK;
+}
+
+}  // namespace th

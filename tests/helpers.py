@@ -1,0 +1,81 @@
+"""Shared test helpers: build oracle-side inputs for a workload and run a plan's
+manifest on the CPU with numpy (a test-only executor of the host planner's
+output; the product path has no CPU route)."""
+import numpy as np
+
+import synth
+from oracle import layouts, reshard, rne
+
+NPBITS = {"bf16": np.uint16, "f32": np.uint32}
+ES = {"bf16": 2, "f32": 4}
+
+
+def holder_tensors_cpu(model, lay, seed, pattern=False):
+    """Registered tensors of a holder as 2-D bit arrays (seeded values, norms = 1.0)."""
+    lts = layouts.logical_tensors(model)
+    out = []
+    for i, t in enumerate(layouts.registered_tensors(model, lay)):
+        n = t["rows"] * t["cols"]
+        is_norm = lts[t["parts"][0][0]]["role"] == "norm"
+        if pattern:
+            v = synth.id_pattern_values(n, t["dtype"], i)
+        else:
+            v = synth.weight_values(n, t["dtype"], seed * 100 + lay["tp_rank"] * 10 + lay["ep_rank"], i, is_norm=is_norm)
+        out.append(synth.to_bits(v).reshape(t["rows"], t["cols"]))
+    return out
+
+
+def narrow_bytes(src_bytes):
+    return rne.narrow(src_bytes.view(np.uint32)).view(np.uint8)
+
+
+def exec_copy(src, dst, soff, sstride, doff, dstride, nrows, ncols, es_s, es_d, pad=0):
+    """Row-by-row byte copy of an nrows x ncols element rectangle, narrowing if es_s=4, es_d=2."""
+    for r in range(int(nrows)):
+        s = src[soff + r * sstride: soff + r * sstride + ncols * es_s]
+        assert len(s) == ncols * es_s, "source read out of bounds"
+        if es_s != es_d:
+            assert (es_s, es_d) == (4, 2)
+            s = narrow_bytes(np.ascontiguousarray(s))
+        a = doff + r * dstride
+        assert a + len(s) <= len(dst), "destination write out of bounds"
+        dst[a:a + len(s)] = s
+    if pad:
+        end = doff + (nrows - 1) * dstride + ncols * es_d
+        dst[end:end + pad] = 0
+
+
+def exec_runs_pack(plan, src_flat, fill=0xEE):
+    """Run the manifest's runs on the CPU: source tensors (flat uint8 views) -> list of chunk buffers."""
+    chunks = [np.full(plan.chunk_bytes(c), fill, dtype=np.uint8) for c in range(plan.num_chunks)]
+    for i in range(plan.num_runs):
+        r = plan.run(i)
+        exec_copy(src_flat[r.src_tensor], chunks[r.chunk], r.src_byte_off, r.src_byte_stride,
+                  r.chunk_byte_off, r.wire_byte_stride, r.nrows, r.row_len,
+                  4 if r.src_dtype == 2 else 2, 4 if r.dst_dtype == 2 else 2, r.pad_bytes)
+    return chunks
+
+
+def exec_runs_unpack(plan, chunks, dst_flat):
+    for i in range(plan.num_runs):
+        r = plan.run(i)
+        es = 4 if r.dst_dtype == 2 else 2
+        exec_copy(chunks[r.chunk], dst_flat[r.dst_tensor], r.chunk_byte_off, r.wire_byte_stride,
+                  r.dst_byte_off, r.dst_byte_stride, r.nrows, r.row_len, es, es)
+
+
+def exec_tiles(plan, side, src_bufs, dst_bufs, chunk_range=None):
+    """Run the device work list of one direction on the CPU."""
+    lo, hi = 0, plan.num_tiles(side)
+    if chunk_range is not None:
+        lo = plan.chunk_first_tile(side, chunk_range[0])
+        hi = plan.chunk_first_tile(side, chunk_range[1])
+    for i in range(lo, hi):
+        t = plan.tile(side, i)
+        exec_copy(src_bufs[t.src_buf], dst_bufs[t.dst_buf], t.src_byte_off, t.src_byte_stride,
+                  t.dst_byte_off, t.dst_byte_stride, t.nrows, t.ncols, t.elem_bytes_src, t.elem_bytes_dst,
+                  t.pad_bytes)
+
+
+def flat_u8(arrs):
+    return [np.ascontiguousarray(a).reshape(-1).view(np.uint8) for a in arrs]

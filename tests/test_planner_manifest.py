@@ -1,0 +1,276 @@
+"""Host-side tests of the C-ABI library (no GPU): the planner's manifest, run on
+the CPU by a test-only numpy executor, must reproduce the oracle's wire stream
+and destination tensors bit for bit; error paths; exported symbols."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import synth
+import paper_2604_09107_amd as th
+from oracle import layouts, reshard, segments
+from helpers import (exec_runs_pack, exec_runs_unpack, exec_tiles, flat_u8, holder_tensors_cpu)
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HOST = th.TH_FLAG_HOST_ONLY
+MODEL_WORKLOADS = ["cfg1_tiny_tp2_to_tp1", "small_dense_tp1_to_tp4", "small_dense_tp4_to_tp2", "small_moe_ep4_to_tp2"]
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "th.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(th_[a-z0-9_]+)\s*\(", text))
+    assert {"th_plan_create", "th_plan_create_from_segments", "th_pack", "th_unpack", "th_plan_destroy"} <= names
+    lib = ctypes.CDLL(th.library_path())
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+    assert th.th_version()
+
+
+@pytest.mark.parametrize("name", MODEL_WORKLOADS)
+def test_tensor_lists_match_oracle(name):
+    w = synth.workload(name)
+    plan = th.th_plan_create(w["model"], w["holders"][0], w["reader"], w["chunk_bytes"], HOST)
+    for side, lay in ((0, w["holders"][0]), (1, w["reader"])):
+        want = layouts.registered_tensors(w["model"], lay)
+        got = plan.tensors(side)
+        assert [(t["name"], t["rows"], t["cols"], t["dtype"]) for t in got] == \
+               [(t["name"], t["rows"], t["cols"], t["dtype"]) for t in want]
+    plan.destroy()
+
+
+@pytest.mark.parametrize("tile_bytes", [4096, 65536])
+@pytest.mark.parametrize("name", MODEL_WORKLOADS)
+def test_manifest_reproduces_oracle(name, tile_bytes):
+    w = synth.workload(name)
+    model, dst = w["model"], w["reader"]
+    old = th.th_config_get(th.TH_CFG_TILE_BYTES)
+    th.th_config_set(th.TH_CFG_TILE_BYTES, tile_bytes)
+    try:
+        want_dst = reshard.empty_tensors(model, dst, fill=0x5A5A)
+        got_runs = reshard.empty_tensors(model, dst, fill=0x5A5A)
+        got_tiles = reshard.empty_tensors(model, dst, fill=0x5A5A)
+        for src in w["holders"]:
+            tensors = holder_tensors_cpu(model, src, w["seed"], pattern=True)
+            wire = reshard.pack(model, src, dst, tensors)
+            reshard.unpack(model, src, dst, wire, want_dst)
+            want_chunks = reshard.chunks(wire, w["chunk_bytes"])
+
+            plan = th.th_plan_create(model, src, dst, w["chunk_bytes"], HOST)
+            assert plan.wire_bytes == len(wire)
+            assert plan.num_chunks == len(want_chunks)
+            assert [plan.chunk_bytes(c) for c in range(plan.num_chunks)] == [len(c) for c in want_chunks]
+            assert plan.payload_bytes == sum(
+                len(it["src_r"]) * len(it["src_c"]) * reshard.ESIZE[it["dst_dtype"]]
+                for it in reshard.plan_items(model, src, dst))
+            # runs (chunk manifest)
+            chunks = exec_runs_pack(plan, flat_u8(tensors))
+            for c, (g, x) in enumerate(zip(chunks, want_chunks)):
+                assert np.array_equal(g, x), "runs: chunk %d" % c
+            exec_runs_unpack(plan, chunks, flat_u8(got_runs))
+            # tiles (device work list), both directions
+            tchunks = [np.full(len(c), 0xEE, dtype=np.uint8) for c in want_chunks]
+            exec_tiles(plan, 0, flat_u8(tensors), tchunks)
+            for c, (g, x) in enumerate(zip(tchunks, want_chunks)):
+                assert np.array_equal(g, x), "tiles: chunk %d" % c
+            exec_tiles(plan, 1, tchunks, flat_u8(got_tiles))
+            # tiles are grouped by chunk
+            for side in (0, 1):
+                firsts = [plan.chunk_first_tile(side, c) for c in range(plan.num_chunks + 1)]
+                assert firsts[0] == 0 and firsts[-1] == plan.num_tiles(side) and firsts == sorted(firsts)
+                for c in range(plan.num_chunks):
+                    for i in range(firsts[c], firsts[c + 1]):
+                        t = plan.tile(side, i)
+                        assert (t.dst_buf if side == 0 else t.src_buf) == c
+            plan.destroy()
+        for a, b, x in zip(got_runs, got_tiles, want_dst):
+            assert np.array_equal(a, x) and np.array_equal(b, x)
+    finally:
+        th.th_config_set(th.TH_CFG_TILE_BYTES, old)
+
+
+def test_chunks_are_self_contained():
+    """Unpacking any subset of chunks, in any order, touches only that subset's elements."""
+    w = synth.workload("small_dense_tp1_to_tp4")
+    model, src, dst = w["model"], w["holders"][0], w["reader"]
+    tensors = holder_tensors_cpu(model, src, 1, pattern=True)
+    want = reshard.empty_tensors(model, dst, fill=0)
+    wire = reshard.pack(model, src, dst, tensors)
+    reshard.unpack(model, src, dst, wire, want)
+    plan = th.th_plan_create(model, src, dst, 64 * 1024, HOST)
+    n = plan.num_chunks
+    assert n > 8
+    chunks = [np.full(plan.chunk_bytes(c), 0xEE, dtype=np.uint8) for c in range(n)]
+    got = reshard.empty_tensors(model, dst, fill=0)
+    for c in list(range(n - 1, -1, -2)) + list(range(n - 2, -1, -2)):  # odd/even, backwards
+        exec_tiles(plan, 0, flat_u8(tensors), chunks, (c, c + 1))
+        assert np.array_equal(chunks[c], reshard.chunks(wire, 64 * 1024)[c])
+        exec_tiles(plan, 1, chunks, flat_u8(got), (c, c + 1))
+    for g, x in zip(got, want):
+        assert np.array_equal(g, x)
+    plan.destroy()
+
+
+def scatter_segments(d, dst_dtype=th.TH_BF16):
+    n = len(d["perm"])
+    segs = np.zeros(n, dtype=th.binding.SEGMENT_NP)
+    segs["src_tensor"] = d["seg_src_tensor"]
+    segs["dst_tensor"] = 0
+    segs["src_elem_off"] = d["seg_src_off"]
+    segs["dst_elem_off"] = d["seg_dst_off"]
+    segs["src_row_stride"] = d["seg_src_stride"]
+    segs["dst_row_stride"] = d["seg_dst_stride"]
+    segs["nrows"] = d["seg_nrows"]
+    segs["row_len"] = d["seg_row_len"]
+    segs["src_dtype"] = th.TH_F32
+    segs["dst_dtype"] = dst_dtype
+    return segs
+
+
+@pytest.mark.parametrize("chunk_bytes,tile_bytes", [(4096, 4096), (65536, 8192), (1 << 20, 65536)])
+def test_explicit_segments_manifest_reproduces_oracle(chunk_bytes, tile_bytes):
+    d = synth.scatter_description(150, 21, min_bytes=256, max_bytes=65536)
+    pool = synth.to_bits(synth.scatter_values(d["pool_elems"], 21, special_rate=0.05))
+    srcs = [pool[o:o + m] for o, m in zip(d["pool_off"], d["n_elems"])]
+    osegs = dict(src_tensor=d["seg_src_tensor"], dst_tensor=np.zeros(150, dtype=np.int64),
+                 src_off=d["seg_src_off"], src_stride=d["seg_src_stride"], dst_off=d["seg_dst_off"],
+                 dst_stride=d["seg_dst_stride"], nrows=d["seg_nrows"], row_len=d["seg_row_len"])
+    wire = segments.pack(osegs, srcs, "f32", "bf16")
+    arena = np.full(d["arena_elems"] + 16, 0x7777, dtype=np.uint16)
+    segments.unpack(osegs, wire, [arena], "bf16")
+
+    old = th.th_config_get(th.TH_CFG_TILE_BYTES)
+    th.th_config_set(th.TH_CFG_TILE_BYTES, tile_bytes)
+    try:
+        plan = th.th_plan_create_from_segments(scatter_segments(d), d["n_elems"], [len(arena)], chunk_bytes, HOST)
+    finally:
+        th.th_config_set(th.TH_CFG_TILE_BYTES, old)
+    assert plan.wire_bytes == len(wire)
+    assert plan.src_read_bytes == 2 * plan.payload_bytes == 4 * d["arena_elems"]
+    want_chunks = reshard.chunks(wire, chunk_bytes)
+    for use_tiles in (False, True):
+        if use_tiles:
+            chunks = [np.full(len(c), 0xEE, dtype=np.uint8) for c in want_chunks]
+            exec_tiles(plan, 0, flat_u8(srcs), chunks)
+        else:
+            chunks = exec_runs_pack(plan, flat_u8(srcs))
+        for c, (g, x) in enumerate(zip(chunks, want_chunks)):
+            assert np.array_equal(g, x), (use_tiles, c)
+        got = np.full(len(arena), 0x7777, dtype=np.uint16)
+        if use_tiles:
+            exec_tiles(plan, 1, chunks, [got.view(np.uint8)])
+        else:
+            exec_runs_unpack(plan, chunks, [got.view(np.uint8)])
+        assert np.array_equal(got, arena)
+    plan.destroy()
+
+
+def test_error_paths():
+    w = synth.workload("cfg1_tiny_tp2_to_tp1")
+    model, src, dst = w["model"], w["holders"][0], w["reader"]
+    with pytest.raises(th.ThError) as e:
+        th.th_plan_create(dict(model, vocab=1001), src, dst, 1 << 20, HOST)
+    assert e.value.code == -2 and "vocab" in str(e.value) or "embed" in str(e.value)
+    with pytest.raises(th.ThError) as e:  # 4 ranks, 2 KV heads
+        th.th_plan_create(model, synth.layout(4, 0), dst, 1 << 20, HOST)
+    assert e.value.code == -3
+    with pytest.raises(th.ThError) as e:
+        th.th_plan_create(model, src, dst, 1000, HOST)  # not a multiple of 16
+    assert e.value.code == -1
+    with pytest.raises(th.ThError) as e:
+        th.th_plan_create(model, synth.layout(2, 2), dst, 1 << 20, HOST)  # rank out of range
+    assert e.value.code == -1
+    with pytest.raises(th.ThError) as e:  # reader keeps fp32 norms but holder stores bf16: widening
+        th.th_plan_create(model, synth.layout(2, 0, f32_store="bf16"), synth.layout(1, 0, f32_store="f32"), 1 << 20, HOST)
+    assert e.value.code == -3
+    plan = th.th_plan_create(model, src, dst, 1 << 20, HOST)
+    with pytest.raises(th.ThError) as e:
+        th.th_pack(plan, [0] * plan.num_tensors(0), [0], 0, 1)
+    assert e.value.code == -1 and "HOST_ONLY" in str(e.value)
+    with pytest.raises(th.ThError):
+        plan.tensor_info(0, 10 ** 6)
+    plan.destroy()
+    plan.destroy()  # idempotent in the binding
+    with pytest.raises(th.ThError):
+        th.th_config_set(th.TH_CFG_TILE_BYTES, 1000)
+    with pytest.raises(th.ThError):
+        th.th_config_set(99, 0)
+
+    # explicit segments: out-of-range, overlapping destination rows, dtype clash
+    S = th.binding.SEGMENT_NP
+    seg = np.zeros(1, dtype=S)
+    seg["nrows"], seg["row_len"], seg["src_row_stride"], seg["dst_row_stride"] = 4, 8, 8, 8
+    seg["src_dtype"], seg["dst_dtype"] = th.TH_F32, th.TH_BF16
+    th.th_plan_create_from_segments(seg, [32], [32], 4096, HOST).destroy()
+    with pytest.raises(th.ThError) as e:
+        th.th_plan_create_from_segments(seg, [31], [32], 4096, HOST)
+    assert e.value.code == -4
+    with pytest.raises(th.ThError) as e:
+        th.th_plan_create_from_segments(seg, [32], [31], 4096, HOST)
+    assert e.value.code == -4
+    bad = seg.copy()
+    bad["dst_row_stride"] = 7
+    with pytest.raises(th.ThError) as e:
+        th.th_plan_create_from_segments(bad, [32], [32], 4096, HOST)
+    assert e.value.code == -1
+    bad = seg.copy()
+    bad["src_dtype"], bad["dst_dtype"] = th.TH_BF16, th.TH_F32
+    with pytest.raises(th.ThError) as e:
+        th.th_plan_create_from_segments(bad, [32], [32], 4096, HOST)
+    assert e.value.code == -3
+    bad = seg.copy()
+    bad["src_tensor"] = 1
+    with pytest.raises(th.ThError) as e:
+        th.th_plan_create_from_segments(bad, [32], [32], 4096, HOST)
+    assert e.value.code == -4
+
+
+def test_empty_plan_and_empty_segments():
+    p = th.th_plan_create_from_segments(np.zeros(0, dtype=th.binding.SEGMENT_NP), [], [], 4096, HOST)
+    assert p.num_chunks == 0 and p.wire_bytes == 0 and p.num_runs == 0
+    p.destroy()
+    seg = np.zeros(2, dtype=th.binding.SEGMENT_NP)
+    seg["src_dtype"], seg["dst_dtype"] = th.TH_BF16, th.TH_BF16
+    seg["nrows"][1], seg["row_len"][1], seg["src_row_stride"][1], seg["dst_row_stride"][1] = 1, 3, 3, 3
+    p = th.th_plan_create_from_segments(seg, [8], [8], 4096, HOST)  # first segment is empty
+    assert p.num_runs == 1 and p.wire_bytes == 6
+    p.destroy()
+
+
+def test_full_size_plans_cover_every_destination_element_once():
+    """Full-size configurations, manifest only: payload equals the reader's bytes and no
+    two runs overlap on the wire or in the destination (interval check, no data)."""
+    for name in ("cfg2_8b_tp1_to_tp4", "cfg4_moe_ep8_to_tp2"):
+        w = synth.workload(name)
+        model, dst = w["model"], w["reader"]
+        plan = th.th_plan_create(model, w["holders"][0], dst, w["chunk_bytes"], HOST)
+        assert plan.wire_bytes == reshard.wire_bytes(model, w["holders"][0], dst)
+        dst_regs = layouts.registered_tensors(model, dst)
+        per_tensor = {}
+        wire_iv = []
+        for i in range(plan.num_runs):
+            r = plan.run(i)
+            es = 4 if r.dst_dtype == 2 else 2
+            if r.dst_byte_stride == r.row_len * es or r.nrows == 1:
+                per_tensor.setdefault(r.dst_tensor, []).append((r.dst_byte_off, r.dst_byte_off + r.nrows * r.row_len * es))
+            else:
+                for k in range(r.nrows):
+                    a = r.dst_byte_off + k * r.dst_byte_stride
+                    per_tensor.setdefault(r.dst_tensor, []).append((a, a + r.row_len * es))
+            assert r.wire_byte_stride == r.row_len * es or r.nrows == 1  # these configs are dense on the wire
+            a = r.chunk * w["chunk_bytes"] + r.chunk_byte_off
+            wire_iv.append((a, a + r.nrows * r.row_len * es))
+        wire_iv.sort()
+        assert wire_iv[0][0] == 0 and wire_iv[-1][1] == plan.wire_bytes
+        assert all(a[1] == b[0] for a, b in zip(wire_iv, wire_iv[1:]))  # 16-byte multiples: no gaps here
+        covered = 0
+        for t, iv in per_tensor.items():
+            iv.sort()
+            assert all(a[1] <= b[0] for a, b in zip(iv, iv[1:])), dst_regs[t]["name"]
+            covered += sum(b - a for a, b in iv)
+        assert covered == plan.payload_bytes
+        if name.startswith("cfg2"):
+            assert covered == sum(t["rows"] * t["cols"] * reshard.ESIZE[t["dtype"]] for t in dst_regs)
+        plan.destroy()
