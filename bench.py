@@ -1,0 +1,188 @@
+"""Benchmark of the reshard hot path on one MI355X.
+
+One step = th_pack of every chunk + th_unpack of every chunk of the workload's
+plan(s), inputs resident in HBM.  Prints one JSON line (see the design notes for
+the byte accounting).  The plan (host planner + one table upload) is created
+once per (holder, reader, model) and reused for every weight version, so it is
+timed separately and reported as plan_ms.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
+
+
+def build_inputs(th, dev, synth, w, torch):
+    """Plans, resident source tensors, wire buffers and destination tensors of a model workload."""
+    from oracle import layouts  # only for tensor roles of the synthetic values (norm vs weight)
+    model, dst = w["model"], w["reader"]
+    lts = layouts.logical_tensors(model)
+    jobs = []
+    dst_dev = None
+    plan_ms = 0.0
+    for h, src in enumerate(w["holders"]):
+        t0 = time.perf_counter()
+        plan = th.th_plan_create(model, src, dst, w["chunk_bytes"])
+        plan_ms += (time.perf_counter() - t0) * 1e3
+        regs = layouts.registered_tensors(model, src)
+        src_dev = [synth.weight_values(t["rows"] * t["cols"], t["dtype"], w["seed"] * 16 + h, i, "cuda",
+                                       is_norm=lts[t["parts"][0][0]]["role"] == "norm")
+                   for i, t in enumerate(regs)]
+        if dst_dev is None:
+            dst_dev = dev.alloc_tensors(plan, 1, fill_bits=0)
+        wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=0)
+        jobs.append(dict(plan=plan, src=src_dev, src_ptrs=dev.ptrs(src_dev), wire=wire_dev, wptrs=wptrs,
+                         layout=src, regs=regs))
+    return jobs, dst_dev, dev.ptrs(dst_dev), plan_ms
+
+
+def cpu_baseline(synth, w, jobs, budget_s=15.0):
+    """The oracle as it stands, on the host cores, over a bounded prefix of the same workload:
+    plan items (holder tensors in wire order) until about budget_s seconds of oracle work."""
+    import numpy as np
+    from oracle import reshard
+    model, dst = w["model"], w["reader"]
+    job = jobs[0]
+    dst_cpu = {}
+    sweep_bytes = 0
+    spent = 0.0
+    n_items = 0
+    dst_regs = None
+    for it in reshard.plan_items(model, job["layout"], dst):
+        reg = job["regs"][it["src_id"]]
+        src_bits = synth.to_bits(job["src"][it["src_id"]]).reshape(reg["rows"], reg["cols"])  # D2H, not timed
+        if it["dst_id"] not in dst_cpu:
+            if dst_regs is None:
+                from oracle import layouts
+                dst_regs = layouts.registered_tensors(model, dst)
+            t = dst_regs[it["dst_id"]]
+            dst_cpu = {it["dst_id"]: np.zeros((t["rows"], t["cols"]), dtype=reshard.NPBITS[t["dtype"]])}
+        t0 = time.perf_counter()
+        wire = reshard.item_wire(it, src_bits)                                  # pack: gather + convert
+        nr, nc = len(it["src_r"]), len(it["src_c"])
+        dst_cpu[it["dst_id"]][np.ix_(it["dst_r"], it["dst_c"])] = wire.reshape(nr, nc)  # unpack: scatter
+        spent += time.perf_counter() - t0
+        n = nr * nc
+        sweep_bytes += n * (reshard.ESIZE[it["src_dtype"]] + 3 * reshard.ESIZE[it["dst_dtype"]])
+        n_items += 1
+        if spent >= budget_s:
+            break
+    return dict(value=round(sweep_bytes / spent / 1e9, 3), unit="GB/s", cores=1, kind="oracle",
+                sample="first %d plan items of the workload in wire order (%.2f GB moved, %.1f s of oracle time)"
+                       % (n_items, sweep_bytes / 1e9, spent))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2_8b_tp1_to_tp4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tile-bytes", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the reshard path has no cross-GPU step (every holder/reader pair is an "
+              "independent plan); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth
+    import paper_2604_09107_amd as th
+    from paper_2604_09107_amd import device as dev
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    if args.tile_bytes:
+        th.th_config_set(th.TH_CFG_TILE_BYTES, args.tile_bytes)
+    w = synth.workload(args.workload)
+    jobs, dst_dev, dst_ptrs, plan_ms = build_inputs(th, dev, synth, w, torch)
+    stream = dev.current_stream()
+
+    pack_bytes = sum(j["plan"].src_read_bytes + j["plan"].payload_bytes for j in jobs)     # read src + write wire
+    unpack_bytes = sum(2 * j["plan"].payload_bytes for j in jobs)                           # read wire + write dst
+    sweep_bytes = pack_bytes + unpack_bytes
+
+    def step(events=None):
+        for call, side in ((th.th_pack, 0), (th.th_unpack, 1)):
+            for j in jobs:
+                n = j["plan"].num_chunks
+                if events is not None:
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                if side == 0:
+                    th.th_pack(j["plan"], j["src_ptrs"], j["wptrs"], 0, n, stream)
+                else:
+                    th.th_unpack(j["plan"], j["wptrs"], 0, n, dst_ptrs, stream)
+                if events is not None:
+                    e1.record()
+                    events[side].append((e0, e1))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = ([], [])
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # Per-launch durations from events recorded around every launch, on the launch stream, inside
+    # the timed region (one kernel launch per th_pack / th_unpack call).
+    n_launch = len(events[0])
+    pack_ms = sum(a.elapsed_time(b) for a, b in events[0]) / n_launch
+    unpack_ms = sum(a.elapsed_time(b) for a, b in events[1]) / n_launch
+    k_pack = pack_bytes / len(jobs) / (pack_ms * 1e-3) / 1e9      # algorithmic bytes of an average launch
+    k_unpack = unpack_bytes / len(jobs) / (unpack_ms * 1e-3) / 1e9
+    dom = ("th_pack", k_pack, pack_ms) if pack_ms >= unpack_ms else ("th_unpack", k_unpack, unpack_ms)
+
+    # practical ceiling: a plain device-to-device copy of the same number of bytes
+    nbytes = jobs[0]["plan"].payload_bytes
+    a = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    b = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    for _ in range(3):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(10):
+        b.copy_(a)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 2 * nbytes * 10 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del a, b
+
+    value = sweep_bytes / (ms_per_step * 1e-3) / 1e9
+    out = {
+        "metric": "reshard pack+unpack effective HBM GB/s",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "model": w["model_name"], "chunk_bytes": w["chunk_bytes"],
+                   "holders": len(jobs), "payload_bytes": sum(j["plan"].payload_bytes for j in jobs),
+                   "sweep_bytes": sweep_bytes, "chunks": sum(j["plan"].num_chunks for j in jobs),
+                   "tile_bytes": th.th_config_get(th.TH_CFG_TILE_BYTES)},
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
+        "plan_ms": round(plan_ms, 3),
+        "kernels": {"th_pack": {"ms": round(pack_ms, 4), "GB/s": round(k_pack, 1)},
+                    "th_unpack": {"ms": round(unpack_ms, 4), "GB/s": round(k_unpack, 1)}},
+        "d2d_copy_GB/s": round(copy_gbps, 1),
+        "roofline": {"bound": "hbm", "kernel": dom[0], "achieved": round(dom[1], 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(dom[1] / HBM_PEAK_GBPS, 4), "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(synth, w, jobs)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,250 @@
+"""GPU parity: th_pack / th_unpack through the C ABI against the CPU oracle,
+bit for bit (tolerance 0, including the fp32 -> bf16 narrowing), on the same
+seeded inputs.  Sizes here finish in seconds on the oracle and still span many
+tiles, several chunks and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+import paper_2604_09107_amd as th
+from paper_2604_09107_amd import device as dev
+from oracle import layouts, reshard, segments
+from helpers import holder_tensors_cpu
+from test_planner_manifest import scatter_segments
+
+pytestmark = pytest.mark.gpu
+
+SENT16 = 0xA5C3
+SENT8 = 0xEE
+
+
+def to_dev(bits2d):
+    return synth.from_bits(np.ascontiguousarray(bits2d).reshape(-1), "cuda")
+
+
+def run_model_workload(w, pattern, chunk_order=None, tile_bytes=None):
+    """Pack every holder's stream and unpack into one reader; returns (got dst bits, want dst bits, mask)."""
+    model, dst = w["model"], w["reader"]
+    old = th.th_config_get(th.TH_CFG_TILE_BYTES)
+    if tile_bytes:
+        th.th_config_set(th.TH_CFG_TILE_BYTES, tile_bytes)
+    try:
+        plans = [th.th_plan_create(model, src, dst, w["chunk_bytes"]) for src in w["holders"]]
+    finally:
+        th.th_config_set(th.TH_CFG_TILE_BYTES, old)
+    dst_dev = dev.alloc_tensors(plans[0], 1, fill_bits=SENT16)
+    want = reshard.empty_tensors(model, dst, fill=SENT16)
+    for t, wnt in zip(layouts.registered_tensors(model, dst), want):
+        if t["dtype"] == "f32":
+            wnt[...] = SENT16 * 0x10001
+    stream = dev.current_stream()
+    for src, plan in zip(w["holders"], plans):
+        tensors = holder_tensors_cpu(model, src, w["seed"], pattern=pattern)
+        src_dev = [to_dev(t) for t in tensors]
+        wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=SENT8)
+        n = plan.num_chunks
+        order = chunk_order(n) if chunk_order else [(0, n)]
+        for first, count in order:
+            th.th_pack(plan, dev.ptrs(src_dev), wptrs[first:first + count], first, count, stream)
+        torch.cuda.synchronize()
+        wire = reshard.pack(model, src, dst, tensors)
+        got_wire = wire_dev.cpu().numpy()[:plan.wire_bytes]
+        assert plan.wire_bytes == len(wire)
+        bad = np.nonzero(got_wire != wire)[0]
+        assert bad.size == 0, "wire differs first at byte %d of %d (%d bytes differ)" % (bad[0], len(wire), bad.size)
+        for first, count in order:
+            th.th_unpack(plan, wptrs[first:first + count], first, count, dev.ptrs(dst_dev), stream)
+        torch.cuda.synchronize()
+        reshard.unpack(model, src, dst, wire, want)
+    for p in plans:
+        p.destroy()
+    return [synth.to_bits(t) for t in dst_dev], [x.reshape(-1) for x in want]
+
+
+def assert_same(got, want, names=None):
+    for i, (g, x) in enumerate(zip(got, want)):
+        bad = np.nonzero(g != x)[0]
+        assert bad.size == 0, "tensor %d%s differs first at element %d (%d differ)" % (
+            i, " " + names[i] if names else "", bad[0], bad.size)
+
+
+@pytest.mark.parametrize("pattern", [False, True])
+@pytest.mark.parametrize("name", ["cfg1_tiny_tp2_to_tp1", "small_dense_tp1_to_tp4", "small_dense_tp4_to_tp2",
+                                  "small_moe_ep4_to_tp2"])
+def test_model_workloads_bit_exact(name, pattern):
+    w = synth.workload(name)
+    got, want = run_model_workload(w, pattern)
+    assert_same(got, want, [t["name"] for t in layouts.registered_tensors(w["model"], w["reader"])])
+
+
+@pytest.mark.parametrize("tile_bytes", [4096, 16384, 262144])
+def test_tile_sizes(tile_bytes):
+    w = synth.workload("small_dense_tp1_to_tp4")
+    got, want = run_model_workload(w, True, tile_bytes=tile_bytes)
+    assert_same(got, want)
+
+
+def test_chunk_subsets_in_any_order():
+    w = synth.workload("small_dense_tp1_to_tp4")
+    w["chunk_bytes"] = 64 * 1024
+
+    def order(n):
+        singles = [(c, 1) for c in range(n - 1, -1, -3)]
+        rest = [c for c in range(n) if (n - 1 - c) % 3]
+        return singles + [(c, 1) for c in rest[::2]] + [(c, 1) for c in rest[1::2]]
+
+    got, want = run_model_workload(w, True, chunk_order=order)
+    assert_same(got, want)
+
+    def ranges(n):
+        return [(n // 2, n - n // 2), (0, n // 2)]
+
+    got, want = run_model_workload(w, True, chunk_order=ranges)
+    assert_same(got, want)
+
+
+def test_moe_untouched_expert_slabs_keep_their_sentinel():
+    """Holder is one expert-parallel rank: only its experts' slabs of the stacked tensors may change."""
+    w = synth.workload("small_moe_ep4_to_tp2")
+    got, want = run_model_workload(w, False)
+    assert_same(got, want)
+    regs = layouts.registered_tensors(w["model"], w["reader"])
+    stacked = [i for i, t in enumerate(regs) if ".experts.w" in t["name"]]
+    assert stacked
+    for i in stacked:
+        slabs = got[i].reshape(16, -1)
+        assert np.all(slabs[:4] == SENT16) and np.all(slabs[8:] == SENT16) and not np.all(slabs[4:8] == SENT16)
+
+
+def run_scatter(n_tensors, seed, chunk_bytes, max_bytes, misalign_pool=1, special_rate=0.05):
+    d = synth.scatter_description(n_tensors, seed, min_bytes=256, max_bytes=max_bytes)
+    # the pool starts 4 bytes past a 16-byte boundary: sources are only 4-byte aligned
+    pool_dev = torch.empty(d["pool_elems"] + 4, dtype=torch.float32, device="cuda")[misalign_pool:]
+    pool_dev[:d["pool_elems"]] = synth.scatter_values(d["pool_elems"], seed, "cuda", special_rate)
+    pool = synth.to_bits(pool_dev[:d["pool_elems"]])
+    srcs = [pool[o:o + m] for o, m in zip(d["pool_off"], d["n_elems"])]
+    src_ptrs = pool_dev.data_ptr() + d["pool_off"].astype(np.uint64) * np.uint64(4)
+    # the arena starts 2 bytes past a 16-byte boundary: destination is only 2-byte aligned
+    arena_dev = torch.empty(d["arena_elems"] + 9, dtype=torch.bfloat16, device="cuda")
+    arena_dev.view(torch.int16).fill_(0x7777)
+    arena_view = arena_dev[1:]
+    osegs = dict(src_tensor=d["seg_src_tensor"], dst_tensor=np.zeros(n_tensors, dtype=np.int64),
+                 src_off=d["seg_src_off"], src_stride=d["seg_src_stride"], dst_off=d["seg_dst_off"],
+                 dst_stride=d["seg_dst_stride"], nrows=d["seg_nrows"], row_len=d["seg_row_len"])
+    wire = segments.pack(osegs, srcs, "f32", "bf16")
+    arena = np.full(d["arena_elems"] + 8, 0x7777, dtype=np.uint16)
+    segments.unpack(osegs, wire, [arena], "bf16")
+
+    plan = th.th_plan_create_from_segments(scatter_segments(d), d["n_elems"], [len(arena)], chunk_bytes)
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=SENT8)
+    stream = dev.current_stream()
+    th.th_pack(plan, src_ptrs, wptrs, 0, plan.num_chunks, stream)
+    th.th_unpack(plan, wptrs, 0, plan.num_chunks, [arena_view.data_ptr()], stream)
+    torch.cuda.synchronize()
+    got_wire = wire_dev.cpu().numpy()[:plan.wire_bytes]
+    assert len(wire) == plan.wire_bytes
+    bad = np.nonzero(got_wire != wire)[0]
+    assert bad.size == 0, "wire differs first at byte %d (%d differ)" % (bad[0], bad.size)
+    got = synth.to_bits(arena_dev)
+    assert got[0] == 0x7777
+    bad = np.nonzero(got[1:] != arena)[0]
+    assert bad.size == 0, "arena differs first at element %d (%d differ)" % (bad[0], bad.size)
+    plan.destroy()
+    return d
+
+
+@pytest.mark.parametrize("n,seed,chunk,maxb", [(200, 31, 64 * 1024, 1 << 16), (600, 32, 1 << 20, 1 << 20),
+                                               (60, 33, 4096, 1 << 14)])
+def test_scattered_fp32_to_bf16_bit_exact(n, seed, chunk, maxb):
+    run_scatter(n, seed, chunk, maxb)
+
+
+def test_all_special_values_narrowed_like_the_oracle():
+    run_scatter(100, 34, 1 << 18, 1 << 18, special_rate=1.0)
+
+
+def test_same_dtype_any_alignment_and_fp32_passthrough():
+    """Explicit segments with bf16 -> bf16 at odd element offsets and fp32 -> fp32 copies."""
+    rng = np.random.default_rng(40)
+    n_seg = 300
+    S = th.binding.SEGMENT_NP
+    for dt, npdt, th_dt in (("bf16", np.uint16, th.TH_BF16), ("f32", np.uint32, th.TH_F32)):
+        src_len, dst_len = 1 << 20, 1 << 20
+        src = rng.integers(0, 1 << 16, size=src_len).astype(npdt)
+        segs = np.zeros(n_seg, dtype=S)
+        osegs = {k: np.zeros(n_seg, dtype=np.int64) for k in
+                 ("src_tensor", "dst_tensor", "src_off", "src_stride", "dst_off", "dst_stride", "nrows", "row_len")}
+        d_off = 0
+        for k in range(n_seg):
+            row_len = int(rng.integers(1, 700))
+            nrows = int(rng.integers(1, 9))
+            s_stride = row_len + int(rng.integers(0, 50))
+            d_stride = row_len + int(rng.integers(0, 9))
+            s_off = int(rng.integers(0, src_len - nrows * s_stride))
+            for key, v in (("src_off", s_off), ("src_stride", s_stride), ("dst_off", d_off), ("dst_stride", d_stride),
+                           ("nrows", nrows), ("row_len", row_len)):
+                osegs[key][k] = v
+            d_off += nrows * d_stride + int(rng.integers(0, 5))
+        assert d_off < dst_len
+        segs["src_elem_off"], segs["src_row_stride"] = osegs["src_off"], osegs["src_stride"]
+        segs["dst_elem_off"], segs["dst_row_stride"] = osegs["dst_off"], osegs["dst_stride"]
+        segs["nrows"], segs["row_len"] = osegs["nrows"], osegs["row_len"]
+        segs["src_dtype"] = segs["dst_dtype"] = th_dt
+        wire = segments.pack(osegs, [src], dt, dt)
+        sent = 0x7777 if dt == "bf16" else 0x77777777
+        want = np.full(dst_len, sent, dtype=npdt)
+        segments.unpack(osegs, wire, [want], dt)
+
+        plan = th.th_plan_create_from_segments(segs, [src_len], [dst_len], 32 * 1024)
+        src_dev = synth.from_bits(src, "cuda")
+        dst_dev = synth.from_bits(np.full(dst_len, sent, dtype=npdt), "cuda")
+        wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=SENT8)
+        th.th_pack(plan, [src_dev.data_ptr()], wptrs, 0, plan.num_chunks, dev.current_stream())
+        th.th_unpack(plan, wptrs, 0, plan.num_chunks, [dst_dev.data_ptr()], dev.current_stream())
+        torch.cuda.synchronize()
+        assert np.array_equal(wire_dev.cpu().numpy()[:plan.wire_bytes], wire)
+        assert np.array_equal(synth.to_bits(dst_dev), want)
+        plan.destroy()
+
+
+def test_argument_errors_are_synchronous_and_nothing_runs():
+    w = synth.workload("cfg1_tiny_tp2_to_tp1")
+    plan = th.th_plan_create(w["model"], w["holders"][0], w["reader"], w["chunk_bytes"])
+    src_dev = dev.alloc_tensors(plan, 0)
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=SENT8)
+    with pytest.raises(th.ThError) as e:
+        th.th_pack(plan, dev.ptrs(src_dev)[:-1], wptrs, 0, plan.num_chunks)
+    assert e.value.code == -1
+    with pytest.raises(th.ThError) as e:
+        th.th_pack(plan, dev.ptrs(src_dev), wptrs[:1], plan.num_chunks, 1)
+    assert e.value.code == -4
+    p = dev.ptrs(src_dev).copy()
+    p[2] += 2  # misaligned base pointer
+    with pytest.raises(th.ThError) as e:
+        th.th_pack(plan, p, wptrs, 0, plan.num_chunks)
+    assert e.value.code == -1 and "misaligned" in str(e.value)
+    wp = wptrs.copy()
+    wp[0] += 8
+    with pytest.raises(th.ThError) as e:
+        th.th_pack(plan, dev.ptrs(src_dev), wp, 0, plan.num_chunks)
+    assert e.value.code == -1
+    th.th_pack(plan, dev.ptrs(src_dev), wptrs[:0], 0, 0)  # empty range is a no-op
+    torch.cuda.synchronize()
+    assert bool((wire_dev == SENT8).all())
+    plan.destroy()
+
+
+def test_pointer_tables_may_change_between_calls():
+    """Re-registration: the same plan serves different tensor / wire buffers call after call."""
+    w = synth.workload("cfg1_tiny_tp2_to_tp1")
+    model, src, dst = w["model"], w["holders"][0], w["reader"]
+    plan = th.th_plan_create(model, src, dst, w["chunk_bytes"])
+    for rep in range(12):  # more distinct tables than the library caches
+        tensors = holder_tensors_cpu(model, src, 100 + rep)
+        src_dev = [to_dev(t) for t in tensors]
+        wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=SENT8)
+        th.th_pack(plan, dev.ptrs(src_dev), wptrs, 0, plan.num_chunks, dev.current_stream())
+        torch.cuda.synchronize()
+        assert np.array_equal(wire_dev.cpu().numpy()[:plan.wire_bytes], reshard.pack(model, src, dst, tensors))
+    plan.destroy()
