@@ -159,6 +159,16 @@ def main():
     c1.record()
     torch.cuda.synchronize()
     copy_gbps = 2 * nbytes * 10 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    # ... and the library's own plain copy kernel (same launch shape as the aligned path)
+    n16 = nbytes // 16 * 16
+    for _ in range(3):
+        th.th_reference_copy(b.data_ptr(), a.data_ptr(), n16, stream)
+    c0.record()
+    for _ in range(10):
+        th.th_reference_copy(b.data_ptr(), a.data_ptr(), n16, stream)
+    c1.record()
+    torch.cuda.synchronize()
+    ref_gbps = 2 * n16 * 10 / (c0.elapsed_time(c1) * 1e-3) / 1e9
     del a, b
 
     value = sweep_bytes / (ms_per_step * 1e-3) / 1e9
@@ -175,7 +185,7 @@ def main():
         "plan_ms": round(plan_ms, 3),
         "kernels": {"th_pack": {"ms": round(pack_ms, 4), "GB/s": round(k_pack, 1)},
                     "th_unpack": {"ms": round(unpack_ms, 4), "GB/s": round(k_unpack, 1)}},
-        "d2d_copy_GB/s": round(copy_gbps, 1),
+        "d2d_copy_GB/s": {"torch_copy_": round(copy_gbps, 1), "th_reference_copy": round(ref_gbps, 1)},
         "roofline": {"bound": "hbm", "kernel": dom[0], "achieved": round(dom[1], 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(dom[1] / HBM_PEAK_GBPS, 4), "traffic": None},
     }

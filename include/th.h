@@ -214,17 +214,19 @@ size_t th_plan_num_runs(const th_plan* plan);
 int th_plan_get_run(const th_plan* plan, size_t i, th_run* out);
 
 /* The device work list, for inspection.  side 0 = th_pack's tiles, 1 =
- * th_unpack's.  Tiles are ordered by chunk; each is one workgroup's share: a
- * sub-rectangle of a run, described as a copy from (src_buf, src_byte_off) to
- * (dst_buf, dst_byte_off).  For side 0 src_buf is a source tensor id and
- * dst_buf a chunk index; for side 1 src_buf is a chunk index and dst_buf a
- * destination tensor id.  ncols is in elements of width `elem_bytes_dst` on the
- * destination and `elem_bytes_src` on the source. */
+ * th_unpack's.  Tiles are ordered by chunk; each is one workgroup's share of a
+ * run, described as a copy from (src_buf, src_byte_off) to (dst_buf,
+ * dst_byte_off).  For side 0 src_buf is a source tensor id and dst_buf a chunk
+ * index; for side 1 src_buf is a chunk index and dst_buf a destination tensor
+ * id.  A tile covers `count` consecutive elements, in row-major order, of a
+ * rectangle whose rows hold row_len elements and lie *_byte_stride apart: it
+ * starts at column first_col of the row at the byte offsets and continues at
+ * column 0 of the following rows. */
 typedef struct th_tile_info {
     uint32_t src_buf, dst_buf;
     uint64_t src_byte_off, src_byte_stride;
     uint64_t dst_byte_off, dst_byte_stride;
-    uint64_t nrows, ncols;
+    uint64_t first_col, row_len, count;
     uint8_t elem_bytes_src, elem_bytes_dst;
     uint8_t kind;      /* 0 = 16-byte vector path, 1 = any-alignment path */
     uint8_t pad_bytes; /* zero bytes written after the tile's last element (pack side) */
@@ -235,11 +237,18 @@ int th_plan_get_tile(const th_plan* plan, int side, size_t i, th_tile_info* out)
 /* first tile of `chunk` on `side`; chunk == num_chunks gives the tile count */
 size_t th_plan_chunk_first_tile(const th_plan* plan, int side, uint32_t chunk);
 
+/* Yardstick, not part of the transfer path: a plain device-to-device copy of
+ * nbytes (multiple of 16; dst / src device pointers, 16-byte aligned, not
+ * overlapping) enqueued on hip_stream with the same launch shape as the aligned
+ * pack / unpack path.  Benchmarks use it as the practical bandwidth ceiling and as
+ * the known-size kernel against which HBM byte counters are scaled. */
+int th_reference_copy(void* dst, const void* src, size_t nbytes, void* hip_stream);
+
 /* Process-wide tuning knobs, read when a plan is created.  Returns TH_ERR_ARG
  * for an unknown key or an out-of-range value. */
 enum {
     TH_CFG_TILE_BYTES = 1 /* destination bytes per tile (one workgroup's share);
-                             multiple of 4096 in [4096, 1048576 - 4096]; default 65536 */
+                             multiple of 4096 in [4096, 524288]; default 16384 */
 };
 int th_config_set(int key, uint64_t value);
 uint64_t th_config_get(int key);

@@ -76,7 +76,7 @@ class TileInfo(C.Structure):
     _fields_ = [("src_buf", C.c_uint32), ("dst_buf", C.c_uint32),
                 ("src_byte_off", C.c_uint64), ("src_byte_stride", C.c_uint64),
                 ("dst_byte_off", C.c_uint64), ("dst_byte_stride", C.c_uint64),
-                ("nrows", C.c_uint64), ("ncols", C.c_uint64),
+                ("first_col", C.c_uint64), ("row_len", C.c_uint64), ("count", C.c_uint64),
                 ("elem_bytes_src", C.c_uint8), ("elem_bytes_dst", C.c_uint8), ("kind", C.c_uint8),
                 ("pad_bytes", C.c_uint8), ("reserved", C.c_uint8 * 4)]
 
@@ -109,6 +109,7 @@ _get_run = _sig("th_plan_get_run", C.c_int, _P, C.c_size_t, C.POINTER(Run))
 _num_tiles = _sig("th_plan_num_tiles", C.c_size_t, _P, C.c_int)
 _get_tile = _sig("th_plan_get_tile", C.c_int, _P, C.c_int, C.c_size_t, C.POINTER(TileInfo))
 _chunk_first_tile = _sig("th_plan_chunk_first_tile", C.c_size_t, _P, C.c_int, C.c_uint32)
+_reference_copy = _sig("th_reference_copy", C.c_int, _P, _P, C.c_size_t, _P)
 _config_set = _sig("th_config_set", C.c_int, C.c_int, C.c_uint64)
 _config_get = _sig("th_config_get", C.c_uint64, C.c_int)
 _last_error = _sig("th_last_error", C.c_char_p)
@@ -237,6 +238,10 @@ def th_unpack(plan, wire_ptrs, chunk_first, chunk_count, dst_ptrs, stream=0):
 
 def th_plan_destroy(plan):
     plan.destroy()
+
+
+def th_reference_copy(dst_ptr, src_ptr, nbytes, stream=0):
+    _check(_reference_copy(dst_ptr, src_ptr, nbytes, stream))
 
 
 def th_config_set(key, value):

@@ -10,21 +10,23 @@ LIB = os.path.join(HERE, "libtensorhub_reshard.so")
 SOURCES = ["th_api.cpp", "th_layouts.cpp", "th_planner.cpp", "th_kernels.hip"]
 
 
-def build_library(verbose=False):
+def build_library(verbose=False, defines=(), out=None):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB + ".tmp%d" % os.getpid()
+    out = out or LIB
+    tmp = out + ".tmp%d" % os.getpid()
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wall", "-Wno-unused-command-line-argument",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    cmd += ["-D" + d for d in defines]
     for s in SOURCES:
         cmd += ["-x", "hip", os.path.join(CSRC, s)]
     cmd += ["-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, out)
+    return out
 
 
 if __name__ == "__main__":

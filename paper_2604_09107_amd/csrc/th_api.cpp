@@ -407,11 +407,19 @@ int th_plan_get_tile(const th_plan* p, int side, size_t i, th_tile_info* out) {
     out->src_byte_stride = t.src_stride;
     out->dst_byte_off = t.dst_off;
     out->dst_byte_stride = t.dst_stride;
-    out->nrows = t.nrows;
     const bool vec = (t.flags & TILE_KIND_MASK) == TILE_KIND_VEC;
     out->elem_bytes_src = (t.flags & TILE_SRC_F32) ? 4 : 2;
     out->elem_bytes_dst = (t.flags & TILE_DST_F32) ? 4 : 2;
-    out->ncols = vec ? (uint64_t)t.ncols * 16 / out->elem_bytes_dst : t.ncols;
+    const uint64_t per_vec = 16 / out->elem_bytes_dst;
+    if (vec) {
+        out->first_col = (uint64_t)t.col0 * per_vec;
+        out->row_len = (uint64_t)t.ncols * per_vec;
+        out->count = (uint64_t)t.count * per_vec;
+    } else {
+        out->first_col = 0;
+        out->row_len = t.ncols;
+        out->count = (uint64_t)t.count * t.ncols;
+    }
     out->kind = vec ? 0 : 1;
     out->pad_bytes = (uint8_t)((t.flags & TILE_PAD_MASK) >> TILE_PAD_SHIFT);
     return TH_OK;
@@ -422,12 +430,21 @@ size_t th_plan_chunk_first_tile(const th_plan* p, int side, uint32_t chunk) {
     return (size_t)p->m.chunk_tile0[side][chunk];
 }
 
+int th_reference_copy(void* dst, const void* src, size_t nbytes, void* hip_stream) {
+    if ((nbytes && (!dst || !src)) || nbytes % 16 || reinterpret_cast<uintptr_t>(dst) % 16 ||
+        reinterpret_cast<uintptr_t>(src) % 16) {
+        set_error("reference copy needs 16-byte aligned pointers and a size that is a multiple of 16");
+        return TH_ERR_ARG;
+    }
+    return nbytes ? launch_reference_copy(dst, src, nbytes, hip_stream) : TH_OK;
+}
+
 int th_config_set(int key, uint64_t value) {
     std::lock_guard<std::mutex> lk(g_cfg_mu);
     switch (key) {
         case TH_CFG_TILE_BYTES:
-            if (value < 4096 || value > 1048576 - 4096 || value % 4096) {
-                set_error("tile bytes must be a multiple of 4096 in [4096, 1044480]");
+            if (value < 4096 || value > 524288 || value % 4096) {
+                set_error("tile bytes must be a multiple of 4096 in [4096, 524288]");
                 return TH_ERR_ARG;
             }
             g_tuning.tile_bytes = value;

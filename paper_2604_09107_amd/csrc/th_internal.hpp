@@ -42,12 +42,17 @@ struct alignas(64) Tile {
     uint64_t dst_stride;
     uint32_t src_buf;  // pack: source tensor id; unpack: chunk index
     uint32_t dst_buf;  // pack: chunk index;      unpack: destination tensor id
-    uint32_t nrows;
+    uint32_t count;  // KIND_VEC: 16-byte vectors in the tile; KIND_ANY: rows in the tile
     uint32_t ncols;  // KIND_VEC: 16-byte vectors per row; KIND_ANY: elements per row
     uint32_t flags;  // see below
-    uint32_t magic;  // KIND_VEC with nrows > 1: floor(2^32 / ncols) + 1
-    uint32_t reserved[2];
+    uint32_t magic;  // KIND_VEC: floor(2^32 / ncols) + 1, or 0 when ncols >= the tile's vector capacity
+    uint32_t col0;   // KIND_VEC: column (in vectors) of the tile's first vector within its first row
+    uint32_t reserved;
 };
+// A KIND_VEC tile is a run of `count` consecutive vectors of a row-major rectangle whose rows
+// hold `ncols` vectors: it starts at column col0 of the row that src_off / dst_off point to and
+// wraps to the next row (+ stride) after column ncols-1.  A KIND_ANY tile is `count` whole rows
+// (or one piece of a long row) of `ncols` elements.
 static_assert(sizeof(Tile) == 64, "tile record is one 64-byte line");
 
 enum : uint32_t {
@@ -62,7 +67,10 @@ enum : uint32_t {
     TILE_PAD_MASK = 0xF << TILE_PAD_SHIFT,
 };
 
-constexpr int kBlockThreads = 256;
+#ifndef TH_BLOCK_THREADS
+#define TH_BLOCK_THREADS 1024
+#endif
+constexpr int kBlockThreads = TH_BLOCK_THREADS;  // threads per workgroup (one tile each)
 
 struct Manifest {
     std::vector<TensorInfo> tensors[2];  // 0 = source side, 1 = destination side
@@ -75,7 +83,7 @@ struct Manifest {
 };
 
 struct Tuning {
-    uint64_t tile_bytes = 65536;
+    uint64_t tile_bytes = 16384;  // one 128-bit vector per thread of a workgroup
 };
 Tuning current_tuning();
 
@@ -97,5 +105,7 @@ inline unsigned esize(int dtype) { return dtype == TH_F32 ? 4u : 2u; }
 int launch_tiles(bool is_pack, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first,
                  void* stream);
+
+int launch_reference_copy(void* dst, const void* src, uint64_t nbytes, void* stream);
 
 }  // namespace th

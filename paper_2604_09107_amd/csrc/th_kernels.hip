@@ -1,8 +1,8 @@
 // gfx950 kernels of the reshard path: one launch moves every tile of a chunk range.
 //
 // Pure data movement, bound by HBM bandwidth: no matrix cores.  One workgroup of
-// 256 threads (4 wavefronts of 64) takes one 64-byte tile record, which the
-// scalar unit fetches once for the whole workgroup, resolves its two base
+// kBlockThreads threads (wavefronts of 64) takes one 64-byte tile record, which
+// the scalar unit fetches once for the whole workgroup, resolves its two base
 // pointers through the pointer tables, and copies a sub-rectangle:
 //
 //   vector path  every address is a multiple of 16 bytes: 128-bit loads and stores,
@@ -21,17 +21,30 @@
 namespace th {
 namespace {
 
+// Pointers read from the pointer tables are generic; every buffer of this path lives in
+// device memory, so address them as global (global_load / global_store, not flat).
+#define TH_GLOBAL __attribute__((address_space(1)))
+
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef const TH_GLOBAL char* gsrc_t;
+typedef TH_GLOBAL char* gdst_t;
 
 // 16 bytes at an address that is only element-aligned
 struct __attribute__((packed, aligned(2))) Unaligned2 { u32x4 v; };
 struct __attribute__((packed, aligned(4))) Unaligned4 { u32x4 v; };
 
-constexpr int kUnroll = 8;  // 128-bit accesses in flight per lane on the vector path
+#ifndef TH_UNROLL
+#define TH_UNROLL 4
+#endif
+constexpr int kUnroll = TH_UNROLL;  // 128-bit accesses in flight per lane on the vector path
 
-__device__ __forceinline__ u32x4 ld16(const char* p) { return *reinterpret_cast<const u32x4*>(p); }
-__device__ __forceinline__ void st16(char* p, u32x4 v) { *reinterpret_cast<u32x4*>(p) = v; }
+// Streaming accesses: every byte is touched once, so mark them non-temporal.
+__device__ __forceinline__ u32x4 ld16(gsrc_t p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const TH_GLOBAL u32x4*>(p));
+}
+__device__ __forceinline__ void st16(gdst_t p, u32x4 v) {
+    __builtin_nontemporal_store(v, reinterpret_cast<TH_GLOBAL u32x4*>(p));
+}
 
 // fp32 bits -> bf16 bits, round to nearest even in integer arithmetic.  No flush of
 // subnormals; overflow carries into infinity; a NaN keeps its sign and top payload bits
@@ -47,53 +60,30 @@ __device__ __forceinline__ uint32_t narrow_pair(uint32_t lo, uint32_t hi) {
 
 // ---- vector path ----------------------------------------------------------------------------
 
-__device__ __forceinline__ void copy_vec_1d(const char* __restrict__ src, char* __restrict__ dst, uint32_t nv) {
+// `count` consecutive vectors of a row-major rectangle with `vpr` vectors per row, starting at
+// column col0 of the row that src / dst point to.  Vector i of the tile sits at linear position
+// x = col0 + i: row x / vpr, column x % vpr.  magic != 0: vpr < 2^15 and x < 2^16, so the
+// multiply-high division is exact; magic == 0: vpr is at least the tile's capacity, so x < 2*vpr
+// and the quotient is 0 or 1.
+__device__ __forceinline__ void copy_vec(gsrc_t src, gdst_t dst, uint64_t ss, uint64_t ds, uint32_t count,
+                                         uint32_t vpr, uint32_t col0, uint32_t magic) {
     const uint32_t tid = threadIdx.x;
     constexpr uint32_t kStep = kBlockThreads * kUnroll;
-    uint32_t base = 0;
-    for (; base + kStep <= nv; base += kStep) {
+    for (uint32_t base = 0; base < count; base += kStep) {
         u32x4 v[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) v[u] = ld16(src + (size_t)(base + u * kBlockThreads + tid) * 16);
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) st16(dst + (size_t)(base + u * kBlockThreads + tid) * 16, v[u]);
-    }
-    if (base < nv) {
-        u32x4 v[kUnroll];
+        uint32_t row[kUnroll], col[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const uint32_t i = base + u * kBlockThreads + tid;
-            if (i < nv) v[u] = ld16(src + (size_t)i * 16);
+            const uint32_t x = col0 + i;
+            row[u] = magic ? __umulhi(x, magic) : (x >= vpr ? 1u : 0u);
+            col[u] = x - row[u] * vpr;
+            if (i < count) v[u] = ld16(src + (size_t)row[u] * ss + (size_t)col[u] * 16);
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const uint32_t i = base + u * kBlockThreads + tid;
-            if (i < nv) st16(dst + (size_t)i * 16, v[u]);
-        }
-    }
-}
-
-__device__ __forceinline__ void copy_vec_2d(const char* __restrict__ src, char* __restrict__ dst,
-                                            uint64_t ss, uint64_t ds, uint32_t nrows, uint32_t ncols,
-                                            uint32_t magic) {
-    const uint32_t tid = threadIdx.x;
-    const uint32_t nv = nrows * ncols;  // < 65536 by construction of the tiles
-    constexpr uint32_t kStep = kBlockThreads * kUnroll;
-    for (uint32_t base = 0; base < nv; base += kStep) {
-        u32x4 v[kUnroll];
-        size_t doff[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const uint32_t i = base + u * kBlockThreads + tid;
-            const uint32_t r = __umulhi(i, magic);  // i / ncols, exact for i, ncols < 2^16
-            const uint32_t c = i - r * ncols;
-            doff[u] = (size_t)r * ds + (size_t)c * 16;
-            if (i < nv) v[u] = ld16(src + (size_t)r * ss + (size_t)c * 16);
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const uint32_t i = base + u * kBlockThreads + tid;
-            if (i < nv) st16(dst + doff[u], v[u]);
+            if (i < count) st16(dst + (size_t)row[u] * ds + (size_t)col[u] * 16, v[u]);
         }
     }
 }
@@ -101,20 +91,20 @@ __device__ __forceinline__ void copy_vec_2d(const char* __restrict__ src, char* 
 // ---- any-alignment path -------------------------------------------------------------------------
 
 template <int SES>
-__device__ __forceinline__ uint32_t load_elem(const char* p) {
-    if (SES == 4) return *reinterpret_cast<const uint32_t*>(p);
-    return *reinterpret_cast<const uint16_t*>(p);
+__device__ __forceinline__ uint32_t load_elem(gsrc_t p) {
+    if (SES == 4) return *reinterpret_cast<const TH_GLOBAL uint32_t*>(p);
+    return *reinterpret_cast<const TH_GLOBAL uint16_t*>(p);
 }
 
 // One 16-byte destination slot from element-aligned source data.
 template <int SES, int DES>
-__device__ __forceinline__ u32x4 load_slot(const char* s) {
+__device__ __forceinline__ u32x4 load_slot(gsrc_t s) {
     if (SES == DES) {
-        if (SES == 2) return reinterpret_cast<const Unaligned2*>(s)->v;
-        return reinterpret_cast<const Unaligned4*>(s)->v;
+        if (SES == 2) return reinterpret_cast<const TH_GLOBAL Unaligned2*>(s)->v;
+        return reinterpret_cast<const TH_GLOBAL Unaligned4*>(s)->v;
     } else {  // 8 fp32 -> 8 bf16
-        const u32x4 a = reinterpret_cast<const Unaligned4*>(s)->v;
-        const u32x4 b = reinterpret_cast<const Unaligned4*>(s + 16)->v;
+        const u32x4 a = reinterpret_cast<const TH_GLOBAL Unaligned4*>(s)->v;
+        const u32x4 b = reinterpret_cast<const TH_GLOBAL Unaligned4*>(s + 16)->v;
         u32x4 o;
         o.x = narrow_pair(a.x, a.y);
         o.y = narrow_pair(a.z, a.w);
@@ -125,26 +115,26 @@ __device__ __forceinline__ u32x4 load_slot(const char* s) {
 }
 
 template <int SES, int DES>
-__device__ __forceinline__ void copy_elem(const char* s, char* d) {
+__device__ __forceinline__ void copy_elem(gsrc_t s, gdst_t d) {
     uint32_t v = load_elem<SES>(s);
     if (SES == 4 && DES == 2) v = narrow_rne(v);
     if (DES == 4)
-        *reinterpret_cast<uint32_t*>(d) = v;
+        *reinterpret_cast<TH_GLOBAL uint32_t*>(d) = v;
     else
-        *reinterpret_cast<uint16_t*>(d) = (uint16_t)v;
+        *reinterpret_cast<TH_GLOBAL uint16_t*>(d) = (uint16_t)v;
 }
 
 template <int SES, int DES>
-__device__ __forceinline__ void copy_any(const char* __restrict__ src, char* __restrict__ dst, uint64_t ss,
-                                         uint64_t ds, uint32_t nrows, uint32_t ncols, uint32_t lg) {
+__device__ __forceinline__ void copy_any(gsrc_t src, gdst_t dst, uint64_t ss, uint64_t ds, uint32_t nrows,
+                                         uint32_t ncols, uint32_t lg) {
     constexpr int EPV = 16 / DES;  // elements per 16-byte destination slot
     const uint32_t tid = threadIdx.x;
     const uint32_t lanes = 1u << lg;             // threads that share a row
     const uint32_t groups = kBlockThreads >> lg;  // rows in flight
     const uint32_t lane = tid & (lanes - 1);
     for (uint32_t r = tid >> lg; r < nrows; r += groups) {
-        const char* s = src + (size_t)r * ss;
-        char* d = dst + (size_t)r * ds;
+        gsrc_t s = src + (size_t)r * ss;
+        gdst_t d = dst + (size_t)r * ds;
         // elements between the previous 16-byte boundary and the row start
         const uint32_t lead = (uint32_t)(reinterpret_cast<uintptr_t>(d) & 15u) / DES;
         const uint32_t nslots = (lead + ncols + EPV - 1) / EPV;
@@ -168,20 +158,24 @@ __global__ __launch_bounds__(kBlockThreads) void th_tiles_kernel(const Tile* __r
                                                                   const void* const* __restrict__ src_table,
                                                                   void* const* __restrict__ dst_table,
                                                                   uint32_t wire_first) {
-    const Tile& t = tiles[blockIdx.x];  // uniform: fetched by the scalar unit
+    // Workgroups are dealt to the 8 XCDs round-robin (workgroup b runs on XCD b mod 8).  Give
+    // each XCD one contiguous eighth of the tile list so that it streams through its own
+    // address range instead of every 8th tile.
+    uint32_t b = blockIdx.x;
+    const uint32_t per_xcd = gridDim.x >> 3;
+    if (b < per_xcd * 8) b = (b & 7) * per_xcd + (b >> 3);
+
+    const Tile& t = tiles[b];  // uniform: fetched by the scalar unit
     const uint32_t flags = t.flags;
-    const uint32_t nrows = t.nrows, ncols = t.ncols;
+    const uint32_t nrows = t.count, ncols = t.ncols;
     const uint64_t ss = t.src_stride, ds = t.dst_stride;
     const uint32_t sb = PACK ? t.src_buf : t.src_buf - wire_first;
     const uint32_t db = PACK ? t.dst_buf - wire_first : t.dst_buf;
-    const char* src = static_cast<const char*>(src_table[sb]) + t.src_off;
-    char* dst = static_cast<char*>(dst_table[db]) + t.dst_off;
+    gsrc_t src = (gsrc_t)(static_cast<const char*>(src_table[sb]) + t.src_off);
+    gdst_t dst = (gdst_t)(static_cast<char*>(dst_table[db]) + t.dst_off);
 
     if ((flags & TILE_KIND_MASK) == TILE_KIND_VEC) {
-        if (nrows == 1)
-            copy_vec_1d(src, dst, ncols);
-        else
-            copy_vec_2d(src, dst, ss, ds, nrows, ncols, t.magic);
+        copy_vec(src, dst, ss, ds, t.count, ncols, t.col0, t.magic);
         return;
     }
     const uint32_t lg = (flags & TILE_LG_LANES_MASK) >> TILE_LG_LANES_SHIFT;
@@ -198,10 +192,22 @@ __global__ __launch_bounds__(kBlockThreads) void th_tiles_kernel(const Tile* __r
         // zero the alignment gap that follows a tensor's last element on the wire
         const uint32_t pad = (flags & TILE_PAD_MASK) >> TILE_PAD_SHIFT;
         if (threadIdx.x * 2 < pad) {
-            char* end = dst + (size_t)(nrows - 1) * ds + (size_t)ncols * des;
-            *reinterpret_cast<uint16_t*>(end + threadIdx.x * 2) = 0;
+            gdst_t end = dst + (size_t)(nrows - 1) * ds + (size_t)ncols * des;
+            *reinterpret_cast<TH_GLOBAL uint16_t*>(end + threadIdx.x * 2) = 0;
         }
     }
+}
+
+// Plain contiguous copy with the same launch shape as the vector path (one 128-bit vector per
+// thread, XCD-contiguous workgroup order, streaming hints): the yardstick for what a copy can
+// reach on this memory system, and the known-size kernel that HBM byte counters are scaled by.
+__global__ __launch_bounds__(kBlockThreads) void th_reference_copy_kernel(const u32x4* __restrict__ src,
+                                                                           u32x4* __restrict__ dst, uint64_t nvec) {
+    uint32_t b = blockIdx.x;
+    const uint32_t per_xcd = gridDim.x >> 3;
+    if (b < per_xcd * 8) b = (b & 7) * per_xcd + (b >> 3);
+    const uint64_t i = (uint64_t)b * kBlockThreads + threadIdx.x;
+    if (i < nvec) st16((gdst_t)(dst + i), ld16((gsrc_t)(src + i)));
 }
 
 }  // namespace
@@ -225,6 +231,26 @@ int launch_tiles(bool is_pack, const Tile* tiles, uint64_t tile0, uint64_t ntile
         }
         tile0 += n;
         ntiles -= n;
+    }
+    return TH_OK;
+}
+
+int launch_reference_copy(void* dst, const void* src, uint64_t nbytes, void* stream) {
+    const uint64_t nvec = nbytes / 16;
+    uint64_t done = 0;
+    constexpr uint64_t kMaxVec = (uint64_t)(1u << 30) * kBlockThreads;
+    while (done < nvec) {
+        const uint64_t n = nvec - done < kMaxVec ? nvec - done : kMaxVec;
+        const uint32_t grid = (uint32_t)((n + kBlockThreads - 1) / kBlockThreads);
+        hipLaunchKernelGGL(th_reference_copy_kernel, dim3(grid), dim3(kBlockThreads), 0,
+                           static_cast<hipStream_t>(stream), static_cast<const u32x4*>(src) + done,
+                           static_cast<u32x4*>(dst) + done, n);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) {
+            set_error("kernel launch failed: %s", hipGetErrorString(e));
+            return TH_ERR_HIP;
+        }
+        done += n;
     }
     return TH_OK;
 }

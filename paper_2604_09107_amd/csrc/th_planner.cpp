@@ -44,6 +44,39 @@ void tile_run(std::vector<Tile>& out, Side S, Side D, uint64_t nrows, uint64_t n
     const uint64_t units = ncols * D.es / unit_d;                        // column units per row
     const uint64_t row_bytes = ncols * D.es;
 
+    if (vec) {
+        // Cut the rectangle's vectors, taken in row-major order, into equal runs: every tile is
+        // full whatever the row length; a tile may start mid-row and wrap over row ends.
+        const uint64_t cap = tile_bytes / 16;  // vectors per tile
+        const uint64_t total = nrows * units;
+        for (uint64_t v0 = 0; v0 < total; v0 += cap) {
+            Tile t;
+            std::memset(&t, 0, sizeof t);
+            const uint64_t row0 = nrows == 1 ? 0 : v0 / units;
+            const uint64_t col0 = nrows == 1 ? 0 : v0 % units;
+            const uint64_t lin = nrows == 1 ? v0 * 16 : 0;  // a single row needs no wrapping
+            t.src_off = S.off + row0 * S.stride + lin;
+            t.dst_off = D.off + row0 * D.stride + lin;
+            t.src_stride = S.stride;
+            t.dst_stride = D.stride;
+            t.src_buf = S.buf;
+            t.dst_buf = D.buf;
+            t.count = (uint32_t)std::min(cap, total - v0);
+            t.flags = flags;
+            if (nrows == 1 || units >= cap) {
+                // at most one wrap inside a tile: the kernel compares instead of dividing
+                t.ncols = nrows == 1 ? 0xFFFFFFFFu : (uint32_t)units;
+                t.magic = 0;
+            } else {
+                t.ncols = (uint32_t)units;
+                t.magic = (uint32_t)((1ull << 32) / units) + 1;
+            }
+            t.col0 = (uint32_t)col0;
+            out.push_back(t);
+        }
+        return;
+    }
+
     auto emit = [&](uint64_t r0, uint64_t nr, uint64_t u0, uint64_t nu, bool last) {
         Tile t;
         std::memset(&t, 0, sizeof t);
@@ -53,15 +86,11 @@ void tile_run(std::vector<Tile>& out, Side S, Side D, uint64_t nrows, uint64_t n
         t.dst_stride = D.stride;
         t.src_buf = S.buf;
         t.dst_buf = D.buf;
-        t.nrows = (uint32_t)nr;
+        t.count = (uint32_t)nr;
         t.ncols = (uint32_t)nu;
         t.flags = flags;
-        if (vec) {
-            t.magic = nr > 1 ? (uint32_t)((1ull << 32) / nu) + 1 : 0;
-        } else {
-            const uint64_t slots = (nu * D.es + 15) / 16 + 1;  // 16-byte destination slots a row can touch
-            t.flags |= std::min(8u, ceil_log2(slots)) << TILE_LG_LANES_SHIFT;
-        }
+        const uint64_t slots = (nu * D.es + 15) / 16 + 1;  // 16-byte destination slots a row can touch
+        t.flags |= std::min(8u, ceil_log2(slots)) << TILE_LG_LANES_SHIFT;
         if (last && pad) t.flags |= (uint32_t)pad << TILE_PAD_SHIFT;
         out.push_back(t);
     };
@@ -69,8 +98,7 @@ void tile_run(std::vector<Tile>& out, Side S, Side D, uint64_t nrows, uint64_t n
     if (nrows == 1 || row_bytes >= tile_bytes) {
         // long rows: each row is cut into equal column pieces of at most one tile
         const uint64_t k = (row_bytes + tile_bytes - 1) / tile_bytes;
-        uint64_t per = (units + k - 1) / k;
-        if (!vec) per = (per + 7) / 8 * 8;
+        const uint64_t per = ((units + k - 1) / k + 7) / 8 * 8;
         for (uint64_t r = 0; r < nrows; ++r)
             for (uint64_t u = 0; u < units; u += per)
                 emit(r, 1, u, std::min(per, units - u), r + 1 == nrows && u + per >= units);

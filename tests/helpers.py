@@ -72,9 +72,17 @@ def exec_tiles(plan, side, src_bufs, dst_bufs, chunk_range=None):
         hi = plan.chunk_first_tile(side, chunk_range[1])
     for i in range(lo, hi):
         t = plan.tile(side, i)
-        exec_copy(src_bufs[t.src_buf], dst_bufs[t.dst_buf], t.src_byte_off, t.src_byte_stride,
-                  t.dst_byte_off, t.dst_byte_stride, t.nrows, t.ncols, t.elem_bytes_src, t.elem_bytes_dst,
-                  t.pad_bytes)
+        src, dst = src_bufs[t.src_buf], dst_bufs[t.dst_buf]
+        left, col, row = int(t.count), int(t.first_col), 0
+        assert col < t.row_len
+        while left:
+            n = min(int(t.row_len) - col, left)
+            exec_copy(src, dst, t.src_byte_off + row * t.src_byte_stride + col * t.elem_bytes_src, 0,
+                      t.dst_byte_off + row * t.dst_byte_stride + col * t.elem_bytes_dst, 0, 1, n,
+                      t.elem_bytes_src, t.elem_bytes_dst, t.pad_bytes if n == left else 0)
+            left -= n
+            row += 1
+            col = 0
 
 
 def flat_u8(arrs):
