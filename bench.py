@@ -79,6 +79,56 @@ def cpu_baseline(synth, w, jobs, budget_s=15.0):
                        % (n_items, sweep_bytes / 1e9, spent))
 
 
+def build_scatter_inputs(th, dev, synth, w, torch):
+    """The scattered sweep: fp32 pool (4-byte aligned tensors), explicit segments, dense bf16 arena."""
+    import numpy as np
+    d = synth.scatter_description(w["n_tensors"], w["seed"])
+    pool = synth.scatter_values(d["pool_elems"] + 3, w["seed"], "cuda")[1:]
+    arena_store = torch.zeros(d["arena_elems"] + 9, dtype=torch.bfloat16, device="cuda")
+    arena = arena_store[1:]
+    n = w["n_tensors"]
+    segs = np.zeros(n, dtype=th.binding.SEGMENT_NP)
+    segs["src_tensor"], segs["dst_tensor"] = d["seg_src_tensor"], 0
+    segs["src_elem_off"], segs["dst_elem_off"] = d["seg_src_off"], d["seg_dst_off"]
+    segs["src_row_stride"], segs["dst_row_stride"] = d["seg_src_stride"], d["seg_dst_stride"]
+    segs["nrows"], segs["row_len"] = d["seg_nrows"], d["seg_row_len"]
+    segs["src_dtype"], segs["dst_dtype"] = th.TH_F32, th.TH_BF16
+    t0 = time.perf_counter()
+    plan = th.th_plan_create_from_segments(segs, d["n_elems"], [d["arena_elems"] + 8], w["chunk_bytes"])
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=0)
+    src_ptrs = pool.data_ptr() + d["pool_off"].astype(np.uint64) * np.uint64(4)
+    job = dict(plan=plan, src=pool, src_ptrs=src_ptrs, wire=wire_dev, wptrs=wptrs, desc=d, keep=arena_store)
+    return [job], [arena], np.array([arena.data_ptr()], dtype=np.uint64), plan_ms
+
+
+def cpu_baseline_scatter(synth, w, jobs, budget_s=15.0):
+    """The segment oracle on the host over a bounded prefix of the wire order."""
+    import numpy as np
+    from oracle import segments
+    d, pool = jobs[0]["desc"], jobs[0]["src"]
+    n = w["n_tensors"]
+    osegs = dict(src_tensor=d["seg_src_tensor"], dst_tensor=np.zeros(n, dtype=np.int64),
+                 src_off=d["seg_src_off"], src_stride=d["seg_src_stride"], dst_off=d["seg_dst_off"],
+                 dst_stride=d["seg_dst_stride"], nrows=d["seg_nrows"], row_len=d["seg_row_len"])
+    spent, sweep_bytes, k = 0.0, 0, 0
+    while k < n and spent < budget_s:
+        t = int(d["seg_src_tensor"][k])
+        o, m = int(d["pool_off"][t]), int(d["n_elems"][t])
+        src = {t: synth.to_bits(pool[o:o + m])}                      # D2H, not timed
+        nel = int(d["seg_nrows"][k]) * int(d["seg_row_len"][k])
+        out = np.zeros(nel, dtype=np.uint16)
+        t0 = time.perf_counter()
+        wire = segments.segment_wire(osegs, k, src, "f32", "bf16")  # pack: gather + narrow
+        out[:] = wire                                                # unpack: dense destination slice
+        spent += time.perf_counter() - t0
+        sweep_bytes += nel * 10
+        k += 1
+    return dict(value=round(sweep_bytes / spent / 1e9, 3), unit="GB/s", cores=1, kind="oracle",
+                sample="first %d segments of the wire order (%.2f GB moved, %.1f s of oracle time)"
+                       % (k, sweep_bytes / 1e9, spent))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -86,7 +136,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2_8b_tp1_to_tp4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--tile-bytes", type=int, default=0)
+    ap.add_argument("--tile-bytes", type=int, default=0, help="override the vector-path tile size")
+    ap.add_argument("--tile-bytes-any", type=int, default=0, help="override the any-alignment tile size")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the reshard path has no cross-GPU step (every holder/reader pair is an "
@@ -102,8 +153,13 @@ def main():
     torch.cuda.set_device(0)
     if args.tile_bytes:
         th.th_config_set(th.TH_CFG_TILE_BYTES, args.tile_bytes)
+    if args.tile_bytes_any:
+        th.th_config_set(th.TH_CFG_TILE_BYTES_ANY, args.tile_bytes_any)
     w = synth.workload(args.workload)
-    jobs, dst_dev, dst_ptrs, plan_ms = build_inputs(th, dev, synth, w, torch)
+    if w["kind"] == "scatter":
+        jobs, dst_dev, dst_ptrs, plan_ms = build_scatter_inputs(th, dev, synth, w, torch)
+    else:
+        jobs, dst_dev, dst_ptrs, plan_ms = build_inputs(th, dev, synth, w, torch)
     stream = dev.current_stream()
 
     pack_bytes = sum(j["plan"].src_read_bytes + j["plan"].payload_bytes for j in jobs)     # read src + write wire
@@ -176,11 +232,12 @@ def main():
         "metric": "reshard pack+unpack effective HBM GB/s",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "f32->bf16 (integer RNE)" if w["kind"] == "scatter" else "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "model": w["model_name"], "chunk_bytes": w["chunk_bytes"],
                    "holders": len(jobs), "payload_bytes": sum(j["plan"].payload_bytes for j in jobs),
                    "sweep_bytes": sweep_bytes, "chunks": sum(j["plan"].num_chunks for j in jobs),
-                   "tile_bytes": th.th_config_get(th.TH_CFG_TILE_BYTES)},
+                   "tile_bytes": th.th_config_get(th.TH_CFG_TILE_BYTES),
+                   "tile_bytes_any": th.th_config_get(th.TH_CFG_TILE_BYTES_ANY)},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "plan_ms": round(plan_ms, 3),
         "kernels": {"th_pack": {"ms": round(pack_ms, 4), "GB/s": round(k_pack, 1)},
@@ -190,7 +247,7 @@ def main():
                      "unit": "GB/s", "frac": round(dom[1] / HBM_PEAK_GBPS, 4), "traffic": None},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(synth, w, jobs)
+        out["cpu_baseline"] = (cpu_baseline_scatter if w["kind"] == "scatter" else cpu_baseline)(synth, w, jobs)
     print(json.dumps(out))
 
 

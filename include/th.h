@@ -228,7 +228,8 @@ typedef struct th_tile_info {
     uint64_t dst_byte_off, dst_byte_stride;
     uint64_t first_col, row_len, count;
     uint8_t elem_bytes_src, elem_bytes_dst;
-    uint8_t kind;      /* 0 = 16-byte vector path, 1 = any-alignment path */
+    uint8_t kind;      /* 0 = 16-byte vector path, 1 = any-alignment strided path, 2 = any-alignment
+                          path with a contiguous destination */
     uint8_t pad_bytes; /* zero bytes written after the tile's last element (pack side) */
     uint8_t reserved[4];
 } th_tile_info;
@@ -247,8 +248,9 @@ int th_reference_copy(void* dst, const void* src, size_t nbytes, void* hip_strea
 /* Process-wide tuning knobs, read when a plan is created.  Returns TH_ERR_ARG
  * for an unknown key or an out-of-range value. */
 enum {
-    TH_CFG_TILE_BYTES = 1 /* destination bytes per tile (one workgroup's share);
-                             multiple of 4096 in [4096, 524288]; default 16384 */
+    TH_CFG_TILE_BYTES = 1,    /* destination bytes per tile (one workgroup's share) on the 16-byte
+                                 vector path; multiple of 4096 in [4096, 524288]; default 16384 */
+    TH_CFG_TILE_BYTES_ANY = 2 /* same for the any-alignment paths; default 32768 */
 };
 int th_config_set(int key, uint64_t value);
 uint64_t th_config_get(int key);

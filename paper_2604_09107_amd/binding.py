@@ -14,6 +14,7 @@ _LIB_PATH = os.path.join(_HERE, "libtensorhub_reshard.so")
 TH_BF16, TH_F32 = 1, 2
 TH_FLAG_HOST_ONLY, TH_FLAG_PTRS_ALIGNED16 = 1, 2
 TH_CFG_TILE_BYTES = 1
+TH_CFG_TILE_BYTES_ANY = 2
 TH_MODEL_DENSE, TH_MODEL_MOE = 1, 2
 _DTYPE = {"bf16": TH_BF16, "f32": TH_F32}
 _DTYPE_NAME = {TH_BF16: "bf16", TH_F32: "f32", 0: None}

@@ -415,12 +415,19 @@ int th_plan_get_tile(const th_plan* p, int side, size_t i, th_tile_info* out) {
         out->first_col = (uint64_t)t.col0 * per_vec;
         out->row_len = (uint64_t)t.ncols * per_vec;
         out->count = (uint64_t)t.count * per_vec;
+    } else if ((t.flags & TILE_KIND_MASK) == TILE_KIND_DENSE) {
+        out->first_col = t.col0;
+        out->row_len = t.ncols;
+        out->count = t.count;
+        // contiguous destination: consecutive rows follow each other; the first one is short by first_col
+        out->dst_byte_stride = (uint64_t)t.ncols * out->elem_bytes_dst;
+        out->dst_byte_off = t.dst_off - (uint64_t)t.col0 * out->elem_bytes_dst;
     } else {
         out->first_col = 0;
         out->row_len = t.ncols;
         out->count = (uint64_t)t.count * t.ncols;
     }
-    out->kind = vec ? 0 : 1;
+    out->kind = (uint8_t)(t.flags & TILE_KIND_MASK);
     out->pad_bytes = (uint8_t)((t.flags & TILE_PAD_MASK) >> TILE_PAD_SHIFT);
     return TH_OK;
 }
@@ -449,6 +456,13 @@ int th_config_set(int key, uint64_t value) {
             }
             g_tuning.tile_bytes = value;
             return TH_OK;
+        case TH_CFG_TILE_BYTES_ANY:
+            if (value < 4096 || value > 524288 || value % 4096) {
+                set_error("tile bytes must be a multiple of 4096 in [4096, 524288]");
+                return TH_ERR_ARG;
+            }
+            g_tuning.tile_bytes_any = value;
+            return TH_OK;
     }
     set_error("unknown configuration key %d", key);
     return TH_ERR_ARG;
@@ -456,7 +470,7 @@ int th_config_set(int key, uint64_t value) {
 
 uint64_t th_config_get(int key) {
     std::lock_guard<std::mutex> lk(g_cfg_mu);
-    return key == TH_CFG_TILE_BYTES ? g_tuning.tile_bytes : 0;
+    return key == TH_CFG_TILE_BYTES ? g_tuning.tile_bytes : key == TH_CFG_TILE_BYTES_ANY ? g_tuning.tile_bytes_any : 0;
 }
 
 const char* th_last_error(void) { return g_err; }

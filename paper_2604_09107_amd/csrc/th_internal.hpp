@@ -42,29 +42,35 @@ struct alignas(64) Tile {
     uint64_t dst_stride;
     uint32_t src_buf;  // pack: source tensor id; unpack: chunk index
     uint32_t dst_buf;  // pack: chunk index;      unpack: destination tensor id
-    uint32_t count;  // KIND_VEC: 16-byte vectors in the tile; KIND_ANY: rows in the tile
-    uint32_t ncols;  // KIND_VEC: 16-byte vectors per row; KIND_ANY: elements per row
+    uint32_t count;  // KIND_VEC: 16-byte vectors in the tile; KIND_DENSE: elements; KIND_ANY: rows
+    uint32_t ncols;  // KIND_VEC: 16-byte vectors per row; KIND_DENSE / KIND_ANY: elements per row
     uint32_t flags;  // see below
-    uint32_t magic;  // KIND_VEC: floor(2^32 / ncols) + 1, or 0 when ncols >= the tile's vector capacity
-    uint32_t col0;   // KIND_VEC: column (in vectors) of the tile's first vector within its first row
+    uint32_t magic;  // KIND_VEC / KIND_DENSE: floor(2^32 / ncols) + 1, or 0 when ncols >= the tile's capacity
+    uint32_t col0;   // KIND_VEC / KIND_DENSE: column of the tile's first vector / element within its first row
     uint32_t reserved;
 };
 // A KIND_VEC tile is a run of `count` consecutive vectors of a row-major rectangle whose rows
 // hold `ncols` vectors: it starts at column col0 of the row that src_off / dst_off point to and
-// wraps to the next row (+ stride) after column ncols-1.  A KIND_ANY tile is `count` whole rows
-// (or one piece of a long row) of `ncols` elements.
+// wraps to the next row (+ stride) after column ncols-1.  A KIND_DENSE tile is the same in
+// elements, with the destination contiguous (dst_off is the first element's byte offset, the
+// source wraps).  A KIND_ANY tile is `count` whole rows (or one piece of a long row) of `ncols`
+// elements.
 static_assert(sizeof(Tile) == 64, "tile record is one 64-byte line");
 
 enum : uint32_t {
     TILE_KIND_MASK = 0x3,
     TILE_KIND_VEC = 0,   // every address and the row length are multiples of 16 bytes, no conversion
-    TILE_KIND_ANY = 1,   // element-aligned addresses, optional fp32 -> bf16 narrowing
+    TILE_KIND_ANY = 1,   // element-aligned addresses, optional fp32 -> bf16 narrowing, strided destination
+    TILE_KIND_DENSE = 2, // like ANY, but the destination bytes of the tile are contiguous
     TILE_SRC_F32 = 1u << 2,
     TILE_DST_F32 = 1u << 3,
-    TILE_LG_LANES_SHIFT = 8,  // KIND_ANY: log2 of the threads that share one row (0..8)
+    TILE_LG_LANES_SHIFT = 8,  // KIND_ANY: log2 of the threads that share one row (0..10)
     TILE_LG_LANES_MASK = 0xF << TILE_LG_LANES_SHIFT,
     TILE_PAD_SHIFT = 16,  // zero bytes (0..14) to write after the tile's last element
     TILE_PAD_MASK = 0xF << TILE_PAD_SHIFT,
+    TILE_HEAD_SKIP = 1u << 20,  // KIND_DENSE: not the first tile of its run: the slot straddling the
+                                // tile start is written by the previous tile
+    TILE_TAIL_OK = 1u << 21,    // KIND_DENSE: not the last tile of its run: write the straddling slot whole
 };
 
 #ifndef TH_BLOCK_THREADS
@@ -83,7 +89,8 @@ struct Manifest {
 };
 
 struct Tuning {
-    uint64_t tile_bytes = 16384;  // one 128-bit vector per thread of a workgroup
+    uint64_t tile_bytes = 16384;      // vector path: one 128-bit vector per thread of a workgroup
+    uint64_t tile_bytes_any = 32768;  // any-alignment paths: two destination slots per thread
 };
 Tuning current_tuning();
 

@@ -7,10 +7,13 @@
 //
 //   vector path  every address is a multiple of 16 bytes: 128-bit loads and stores,
 //                kUnroll of them in flight per lane before the first store;
-//   any path     element-aligned addresses and/or fp32 -> bf16 narrowing: the
-//                destination side is cut into aligned 16-byte slots so that all
-//                interior stores are 128-bit; the source side uses unaligned
-//                vector loads; edge slots fall back to per-element accesses.
+//   dense path   element-aligned addresses and/or fp32 -> bf16 narrowing into a
+//                contiguous destination (every wire run of an explicit-segment plan):
+//                each thread owns one aligned 16-byte destination slot and gathers its
+//                elements from the source rows with unaligned vector loads, so every
+//                interior store is 128-bit even when rows are a few elements long;
+//   any path     the same for a strided destination: each destination row is cut into
+//                aligned 16-byte slots; row-edge slots fall back to per-element accesses.
 //
 // The same kernel serves th_pack (tensor -> wire chunk) and th_unpack (wire chunk
 // -> tensor); only which pointer table is indexed by chunk differs.
@@ -58,6 +61,14 @@ __device__ __forceinline__ uint32_t narrow_pair(uint32_t lo, uint32_t hi) {
     return narrow_rne(lo) | (narrow_rne(hi) << 16);
 }
 
+// x / d for the linear position x of a tile element in a rectangle with d units per row.
+// magic != 0: d >= 2 and x * d < 2^32, so multiply-high by floor(2^32 / d) + 1 is exact;
+// magic == 0: d == 1, or d is so large that the positions a tile touches satisfy x < 2 * d.
+__device__ __forceinline__ uint32_t div_rows(uint32_t x, uint32_t d, uint32_t magic) {
+    if (d == 1) return x;
+    return magic ? __umulhi(x, magic) : (x >= d ? 1u : 0u);
+}
+
 // ---- vector path ----------------------------------------------------------------------------
 
 // `count` consecutive vectors of a row-major rectangle with `vpr` vectors per row, starting at
@@ -76,7 +87,7 @@ __device__ __forceinline__ void copy_vec(gsrc_t src, gdst_t dst, uint64_t ss, ui
         for (int u = 0; u < kUnroll; ++u) {
             const uint32_t i = base + u * kBlockThreads + tid;
             const uint32_t x = col0 + i;
-            row[u] = magic ? __umulhi(x, magic) : (x >= vpr ? 1u : 0u);
+            row[u] = div_rows(x, vpr, magic);
             col[u] = x - row[u] * vpr;
             if (i < count) v[u] = ld16(src + (size_t)row[u] * ss + (size_t)col[u] * 16);
         }
@@ -124,6 +135,129 @@ __device__ __forceinline__ void copy_elem(gsrc_t s, gdst_t d) {
         *reinterpret_cast<TH_GLOBAL uint16_t*>(d) = (uint16_t)v;
 }
 
+// Gather up to EPV consecutive elements of a rectangle (rows of nc elements, ss bytes apart)
+// starting at (row, col), converting on the way; element j is fetched iff first <= j < last.
+// All loads are issued before the first use, so a partial slot costs one memory latency.
+template <int SES, int DES>
+__device__ __forceinline__ void gather_slot(gsrc_t src, uint64_t ss, uint32_t nc, uint32_t row, uint32_t col,
+                                            int first, int last, uint32_t (&v)[16 / DES]) {
+    constexpr int EPV = 16 / DES;
+#pragma unroll
+    for (int j = 0; j < EPV; ++j) {
+        v[j] = 0;
+        if (j >= first && j < last) {
+            v[j] = load_elem<SES>(src + (size_t)row * ss + (size_t)col * SES);
+            if (++col == nc) {
+                col = 0;
+                ++row;
+            }
+        }
+    }
+    if (SES == 4 && DES == 2) {
+#pragma unroll
+        for (int j = 0; j < EPV; ++j) v[j] = narrow_rne(v[j]);
+    }
+}
+
+template <int DES>
+__device__ __forceinline__ u32x4 pack_slot(const uint32_t (&v)[16 / DES]) {
+    constexpr int EPV = 16 / DES;
+    u32x4 o;
+    if (DES == 4) {
+        o.x = v[0], o.y = v[1], o.z = v[2], o.w = v[3];
+    } else {
+        o.x = v[0] | (v[1] << 16), o.y = v[2] | (v[3] << 16);
+        o.z = v[4 % EPV] | (v[5 % EPV] << 16), o.w = v[6 % EPV] | (v[7 % EPV] << 16);
+    }
+    return o;
+}
+
+template <int DES>
+__device__ __forceinline__ void store_slot(gdst_t d, const uint32_t (&v)[16 / DES], int first, int last) {
+    constexpr int EPV = 16 / DES;
+    if (first == 0 && last == EPV) {
+        st16(d, pack_slot<DES>(v));
+    } else {
+#pragma unroll
+        for (int j = 0; j < EPV; ++j) {
+            if (j >= first && j < last) {
+                if (DES == 4)
+                    *reinterpret_cast<TH_GLOBAL uint32_t*>(d + j * DES) = v[j];
+                else
+                    *reinterpret_cast<TH_GLOBAL uint16_t*>(d + j * DES) = (uint16_t)v[j];
+            }
+        }
+    }
+}
+
+// Contiguous destination: each thread owns one aligned 16-byte slot of the tile's destination
+// bytes and gathers its elements from the source rectangle, whose rows hold nc elements and lie
+// ss bytes apart; element e of the tile sits at linear position x = col0 + e of that rectangle.
+// A slot that straddles the boundary between two tiles of one run is written whole by the
+// earlier tile (tail_ok) and skipped by the later one (head_skip), so inside a run every store
+// is one 128-bit store whatever the alignment of the base pointer; only a run's first and last
+// slot can be partial.  Division as on the vector path (magic == 0: at most one wrap per tile).
+template <int SES, int DES>
+__device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, uint32_t count, uint32_t nc,
+                                           uint32_t col0, uint32_t magic, bool head_skip, bool tail_ok) {
+    constexpr int EPV = 16 / DES;
+    const uint32_t lead = (uint32_t)(reinterpret_cast<uintptr_t>(dst) & 15u) / DES;
+    const uint32_t nslots = (lead + count + EPV - 1) / EPV;
+    const uint32_t limit = tail_ok ? count + EPV : count;  // elements this tile may write
+    for (uint32_t t = threadIdx.x + ((head_skip && lead) ? 1u : 0u); t < nslots; t += kBlockThreads) {
+        const int32_t e0 = (int32_t)(t * EPV) - (int32_t)lead;
+        const int first = e0 < 0 ? -e0 : 0;
+        const int last = (uint32_t)(e0 + EPV) <= limit ? EPV : (int)(limit - (uint32_t)e0);
+        const uint32_t x = col0 + (uint32_t)(e0 + first);
+        const uint32_t row = div_rows(x, nc, magic);
+        const uint32_t col = x - row * nc;
+        gdst_t d = dst + (ptrdiff_t)e0 * DES;
+        // One store instruction for every full slot of the wavefront, however its elements were
+        // fetched: lanes that take different fetch paths must not write their parts of a cache line
+        // at different times.
+        const bool full = first == 0 && last == EPV;
+        u32x4 o;
+        uint32_t v[EPV];
+        if (full && col + EPV <= nc) {
+            o = load_slot<SES, DES>(src + (size_t)row * ss + (size_t)col * SES);
+        } else {
+            if (full) {
+                // the slot's elements come from two or more rows: branch-free walk, all loads first
+                uint32_t r = row, c = col;
+#pragma unroll
+                for (int j = 0; j < EPV; ++j) {
+                    v[j] = load_elem<SES>(src + (size_t)r * ss + (size_t)c * SES);
+                    const bool wrap = ++c == nc;
+                    c = wrap ? 0u : c;
+                    r += wrap ? 1u : 0u;
+                }
+                if (SES == 4 && DES == 2) {
+#pragma unroll
+                    for (int j = 0; j < EPV; ++j) v[j] = narrow_rne(v[j]);
+                }
+            } else {
+                gather_slot<SES, DES>(src, ss, nc, row, col, first, last, v);
+            }
+            o = pack_slot<DES>(v);
+        }
+        if (full) {
+            st16(d, o);
+        } else {
+            const uint32_t w[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+            for (int j = 0; j < EPV; ++j) {
+                if (j >= first && j < last) {
+                    if (DES == 4)
+                        *reinterpret_cast<TH_GLOBAL uint32_t*>(d + j * DES) = w[j % 4];
+                    else
+                        *reinterpret_cast<TH_GLOBAL uint16_t*>(d + j * DES) = (uint16_t)(w[(j / 2) % 4] >> (16 * (j & 1)));
+                }
+            }
+        }
+    }
+}
+
+// Strided destination: each destination row is cut into aligned 16-byte slots of its own.
 template <int SES, int DES>
 __device__ __forceinline__ void copy_any(gsrc_t src, gdst_t dst, uint64_t ss, uint64_t ds, uint32_t nrows,
                                          uint32_t ncols, uint32_t lg) {
@@ -143,11 +277,11 @@ __device__ __forceinline__ void copy_any(gsrc_t src, gdst_t dst, uint64_t ss, ui
             if (e0 >= 0 && (uint32_t)e0 + EPV <= ncols) {
                 st16(d + (size_t)e0 * DES, load_slot<SES, DES>(s + (size_t)e0 * SES));
             } else {
-#pragma unroll
-                for (int j = 0; j < EPV; ++j) {
-                    const int32_t e = e0 + j;
-                    if (e >= 0 && (uint32_t)e < ncols) copy_elem<SES, DES>(s + (size_t)e * SES, d + (size_t)e * DES);
-                }
+                const int first = e0 < 0 ? -e0 : 0;
+                const int last = (uint32_t)(e0 + EPV) <= ncols ? EPV : (int)(ncols - (uint32_t)e0);
+                uint32_t v[EPV];
+                gather_slot<SES, DES>(s, 0, 0xFFFFFFFFu, 0, (uint32_t)(e0 + first), first, last, v);
+                store_slot<DES>(d + (ptrdiff_t)e0 * DES, v, first, last);
             }
         }
     }
@@ -176,6 +310,25 @@ __global__ __launch_bounds__(kBlockThreads) void th_tiles_kernel(const Tile* __r
 
     if ((flags & TILE_KIND_MASK) == TILE_KIND_VEC) {
         copy_vec(src, dst, ss, ds, t.count, ncols, t.col0, t.magic);
+        return;
+    }
+    if ((flags & TILE_KIND_MASK) == TILE_KIND_DENSE) {
+        const uint32_t count = t.count;
+        const bool head_skip = (flags & TILE_HEAD_SKIP) != 0, tail_ok = (flags & TILE_TAIL_OK) != 0;
+        unsigned des = 2;
+        if (flags & TILE_DST_F32) {
+            copy_dense<4, 4>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok);
+            des = 4;
+        } else if (flags & TILE_SRC_F32) {
+            copy_dense<4, 2>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok);
+        } else {
+            copy_dense<2, 2>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok);
+        }
+        if (PACK) {
+            const uint32_t pad = (flags & TILE_PAD_MASK) >> TILE_PAD_SHIFT;
+            if (threadIdx.x * 2 < pad)
+                *reinterpret_cast<TH_GLOBAL uint16_t*>(dst + (size_t)count * des + threadIdx.x * 2) = 0;
+        }
         return;
     }
     const uint32_t lg = (flags & TILE_LG_LANES_MASK) >> TILE_LG_LANES_SHIFT;

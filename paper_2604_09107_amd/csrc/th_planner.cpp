@@ -28,7 +28,7 @@ struct Side {  // one end of a copy, in bytes
 
 // Append the tiles of one run, seen as a copy S -> D of nrows x ncols elements.
 void tile_run(std::vector<Tile>& out, Side S, Side D, uint64_t nrows, uint64_t ncols, unsigned pad,
-              bool bases_aligned16, uint64_t tile_bytes, bool& used_vec) {
+              bool bases_aligned16, const Tuning& tune, bool& used_vec) {
     // rows that follow each other without a gap on both ends are one long row
     if (nrows > 1 && S.stride == ncols * S.es && D.stride == ncols * D.es) {
         ncols *= nrows;
@@ -37,6 +37,7 @@ void tile_run(std::vector<Tile>& out, Side S, Side D, uint64_t nrows, uint64_t n
     const bool vec = bases_aligned16 && pad == 0 && S.es == D.es && S.off % 16 == 0 && D.off % 16 == 0 &&
                      (ncols * D.es) % 16 == 0 && (nrows == 1 || (S.stride % 16 == 0 && D.stride % 16 == 0));
     used_vec = vec;
+    const uint64_t tile_bytes = vec ? tune.tile_bytes : tune.tile_bytes_any;
     uint32_t flags = vec ? TILE_KIND_VEC : TILE_KIND_ANY;
     if (S.es == 4) flags |= TILE_SRC_F32;
     if (D.es == 4) flags |= TILE_DST_F32;
@@ -63,7 +64,7 @@ void tile_run(std::vector<Tile>& out, Side S, Side D, uint64_t nrows, uint64_t n
             t.dst_buf = D.buf;
             t.count = (uint32_t)std::min(cap, total - v0);
             t.flags = flags;
-            if (nrows == 1 || units >= cap) {
+            if (nrows == 1 || units >= cap || units == 1) {
                 // at most one wrap inside a tile: the kernel compares instead of dividing
                 t.ncols = nrows == 1 ? 0xFFFFFFFFu : (uint32_t)units;
                 t.magic = 0;
@@ -73,6 +74,55 @@ void tile_run(std::vector<Tile>& out, Side S, Side D, uint64_t nrows, uint64_t n
             }
             t.col0 = (uint32_t)col0;
             out.push_back(t);
+        }
+        return;
+    }
+
+    if (nrows == 1 || D.stride == ncols * D.es) {
+        // Dense destination (every wire run of an explicit-segment plan, every one-row run): cut the
+        // destination bytes at 16-byte boundaries so that each thread owns one aligned 16-byte slot
+        // and gathers its elements from the source rows, wrapping at row ends.
+        const uint64_t total = nrows * ncols;          // elements
+        const uint64_t end = D.off + total * D.es;     // bytes
+        // at most 32768 elements per tile keeps the kernel's multiply-high division exact
+        const uint64_t tb = std::min<uint64_t>(tile_bytes, 32768ull * D.es);
+        const uint64_t cap = tb / D.es;                // elements a tile can hold
+        uint64_t pos = D.off;
+        while (pos < end) {
+            // The first tile of a run is one slot short so that, with a base pointer that is not
+            // 16-byte aligned, its partial leading slot still leaves it at most tb / 16 slots.
+            const uint64_t room = (pos == D.off && tb > 16) ? tb - 16 : tb;
+            uint64_t stop = std::min(end, pos / 16 * 16 + room);
+            // a tile that is not the last of its run writes the 16-byte slot straddling its end
+            // whole, so at least 16 more bytes of the run must follow it
+            if (end - stop < 16) stop = end;
+            const uint64_t e0 = (pos - D.off) / D.es;
+            Tile t;
+            std::memset(&t, 0, sizeof t);
+            const uint64_t row0 = nrows == 1 ? 0 : e0 / ncols;
+            const uint64_t col0 = nrows == 1 ? 0 : e0 % ncols;
+            t.src_off = S.off + row0 * S.stride + (nrows == 1 ? e0 * S.es : 0);
+            t.dst_off = pos;
+            t.src_stride = S.stride;
+            t.dst_stride = 0;
+            t.src_buf = S.buf;
+            t.dst_buf = D.buf;
+            t.count = (uint32_t)((stop - pos) / D.es);
+            t.flags = (flags & ~TILE_KIND_MASK) | TILE_KIND_DENSE;
+            if (nrows == 1 || ncols >= cap + 16 || ncols == 1) {
+                // at most one row end inside the elements a tile touches (its own plus one slot)
+                t.ncols = nrows == 1 ? 0xFFFFFFFFu : (uint32_t)ncols;
+                t.magic = 0;
+            } else {
+                t.ncols = (uint32_t)ncols;
+                t.magic = (uint32_t)((1ull << 32) / ncols) + 1;
+            }
+            t.col0 = (uint32_t)col0;
+            if (pos != D.off) t.flags |= TILE_HEAD_SKIP;
+            if (stop != end) t.flags |= TILE_TAIL_OK;
+            if (stop == end && pad) t.flags |= (uint32_t)pad << TILE_PAD_SHIFT;
+            out.push_back(t);
+            pos = stop;
         }
         return;
     }
@@ -90,7 +140,7 @@ void tile_run(std::vector<Tile>& out, Side S, Side D, uint64_t nrows, uint64_t n
         t.ncols = (uint32_t)nu;
         t.flags = flags;
         const uint64_t slots = (nu * D.es + 15) / 16 + 1;  // 16-byte destination slots a row can touch
-        t.flags |= std::min(8u, ceil_log2(slots)) << TILE_LG_LANES_SHIFT;
+        t.flags |= std::min(10u, ceil_log2(slots)) << TILE_LG_LANES_SHIFT;
         if (last && pad) t.flags |= (uint32_t)pad << TILE_PAD_SHIFT;
         out.push_back(t);
     };
@@ -275,8 +325,7 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
                 D = Side{r.dst_tensor, r.dst_byte_off, r.dst_byte_stride, es_w};
             }
             bool vec = false;
-            tile_run(tiles, S, D, r.nrows, r.row_len, side == 0 ? r.pad_bytes : 0, ptrs_aligned16,
-                     tune.tile_bytes, vec);
+            tile_run(tiles, S, D, r.nrows, r.row_len, side == 0 ? r.pad_bytes : 0, ptrs_aligned16, tune, vec);
             TensorInfo& t = side == 0 ? m.tensors[0][r.src_tensor] : m.tensors[1][r.dst_tensor];
             t.used = true;
             t.need16 = t.need16 || vec;

@@ -68,6 +68,10 @@ WORKLOADS = {
         model="moe", seed=4, chunk_bytes=4 * MiB,
         holders=[layout(1, 0, ep_size=8, ep_rank=0)],
         reader=layout(2, 0, experts_stacked=1, f32_store="bf16")),
+    # 100,000 fp32 master tensors (tilted size distribution, ~40 GB), 2-D strided sub-slices in a
+    # random wire order, narrowed to bf16 through 16 MiB chunks into a dense arena
+    "cfg5_scatter_fp32_to_bf16": dict(kind="scatter", n_tensors=100_000, seed=5, chunk_bytes=16 * MiB),
+    "small_scatter": dict(kind="scatter", n_tensors=2_000, seed=15, chunk_bytes=1 * MiB),
     # reduced variants
     "small_dense_tp1_to_tp4": dict(
         model="dense_small", seed=12, chunk_bytes=1 * MiB,
@@ -87,6 +91,10 @@ WORKLOADS = {
 def workload(name):
     w = dict(WORKLOADS[name])
     w["name"] = name
-    w["model_name"] = w["model"]
-    w["model"] = dict(MODELS[w["model"]])
+    w.setdefault("kind", "model")
+    if w["kind"] == "model":
+        w["model_name"] = w["model"]
+        w["model"] = dict(MODELS[w["model"]])
+    else:
+        w["model_name"] = "scattered fp32 tensors"
     return w

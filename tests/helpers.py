@@ -1,6 +1,8 @@
 """Shared test helpers: build oracle-side inputs for a workload and run a plan's
 manifest on the CPU with numpy (a test-only executor of the host planner's
 output; the product path has no CPU route)."""
+import contextlib
+
 import numpy as np
 
 import synth
@@ -83,6 +85,21 @@ def exec_tiles(plan, side, src_bufs, dst_bufs, chunk_range=None):
             left -= n
             row += 1
             col = 0
+
+
+@contextlib.contextmanager
+def tile_sizes(tile_bytes):
+    """Plans created inside the block use `tile_bytes` for every tile kind (None: library defaults)."""
+    import paper_2604_09107_amd as th
+    old = th.th_config_get(th.TH_CFG_TILE_BYTES), th.th_config_get(th.TH_CFG_TILE_BYTES_ANY)
+    try:
+        if tile_bytes:
+            th.th_config_set(th.TH_CFG_TILE_BYTES, tile_bytes)
+            th.th_config_set(th.TH_CFG_TILE_BYTES_ANY, tile_bytes)
+        yield
+    finally:
+        th.th_config_set(th.TH_CFG_TILE_BYTES, old[0])
+        th.th_config_set(th.TH_CFG_TILE_BYTES_ANY, old[1])
 
 
 def flat_u8(arrs):

@@ -10,7 +10,7 @@ import synth
 import paper_2604_09107_amd as th
 from paper_2604_09107_amd import device as dev
 from oracle import layouts, reshard, segments
-from helpers import holder_tensors_cpu
+from helpers import holder_tensors_cpu, tile_sizes
 from test_planner_manifest import scatter_segments
 
 pytestmark = pytest.mark.gpu
@@ -26,13 +26,8 @@ def to_dev(bits2d):
 def run_model_workload(w, pattern, chunk_order=None, tile_bytes=None):
     """Pack every holder's stream and unpack into one reader; returns (got dst bits, want dst bits, mask)."""
     model, dst = w["model"], w["reader"]
-    old = th.th_config_get(th.TH_CFG_TILE_BYTES)
-    if tile_bytes:
-        th.th_config_set(th.TH_CFG_TILE_BYTES, tile_bytes)
-    try:
+    with tile_sizes(tile_bytes):
         plans = [th.th_plan_create(model, src, dst, w["chunk_bytes"]) for src in w["holders"]]
-    finally:
-        th.th_config_set(th.TH_CFG_TILE_BYTES, old)
     dst_dev = dev.alloc_tensors(plans[0], 1, fill_bits=SENT16)
     want = reshard.empty_tensors(model, dst, fill=SENT16)
     for t, wnt in zip(layouts.registered_tensors(model, dst), want):
@@ -206,6 +201,103 @@ def test_same_dtype_any_alignment_and_fp32_passthrough():
         assert np.array_equal(wire_dev.cpu().numpy()[:plan.wire_bytes], wire)
         assert np.array_equal(synth.to_bits(dst_dev), want)
         plan.destroy()
+
+
+@pytest.mark.parametrize("tile_bytes", [4096, 16384])
+@pytest.mark.parametrize("src_dt,dst_dt", [("f32", "bf16"), ("bf16", "bf16"), ("f32", "f32")])
+def test_short_rows_into_dense_destination(src_dt, dst_dt, tile_bytes):
+    """Rows of 1..40 elements gathered into a dense destination: tiles wrap over many row ends,
+    start mid-row, and the destination base is misaligned by 0..14 bytes."""
+    rng = np.random.default_rng(50)
+    S = th.binding.SEGMENT_NP
+    es_d = 2 if dst_dt == "bf16" else 4
+    npd = {"bf16": np.uint16, "f32": np.uint32}
+    n_seg = 120
+    osegs = {k: np.zeros(n_seg, dtype=np.int64) for k in
+             ("src_tensor", "dst_tensor", "src_off", "src_stride", "dst_off", "dst_stride", "nrows", "row_len")}
+    src_len = 1 << 21
+    d_off = 0
+    for k in range(n_seg):
+        row_len = int(rng.integers(1, 41)) if k % 7 else int(rng.integers(8000, 9000))
+        nrows = int(rng.integers(1, 2500)) if row_len < 100 else int(rng.integers(1, 4))
+        s_stride = row_len + int(rng.integers(0, 6))
+        osegs["src_off"][k] = int(rng.integers(0, src_len - nrows * s_stride))
+        osegs["src_stride"][k], osegs["nrows"][k], osegs["row_len"][k] = s_stride, nrows, row_len
+        osegs["dst_off"][k], osegs["dst_stride"][k] = d_off, row_len
+        d_off += nrows * row_len + int(rng.integers(0, 3))
+    dst_len = d_off + 16
+    if src_dt == "f32":
+        src = synth.to_bits(synth.scatter_values(src_len, 51, special_rate=0.1))
+    else:
+        src = rng.integers(0, 1 << 16, size=src_len).astype(np.uint16)
+    wire = segments.pack(osegs, [src], src_dt, dst_dt)
+    sent = 0x7777 if dst_dt == "bf16" else 0x77777777
+    segs = np.zeros(n_seg, dtype=S)
+    segs["src_elem_off"], segs["src_row_stride"] = osegs["src_off"], osegs["src_stride"]
+    segs["dst_elem_off"], segs["dst_row_stride"] = osegs["dst_off"], osegs["dst_stride"]
+    segs["nrows"], segs["row_len"] = osegs["nrows"], osegs["row_len"]
+    segs["src_dtype"] = th.TH_F32 if src_dt == "f32" else th.TH_BF16
+    segs["dst_dtype"] = th.TH_F32 if dst_dt == "f32" else th.TH_BF16
+    with tile_sizes(tile_bytes):
+        plan = th.th_plan_create_from_segments(segs, [src_len], [dst_len], 1 << 20)
+    src_dev = synth.from_bits(src, "cuda")
+    for shift in (0, 1, 3, 7):  # destination base misaligned by shift elements
+        if shift * es_d >= 16:
+            continue
+        want = np.full(dst_len, sent, dtype=npd[dst_dt])
+        segments.unpack(osegs, wire, [want], dst_dt)
+        store = synth.from_bits(np.full(dst_len + 8, sent, dtype=npd[dst_dt]), "cuda")
+        wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=SENT8)
+        th.th_pack(plan, [src_dev.data_ptr()], wptrs, 0, plan.num_chunks, dev.current_stream())
+        th.th_unpack(plan, wptrs, 0, plan.num_chunks, [store.data_ptr() + shift * es_d], dev.current_stream())
+        torch.cuda.synchronize()
+        assert np.array_equal(wire_dev.cpu().numpy()[:plan.wire_bytes], wire)
+        got = synth.to_bits(store)
+        assert np.all(got[:shift] == sent) and np.all(got[shift + dst_len:] == sent)
+        bad = np.nonzero(got[shift:shift + dst_len] != want)[0]
+        assert bad.size == 0, "shift %d: first difference at element %d (%d differ)" % (shift, bad[0], bad.size)
+    plan.destroy()
+
+
+def test_aligned_rows_of_one_to_five_vectors():
+    """Vector path with very short rows (16..80 bytes), strided on both sides."""
+    rng = np.random.default_rng(60)
+    S = th.binding.SEGMENT_NP
+    n_seg = 60
+    osegs = {k: np.zeros(n_seg, dtype=np.int64) for k in
+             ("src_tensor", "dst_tensor", "src_off", "src_stride", "dst_off", "dst_stride", "nrows", "row_len")}
+    src_len = 1 << 21
+    d_off = 0
+    for k in range(n_seg):
+        row_len = 8 * int(rng.integers(1, 6))
+        nrows = int(rng.integers(1, 3000))
+        s_stride = row_len + 8 * int(rng.integers(0, 4))
+        d_stride = row_len + 8 * int(rng.integers(0, 3))
+        osegs["src_off"][k] = 8 * int(rng.integers(0, (src_len - nrows * s_stride) // 8))
+        osegs["src_stride"][k], osegs["nrows"][k], osegs["row_len"][k] = s_stride, nrows, row_len
+        osegs["dst_off"][k], osegs["dst_stride"][k] = d_off, d_stride
+        d_off += nrows * d_stride + 8 * int(rng.integers(0, 3))
+    dst_len = d_off + 16
+    src = rng.integers(0, 1 << 16, size=src_len).astype(np.uint16)
+    wire = segments.pack(osegs, [src], "bf16", "bf16")
+    want = np.full(dst_len, 0x7777, dtype=np.uint16)
+    segments.unpack(osegs, wire, [want], "bf16")
+    segs = np.zeros(n_seg, dtype=S)
+    segs["src_elem_off"], segs["src_row_stride"] = osegs["src_off"], osegs["src_stride"]
+    segs["dst_elem_off"], segs["dst_row_stride"] = osegs["dst_off"], osegs["dst_stride"]
+    segs["nrows"], segs["row_len"] = osegs["nrows"], osegs["row_len"]
+    segs["src_dtype"] = segs["dst_dtype"] = th.TH_BF16
+    plan = th.th_plan_create_from_segments(segs, [src_len], [dst_len], 1 << 20, th.TH_FLAG_PTRS_ALIGNED16)
+    assert all(plan.tile(side, i).kind == 0 for side in (0, 1) for i in range(0, plan.num_tiles(side), 7))
+    src_dev = synth.from_bits(src, "cuda")
+    dst_dev = synth.from_bits(np.full(dst_len, 0x7777, dtype=np.uint16), "cuda")
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=SENT8)
+    th.th_pack(plan, [src_dev.data_ptr()], wptrs, 0, plan.num_chunks, dev.current_stream())
+    th.th_unpack(plan, wptrs, 0, plan.num_chunks, [dst_dev.data_ptr()], dev.current_stream())
+    torch.cuda.synchronize()
+    assert np.array_equal(wire_dev.cpu().numpy()[:plan.wire_bytes], wire)
+    assert np.array_equal(synth.to_bits(dst_dev), want)
+    plan.destroy()
 
 
 def test_argument_errors_are_synchronous_and_nothing_runs():

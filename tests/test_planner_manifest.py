@@ -47,7 +47,9 @@ def test_manifest_reproduces_oracle(name, tile_bytes):
     w = synth.workload(name)
     model, dst = w["model"], w["reader"]
     old = th.th_config_get(th.TH_CFG_TILE_BYTES)
+    old_any = th.th_config_get(th.TH_CFG_TILE_BYTES_ANY)
     th.th_config_set(th.TH_CFG_TILE_BYTES, tile_bytes)
+    th.th_config_set(th.TH_CFG_TILE_BYTES_ANY, tile_bytes)
     try:
         want_dst = reshard.empty_tensors(model, dst, fill=0x5A5A)
         got_runs = reshard.empty_tensors(model, dst, fill=0x5A5A)
@@ -89,6 +91,7 @@ def test_manifest_reproduces_oracle(name, tile_bytes):
             assert np.array_equal(a, x) and np.array_equal(b, x)
     finally:
         th.th_config_set(th.TH_CFG_TILE_BYTES, old)
+        th.th_config_set(th.TH_CFG_TILE_BYTES_ANY, old_any)
 
 
 def test_chunks_are_self_contained():
@@ -142,11 +145,14 @@ def test_explicit_segments_manifest_reproduces_oracle(chunk_bytes, tile_bytes):
     segments.unpack(osegs, wire, [arena], "bf16")
 
     old = th.th_config_get(th.TH_CFG_TILE_BYTES)
+    old_any = th.th_config_get(th.TH_CFG_TILE_BYTES_ANY)
     th.th_config_set(th.TH_CFG_TILE_BYTES, tile_bytes)
+    th.th_config_set(th.TH_CFG_TILE_BYTES_ANY, tile_bytes)
     try:
         plan = th.th_plan_create_from_segments(scatter_segments(d), d["n_elems"], [len(arena)], chunk_bytes, HOST)
     finally:
         th.th_config_set(th.TH_CFG_TILE_BYTES, old)
+        th.th_config_set(th.TH_CFG_TILE_BYTES_ANY, old_any)
     assert plan.wire_bytes == len(wire)
     assert plan.src_read_bytes == 2 * plan.payload_bytes == 4 * d["arena_elems"]
     want_chunks = reshard.chunks(wire, chunk_bytes)
