@@ -137,6 +137,7 @@ def main():
     ap.add_argument("--workload", default="cfg2_8b_tp1_to_tp4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile-bytes", type=int, default=0, help="override the vector-path tile size")
+    ap.add_argument("--no-specialize", action="store_true", help="always launch the all-paths kernel")
     ap.add_argument("--tile-bytes-any", type=int, default=0, help="override the any-alignment tile size")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -153,6 +154,8 @@ def main():
     torch.cuda.set_device(0)
     if args.tile_bytes:
         th.th_config_set(th.TH_CFG_TILE_BYTES, args.tile_bytes)
+    if args.no_specialize:
+        th.th_config_set(th.TH_CFG_SPECIALIZE, 0)
     if args.tile_bytes_any:
         th.th_config_set(th.TH_CFG_TILE_BYTES_ANY, args.tile_bytes_any)
     w = synth.workload(args.workload)

@@ -214,7 +214,9 @@ size_t th_plan_num_runs(const th_plan* plan);
 int th_plan_get_run(const th_plan* plan, size_t i, th_run* out);
 
 /* The device work list, for inspection.  side 0 = th_pack's tiles, 1 =
- * th_unpack's.  Tiles are ordered by chunk; each is one workgroup's share of a
+ * th_unpack's.  A side's list holds first every tile of the 16-byte vector path
+ * (path class 0), then every other tile (class 1), each sub-list ordered by
+ * chunk, so a chunk range is at most two launches.  A tile is one workgroup's share of a
  * run, described as a copy from (src_buf, src_byte_off) to (dst_buf,
  * dst_byte_off).  For side 0 src_buf is a source tensor id and dst_buf a chunk
  * index; for side 1 src_buf is a chunk index and dst_buf a destination tensor
@@ -235,8 +237,9 @@ typedef struct th_tile_info {
 } th_tile_info;
 size_t th_plan_num_tiles(const th_plan* plan, int side);
 int th_plan_get_tile(const th_plan* plan, int side, size_t i, th_tile_info* out);
-/* first tile of `chunk` on `side`; chunk == num_chunks gives the tile count */
-size_t th_plan_chunk_first_tile(const th_plan* plan, int side, uint32_t chunk);
+/* index (into the side's list) of the first tile of `chunk` within sub-list `path_class`;
+ * chunk == num_chunks gives the end of that sub-list */
+size_t th_plan_chunk_first_tile(const th_plan* plan, int side, int path_class, uint32_t chunk);
 
 /* Yardstick, not part of the transfer path: a plain device-to-device copy of
  * nbytes (multiple of 16; dst / src device pointers, 16-byte aligned, not
@@ -250,7 +253,9 @@ int th_reference_copy(void* dst, const void* src, size_t nbytes, void* hip_strea
 enum {
     TH_CFG_TILE_BYTES = 1,    /* destination bytes per tile (one workgroup's share) on the 16-byte
                                  vector path; multiple of 4096 in [4096, 524288]; default 16384 */
-    TH_CFG_TILE_BYTES_ANY = 2 /* same for the any-alignment paths; default 32768 */
+    TH_CFG_TILE_BYTES_ANY = 2, /* same for the any-alignment paths; default 32768 */
+    TH_CFG_SPECIALIZE = 3      /* nonzero (default): vector-path tiles are launched with a kernel that
+                                  contains only that path */
 };
 int th_config_set(int key, uint64_t value);
 uint64_t th_config_get(int key);

@@ -15,6 +15,7 @@ TH_BF16, TH_F32 = 1, 2
 TH_FLAG_HOST_ONLY, TH_FLAG_PTRS_ALIGNED16 = 1, 2
 TH_CFG_TILE_BYTES = 1
 TH_CFG_TILE_BYTES_ANY = 2
+TH_CFG_SPECIALIZE = 3
 TH_MODEL_DENSE, TH_MODEL_MOE = 1, 2
 _DTYPE = {"bf16": TH_BF16, "f32": TH_F32}
 _DTYPE_NAME = {TH_BF16: "bf16", TH_F32: "f32", 0: None}
@@ -109,7 +110,7 @@ _num_runs = _sig("th_plan_num_runs", C.c_size_t, _P)
 _get_run = _sig("th_plan_get_run", C.c_int, _P, C.c_size_t, C.POINTER(Run))
 _num_tiles = _sig("th_plan_num_tiles", C.c_size_t, _P, C.c_int)
 _get_tile = _sig("th_plan_get_tile", C.c_int, _P, C.c_int, C.c_size_t, C.POINTER(TileInfo))
-_chunk_first_tile = _sig("th_plan_chunk_first_tile", C.c_size_t, _P, C.c_int, C.c_uint32)
+_chunk_first_tile = _sig("th_plan_chunk_first_tile", C.c_size_t, _P, C.c_int, C.c_int, C.c_uint32)
 _reference_copy = _sig("th_reference_copy", C.c_int, _P, _P, C.c_size_t, _P)
 _config_set = _sig("th_config_set", C.c_int, C.c_int, C.c_uint64)
 _config_get = _sig("th_config_get", C.c_uint64, C.c_int)
@@ -190,8 +191,8 @@ class Plan:
         _check(_get_tile(self.handle, side, i, C.byref(t)))
         return t
 
-    def chunk_first_tile(self, side, chunk):
-        return _chunk_first_tile(self.handle, side, chunk)
+    def chunk_first_tile(self, side, path_class, chunk):
+        return _chunk_first_tile(self.handle, side, path_class, chunk)
 
     def destroy(self):
         if self._h is not None:

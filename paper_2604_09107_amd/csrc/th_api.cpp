@@ -130,6 +130,7 @@ struct PtrCache {
 struct th_plan {
     th::Manifest m;
     bool host_only = false;
+    bool specialize = true;
     int device = -1;
     th::Tile* d_tiles[2] = {nullptr, nullptr};
     // guarded by mu: pointer-table caches (tensor side per direction, wire side per direction)
@@ -155,7 +156,9 @@ int upload_tables(th_plan* p) {
 }
 
 int finish_plan(th_plan* p, size_t chunk_bytes, unsigned flags, bool aligned16, th_plan** out) {
-    int rc = finish_manifest(p->m, chunk_bytes, aligned16, current_tuning());
+    const Tuning tune = current_tuning();
+    p->specialize = tune.specialize;
+    int rc = finish_manifest(p->m, chunk_bytes, aligned16, tune);
     if (rc == TH_OK) {
         p->host_only = (flags & TH_FLAG_HOST_ONLY) != 0;
         if (!p->host_only) rc = upload_tables(p);
@@ -195,9 +198,12 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
         set_error("null pointer array");
         return TH_ERR_ARG;
     }
-    const uint64_t tile0 = m.chunk_tile0[side][chunk_first];
-    const uint64_t ntiles = m.chunk_tile0[side][chunk_first + chunk_count] - tile0;
-    if (ntiles == 0) return TH_OK;
+    uint64_t tile0[2], ntiles[2];
+    for (int k = 0; k < 2; ++k) {
+        tile0[k] = m.chunk_tile0[side][k][chunk_first];
+        ntiles[k] = m.chunk_tile0[side][k][chunk_first + chunk_count] - tile0[k];
+    }
+    if (ntiles[0] + ntiles[1] == 0) return TH_OK;
 
     std::vector<uintptr_t> tkey(n_tensors), wkey((size_t)chunk_count + 1);
     for (uint32_t i = 0; i < n_tensors; ++i) tkey[i] = reinterpret_cast<uintptr_t>(tensor_ptrs[i]);
@@ -235,13 +241,17 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
     }
     const void* const* wire_tab = reinterpret_cast<const void* const*>(ws->dev + 1);
     const void* const* tens_tab = reinterpret_cast<const void* const*>(ts->dev);
-    int rc;
-    if (side == 0)
-        rc = launch_tiles(true, p->d_tiles[0], tile0, ntiles, tens_tab, const_cast<void* const*>(wire_tab),
-                          chunk_first, stream);
-    else
-        rc = launch_tiles(false, p->d_tiles[1], tile0, ntiles, wire_tab, const_cast<void* const*>(tens_tab),
-                          chunk_first, stream);
+    int rc = TH_OK;
+    for (int k = 0; k < 2 && rc == TH_OK; ++k) {
+        if (!ntiles[k]) continue;
+        const bool vec_only = k == 0 && p->specialize;
+        if (side == 0)
+            rc = launch_tiles(true, vec_only, p->d_tiles[0], tile0[k], ntiles[k], tens_tab,
+                              const_cast<void* const*>(wire_tab), chunk_first, stream);
+        else
+            rc = launch_tiles(false, vec_only, p->d_tiles[1], tile0[k], ntiles[k], wire_tab,
+                              const_cast<void* const*>(tens_tab), chunk_first, stream);
+    }
     if (rc != TH_OK) return rc;
     for (PtrSlot* s : {ts, ws}) {
         hipError_t e = hipEventRecord(s->used, static_cast<hipStream_t>(stream));
@@ -432,9 +442,9 @@ int th_plan_get_tile(const th_plan* p, int side, size_t i, th_tile_info* out) {
     return TH_OK;
 }
 
-size_t th_plan_chunk_first_tile(const th_plan* p, int side, uint32_t chunk) {
-    if (!p || (side != 0 && side != 1) || chunk > p->m.n_chunks) return 0;
-    return (size_t)p->m.chunk_tile0[side][chunk];
+size_t th_plan_chunk_first_tile(const th_plan* p, int side, int path_class, uint32_t chunk) {
+    if (!p || (side != 0 && side != 1) || (path_class != 0 && path_class != 1) || chunk > p->m.n_chunks) return 0;
+    return (size_t)p->m.chunk_tile0[side][path_class][chunk];
 }
 
 int th_reference_copy(void* dst, const void* src, size_t nbytes, void* hip_stream) {
@@ -456,6 +466,9 @@ int th_config_set(int key, uint64_t value) {
             }
             g_tuning.tile_bytes = value;
             return TH_OK;
+        case TH_CFG_SPECIALIZE:
+            g_tuning.specialize = value != 0;
+            return TH_OK;
         case TH_CFG_TILE_BYTES_ANY:
             if (value < 4096 || value > 524288 || value % 4096) {
                 set_error("tile bytes must be a multiple of 4096 in [4096, 524288]");
@@ -470,7 +483,8 @@ int th_config_set(int key, uint64_t value) {
 
 uint64_t th_config_get(int key) {
     std::lock_guard<std::mutex> lk(g_cfg_mu);
-    return key == TH_CFG_TILE_BYTES ? g_tuning.tile_bytes : key == TH_CFG_TILE_BYTES_ANY ? g_tuning.tile_bytes_any : 0;
+    return key == TH_CFG_TILE_BYTES ? g_tuning.tile_bytes : key == TH_CFG_TILE_BYTES_ANY ? g_tuning.tile_bytes_any
+           : key == TH_CFG_SPECIALIZE ? (uint64_t)g_tuning.specialize : 0;
 }
 
 const char* th_last_error(void) { return g_err; }

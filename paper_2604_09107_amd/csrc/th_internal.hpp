@@ -82,8 +82,11 @@ struct Manifest {
     std::vector<TensorInfo> tensors[2];  // 0 = source side, 1 = destination side
     std::vector<Segment> segments;       // wire order
     std::vector<th_run> runs;            // segments cut at chunk boundaries, wire order
-    std::vector<Tile> tiles[2];          // 0 = pack, 1 = unpack; ordered by chunk
-    std::vector<uint64_t> chunk_tile0[2];  // first tile of each chunk (+ total at the end)
+    // Work list per direction (0 = pack, 1 = unpack): first every KIND_VEC tile, then every other
+    // tile, each sub-list ordered by chunk, so that a chunk range is two contiguous tile ranges and
+    // the vector-path range can be launched with the kernel that holds only that path.
+    std::vector<Tile> tiles[2];
+    std::vector<uint64_t> chunk_tile0[2][2];  // [side][class]: first tile of each chunk (+ end of the sub-list)
     uint64_t chunk_bytes = 0, wire_bytes = 0, payload_bytes = 0, src_read_bytes = 0;
     uint32_t n_chunks = 0;
 };
@@ -91,6 +94,7 @@ struct Manifest {
 struct Tuning {
     uint64_t tile_bytes = 16384;      // vector path: one 128-bit vector per thread of a workgroup
     uint64_t tile_bytes_any = 32768;  // any-alignment paths: two destination slots per thread
+    bool specialize = true;           // launch vector-path tiles with the kernel that holds only that path
 };
 Tuning current_tuning();
 
@@ -109,7 +113,8 @@ inline unsigned esize(int dtype) { return dtype == TH_F32 ? 4u : 2u; }
 // ---- device side (th_kernels.hip) ------------------------------------------------------------
 // Launches one kernel over tiles [tile0, tile0 + ntiles) of `tiles` (device pointer).
 // wire_first: chunk index that entry 0 of the wire pointer table stands for.
-int launch_tiles(bool is_pack, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
+// vec_only: every tile of the range is KIND_VEC (selects the kernel without the other paths).
+int launch_tiles(bool is_pack, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first,
                  void* stream);
 

@@ -287,7 +287,7 @@ __device__ __forceinline__ void copy_any(gsrc_t src, gdst_t dst, uint64_t ss, ui
     }
 }
 
-template <bool PACK>
+template <bool PACK, bool VEC_ONLY>
 __global__ __launch_bounds__(kBlockThreads) void th_tiles_kernel(const Tile* __restrict__ tiles,
                                                                   const void* const* __restrict__ src_table,
                                                                   void* const* __restrict__ dst_table,
@@ -308,7 +308,7 @@ __global__ __launch_bounds__(kBlockThreads) void th_tiles_kernel(const Tile* __r
     gsrc_t src = (gsrc_t)(static_cast<const char*>(src_table[sb]) + t.src_off);
     gdst_t dst = (gdst_t)(static_cast<char*>(dst_table[db]) + t.dst_off);
 
-    if ((flags & TILE_KIND_MASK) == TILE_KIND_VEC) {
+    if (VEC_ONLY || (flags & TILE_KIND_MASK) == TILE_KIND_VEC) {
         copy_vec(src, dst, ss, ds, t.count, ncols, t.col0, t.magic);
         return;
     }
@@ -365,18 +365,16 @@ __global__ __launch_bounds__(kBlockThreads) void th_reference_copy_kernel(const 
 
 }  // namespace
 
-int launch_tiles(bool is_pack, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
+int launch_tiles(bool is_pack, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     constexpr uint64_t kMaxGrid = 1u << 30;
+    auto kernel = is_pack ? (vec_only ? th_tiles_kernel<true, true> : th_tiles_kernel<true, false>)
+                          : (vec_only ? th_tiles_kernel<false, true> : th_tiles_kernel<false, false>);
     while (ntiles) {
         const uint64_t n = ntiles < kMaxGrid ? ntiles : kMaxGrid;
-        if (is_pack)
-            hipLaunchKernelGGL(th_tiles_kernel<true>, dim3((uint32_t)n), dim3(kBlockThreads), 0, st,
-                               tiles + tile0, src_table, dst_table, wire_first);
-        else
-            hipLaunchKernelGGL(th_tiles_kernel<false>, dim3((uint32_t)n), dim3(kBlockThreads), 0, st,
-                               tiles + tile0, src_table, dst_table, wire_first);
+        hipLaunchKernelGGL(kernel, dim3((uint32_t)n), dim3(kBlockThreads), 0, st, tiles + tile0, src_table,
+                           dst_table, wire_first);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) {
             set_error("kernel launch failed: %s", hipGetErrorString(e));

@@ -331,12 +331,20 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
             t.need16 = t.need16 || vec;
         }
         auto chunk_of = [side](const Tile& t) { return side == 0 ? t.dst_buf : t.src_buf; };
-        std::stable_sort(tiles.begin(), tiles.end(),
-                         [&](const Tile& a, const Tile& b) { return chunk_of(a) < chunk_of(b); });
-        std::vector<uint64_t>& first = m.chunk_tile0[side];
-        first.assign((size_t)m.n_chunks + 1, 0);
-        for (const Tile& t : tiles) first[chunk_of(t) + 1]++;
-        for (size_t c = 0; c < m.n_chunks; ++c) first[c + 1] += first[c];
+        auto class_of = [](const Tile& t) { return (t.flags & TILE_KIND_MASK) == TILE_KIND_VEC ? 0u : 1u; };
+        std::stable_sort(tiles.begin(), tiles.end(), [&](const Tile& a, const Tile& b) {
+            return class_of(a) != class_of(b) ? class_of(a) < class_of(b) : chunk_of(a) < chunk_of(b);
+        });
+        uint64_t n_class[2] = {0, 0};
+        for (const Tile& t : tiles) n_class[class_of(t)]++;
+        for (unsigned k = 0; k < 2; ++k) {
+            std::vector<uint64_t>& first = m.chunk_tile0[side][k];
+            first.assign((size_t)m.n_chunks + 1, 0);
+            for (const Tile& t : tiles)
+                if (class_of(t) == k) first[chunk_of(t) + 1]++;
+            first[0] = k == 0 ? 0 : n_class[0];
+            for (size_t c = 0; c < m.n_chunks; ++c) first[c + 1] += first[c];
+        }
     }
     return TH_OK;
 }

@@ -68,11 +68,12 @@ def exec_runs_unpack(plan, chunks, dst_flat):
 
 def exec_tiles(plan, side, src_bufs, dst_bufs, chunk_range=None):
     """Run the device work list of one direction on the CPU."""
-    lo, hi = 0, plan.num_tiles(side)
-    if chunk_range is not None:
-        lo = plan.chunk_first_tile(side, chunk_range[0])
-        hi = plan.chunk_first_tile(side, chunk_range[1])
-    for i in range(lo, hi):
+    if chunk_range is None:
+        todo = range(plan.num_tiles(side))
+    else:  # a chunk range is one tile range per path class
+        todo = [i for k in (0, 1) for i in range(plan.chunk_first_tile(side, k, chunk_range[0]),
+                                                 plan.chunk_first_tile(side, k, chunk_range[1]))]
+    for i in todo:
         t = plan.tile(side, i)
         src, dst = src_bufs[t.src_buf], dst_bufs[t.dst_buf]
         left, col, row = int(t.count), int(t.first_col), 0

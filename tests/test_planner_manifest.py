@@ -78,14 +78,19 @@ def test_manifest_reproduces_oracle(name, tile_bytes):
             for c, (g, x) in enumerate(zip(tchunks, want_chunks)):
                 assert np.array_equal(g, x), "tiles: chunk %d" % c
             exec_tiles(plan, 1, tchunks, flat_u8(got_tiles))
-            # tiles are grouped by chunk
+            # tiles: vector-path tiles first, then the others, each sub-list grouped by chunk
             for side in (0, 1):
-                firsts = [plan.chunk_first_tile(side, c) for c in range(plan.num_chunks + 1)]
-                assert firsts[0] == 0 and firsts[-1] == plan.num_tiles(side) and firsts == sorted(firsts)
-                for c in range(plan.num_chunks):
-                    for i in range(firsts[c], firsts[c + 1]):
-                        t = plan.tile(side, i)
-                        assert (t.dst_buf if side == 0 else t.src_buf) == c
+                n = plan.num_chunks
+                f0 = [plan.chunk_first_tile(side, 0, c) for c in range(n + 1)]
+                f1 = [plan.chunk_first_tile(side, 1, c) for c in range(n + 1)]
+                assert f0[0] == 0 and f0[-1] == f1[0] and f1[-1] == plan.num_tiles(side)
+                assert f0 == sorted(f0) and f1 == sorted(f1)
+                for k, firsts in ((0, f0), (1, f1)):
+                    for c in range(n):
+                        for i in range(firsts[c], firsts[c + 1]):
+                            t = plan.tile(side, i)
+                            assert (t.dst_buf if side == 0 else t.src_buf) == c
+                            assert (t.kind == 0) == (k == 0)
             plan.destroy()
         for a, b, x in zip(got_runs, got_tiles, want_dst):
             assert np.array_equal(a, x) and np.array_equal(b, x)
