@@ -18,6 +18,28 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 
+# HBM bytes per launch (FETCH_SIZE + WRITE_SIZE from two rocprofv3 --pmc runs, each scaled by what
+# the counter reads for th_reference_copy of known size; summaries under profiles/).  Valid only for
+# the kernel sources they were taken with: bench.py reports null once those files have changed.
+TRAFFIC_SOURCES = ("th_kernels.hip", "th_planner.cpp", "th_internal.hpp")
+TRAFFIC_SHA256 = "3d568fd7109a1553450de6abf274393100afb992038524e196843de505f0f85c"
+TRAFFIC_BYTES = {
+    "cfg2_8b_tp1_to_tp4": {"th_pack": 8063029000, "th_unpack": 8062360000},
+    "cfg3_70b_tp8_to_tp4": {"th_pack": 35421357000, "th_unpack": 35416100000},
+    "cfg4_moe_ep8_to_tp2": {"th_pack": 5832600000, "th_unpack": 5832200000},
+    "cfg5_scatter_fp32_to_bf16": {"th_pack": 36895500000, "th_unpack": 22646600000},
+}
+
+
+def measured_traffic(workload, kernel):
+    import hashlib
+    h = hashlib.sha256()
+    for f in TRAFFIC_SOURCES:
+        h.update(open(os.path.join(ROOT, "paper_2604_09107_amd", "csrc", f), "rb").read())
+    if h.hexdigest() != TRAFFIC_SHA256:
+        return None
+    return TRAFFIC_BYTES.get(workload, {}).get(kernel)
+
 
 def build_inputs(th, dev, synth, w, torch):
     """Plans, resident source tensors, wire buffers and destination tensors of a model workload."""
@@ -247,7 +269,8 @@ def main():
                     "th_unpack": {"ms": round(unpack_ms, 4), "GB/s": round(k_unpack, 1)}},
         "d2d_copy_GB/s": {"torch_copy_": round(copy_gbps, 1), "th_reference_copy": round(ref_gbps, 1)},
         "roofline": {"bound": "hbm", "kernel": dom[0], "achieved": round(dom[1], 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(dom[1] / HBM_PEAK_GBPS, 4), "traffic": None},
+                     "unit": "GB/s", "frac": round(dom[1] / HBM_PEAK_GBPS, 4),
+                     "traffic": measured_traffic(args.workload, dom[0])},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = (cpu_baseline_scatter if w["kind"] == "scatter" else cpu_baseline)(synth, w, jobs)
