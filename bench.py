@@ -252,6 +252,19 @@ def main():
     ref_gbps = 2 * n16 * 10 / (c0.elapsed_time(c1) * 1e-3) / 1e9
     del a, b
 
+    # co-located variant: th_reshard straight from holder tensors to reader tensors (no wire)
+    direct_bytes = sum(j["plan"].src_read_bytes + j["plan"].payload_bytes for j in jobs)
+    for _ in range(3):
+        for j in jobs:
+            th.th_reshard(j["plan"], j["src_ptrs"], dst_ptrs, stream)
+    c0.record()
+    for _ in range(10):
+        for j in jobs:
+            th.th_reshard(j["plan"], j["src_ptrs"], dst_ptrs, stream)
+    c1.record()
+    torch.cuda.synchronize()
+    direct_ms = c0.elapsed_time(c1) / 10
+
     value = sweep_bytes / (ms_per_step * 1e-3) / 1e9
     out = {
         "metric": "reshard pack+unpack effective HBM GB/s",
@@ -267,6 +280,7 @@ def main():
         "plan_ms": round(plan_ms, 3),
         "kernels": {"th_pack": {"ms": round(pack_ms, 4), "GB/s": round(k_pack, 1)},
                     "th_unpack": {"ms": round(unpack_ms, 4), "GB/s": round(k_unpack, 1)}},
+        "th_reshard_direct": {"ms": round(direct_ms, 4), "GB/s": round(direct_bytes / (direct_ms * 1e-3) / 1e9, 1)},
         "d2d_copy_GB/s": {"torch_copy_": round(copy_gbps, 1), "th_reference_copy": round(ref_gbps, 1)},
         "roofline": {"bound": "hbm", "kernel": dom[0], "achieved": round(dom[1], 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(dom[1] / HBM_PEAK_GBPS, 4),

@@ -178,6 +178,16 @@ int th_pack(const th_plan* plan, const void* const* src_ptrs, uint32_t n_src,
 int th_unpack(const th_plan* plan, const void* const* wire_ptrs, uint32_t chunk_first,
               uint32_t chunk_count, void* const* dst_ptrs, uint32_t n_dst, void* hip_stream);
 
+/* Co-located holder and reader (trainer and rollout time-sharing one GPU, Sec.
+ * 2.1): move what the reader needs straight from the holder's registered tensors
+ * into the reader's, with the same narrowing, without a wire in between - half
+ * the memory traffic of th_pack + th_unpack.  The result is exactly what
+ * th_unpack(th_pack(...)) over all chunks leaves in the destination tensors.
+ * Pointer arrays as for th_pack / th_unpack.  Source and destination tensors must
+ * not overlap. */
+int th_reshard(const th_plan* plan, const void* const* src_ptrs, uint32_t n_src, void* const* dst_ptrs,
+               uint32_t n_dst, void* hip_stream);
+
 /* Free the plan and its device tables.  NULL is accepted.  The caller must
  * have synchronised every stream that still runs work of this plan. */
 int th_plan_destroy(th_plan* plan);
@@ -214,7 +224,8 @@ size_t th_plan_num_runs(const th_plan* plan);
 int th_plan_get_run(const th_plan* plan, size_t i, th_run* out);
 
 /* The device work list, for inspection.  side 0 = th_pack's tiles, 1 =
- * th_unpack's.  A side's list holds first every tile of the 16-byte vector path
+ * th_unpack's, 2 = th_reshard's (src_buf = source tensor id, dst_buf = destination
+ * tensor id; not divided by chunk).  A side's list holds first every tile of the 16-byte vector path
  * (path class 0), then every other tile (class 1), each sub-list ordered by
  * chunk, so a chunk range is at most two launches.  A tile is one workgroup's share of a
  * run, described as a copy from (src_buf, src_byte_off) to (dst_buf,

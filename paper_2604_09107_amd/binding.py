@@ -97,6 +97,7 @@ _plan_create_seg = _sig("th_plan_create_from_segments", C.c_int, _P, C.c_size_t,
                         C.c_size_t, C.c_uint, C.POINTER(_P))
 _pack = _sig("th_pack", C.c_int, _P, _P, C.c_uint32, _P, C.c_uint32, C.c_uint32, _P)
 _unpack = _sig("th_unpack", C.c_int, _P, _P, C.c_uint32, C.c_uint32, _P, C.c_uint32, _P)
+_reshard = _sig("th_reshard", C.c_int, _P, _P, C.c_uint32, _P, C.c_uint32, _P)
 _destroy = _sig("th_plan_destroy", C.c_int, _P)
 _num_chunks = _sig("th_plan_num_chunks", C.c_uint32, _P)
 _chunk_bytes = _sig("th_plan_chunk_bytes", C.c_size_t, _P, C.c_uint32)
@@ -236,6 +237,11 @@ def th_unpack(plan, wire_ptrs, chunk_first, chunk_count, dst_ptrs, stream=0):
     if len(w) != chunk_count:
         raise ValueError("need one wire pointer per chunk in the range")
     _check(_unpack(plan.handle, w.ctypes.data, chunk_first, chunk_count, d.ctypes.data, len(d), stream))
+
+
+def th_reshard(plan, src_ptrs, dst_ptrs, stream=0):
+    s, d = _ptr_array(src_ptrs), _ptr_array(dst_ptrs)
+    _check(_reshard(plan.handle, s.ctypes.data, len(s), d.ctypes.data, len(d), stream))
 
 
 def th_plan_destroy(plan):

@@ -132,7 +132,7 @@ struct th_plan {
     bool host_only = false;
     bool specialize = true;
     int device = -1;
-    th::Tile* d_tiles[2] = {nullptr, nullptr};
+    th::Tile* d_tiles[3] = {nullptr, nullptr, nullptr};
     // guarded by mu: pointer-table caches (tensor side per direction, wire side per direction)
     mutable std::mutex mu;
     mutable th::PtrCache tensor_cache[2], wire_cache[2];
@@ -144,7 +144,7 @@ namespace {
 int upload_tables(th_plan* p) {
     hipError_t e = hipGetDevice(&p->device);
     if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
-    for (int side = 0; side < 2; ++side) {
+    for (int side = 0; side < 3; ++side) {
         const std::vector<Tile>& t = p->m.tiles[side];
         if (t.empty()) continue;
         e = hipMalloc(reinterpret_cast<void**>(&p->d_tiles[side]), t.size() * sizeof(Tile));
@@ -168,6 +168,32 @@ int finish_plan(th_plan* p, size_t chunk_bytes, unsigned flags, bool aligned16, 
         return rc;
     }
     *out = p;
+    return TH_OK;
+}
+
+// Looks up / uploads the device table of the tensor base pointers of one side (0 = source tensors,
+// 1 = destination tensors) and validates a table that was not seen before.  Caller holds p->mu.
+int tensor_table(const th_plan* p, int side, const void* const* ptrs, uint32_t n, PtrSlot** out) {
+    const Manifest& m = p->m;
+    std::vector<uintptr_t> key(n);
+    for (uint32_t i = 0; i < n; ++i) key[i] = reinterpret_cast<uintptr_t>(ptrs[i]);
+    bool fresh = false;
+    PtrSlot* ts = p->tensor_cache[side].get(key, fresh);
+    *out = ts;
+    if (!ts) return TH_ERR_HIP;
+    if (!fresh) return TH_OK;
+    for (uint32_t i = 0; i < n; ++i) {
+        const TensorInfo& t = m.tensors[side][i];
+        if (!t.used) continue;
+        const uintptr_t a = key[i];
+        const uintptr_t need = t.need16 ? 16 : esize(t.dtype);
+        if (a == 0 || a % need) {
+            ts->host.clear();  // do not keep a rejected table
+            set_error("%s tensor %u (%s): pointer %p is %s", side ? "destination" : "source", i, t.name.c_str(),
+                      (void*)a, a ? "misaligned" : "NULL");
+            return TH_ERR_ARG;
+        }
+    }
     return TH_OK;
 }
 
@@ -205,30 +231,14 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
     }
     if (ntiles[0] + ntiles[1] == 0) return TH_OK;
 
-    std::vector<uintptr_t> tkey(n_tensors), wkey((size_t)chunk_count + 1);
-    for (uint32_t i = 0; i < n_tensors; ++i) tkey[i] = reinterpret_cast<uintptr_t>(tensor_ptrs[i]);
+    std::vector<uintptr_t> wkey((size_t)chunk_count + 1);
     wkey[0] = chunk_first;  // entry 0 of the uploaded table is skipped by the kernel's indexing
     for (uint32_t i = 0; i < chunk_count; ++i) wkey[i + 1] = reinterpret_cast<uintptr_t>(wire_ptrs[i]);
 
     std::lock_guard<std::mutex> lk(p->mu);
+    PtrSlot* ts = nullptr;
+    if (int rc = tensor_table(p, side, tensor_ptrs, n_tensors, &ts)) return rc;
     bool fresh = false;
-    PtrSlot* ts = p->tensor_cache[side].get(tkey, fresh);
-    if (!ts) return TH_ERR_HIP;
-    if (fresh) {
-        // validate once per distinct table
-        for (uint32_t i = 0; i < n_tensors; ++i) {
-            const TensorInfo& t = m.tensors[side][i];
-            if (!t.used) continue;
-            const uintptr_t a = tkey[i];
-            const uintptr_t need = t.need16 ? 16 : esize(t.dtype);
-            if (a == 0 || a % need) {
-                ts->host.clear();  // do not keep a rejected table
-                set_error("%s tensor %u (%s): pointer %p is %s", side ? "destination" : "source", i,
-                          t.name.c_str(), (void*)a, a ? "misaligned" : "NULL");
-                return TH_ERR_ARG;
-            }
-        }
-    }
     PtrSlot* ws = p->wire_cache[side].get(wkey, fresh);
     if (!ws) return TH_ERR_HIP;
     if (fresh) {
@@ -246,10 +256,10 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
         if (!ntiles[k]) continue;
         const bool vec_only = k == 0 && p->specialize;
         if (side == 0)
-            rc = launch_tiles(true, vec_only, p->d_tiles[0], tile0[k], ntiles[k], tens_tab,
+            rc = launch_tiles(MODE_PACK, vec_only, p->d_tiles[0], tile0[k], ntiles[k], tens_tab,
                               const_cast<void* const*>(wire_tab), chunk_first, stream);
         else
-            rc = launch_tiles(false, vec_only, p->d_tiles[1], tile0[k], ntiles[k], wire_tab,
+            rc = launch_tiles(MODE_UNPACK, vec_only, p->d_tiles[1], tile0[k], ntiles[k], wire_tab,
                               const_cast<void* const*>(tens_tab), chunk_first, stream);
     }
     if (rc != TH_OK) return rc;
@@ -333,10 +343,54 @@ int th_unpack(const th_plan* plan, const void* const* wire_ptrs, uint32_t chunk_
                     chunk_count, hip_stream);
 }
 
+int th_reshard(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, void* const* dst_ptrs,
+               uint32_t n_dst, void* hip_stream) {
+    if (!p) {
+        set_error("plan is NULL");
+        return TH_ERR_ARG;
+    }
+    if (p->host_only) {
+        set_error("plan was created with TH_FLAG_HOST_ONLY");
+        return TH_ERR_ARG;
+    }
+    const Manifest& m = p->m;
+    if (n_src != m.tensors[0].size() || n_dst != m.tensors[1].size()) {
+        set_error("%u source / %u destination pointers given, plan has %zu / %zu tensors", n_src, n_dst,
+                  m.tensors[0].size(), m.tensors[1].size());
+        return TH_ERR_ARG;
+    }
+    const uint64_t total = m.tiles[2].size();
+    if (total == 0) return TH_OK;
+    if (!src_ptrs || !dst_ptrs) {
+        set_error("null pointer array");
+        return TH_ERR_ARG;
+    }
+    std::lock_guard<std::mutex> lk(p->mu);
+    PtrSlot *ss = nullptr, *ds = nullptr;
+    if (int rc = tensor_table(p, 0, src_ptrs, n_src, &ss)) return rc;
+    if (int rc = tensor_table(p, 1, const_cast<const void* const*>(dst_ptrs), n_dst, &ds)) return rc;
+    const void* const* stab = reinterpret_cast<const void* const*>(ss->dev);
+    void* const* dtab = reinterpret_cast<void* const*>(ds->dev);
+    int rc = TH_OK;
+    if (m.direct_n_vec)
+        rc = launch_tiles(MODE_DIRECT, p->specialize, p->d_tiles[2], 0, m.direct_n_vec, stab, dtab, 0, hip_stream);
+    if (rc == TH_OK && total > m.direct_n_vec)
+        rc = launch_tiles(MODE_DIRECT, false, p->d_tiles[2], m.direct_n_vec, total - m.direct_n_vec, stab, dtab, 0,
+                          hip_stream);
+    if (rc != TH_OK) return rc;
+    for (PtrSlot* s : {ss, ds}) {
+        hipError_t e = hipEventRecord(s->used, static_cast<hipStream_t>(hip_stream));
+        if (e != hipSuccess) return hip_fail(e, "hipEventRecord");
+        s->recorded = true;
+    }
+    return TH_OK;
+}
+
 int th_plan_destroy(th_plan* p) {
     if (!p) return TH_OK;
-    for (int side = 0; side < 2; ++side) {
+    for (int side = 0; side < 3; ++side)
         if (p->d_tiles[side]) (void)hipFree(p->d_tiles[side]);
+    for (int side = 0; side < 2; ++side) {
         p->tensor_cache[side].release();
         p->wire_cache[side].release();
     }
@@ -397,11 +451,11 @@ int th_plan_get_run(const th_plan* p, size_t i, th_run* out) {
 }
 
 size_t th_plan_num_tiles(const th_plan* p, int side) {
-    return (p && (side == 0 || side == 1)) ? p->m.tiles[side].size() : 0;
+    return (p && side >= 0 && side <= 2) ? p->m.tiles[side].size() : 0;
 }
 
 int th_plan_get_tile(const th_plan* p, int side, size_t i, th_tile_info* out) {
-    if (!p || !out || (side != 0 && side != 1)) {
+    if (!p || !out || side < 0 || side > 2) {
         set_error("bad argument");
         return TH_ERR_ARG;
     }

@@ -85,8 +85,9 @@ struct Manifest {
     // Work list per direction (0 = pack, 1 = unpack): first every KIND_VEC tile, then every other
     // tile, each sub-list ordered by chunk, so that a chunk range is two contiguous tile ranges and
     // the vector-path range can be launched with the kernel that holds only that path.
-    std::vector<Tile> tiles[2];
+    std::vector<Tile> tiles[3];               // [2]: direct holder tensor -> reader tensor list (no wire)
     std::vector<uint64_t> chunk_tile0[2][2];  // [side][class]: first tile of each chunk (+ end of the sub-list)
+    uint64_t direct_n_vec = 0;                // KIND_VEC tiles at the front of tiles[2]
     uint64_t chunk_bytes = 0, wire_bytes = 0, payload_bytes = 0, src_read_bytes = 0;
     uint32_t n_chunks = 0;
 };
@@ -112,9 +113,11 @@ inline unsigned esize(int dtype) { return dtype == TH_F32 ? 4u : 2u; }
 
 // ---- device side (th_kernels.hip) ------------------------------------------------------------
 // Launches one kernel over tiles [tile0, tile0 + ntiles) of `tiles` (device pointer).
-// wire_first: chunk index that entry 0 of the wire pointer table stands for.
+// mode: which of the two pointer tables is indexed by chunk (pack: destination, unpack: source,
+// direct: neither).  wire_first: chunk index that entry 0 of the wire pointer table stands for.
 // vec_only: every tile of the range is KIND_VEC (selects the kernel without the other paths).
-int launch_tiles(bool is_pack, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
+enum TileMode { MODE_PACK = 0, MODE_UNPACK = 1, MODE_DIRECT = 2 };
+int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first,
                  void* stream);
 

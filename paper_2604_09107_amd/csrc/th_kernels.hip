@@ -15,8 +15,9 @@
 //   any path     the same for a strided destination: each destination row is cut into
 //                aligned 16-byte slots; row-edge slots fall back to per-element accesses.
 //
-// The same kernel serves th_pack (tensor -> wire chunk) and th_unpack (wire chunk
-// -> tensor); only which pointer table is indexed by chunk differs.
+// The same kernel serves th_pack (tensor -> wire chunk), th_unpack (wire chunk ->
+// tensor) and th_reshard (tensor -> tensor); only which pointer table is indexed by
+// chunk differs.
 #include <hip/hip_runtime.h>
 
 #include "th_internal.hpp"
@@ -328,7 +329,7 @@ __device__ __forceinline__ void copy_any(gsrc_t src, gdst_t dst, uint64_t ss, ui
     }
 }
 
-template <bool PACK, bool VEC_ONLY>
+template <int MODE, bool VEC_ONLY>
 __global__ __launch_bounds__(kBlockThreads) void th_tiles_kernel(const Tile* __restrict__ tiles,
                                                                   const void* const* __restrict__ src_table,
                                                                   void* const* __restrict__ dst_table,
@@ -344,8 +345,9 @@ __global__ __launch_bounds__(kBlockThreads) void th_tiles_kernel(const Tile* __r
     const uint32_t flags = t.flags;
     const uint32_t nrows = t.count, ncols = t.ncols;
     const uint64_t ss = t.src_stride, ds = t.dst_stride;
-    const uint32_t sb = PACK ? t.src_buf : t.src_buf - wire_first;
-    const uint32_t db = PACK ? t.dst_buf - wire_first : t.dst_buf;
+    constexpr bool PACK = MODE == MODE_PACK;
+    const uint32_t sb = MODE == MODE_UNPACK ? t.src_buf - wire_first : t.src_buf;
+    const uint32_t db = MODE == MODE_PACK ? t.dst_buf - wire_first : t.dst_buf;
     gsrc_t src = (gsrc_t)(static_cast<const char*>(src_table[sb]) + t.src_off);
     gdst_t dst = (gdst_t)(static_cast<char*>(dst_table[db]) + t.dst_off);
 
@@ -406,12 +408,16 @@ __global__ __launch_bounds__(kBlockThreads) void th_reference_copy_kernel(const 
 
 }  // namespace
 
-int launch_tiles(bool is_pack, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
+int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     constexpr uint64_t kMaxGrid = 1u << 30;
-    auto kernel = is_pack ? (vec_only ? th_tiles_kernel<true, true> : th_tiles_kernel<true, false>)
-                          : (vec_only ? th_tiles_kernel<false, true> : th_tiles_kernel<false, false>);
+    typedef void (*kernel_t)(const Tile*, const void* const*, void* const*, uint32_t);
+    static const kernel_t kernels[3][2] = {
+        {th_tiles_kernel<MODE_PACK, false>, th_tiles_kernel<MODE_PACK, true>},
+        {th_tiles_kernel<MODE_UNPACK, false>, th_tiles_kernel<MODE_UNPACK, true>},
+        {th_tiles_kernel<MODE_DIRECT, false>, th_tiles_kernel<MODE_DIRECT, true>}};
+    const kernel_t kernel = kernels[mode][vec_only ? 1 : 0];
     while (ntiles) {
         const uint64_t n = ntiles < kMaxGrid ? ntiles : kMaxGrid;
         hipLaunchKernelGGL(kernel, dim3((uint32_t)n), dim3(kBlockThreads), 0, st, tiles + tile0, src_table,

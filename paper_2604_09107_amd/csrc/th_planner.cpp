@@ -346,6 +346,22 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
             for (size_t c = 0; c < m.n_chunks; ++c) first[c + 1] += first[c];
         }
     }
+
+    // ---- direct list: holder tensors -> reader tensors without the wire, one pass over the segments ----
+    {
+        std::vector<Tile>& tiles = m.tiles[2];
+        for (const Segment& g : m.segments) {
+            const unsigned es_s = esize(g.src_dtype), es_d = esize(g.dst_dtype);
+            const Side S{g.src_tensor, g.src_off * es_s, g.src_stride * es_s, es_s};
+            const Side D{g.dst_tensor, g.dst_off * es_d, g.dst_stride * es_d, es_d};
+            bool vec = false;
+            tile_run(tiles, S, D, g.nrows, g.row_len, 0, ptrs_aligned16, tune, vec);
+            if (vec) m.tensors[0][g.src_tensor].need16 = m.tensors[1][g.dst_tensor].need16 = true;
+        }
+        auto is_vec = [](const Tile& t) { return (t.flags & TILE_KIND_MASK) == TILE_KIND_VEC; };
+        std::stable_partition(tiles.begin(), tiles.end(), is_vec);
+        m.direct_n_vec = (uint64_t)std::count_if(tiles.begin(), tiles.end(), is_vec);
+    }
     return TH_OK;
 }
 

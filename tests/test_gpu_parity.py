@@ -300,6 +300,50 @@ def test_aligned_rows_of_one_to_five_vectors():
     plan.destroy()
 
 
+@pytest.mark.parametrize("name", ["cfg1_tiny_tp2_to_tp1", "small_dense_tp1_to_tp4", "small_dense_tp4_to_tp2",
+                                  "small_moe_ep4_to_tp2"])
+def test_direct_reshard_matches_wire_free_definition(name):
+    """th_reshard (no wire) against the oracle's result definition, untouched elements keep the sentinel."""
+    w = synth.workload(name)
+    model, dst = w["model"], w["reader"]
+    tensors = [holder_tensors_cpu(model, src, w["seed"], pattern=True) for src in w["holders"]]
+    want, written = reshard.reshard_by_definition(model, w["holders"], tensors, dst)
+    dst_dev = None
+    for src, ts in zip(w["holders"], tensors):
+        plan = th.th_plan_create(model, src, dst, w["chunk_bytes"])
+        if dst_dev is None:
+            dst_dev = dev.alloc_tensors(plan, 1, fill_bits=SENT16)
+        src_dev = [to_dev(t) for t in ts]
+        th.th_reshard(plan, dev.ptrs(src_dev), dev.ptrs(dst_dev), dev.current_stream())
+        torch.cuda.synchronize()
+        plan.destroy()
+    for g, x, m in zip(dst_dev, want, written):
+        got = synth.to_bits(g)
+        m = m.reshape(-1)
+        assert np.array_equal(got[m], x.reshape(-1)[m])
+        assert np.all(got[~m] == SENT16)
+
+
+def test_direct_reshard_scattered_fp32_to_bf16():
+    d = synth.scatter_description(400, 61, min_bytes=256, max_bytes=1 << 18)
+    pool_dev = synth.scatter_values(d["pool_elems"] + 3, 61, "cuda", 0.05)[1:]
+    pool = synth.to_bits(pool_dev[:d["pool_elems"]])
+    srcs = [pool[o:o + m] for o, m in zip(d["pool_off"], d["n_elems"])]
+    osegs = dict(src_tensor=d["seg_src_tensor"], dst_tensor=np.zeros(400, dtype=np.int64),
+                 src_off=d["seg_src_off"], src_stride=d["seg_src_stride"], dst_off=d["seg_dst_off"],
+                 dst_stride=d["seg_dst_stride"], nrows=d["seg_nrows"], row_len=d["seg_row_len"])
+    want = np.full(d["arena_elems"] + 8, 0x7777, dtype=np.uint16)
+    segments.unpack(osegs, segments.pack(osegs, srcs, "f32", "bf16"), [want], "bf16")
+    plan = th.th_plan_create_from_segments(scatter_segments(d), d["n_elems"], [len(want)], 1 << 20)
+    arena_dev = synth.from_bits(np.full(len(want) + 1, 0x7777, dtype=np.uint16), "cuda")
+    src_ptrs = pool_dev.data_ptr() + d["pool_off"].astype(np.uint64) * np.uint64(4)
+    th.th_reshard(plan, src_ptrs, [arena_dev.data_ptr() + 2], dev.current_stream())
+    torch.cuda.synchronize()
+    got = synth.to_bits(arena_dev)
+    assert got[0] == 0x7777 and np.array_equal(got[1:], want)
+    plan.destroy()
+
+
 def test_argument_errors_are_synchronous_and_nothing_runs():
     w = synth.workload("cfg1_tiny_tp2_to_tp1")
     plan = th.th_plan_create(w["model"], w["holders"][0], w["reader"], w["chunk_bytes"])

@@ -99,6 +99,23 @@ def test_manifest_reproduces_oracle(name, tile_bytes):
         th.th_config_set(th.TH_CFG_TILE_BYTES_ANY, old_any)
 
 
+@pytest.mark.parametrize("name", MODEL_WORKLOADS)
+def test_direct_list_equals_the_wire_free_definition(name):
+    """th_reshard's work list, run on the CPU, gives the oracle's wire-free result definition."""
+    w = synth.workload(name)
+    model, dst = w["model"], w["reader"]
+    tensors = [holder_tensors_cpu(model, src, w["seed"], pattern=True) for src in w["holders"]]
+    want, written = reshard.reshard_by_definition(model, w["holders"], tensors, dst)
+    got = reshard.empty_tensors(model, dst, fill=0)
+    for src, ts in zip(w["holders"], tensors):
+        plan = th.th_plan_create(model, src, dst, w["chunk_bytes"], HOST)
+        assert plan.num_tiles(2) > 0
+        exec_tiles(plan, 2, flat_u8(ts), flat_u8(got))
+        plan.destroy()
+    for g, x in zip(got, want):
+        assert np.array_equal(g, x)
+
+
 def test_chunks_are_self_contained():
     """Unpacking any subset of chunks, in any order, touches only that subset's elements."""
     w = synth.workload("small_dense_tp1_to_tp4")
