@@ -20,4 +20,4 @@ are readings, each listed in the design notes; their pins are mathematical:
 round trips, exactly-once coverage, byte conservation, brute force on tiny
 shapes, agreement with numpy.split, exhaustive RNE checks.
 """
-from . import rne, layouts, reshard, segments  # noqa: F401
+from . import rne, layouts, reshard, segments, checksum  # noqa: F401
