@@ -53,6 +53,7 @@ def build_inputs(th, dev, synth, w, torch):
         t0 = time.perf_counter()
         plan = th.th_plan_create(model, src, dst, w["chunk_bytes"])
         plan_ms += (time.perf_counter() - t0) * 1e3
+        ck_plan = th.th_plan_create(model, src, dst, w["chunk_bytes"], th.TH_FLAG_CHECKSUM)
         regs = layouts.registered_tensors(model, src)
         src_dev = [synth.weight_values(t["rows"] * t["cols"], t["dtype"], w["seed"] * 16 + h, i, "cuda",
                                        is_norm=lts[t["parts"][0][0]]["role"] == "norm")
@@ -60,8 +61,8 @@ def build_inputs(th, dev, synth, w, torch):
         if dst_dev is None:
             dst_dev = dev.alloc_tensors(plan, 1, fill_bits=0)
         wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=0)
-        jobs.append(dict(plan=plan, src=src_dev, src_ptrs=dev.ptrs(src_dev), wire=wire_dev, wptrs=wptrs,
-                         layout=src, regs=regs))
+        jobs.append(dict(plan=plan, ck_plan=ck_plan, src=src_dev, src_ptrs=dev.ptrs(src_dev), wire=wire_dev,
+                         wptrs=wptrs, layout=src, regs=regs))
     return jobs, dst_dev, dev.ptrs(dst_dev), plan_ms
 
 
@@ -118,9 +119,11 @@ def build_scatter_inputs(th, dev, synth, w, torch):
     t0 = time.perf_counter()
     plan = th.th_plan_create_from_segments(segs, d["n_elems"], [d["arena_elems"] + 8], w["chunk_bytes"])
     plan_ms = (time.perf_counter() - t0) * 1e3
+    ck_plan = th.th_plan_create_from_segments(segs, d["n_elems"], [d["arena_elems"] + 8], w["chunk_bytes"],
+                                              th.TH_FLAG_CHECKSUM)
     wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=0)
     src_ptrs = pool.data_ptr() + d["pool_off"].astype(np.uint64) * np.uint64(4)
-    job = dict(plan=plan, src=pool, src_ptrs=src_ptrs, wire=wire_dev, wptrs=wptrs, desc=d, keep=arena_store)
+    job = dict(plan=plan, ck_plan=ck_plan, src=pool, src_ptrs=src_ptrs, wire=wire_dev, wptrs=wptrs, desc=d, keep=arena_store)
     return [job], [arena], np.array([arena.data_ptr()], dtype=np.uint64), plan_ms
 
 
@@ -265,6 +268,29 @@ def main():
     torch.cuda.synchronize()
     direct_ms = c0.elapsed_time(c1) / 10
 
+    # sweep with the per-tensor wire checksums fused into both directions
+    sums = [(torch.zeros(2 * j["plan"].num_tensors(0), dtype=torch.int64, device="cuda"),
+             torch.zeros(2 * j["plan"].num_tensors(0), dtype=torch.int64, device="cuda")) for j in jobs]
+
+    def checksum_step():
+        for j, (ps, us) in zip(jobs, sums):
+            ps.zero_()
+            us.zero_()
+            n = j["ck_plan"].num_chunks
+            th.th_pack_checksum(j["ck_plan"], j["src_ptrs"], j["wptrs"], 0, n, ps.data_ptr(), stream)
+        for j, (ps, us) in zip(jobs, sums):
+            th.th_unpack_checksum(j["ck_plan"], j["wptrs"], 0, j["ck_plan"].num_chunks, dst_ptrs, us.data_ptr(), stream)
+
+    for _ in range(3):
+        checksum_step()
+    c0.record()
+    for _ in range(10):
+        checksum_step()
+    c1.record()
+    torch.cuda.synchronize()
+    checksum_ms = c0.elapsed_time(c1) / 10
+    checksums_agree = all(bool((ps == us).all()) for ps, us in sums)
+
     value = sweep_bytes / (ms_per_step * 1e-3) / 1e9
     out = {
         "metric": "reshard pack+unpack effective HBM GB/s",
@@ -280,6 +306,8 @@ def main():
         "plan_ms": round(plan_ms, 3),
         "kernels": {"th_pack": {"ms": round(pack_ms, 4), "GB/s": round(k_pack, 1)},
                     "th_unpack": {"ms": round(unpack_ms, 4), "GB/s": round(k_unpack, 1)}},
+        "checksum_sweep": {"ms": round(checksum_ms, 4), "GB/s": round(sweep_bytes / (checksum_ms * 1e-3) / 1e9, 1),
+                           "pack_and_unpack_sums_agree": checksums_agree},
         "th_reshard_direct": {"ms": round(direct_ms, 4), "GB/s": round(direct_bytes / (direct_ms * 1e-3) / 1e9, 1)},
         "d2d_copy_GB/s": {"torch_copy_": round(copy_gbps, 1), "th_reference_copy": round(ref_gbps, 1)},
         "roofline": {"bound": "hbm", "kernel": dom[0], "achieved": round(dom[1], 1), "peak": HBM_PEAK_GBPS,

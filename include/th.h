@@ -73,9 +73,13 @@ enum { TH_MODEL_DENSE = 1, TH_MODEL_MOE = 2 };
 /* th_plan_create* flags */
 enum {
     TH_FLAG_HOST_ONLY = 1u << 0,  /* build the manifest only; no device tables, pack/unpack refuse */
-    TH_FLAG_PTRS_ALIGNED16 = 1u << 1 /* th_plan_create_from_segments: caller promises that every
-                                        tensor base pointer is 16-byte aligned (model plans always
-                                        require it) */
+    TH_FLAG_PTRS_ALIGNED16 = 1u << 1, /* th_plan_create_from_segments: caller promises that every
+                                         tensor base pointer is 16-byte aligned (model plans always
+                                         require it) */
+    TH_FLAG_CHECKSUM = 1u << 2        /* allocate what th_pack_checksum / th_unpack_checksum need
+                                         (24 bytes of device memory per tile) and use the larger
+                                         checksum tile size; plain th_pack / th_unpack on such a plan
+                                         work but run a few percent slower */
 };
 
 /* Shape of the model whose weights are transferred (Sec. 2.1: what is resharded).
@@ -178,6 +182,28 @@ int th_pack(const th_plan* plan, const void* const* src_ptrs, uint32_t n_src,
 int th_unpack(const th_plan* plan, const void* const* wire_ptrs, uint32_t chunk_first,
               uint32_t chunk_count, void* const* dst_ptrs, uint32_t n_dst, void* hip_stream);
 
+/* End-to-end checksum fused into the copy (Sec. 4.6: a checksum of each tensor
+ * is attached when it is published and validated after transfer; on the GPU it
+ * can overlap the transfer).  Same as th_pack / th_unpack, and in the same pass
+ * over the data the call adds, for every source tensor t that has bytes in the
+ * chunk range, the terms of those bytes to sums[2t] and sums[2t+1] (device array
+ * of 2 * th_plan_num_tensors(plan, 0) uint64, which the caller zeroes before the
+ * first call of a sweep; calls on chunk ranges that partition the stream add up
+ * to the whole-tensor values).  With h_k the little-endian 16-bit units of the
+ * tensor's run on the wire (its payload bytes, gap excluded; for explicit
+ * segments a run is a maximal sequence of consecutive segments naming the
+ * tensor), sums[2t] = sum h_k and sums[2t+1] = sum (k+1) h_k, both mod 2^64.
+ * th_pack_checksum computes them from what it writes, th_unpack_checksum from
+ * what it reads: equal arrays mean every run arrived intact and in order.
+ * The plan must have been created with TH_FLAG_CHECKSUM.  Concurrent checksum
+ * calls on one plan must not overlap in time (they share per-tile scratch). */
+int th_pack_checksum(const th_plan* plan, const void* const* src_ptrs, uint32_t n_src,
+                     void* const* wire_ptrs, uint32_t chunk_first, uint32_t chunk_count,
+                     uint64_t* sums, void* hip_stream);
+int th_unpack_checksum(const th_plan* plan, const void* const* wire_ptrs, uint32_t chunk_first,
+                       uint32_t chunk_count, void* const* dst_ptrs, uint32_t n_dst, uint64_t* sums,
+                       void* hip_stream);
+
 /* Co-located holder and reader (trainer and rollout time-sharing one GPU, Sec.
  * 2.1): move what the reader needs straight from the holder's registered tensors
  * into the reader's, with the same narrowing, without a wire in between - half
@@ -245,6 +271,10 @@ typedef struct th_tile_info {
                           path with a contiguous destination */
     uint8_t pad_bytes; /* zero bytes written after the tile's last element (pack side) */
     uint8_t reserved[4];
+    uint32_t src_tensor;    /* source tensor whose wire run the tile belongs to */
+    uint32_t reserved2;
+    uint64_t run_unit_base; /* sides 0, 1: 16-bit units between the start of that run and the tile's
+                               wire-side byte offset (the position shift of the tile's checksum terms) */
 } th_tile_info;
 size_t th_plan_num_tiles(const th_plan* plan, int side);
 int th_plan_get_tile(const th_plan* plan, int side, size_t i, th_tile_info* out);
@@ -265,6 +295,8 @@ enum {
     TH_CFG_TILE_BYTES = 1,    /* destination bytes per tile (one workgroup's share) on the 16-byte
                                  vector path; multiple of 4096 in [4096, 524288]; default 16384 */
     TH_CFG_TILE_BYTES_ANY = 2, /* same for the any-alignment paths; default 32768 */
+    TH_CFG_TILE_BYTES_CHECKSUM = 4, /* tile size of both paths in plans created with TH_FLAG_CHECKSUM;
+                                       default 65536 (amortises the per-workgroup reduction) */
     TH_CFG_SPECIALIZE = 3      /* nonzero (default): vector-path tiles are launched with a kernel that
                                   contains only that path */
 };

@@ -12,10 +12,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libtensorhub_reshard.so")
 
 TH_BF16, TH_F32 = 1, 2
-TH_FLAG_HOST_ONLY, TH_FLAG_PTRS_ALIGNED16 = 1, 2
+TH_FLAG_HOST_ONLY, TH_FLAG_PTRS_ALIGNED16, TH_FLAG_CHECKSUM = 1, 2, 4
 TH_CFG_TILE_BYTES = 1
 TH_CFG_TILE_BYTES_ANY = 2
 TH_CFG_SPECIALIZE = 3
+TH_CFG_TILE_BYTES_CHECKSUM = 4
 TH_MODEL_DENSE, TH_MODEL_MOE = 1, 2
 _DTYPE = {"bf16": TH_BF16, "f32": TH_F32}
 _DTYPE_NAME = {TH_BF16: "bf16", TH_F32: "f32", 0: None}
@@ -80,7 +81,8 @@ class TileInfo(C.Structure):
                 ("dst_byte_off", C.c_uint64), ("dst_byte_stride", C.c_uint64),
                 ("first_col", C.c_uint64), ("row_len", C.c_uint64), ("count", C.c_uint64),
                 ("elem_bytes_src", C.c_uint8), ("elem_bytes_dst", C.c_uint8), ("kind", C.c_uint8),
-                ("pad_bytes", C.c_uint8), ("reserved", C.c_uint8 * 4)]
+                ("pad_bytes", C.c_uint8), ("reserved", C.c_uint8 * 4),
+                ("src_tensor", C.c_uint32), ("reserved2", C.c_uint32), ("run_unit_base", C.c_uint64)]
 
 
 def _sig(name, restype, *argtypes):
@@ -97,6 +99,8 @@ _plan_create_seg = _sig("th_plan_create_from_segments", C.c_int, _P, C.c_size_t,
                         C.c_size_t, C.c_uint, C.POINTER(_P))
 _pack = _sig("th_pack", C.c_int, _P, _P, C.c_uint32, _P, C.c_uint32, C.c_uint32, _P)
 _unpack = _sig("th_unpack", C.c_int, _P, _P, C.c_uint32, C.c_uint32, _P, C.c_uint32, _P)
+_pack_sum = _sig("th_pack_checksum", C.c_int, _P, _P, C.c_uint32, _P, C.c_uint32, C.c_uint32, _P, _P)
+_unpack_sum = _sig("th_unpack_checksum", C.c_int, _P, _P, C.c_uint32, C.c_uint32, _P, C.c_uint32, _P, _P)
 _reshard = _sig("th_reshard", C.c_int, _P, _P, C.c_uint32, _P, C.c_uint32, _P)
 _destroy = _sig("th_plan_destroy", C.c_int, _P)
 _num_chunks = _sig("th_plan_num_chunks", C.c_uint32, _P)
@@ -237,6 +241,21 @@ def th_unpack(plan, wire_ptrs, chunk_first, chunk_count, dst_ptrs, stream=0):
     if len(w) != chunk_count:
         raise ValueError("need one wire pointer per chunk in the range")
     _check(_unpack(plan.handle, w.ctypes.data, chunk_first, chunk_count, d.ctypes.data, len(d), stream))
+
+
+def th_pack_checksum(plan, src_ptrs, wire_ptrs, chunk_first, chunk_count, sums_ptr, stream=0):
+    """sums_ptr: device address of 2 * plan.num_tensors(0) uint64, zeroed by the caller before a sweep."""
+    s, w = _ptr_array(src_ptrs), _ptr_array(wire_ptrs)
+    if len(w) != chunk_count:
+        raise ValueError("need one wire pointer per chunk in the range")
+    _check(_pack_sum(plan.handle, s.ctypes.data, len(s), w.ctypes.data, chunk_first, chunk_count, sums_ptr, stream))
+
+
+def th_unpack_checksum(plan, wire_ptrs, chunk_first, chunk_count, dst_ptrs, sums_ptr, stream=0):
+    w, d = _ptr_array(wire_ptrs), _ptr_array(dst_ptrs)
+    if len(w) != chunk_count:
+        raise ValueError("need one wire pointer per chunk in the range")
+    _check(_unpack_sum(plan.handle, w.ctypes.data, chunk_first, chunk_count, d.ctypes.data, len(d), sums_ptr, stream))
 
 
 def th_reshard(plan, src_ptrs, dst_ptrs, stream=0):

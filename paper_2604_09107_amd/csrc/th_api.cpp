@@ -133,6 +133,10 @@ struct th_plan {
     bool specialize = true;
     int device = -1;
     th::Tile* d_tiles[3] = {nullptr, nullptr, nullptr};
+    // checksum support (TH_FLAG_CHECKSUM): per-tile (A, B) pairs and per-tile position bases
+    bool checksum = false;
+    uint64_t* d_partials[2] = {nullptr, nullptr};
+    uint64_t* d_tile_base[2] = {nullptr, nullptr};
     // guarded by mu: pointer-table caches (tensor side per direction, wire side per direction)
     mutable std::mutex mu;
     mutable th::PtrCache tensor_cache[2], wire_cache[2];
@@ -151,16 +155,27 @@ int upload_tables(th_plan* p) {
         if (e != hipSuccess) return hip_fail(e, "hipMalloc(tile table)");
         e = hipMemcpy(p->d_tiles[side], t.data(), t.size() * sizeof(Tile), hipMemcpyHostToDevice);
         if (e != hipSuccess) return hip_fail(e, "hipMemcpy(tile table)");
+        if (p->checksum && side < 2) {
+            e = hipMalloc(reinterpret_cast<void**>(&p->d_partials[side]), t.size() * 2 * sizeof(uint64_t));
+            if (e != hipSuccess) return hip_fail(e, "hipMalloc(checksum partials)");
+            e = hipMalloc(reinterpret_cast<void**>(&p->d_tile_base[side]), t.size() * sizeof(uint64_t));
+            if (e != hipSuccess) return hip_fail(e, "hipMalloc(checksum bases)");
+            e = hipMemcpy(p->d_tile_base[side], p->m.tile_base[side].data(), t.size() * sizeof(uint64_t),
+                          hipMemcpyHostToDevice);
+            if (e != hipSuccess) return hip_fail(e, "hipMemcpy(checksum bases)");
+        }
     }
     return TH_OK;
 }
 
 int finish_plan(th_plan* p, size_t chunk_bytes, unsigned flags, bool aligned16, th_plan** out) {
-    const Tuning tune = current_tuning();
+    Tuning tune = current_tuning();
     p->specialize = tune.specialize;
+    if (flags & TH_FLAG_CHECKSUM) tune.tile_bytes = tune.tile_bytes_any = tune.tile_bytes_checksum;
     int rc = finish_manifest(p->m, chunk_bytes, aligned16, tune);
     if (rc == TH_OK) {
         p->host_only = (flags & TH_FLAG_HOST_ONLY) != 0;
+        p->checksum = (flags & TH_FLAG_CHECKSUM) != 0;
         if (!p->host_only) rc = upload_tables(p);
     }
     if (rc != TH_OK) {
@@ -199,7 +214,8 @@ int tensor_table(const th_plan* p, int side, const void* const* ptrs, uint32_t n
 
 // Shared body of th_pack / th_unpack.  side 0: tensors are the source, wire the destination.
 int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_t n_tensors,
-             const void* const* wire_ptrs, uint32_t chunk_first, uint32_t chunk_count, void* stream) {
+             const void* const* wire_ptrs, uint32_t chunk_first, uint32_t chunk_count, uint64_t* sums,
+             bool want_sums, void* stream) {
     if (!p) {
         set_error("plan is NULL");
         return TH_ERR_ARG;
@@ -209,6 +225,10 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
         return TH_ERR_ARG;
     }
     const Manifest& m = p->m;
+    if (want_sums && (!p->checksum || !sums)) {
+        set_error(sums ? "plan was created without TH_FLAG_CHECKSUM" : "checksum array is NULL");
+        return TH_ERR_ARG;
+    }
     if (n_tensors != m.tensors[side].size()) {
         set_error("%u tensor pointers given, plan has %zu %s tensors", n_tensors, m.tensors[side].size(),
                   side ? "destination" : "source");
@@ -255,12 +275,16 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
     for (int k = 0; k < 2 && rc == TH_OK; ++k) {
         if (!ntiles[k]) continue;
         const bool vec_only = k == 0 && p->specialize;
+        uint64_t* partials = want_sums ? p->d_partials[side] : nullptr;
         if (side == 0)
             rc = launch_tiles(MODE_PACK, vec_only, p->d_tiles[0], tile0[k], ntiles[k], tens_tab,
-                              const_cast<void* const*>(wire_tab), chunk_first, stream);
+                              const_cast<void* const*>(wire_tab), chunk_first, partials, stream);
         else
             rc = launch_tiles(MODE_UNPACK, vec_only, p->d_tiles[1], tile0[k], ntiles[k], wire_tab,
-                              const_cast<void* const*>(tens_tab), chunk_first, stream);
+                              const_cast<void* const*>(tens_tab), chunk_first, partials, stream);
+        if (rc == TH_OK && want_sums)
+            rc = launch_checksum_finalize(p->d_tiles[side], p->d_partials[side], p->d_tile_base[side], tile0[k],
+                                          ntiles[k], sums, stream);
     }
     if (rc != TH_OK) return rc;
     for (PtrSlot* s : {ts, ws}) {
@@ -334,13 +358,26 @@ int th_plan_create_from_segments(const th_segment* segs, size_t n, const uint64_
 int th_pack(const th_plan* plan, const void* const* src_ptrs, uint32_t n_src, void* const* wire_ptrs,
             uint32_t chunk_first, uint32_t chunk_count, void* hip_stream) {
     return run_side(plan, 0, src_ptrs, n_src, const_cast<const void* const*>(wire_ptrs), chunk_first,
-                    chunk_count, hip_stream);
+                    chunk_count, nullptr, false, hip_stream);
+}
+
+int th_pack_checksum(const th_plan* plan, const void* const* src_ptrs, uint32_t n_src, void* const* wire_ptrs,
+                     uint32_t chunk_first, uint32_t chunk_count, uint64_t* sums, void* hip_stream) {
+    return run_side(plan, 0, src_ptrs, n_src, const_cast<const void* const*>(wire_ptrs), chunk_first,
+                    chunk_count, sums, true, hip_stream);
+}
+
+int th_unpack_checksum(const th_plan* plan, const void* const* wire_ptrs, uint32_t chunk_first,
+                       uint32_t chunk_count, void* const* dst_ptrs, uint32_t n_dst, uint64_t* sums,
+                       void* hip_stream) {
+    return run_side(plan, 1, const_cast<const void* const*>(dst_ptrs), n_dst, wire_ptrs, chunk_first,
+                    chunk_count, sums, true, hip_stream);
 }
 
 int th_unpack(const th_plan* plan, const void* const* wire_ptrs, uint32_t chunk_first, uint32_t chunk_count,
               void* const* dst_ptrs, uint32_t n_dst, void* hip_stream) {
     return run_side(plan, 1, const_cast<const void* const*>(dst_ptrs), n_dst, wire_ptrs, chunk_first,
-                    chunk_count, hip_stream);
+                    chunk_count, nullptr, false, hip_stream);
 }
 
 int th_reshard(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, void* const* dst_ptrs,
@@ -373,10 +410,11 @@ int th_reshard(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, vo
     void* const* dtab = reinterpret_cast<void* const*>(ds->dev);
     int rc = TH_OK;
     if (m.direct_n_vec)
-        rc = launch_tiles(MODE_DIRECT, p->specialize, p->d_tiles[2], 0, m.direct_n_vec, stab, dtab, 0, hip_stream);
+        rc = launch_tiles(MODE_DIRECT, p->specialize, p->d_tiles[2], 0, m.direct_n_vec, stab, dtab, 0, nullptr,
+                          hip_stream);
     if (rc == TH_OK && total > m.direct_n_vec)
         rc = launch_tiles(MODE_DIRECT, false, p->d_tiles[2], m.direct_n_vec, total - m.direct_n_vec, stab, dtab, 0,
-                          hip_stream);
+                          nullptr, hip_stream);
     if (rc != TH_OK) return rc;
     for (PtrSlot* s : {ss, ds}) {
         hipError_t e = hipEventRecord(s->used, static_cast<hipStream_t>(hip_stream));
@@ -390,6 +428,10 @@ int th_plan_destroy(th_plan* p) {
     if (!p) return TH_OK;
     for (int side = 0; side < 3; ++side)
         if (p->d_tiles[side]) (void)hipFree(p->d_tiles[side]);
+    for (int side = 0; side < 2; ++side) {
+        if (p->d_partials[side]) (void)hipFree(p->d_partials[side]);
+        if (p->d_tile_base[side]) (void)hipFree(p->d_tile_base[side]);
+    }
     for (int side = 0; side < 2; ++side) {
         p->tensor_cache[side].release();
         p->wire_cache[side].release();
@@ -492,6 +534,8 @@ int th_plan_get_tile(const th_plan* p, int side, size_t i, th_tile_info* out) {
         out->count = (uint64_t)t.count * t.ncols;
     }
     out->kind = (uint8_t)(t.flags & TILE_KIND_MASK);
+    out->src_tensor = t.src_tensor;
+    out->run_unit_base = side < 2 ? p->m.tile_base[side][i] : 0;
     out->pad_bytes = (uint8_t)((t.flags & TILE_PAD_MASK) >> TILE_PAD_SHIFT);
     return TH_OK;
 }
@@ -523,6 +567,13 @@ int th_config_set(int key, uint64_t value) {
         case TH_CFG_SPECIALIZE:
             g_tuning.specialize = value != 0;
             return TH_OK;
+        case TH_CFG_TILE_BYTES_CHECKSUM:
+            if (value < 4096 || value > 524288 || value % 4096) {
+                set_error("tile bytes must be a multiple of 4096 in [4096, 524288]");
+                return TH_ERR_ARG;
+            }
+            g_tuning.tile_bytes_checksum = value;
+            return TH_OK;
         case TH_CFG_TILE_BYTES_ANY:
             if (value < 4096 || value > 524288 || value % 4096) {
                 set_error("tile bytes must be a multiple of 4096 in [4096, 524288]");
@@ -538,7 +589,8 @@ int th_config_set(int key, uint64_t value) {
 uint64_t th_config_get(int key) {
     std::lock_guard<std::mutex> lk(g_cfg_mu);
     return key == TH_CFG_TILE_BYTES ? g_tuning.tile_bytes : key == TH_CFG_TILE_BYTES_ANY ? g_tuning.tile_bytes_any
-           : key == TH_CFG_SPECIALIZE ? (uint64_t)g_tuning.specialize : 0;
+           : key == TH_CFG_SPECIALIZE ? (uint64_t)g_tuning.specialize
+           : key == TH_CFG_TILE_BYTES_CHECKSUM ? g_tuning.tile_bytes_checksum : 0;
 }
 
 const char* th_last_error(void) { return g_err; }

@@ -31,6 +31,7 @@ struct Segment {
     uint64_t wire_off = 0, wire_stride = 0;  // bytes
     uint8_t src_dtype = 0, dst_dtype = 0;
     uint8_t pad_after = 0;  // zero bytes after the segment's last element (wire alignment gap)
+    uint64_t run_start = 0;  // wire byte offset where the run of this segment's source tensor begins
 };
 
 // 64-byte device record: one workgroup's share of a pack or unpack launch.
@@ -47,7 +48,7 @@ struct alignas(64) Tile {
     uint32_t flags;  // see below
     uint32_t magic;  // KIND_VEC / KIND_DENSE: floor(2^32 / ncols) + 1, or 0 when ncols >= the tile's capacity
     uint32_t col0;   // KIND_VEC / KIND_DENSE: column of the tile's first vector / element within its first row
-    uint32_t reserved;
+    uint32_t src_tensor;  // source tensor whose wire run the tile belongs to (checksums)
 };
 // A KIND_VEC tile is a run of `count` consecutive vectors of a row-major rectangle whose rows
 // hold `ncols` vectors: it starts at column col0 of the row that src_off / dst_off point to and
@@ -88,6 +89,10 @@ struct Manifest {
     std::vector<Tile> tiles[3];               // [2]: direct holder tensor -> reader tensor list (no wire)
     std::vector<uint64_t> chunk_tile0[2][2];  // [side][class]: first tile of each chunk (+ end of the sub-list)
     uint64_t direct_n_vec = 0;                // KIND_VEC tiles at the front of tiles[2]
+    std::vector<uint64_t> run_starts;         // per run: Segment::run_start of the segment it was cut from
+    // per pack / unpack tile: 16-bit units between the start of its tensor's wire run and the tile's
+    // wire-side base offset (what a tile-local checksum position has to be shifted by)
+    std::vector<uint64_t> tile_base[2];
     uint64_t chunk_bytes = 0, wire_bytes = 0, payload_bytes = 0, src_read_bytes = 0;
     uint32_t n_chunks = 0;
 };
@@ -95,6 +100,7 @@ struct Manifest {
 struct Tuning {
     uint64_t tile_bytes = 16384;      // vector path: one 128-bit vector per thread of a workgroup
     uint64_t tile_bytes_any = 32768;  // any-alignment paths: two destination slots per thread
+    uint64_t tile_bytes_checksum = 65536;  // both paths in plans with checksums: amortises the workgroup reduction
     bool specialize = true;           // launch vector-path tiles with the kernel that holds only that path
 };
 Tuning current_tuning();
@@ -117,9 +123,14 @@ inline unsigned esize(int dtype) { return dtype == TH_F32 ? 4u : 2u; }
 // direct: neither).  wire_first: chunk index that entry 0 of the wire pointer table stands for.
 // vec_only: every tile of the range is KIND_VEC (selects the kernel without the other paths).
 enum TileMode { MODE_PACK = 0, MODE_UNPACK = 1, MODE_DIRECT = 2 };
+// partials: nullptr, or device array of 2 x uint64 per tile of `tiles` (same indexing) that receives
+// each tile's checksum terms (A, B with tile-local positions).
 int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first,
-                 void* stream);
+                 uint64_t* partials, void* stream);
+// Adds the per-tile terms of tiles [tile0, tile0 + ntiles) into sums[2 * src_tensor + {0, 1}].
+int launch_checksum_finalize(const Tile* tiles, const uint64_t* partials, const uint64_t* tile_base,
+                             uint64_t tile0, uint64_t ntiles, uint64_t* sums, void* stream);
 
 int launch_reference_copy(void* dst, const void* src, uint64_t nbytes, void* stream);
 

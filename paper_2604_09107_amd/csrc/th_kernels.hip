@@ -70,6 +70,98 @@ __device__ __forceinline__ uint32_t div_rows(uint32_t x, uint32_t d, uint32_t ma
     return magic ? __umulhi(x, magic) : (x >= d ? 1u : 0u);
 }
 
+// ---- checksum terms ----------------------------------------------------------------------------
+//
+// Optional per-tensor checksum of the wire (the paper's end-to-end checksum, computed on the GPU
+// while the data moves): over the 16-bit units h_k of a tensor's run on the wire, A = sum h_k and
+// B = sum (k + 1) h_k, both mod 2^64.  Every term depends only on (position, value), so each
+// thread adds the terms of what it moved, with positions counted from the tile's wire-side base;
+// a workgroup writes one (A, B) pair per tile and a small second kernel shifts the pairs to
+// run-relative positions and adds them up per tensor.
+// SUM = 0: off; 1: the wire is the destination (pack); 2: the wire is the source (unpack).
+
+struct Sum {
+    uint32_t a = 0;  // < 2^29 per workgroup for tiles of up to 512 KiB
+    uint64_t b = 0;
+};
+
+// Terms of the 16-bit halves [h0, h1) of the 16 bytes `o`; half 0 sits `pos` units after the tile's
+// wire base (pos < 0 is possible for a slot whose leading halves are not part of the tile).
+// Two-way 16-bit dot products give sum h_i and sum i * h_i in two instructions per dword.
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void sum_halves(Sum& s, u32x4 o, int h0, int h1, int64_t pos) {
+    const uint32_t w[4] = {o.x, o.y, o.z, o.w};
+    uint32_t t = 0, wt = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t keep = ((2 * j >= h0 && 2 * j < h1) ? 0x0000FFFFu : 0u) |
+                              ((2 * j + 1 >= h0 && 2 * j + 1 < h1) ? 0xFFFF0000u : 0u);
+        const u16x2 h = __builtin_bit_cast(u16x2, w[j] & keep);
+        const u16x2 ones = {1, 1};
+        const u16x2 idx = {(unsigned short)(2 * j), (unsigned short)(2 * j + 1)};
+        t = __builtin_amdgcn_udot2(h, ones, t, false);
+        wt = __builtin_amdgcn_udot2(h, idx, wt, false);
+    }
+    s.a += t;
+    s.b += (uint64_t)(pos + 1) * t + wt;
+}
+
+// Terms of one element of ES bytes that sits rel bytes after the tile's wire base.
+template <int ES>
+__device__ __forceinline__ void sum_elem(Sum& s, uint32_t v, uint64_t rel) {
+    const uint64_t k = rel / 2 + 1;
+    const uint32_t lo = v & 0xFFFFu;
+    s.a += lo;
+    s.b += k * lo;
+    if (ES == 4) {
+        const uint32_t hi = v >> 16;
+        s.a += hi;
+        s.b += (k + 1) * hi;
+    }
+}
+
+// Sum of v over the 64 lanes of a wavefront with DPP moves only (no LDS traffic); the total is
+// valid in lane 63.  quad_perm swaps, then row_shr:4, row_shr:8 leave each row's sum in its last
+// lane; row_bcast:15 / row_bcast:31 carry it across the four rows.  Lanes without a source read 0.
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, false);  // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, false);  // row_shr:8
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);  // row_bcast:15
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);  // row_bcast:31
+    return v;
+}
+
+// Workgroup total of the per-thread terms -> out[0..1].  Every thread of the workgroup calls it.
+// The 64-bit B is reduced as three limbs of 21 + 21 + 22 bits so that a wavefront's limb sums fit
+// 32 bits; A is below 2^24 per thread (at most 32 slots of 8 halves).  One thread adds the
+// wavefronts' results in 64-bit arithmetic.
+__device__ __forceinline__ void block_sum_store(const Sum& s, uint64_t* out) {
+    constexpr uint32_t kWaves = kBlockThreads / 64;
+    __shared__ uint32_t part[4 * kWaves];
+    const uint32_t a = wave_sum_u32(s.a);
+    const uint32_t b0 = wave_sum_u32((uint32_t)(s.b & 0x1FFFFFu));
+    const uint32_t b1 = wave_sum_u32((uint32_t)((s.b >> 21) & 0x1FFFFFu));
+    const uint32_t b2 = wave_sum_u32((uint32_t)(s.b >> 42));
+    const uint32_t tid = threadIdx.x;
+    if ((tid & 63) == 63) {
+        uint32_t* p = part + 4 * (tid >> 6);
+        p[0] = a, p[1] = b0, p[2] = b1, p[3] = b2;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        uint64_t ta = 0, tb = 0;
+#pragma unroll
+        for (uint32_t w = 0; w < kWaves; ++w) {
+            ta += part[4 * w];
+            tb += (uint64_t)part[4 * w + 1] + ((uint64_t)part[4 * w + 2] << 21) + ((uint64_t)part[4 * w + 3] << 42);
+        }
+        out[0] = ta;
+        out[1] = tb;
+    }
+}
+
 // ---- vector path ----------------------------------------------------------------------------
 
 // `count` consecutive vectors of a row-major rectangle with `vpr` vectors per row, starting at
@@ -77,8 +169,9 @@ __device__ __forceinline__ uint32_t div_rows(uint32_t x, uint32_t d, uint32_t ma
 // x = col0 + i: row x / vpr, column x % vpr.  magic != 0: vpr < 2^15 and x < 2^16, so the
 // multiply-high division is exact; magic == 0: vpr is at least the tile's capacity, so x < 2*vpr
 // and the quotient is 0 or 1.
+template <int SUM>
 __device__ __forceinline__ void copy_vec(gsrc_t src, gdst_t dst, uint64_t ss, uint64_t ds, uint32_t count,
-                                         uint32_t vpr, uint32_t col0, uint32_t magic) {
+                                         uint32_t vpr, uint32_t col0, uint32_t magic, Sum& acc) {
     const uint32_t tid = threadIdx.x;
     constexpr uint32_t kStep = kBlockThreads * kUnroll;
     for (uint32_t base = 0; base < count; base += kStep) {
@@ -95,12 +188,18 @@ __device__ __forceinline__ void copy_vec(gsrc_t src, gdst_t dst, uint64_t ss, ui
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const uint32_t i = base + u * kBlockThreads + tid;
-            if (i < count) st16(dst + (size_t)row[u] * ds + (size_t)col[u] * 16, v[u]);
+            if (i < count) {
+                st16(dst + (size_t)row[u] * ds + (size_t)col[u] * 16, v[u]);
+                if (SUM) {
+                    const uint64_t rel = (uint64_t)row[u] * (SUM == 1 ? ds : ss) + (uint64_t)col[u] * 16;
+                    sum_halves(acc, v[u], 0, 8, (int64_t)(rel / 2));
+                }
+            }
         }
     }
 }
 
-// ---- any-alignment path -------------------------------------------------------------------------
+// ---- any-alignment paths ------------------------------------------------------------------------
 
 template <int SES>
 __device__ __forceinline__ uint32_t load_elem(gsrc_t p) {
@@ -108,7 +207,7 @@ __device__ __forceinline__ uint32_t load_elem(gsrc_t p) {
     return *reinterpret_cast<const TH_GLOBAL uint16_t*>(p);
 }
 
-// One 16-byte destination slot from element-aligned source data.
+// One 16-byte destination slot from element-aligned, contiguous source data.
 template <int SES, int DES>
 __device__ __forceinline__ u32x4 load_slot(gsrc_t s) {
     if (SES == DES) {
@@ -138,40 +237,6 @@ __device__ __forceinline__ u32x4 load_slot(gsrc_t s) {
     }
 }
 
-template <int SES, int DES>
-__device__ __forceinline__ void copy_elem(gsrc_t s, gdst_t d) {
-    uint32_t v = load_elem<SES>(s);
-    if (SES == 4 && DES == 2) v = narrow_rne(v);
-    if (DES == 4)
-        *reinterpret_cast<TH_GLOBAL uint32_t*>(d) = v;
-    else
-        *reinterpret_cast<TH_GLOBAL uint16_t*>(d) = (uint16_t)v;
-}
-
-// Gather up to EPV consecutive elements of a rectangle (rows of nc elements, ss bytes apart)
-// starting at (row, col), converting on the way; element j is fetched iff first <= j < last.
-// All loads are issued before the first use, so a partial slot costs one memory latency.
-template <int SES, int DES>
-__device__ __forceinline__ void gather_slot(gsrc_t src, uint64_t ss, uint32_t nc, uint32_t row, uint32_t col,
-                                            int first, int last, uint32_t (&v)[16 / DES]) {
-    constexpr int EPV = 16 / DES;
-#pragma unroll
-    for (int j = 0; j < EPV; ++j) {
-        v[j] = 0;
-        if (j >= first && j < last) {
-            v[j] = load_elem<SES>(src + (size_t)row * ss + (size_t)col * SES);
-            if (++col == nc) {
-                col = 0;
-                ++row;
-            }
-        }
-    }
-    if (SES == 4 && DES == 2) {
-#pragma unroll
-        for (int j = 0; j < EPV; ++j) v[j] = narrow_rne(v[j]);
-    }
-}
-
 template <int DES>
 __device__ __forceinline__ u32x4 pack_slot(const uint32_t (&v)[16 / DES]) {
     constexpr int EPV = 16 / DES;
@@ -185,83 +250,50 @@ __device__ __forceinline__ u32x4 pack_slot(const uint32_t (&v)[16 / DES]) {
     return o;
 }
 
-template <int DES>
-__device__ __forceinline__ void store_slot(gdst_t d, const uint32_t (&v)[16 / DES], int first, int last) {
-    constexpr int EPV = 16 / DES;
-    if (first == 0 && last == EPV) {
-        st16(d, pack_slot<DES>(v));
-    } else {
-#pragma unroll
-        for (int j = 0; j < EPV; ++j) {
-            if (j >= first && j < last) {
-                if (DES == 4)
-                    *reinterpret_cast<TH_GLOBAL uint32_t*>(d + j * DES) = v[j];
-                else
-                    *reinterpret_cast<TH_GLOBAL uint16_t*>(d + j * DES) = (uint16_t)v[j];
-            }
-        }
-    }
-}
-
-// Contiguous destination: each thread owns one aligned 16-byte slot of the tile's destination
-// bytes and gathers its elements from the source rectangle, whose rows hold nc elements and lie
-// ss bytes apart; element e of the tile sits at linear position x = col0 + e of that rectangle.
-// A slot that straddles the boundary between two tiles of one run is written whole by the
-// earlier tile (tail_ok) and skipped by the later one (head_skip), so inside a run every store
-// is one 128-bit store whatever the alignment of the base pointer; only a run's first and last
-// slot can be partial.  Division as on the vector path (magic == 0: at most one wrap per tile).
+// A destination slot: 16 bytes, the aligned address they go to, and which of its elements
+// [first, last) belong to the copy (the others are zero and must not be written).
 template <int DES>
 struct Slot {
-    u32x4 o;       // the slot's 16 bytes (elements outside [first, last) are zero)
-    gdst_t d;      // its aligned destination address
+    u32x4 o;
+    gdst_t d;
     int first, last;
 };
 
-template <int SES, int DES>
-__device__ __forceinline__ Slot<DES> fetch_slot(gsrc_t src, gdst_t dst, uint64_t ss, uint32_t nc, uint32_t col0,
-                                                uint32_t magic, uint32_t lead, uint32_t limit, uint32_t t) {
+// Gather the elements [first, last) of a slot from a rectangle (rows of nc elements, ss bytes
+// apart), starting at (row, col) and walking over row ends, converting on the way.  All loads are
+// issued before the first use, so a slot costs one memory latency.  FULL: first = 0, last = EPV.
+template <int SES, int DES, int SUM, bool FULL>
+__device__ __forceinline__ u32x4 gather_slot(gsrc_t src, uint64_t ss, uint32_t nc, uint32_t row, uint32_t col,
+                                             int first, int last, Sum& acc) {
     constexpr int EPV = 16 / DES;
-    Slot<DES> s;
-    const int32_t e0 = (int32_t)(t * EPV) - (int32_t)lead;
-    s.first = e0 < 0 ? -e0 : 0;
-    s.last = (uint32_t)(e0 + EPV) <= limit ? EPV : (int)(limit - (uint32_t)e0);
-    s.d = dst + (ptrdiff_t)e0 * DES;
-    const uint32_t x = col0 + (uint32_t)(e0 + s.first);
-    const uint32_t row = div_rows(x, nc, magic);
-    const uint32_t col = x - row * nc;
-    const bool full = s.first == 0 && s.last == EPV;
-    if (full && col + EPV <= nc) {
-        s.o = load_slot<SES, DES>(src + (size_t)row * ss + (size_t)col * SES);
-    } else {
-        uint32_t v[EPV];
-        if (full) {
-            // the slot's elements come from two or more rows: branch-free walk, all loads first
-            uint32_t r = row, c = col;
+    uint32_t v[EPV];
 #pragma unroll
-            for (int j = 0; j < EPV; ++j) {
-                v[j] = load_elem<SES>(src + (size_t)r * ss + (size_t)c * SES);
-                const bool wrap = ++c == nc;
-                c = wrap ? 0u : c;
-                r += wrap ? 1u : 0u;
-            }
-            if (SES == 4 && DES == 2) {
-#pragma unroll
-                for (int j = 0; j < EPV; ++j) v[j] = narrow_rne(v[j]);
-            }
-        } else {
-            gather_slot<SES, DES>(src, ss, nc, row, col, s.first, s.last, v);
+    for (int j = 0; j < EPV; ++j) {
+        v[j] = 0;
+        if (FULL || (j >= first && j < last)) {
+            const uint64_t rel = (uint64_t)row * ss + (uint64_t)col * SES;
+            v[j] = load_elem<SES>(src + rel);
+            if (SUM == 2) sum_elem<SES>(acc, v[j], rel);
+            const bool wrap = ++col == nc;
+            col = wrap ? 0u : col;
+            row += wrap ? 1u : 0u;
         }
-        s.o = pack_slot<DES>(v);
     }
-    return s;
+    if (SES == 4 && DES == 2) {
+#pragma unroll
+        for (int j = 0; j < EPV; ++j) v[j] = narrow_rne(v[j]);
+    }
+    return pack_slot<DES>(v);
 }
 
 // Every full slot of a wavefront is written by the same store instruction, however its elements
 // were fetched: lanes that took different fetch paths must not write their parts of a cache line
 // at different times (that showed up as 1.2x the ideal HBM write traffic).
-template <int DES>
-__device__ __forceinline__ void commit_slot(const Slot<DES>& s) {
+// rel: byte offset of the slot's element 0 from the tile's wire base when the wire is the destination.
+template <int DES, int SUM>
+__device__ __forceinline__ void commit_slot(const Slot<DES>& s, int64_t rel, Sum& acc) {
     constexpr int EPV = 16 / DES;
+    if (SUM == 1) sum_halves(acc, s.o, s.first * DES / 2, s.last * DES / 2, rel / 2);
     if (s.first == 0 && s.last == EPV) {
         st16(s.d, s.o);
     } else {
@@ -278,9 +310,42 @@ __device__ __forceinline__ void commit_slot(const Slot<DES>& s) {
     }
 }
 
-template <int SES, int DES>
+// Contiguous destination: each thread owns one aligned 16-byte slot of the tile's destination
+// bytes and gathers its elements from the source rectangle, whose rows hold nc elements and lie
+// ss bytes apart; element e of the tile sits at linear position x = col0 + e of that rectangle.
+// A slot that straddles the boundary between two tiles of one run is written whole by the
+// earlier tile (tail_ok) and skipped by the later one (head_skip), so inside a run every store
+// is one 128-bit store whatever the alignment of the base pointer; only a run's first and last
+// slot can be partial.  Division as on the vector path (magic == 0: at most one wrap per tile).
+template <int SES, int DES, int SUM>
+__device__ __forceinline__ Slot<DES> fetch_slot(gsrc_t src, gdst_t dst, uint64_t ss, uint32_t nc, uint32_t col0,
+                                                uint32_t magic, uint32_t lead, uint32_t limit, uint32_t t,
+                                                Sum& acc) {
+    constexpr int EPV = 16 / DES;
+    Slot<DES> s;
+    const int32_t e0 = (int32_t)(t * EPV) - (int32_t)lead;
+    s.first = e0 < 0 ? -e0 : 0;
+    s.last = (uint32_t)(e0 + EPV) <= limit ? EPV : (int)(limit - (uint32_t)e0);
+    s.d = dst + (ptrdiff_t)e0 * DES;
+    const uint32_t x = col0 + (uint32_t)(e0 + s.first);
+    const uint32_t row = div_rows(x, nc, magic);
+    const uint32_t col = x - row * nc;
+    const bool full = s.first == 0 && s.last == EPV;
+    if (full && col + EPV <= nc) {
+        const uint64_t rel = (uint64_t)row * ss + (uint64_t)col * SES;
+        s.o = load_slot<SES, DES>(src + rel);
+        if (SUM == 2) sum_halves(acc, s.o, 0, 8, (int64_t)(rel / 2));
+    } else if (full) {
+        s.o = gather_slot<SES, DES, SUM, true>(src, ss, nc, row, col, 0, EPV, acc);
+    } else {
+        s.o = gather_slot<SES, DES, SUM, false>(src, ss, nc, row, col, s.first, s.last, acc);
+    }
+    return s;
+}
+
+template <int SES, int DES, int SUM>
 __device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, uint32_t count, uint32_t nc,
-                                           uint32_t col0, uint32_t magic, bool head_skip, bool tail_ok) {
+                                           uint32_t col0, uint32_t magic, bool head_skip, bool tail_ok, Sum& acc) {
     constexpr int EPV = 16 / DES;
     const uint32_t lead = (uint32_t)(reinterpret_cast<uintptr_t>(dst) & 15u) / DES;
     const uint32_t nslots = (lead + count + EPV - 1) / EPV;
@@ -288,21 +353,22 @@ __device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, 
     // two slots per thread and pass: both fetched before either is stored
     for (uint32_t t = threadIdx.x + ((head_skip && lead) ? 1u : 0u); t < nslots; t += 2 * kBlockThreads) {
         const uint32_t t2 = t + kBlockThreads;
-        const Slot<DES> a = fetch_slot<SES, DES>(src, dst, ss, nc, col0, magic, lead, limit, t);
+        const Slot<DES> a = fetch_slot<SES, DES, SUM>(src, dst, ss, nc, col0, magic, lead, limit, t, acc);
+        const int64_t rel_a = ((int64_t)t * EPV - (int64_t)lead) * DES;
         if (t2 < nslots) {
-            const Slot<DES> b = fetch_slot<SES, DES>(src, dst, ss, nc, col0, magic, lead, limit, t2);
-            commit_slot<DES>(a);
-            commit_slot<DES>(b);
+            const Slot<DES> b = fetch_slot<SES, DES, SUM>(src, dst, ss, nc, col0, magic, lead, limit, t2, acc);
+            commit_slot<DES, SUM>(a, rel_a, acc);
+            commit_slot<DES, SUM>(b, rel_a + (int64_t)kBlockThreads * 16, acc);
         } else {
-            commit_slot<DES>(a);
+            commit_slot<DES, SUM>(a, rel_a, acc);
         }
     }
 }
 
 // Strided destination: each destination row is cut into aligned 16-byte slots of its own.
-template <int SES, int DES>
+template <int SES, int DES, int SUM>
 __device__ __forceinline__ void copy_any(gsrc_t src, gdst_t dst, uint64_t ss, uint64_t ds, uint32_t nrows,
-                                         uint32_t ncols, uint32_t lg) {
+                                         uint32_t ncols, uint32_t lg, Sum& acc) {
     constexpr int EPV = 16 / DES;  // elements per 16-byte destination slot
     const uint32_t tid = threadIdx.x;
     const uint32_t lanes = 1u << lg;             // threads that share a row
@@ -316,24 +382,29 @@ __device__ __forceinline__ void copy_any(gsrc_t src, gdst_t dst, uint64_t ss, ui
         const uint32_t nslots = (lead + ncols + EPV - 1) / EPV;
         for (uint32_t k = lane; k < nslots; k += lanes) {
             const int32_t e0 = (int32_t)(k * EPV) - (int32_t)lead;  // first element of the slot
-            if (e0 >= 0 && (uint32_t)e0 + EPV <= ncols) {
-                st16(d + (size_t)e0 * DES, load_slot<SES, DES>(s + (size_t)e0 * SES));
-            } else {
-                const int first = e0 < 0 ? -e0 : 0;
-                const int last = (uint32_t)(e0 + EPV) <= ncols ? EPV : (int)(ncols - (uint32_t)e0);
-                uint32_t v[EPV];
-                gather_slot<SES, DES>(s, 0, 0xFFFFFFFFu, 0, (uint32_t)(e0 + first), first, last, v);
-                store_slot<DES>(d + (ptrdiff_t)e0 * DES, v, first, last);
-            }
+            Slot<DES> q;
+            q.first = e0 < 0 ? -e0 : 0;
+            q.last = (uint32_t)(e0 + EPV) <= ncols ? EPV : (int)(ncols - (uint32_t)e0);
+            q.d = d + (ptrdiff_t)e0 * DES;
+            if (q.first == 0 && q.last == EPV)
+                q.o = load_slot<SES, DES>(s + (size_t)e0 * SES);
+            else
+                q.o = gather_slot<SES, DES, 0, false>(s, 0, 0xFFFFFFFFu, 0, (uint32_t)(e0 + q.first), q.first,
+                                                      q.last, acc);
+            // the slot is contiguous on both sides: its element 0 sits at row offset e0 on either
+            const int64_t rel = (int64_t)r * (int64_t)(SUM == 1 ? ds : ss) + (int64_t)e0 * (SUM == 1 ? DES : SES);
+            if (SUM == 2) sum_halves(acc, q.o, q.first * DES / 2, q.last * DES / 2, rel / 2);
+            commit_slot<DES, SUM>(q, rel, acc);
         }
     }
 }
 
-template <int MODE, bool VEC_ONLY>
+template <int MODE, bool VEC_ONLY, bool CHECKSUM>
 __global__ __launch_bounds__(kBlockThreads) void th_tiles_kernel(const Tile* __restrict__ tiles,
                                                                   const void* const* __restrict__ src_table,
                                                                   void* const* __restrict__ dst_table,
-                                                                  uint32_t wire_first) {
+                                                                  uint32_t wire_first,
+                                                                  uint64_t* __restrict__ partials) {
     // Workgroups are dealt to the 8 XCDs round-robin (workgroup b runs on XCD b mod 8).  Give
     // each XCD one contiguous eighth of the tile list so that it streams through its own
     // address range instead of every 8th tile.
@@ -343,54 +414,90 @@ __global__ __launch_bounds__(kBlockThreads) void th_tiles_kernel(const Tile* __r
 
     const Tile& t = tiles[b];  // uniform: fetched by the scalar unit
     const uint32_t flags = t.flags;
-    const uint32_t nrows = t.count, ncols = t.ncols;
+    const uint32_t count = t.count, ncols = t.ncols;
     const uint64_t ss = t.src_stride, ds = t.dst_stride;
     constexpr bool PACK = MODE == MODE_PACK;
+    constexpr int SUM = !CHECKSUM ? 0 : (PACK ? 1 : 2);
     const uint32_t sb = MODE == MODE_UNPACK ? t.src_buf - wire_first : t.src_buf;
     const uint32_t db = MODE == MODE_PACK ? t.dst_buf - wire_first : t.dst_buf;
     gsrc_t src = (gsrc_t)(static_cast<const char*>(src_table[sb]) + t.src_off);
     gdst_t dst = (gdst_t)(static_cast<char*>(dst_table[db]) + t.dst_off);
+    const uint32_t kind = VEC_ONLY ? (uint32_t)TILE_KIND_VEC : (flags & TILE_KIND_MASK);
+    Sum acc;
 
-    if (VEC_ONLY || (flags & TILE_KIND_MASK) == TILE_KIND_VEC) {
-        copy_vec(src, dst, ss, ds, t.count, ncols, t.col0, t.magic);
-        return;
-    }
-    if ((flags & TILE_KIND_MASK) == TILE_KIND_DENSE) {
-        const uint32_t count = t.count;
+    if (kind == TILE_KIND_VEC) {
+        copy_vec<SUM>(src, dst, ss, ds, count, ncols, t.col0, t.magic, acc);
+    } else if (kind == TILE_KIND_DENSE) {
         const bool head_skip = (flags & TILE_HEAD_SKIP) != 0, tail_ok = (flags & TILE_TAIL_OK) != 0;
         unsigned des = 2;
         if (flags & TILE_DST_F32) {
-            copy_dense<4, 4>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok);
+            copy_dense<4, 4, SUM>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok, acc);
             des = 4;
         } else if (flags & TILE_SRC_F32) {
-            copy_dense<4, 2>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok);
+            copy_dense<4, 2, SUM == 2 ? 0 : SUM>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok, acc);
         } else {
-            copy_dense<2, 2>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok);
+            copy_dense<2, 2, SUM>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok, acc);
         }
         if (PACK) {
+            // zero the alignment gap that follows a tensor's last element on the wire
             const uint32_t pad = (flags & TILE_PAD_MASK) >> TILE_PAD_SHIFT;
             if (threadIdx.x * 2 < pad)
                 *reinterpret_cast<TH_GLOBAL uint16_t*>(dst + (size_t)count * des + threadIdx.x * 2) = 0;
         }
-        return;
-    }
-    const uint32_t lg = (flags & TILE_LG_LANES_MASK) >> TILE_LG_LANES_SHIFT;
-    unsigned des = 2;
-    if (flags & TILE_DST_F32) {
-        copy_any<4, 4>(src, dst, ss, ds, nrows, ncols, lg);
-        des = 4;
-    } else if (flags & TILE_SRC_F32) {
-        copy_any<4, 2>(src, dst, ss, ds, nrows, ncols, lg);
     } else {
-        copy_any<2, 2>(src, dst, ss, ds, nrows, ncols, lg);
-    }
-    if (PACK) {
-        // zero the alignment gap that follows a tensor's last element on the wire
-        const uint32_t pad = (flags & TILE_PAD_MASK) >> TILE_PAD_SHIFT;
-        if (threadIdx.x * 2 < pad) {
-            gdst_t end = dst + (size_t)(nrows - 1) * ds + (size_t)ncols * des;
-            *reinterpret_cast<TH_GLOBAL uint16_t*>(end + threadIdx.x * 2) = 0;
+        const uint32_t lg = (flags & TILE_LG_LANES_MASK) >> TILE_LG_LANES_SHIFT;
+        unsigned des = 2;
+        if (flags & TILE_DST_F32) {
+            copy_any<4, 4, SUM>(src, dst, ss, ds, count, ncols, lg, acc);
+            des = 4;
+        } else if (flags & TILE_SRC_F32) {
+            copy_any<4, 2, SUM == 2 ? 0 : SUM>(src, dst, ss, ds, count, ncols, lg, acc);
+        } else {
+            copy_any<2, 2, SUM>(src, dst, ss, ds, count, ncols, lg, acc);
         }
+        if (PACK) {
+            const uint32_t pad = (flags & TILE_PAD_MASK) >> TILE_PAD_SHIFT;
+            if (threadIdx.x * 2 < pad) {
+                gdst_t end = dst + (size_t)(count - 1) * ds + (size_t)ncols * des;
+                *reinterpret_cast<TH_GLOBAL uint16_t*>(end + threadIdx.x * 2) = 0;
+            }
+        }
+    }
+    if (CHECKSUM) block_sum_store(acc, partials + 2 * (size_t)b);
+}
+
+// One thread per tile: shift the tile's pair to positions counted from the start of its tensor's
+// run (B += base * A) and add it to the tensor's sums.  Tiles of one tensor are neighbours in the
+// list, so a wavefront usually holds one tensor and issues one pair of atomics.
+__global__ __launch_bounds__(256) void th_checksum_finalize_kernel(const Tile* __restrict__ tiles,
+                                                                   const uint64_t* __restrict__ partials,
+                                                                   const uint64_t* __restrict__ tile_base,
+                                                                   uint64_t n, uint64_t* __restrict__ sums) {
+    const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    const bool active = i < n;
+    uint32_t tensor = 0xFFFFFFFFu;
+    uint64_t a = 0, bsum = 0;
+    if (active) {
+        tensor = tiles[i].src_tensor;
+        a = partials[2 * i];
+        bsum = partials[2 * i + 1] + tile_base[i] * a;
+    }
+    const uint32_t lead_tensor = __shfl(tensor, 0);
+    const bool same = __all(!active || tensor == lead_tensor);
+    if (same) {
+#pragma unroll
+        for (int off = 32; off; off >>= 1) {
+            a += __shfl_xor(a, off);
+            bsum += __shfl_xor(bsum, off);
+        }
+        if ((threadIdx.x & 63) == 0 && lead_tensor != 0xFFFFFFFFu) {
+            atomicAdd(reinterpret_cast<unsigned long long*>(sums + 2 * (size_t)lead_tensor), (unsigned long long)a);
+            atomicAdd(reinterpret_cast<unsigned long long*>(sums + 2 * (size_t)lead_tensor + 1),
+                      (unsigned long long)bsum);
+        }
+    } else if (active) {
+        atomicAdd(reinterpret_cast<unsigned long long*>(sums + 2 * (size_t)tensor), (unsigned long long)a);
+        atomicAdd(reinterpret_cast<unsigned long long*>(sums + 2 * (size_t)tensor + 1), (unsigned long long)bsum);
     }
 }
 
@@ -409,19 +516,26 @@ __global__ __launch_bounds__(kBlockThreads) void th_reference_copy_kernel(const 
 }  // namespace
 
 int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
-                 const void* const* src_table, void* const* dst_table, uint32_t wire_first, void* stream) {
+                 const void* const* src_table, void* const* dst_table, uint32_t wire_first, uint64_t* partials,
+                 void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     constexpr uint64_t kMaxGrid = 1u << 30;
-    typedef void (*kernel_t)(const Tile*, const void* const*, void* const*, uint32_t);
-    static const kernel_t kernels[3][2] = {
-        {th_tiles_kernel<MODE_PACK, false>, th_tiles_kernel<MODE_PACK, true>},
-        {th_tiles_kernel<MODE_UNPACK, false>, th_tiles_kernel<MODE_UNPACK, true>},
-        {th_tiles_kernel<MODE_DIRECT, false>, th_tiles_kernel<MODE_DIRECT, true>}};
-    const kernel_t kernel = kernels[mode][vec_only ? 1 : 0];
+    typedef void (*kernel_t)(const Tile*, const void* const*, void* const*, uint32_t, uint64_t*);
+    static const kernel_t kernels[3][2][2] = {
+        {{th_tiles_kernel<MODE_PACK, false, false>, th_tiles_kernel<MODE_PACK, false, true>},
+         {th_tiles_kernel<MODE_PACK, true, false>, th_tiles_kernel<MODE_PACK, true, true>}},
+        {{th_tiles_kernel<MODE_UNPACK, false, false>, th_tiles_kernel<MODE_UNPACK, false, true>},
+         {th_tiles_kernel<MODE_UNPACK, true, false>, th_tiles_kernel<MODE_UNPACK, true, true>}},
+        {{th_tiles_kernel<MODE_DIRECT, false, false>, nullptr}, {th_tiles_kernel<MODE_DIRECT, true, false>, nullptr}}};
+    const kernel_t kernel = kernels[mode][vec_only ? 1 : 0][partials ? 1 : 0];
+    if (!kernel) {
+        set_error("no checksum variant of this kernel");
+        return TH_ERR_ARG;
+    }
     while (ntiles) {
         const uint64_t n = ntiles < kMaxGrid ? ntiles : kMaxGrid;
         hipLaunchKernelGGL(kernel, dim3((uint32_t)n), dim3(kBlockThreads), 0, st, tiles + tile0, src_table,
-                           dst_table, wire_first);
+                           dst_table, wire_first, partials ? partials + 2 * tile0 : nullptr);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) {
             set_error("kernel launch failed: %s", hipGetErrorString(e));
@@ -429,6 +543,21 @@ int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uin
         }
         tile0 += n;
         ntiles -= n;
+    }
+    return TH_OK;
+}
+
+int launch_checksum_finalize(const Tile* tiles, const uint64_t* partials, const uint64_t* tile_base, uint64_t tile0,
+                             uint64_t ntiles, uint64_t* sums, void* stream) {
+    if (!ntiles) return TH_OK;
+    const uint64_t grid = (ntiles + 255) / 256;
+    hipLaunchKernelGGL(th_checksum_finalize_kernel, dim3((uint32_t)grid), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), tiles + tile0, partials + 2 * tile0, tile_base + tile0,
+                       ntiles, sums);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("kernel launch failed: %s", hipGetErrorString(e));
+        return TH_ERR_HIP;
     }
     return TH_OK;
 }

@@ -270,6 +270,7 @@ int build_model_segments(const th_model_desc& m, const th_layout& src, const th_
         cuts.erase(std::unique(cuts.begin(), cuts.end()), cuts.end());
 
         wire = (wire + 15) / 16 * 16;
+        const uint64_t run_start = wire;
         const size_t first_seg = man.segments.size();
         std::vector<size_t> open;  // segments of the previous band, by column order
         std::vector<const Piece*> band;
@@ -308,6 +309,7 @@ int build_model_segments(const th_model_desc& m, const th_layout& src, const th_
                 g.wire_stride = width * es;
                 g.src_dtype = (uint8_t)sr.info.dtype;
                 g.dst_dtype = (uint8_t)dt.dtype;
+                g.run_start = run_start;
                 prefix += (uint64_t)p.nc;
                 // continue the segment of the previous band if this one extends it downwards
                 bool merged = false;

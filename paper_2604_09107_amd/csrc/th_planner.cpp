@@ -181,7 +181,7 @@ int segments_from_user(const th_segment* segs, size_t n, const uint64_t* src_ele
             t.dtype = 0;
         }
     }
-    uint64_t wire = 0;
+    uint64_t wire = 0, run_start = 0;
     int64_t prev_tensor = -1;
     for (size_t k = 0; k < n; ++k) {
         const th_segment& u = segs[k];
@@ -224,6 +224,7 @@ int segments_from_user(const th_segment* segs, size_t n, const uint64_t* src_ele
             const uint64_t aligned = (wire + 15) / 16 * 16;
             if (!m.segments.empty()) m.segments.back().pad_after = (uint8_t)(aligned - wire);
             wire = aligned;
+            run_start = wire;
             prev_tensor = u.src_tensor;
         }
         Segment g;
@@ -238,6 +239,7 @@ int segments_from_user(const th_segment* segs, size_t n, const uint64_t* src_ele
         g.src_dtype = u.src_dtype;
         g.dst_dtype = u.dst_dtype;
         g.wire_off = wire;
+        g.run_start = run_start;
         g.wire_stride = u.row_len * esize(u.dst_dtype);
         m.segments.push_back(g);
         wire += u.nrows * u.row_len * esize(u.dst_dtype);
@@ -286,6 +288,7 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
             r.dst_dtype = g.dst_dtype;
             if (r0 + nr == g.nrows && c0 + nc == g.row_len) r.pad_bytes = g.pad_after;
             m.runs.push_back(r);
+            m.run_starts.push_back(g.run_start);
         };
         uint64_t r = 0;
         while (r < g.nrows) {
@@ -311,10 +314,12 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
         }
     }
 
-    // ---- tiles, one list per direction, grouped by chunk ----
+    // ---- tiles, one list per direction: vector-path tiles first, each sub-list grouped by chunk ----
     for (int side = 0; side < 2; ++side) {
-        std::vector<Tile>& tiles = m.tiles[side];
-        for (const th_run& r : m.runs) {
+        std::vector<Tile> tiles;
+        std::vector<uint64_t> base;
+        for (size_t ri = 0; ri < m.runs.size(); ++ri) {
+            const th_run& r = m.runs[ri];
             const unsigned es_s = esize(r.src_dtype), es_w = esize(r.dst_dtype);
             Side S, D;
             if (side == 0) {
@@ -325,16 +330,32 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
                 D = Side{r.dst_tensor, r.dst_byte_off, r.dst_byte_stride, es_w};
             }
             bool vec = false;
+            const size_t before = tiles.size();
             tile_run(tiles, S, D, r.nrows, r.row_len, side == 0 ? r.pad_bytes : 0, ptrs_aligned16, tune, vec);
+            for (size_t i = before; i < tiles.size(); ++i) {
+                Tile& t = tiles[i];
+                t.src_tensor = r.src_tensor;
+                const uint64_t wire_off = (uint64_t)r.chunk * CB + (side == 0 ? t.dst_off : t.src_off);
+                base.push_back((wire_off - m.run_starts[ri]) / 2);
+            }
             TensorInfo& t = side == 0 ? m.tensors[0][r.src_tensor] : m.tensors[1][r.dst_tensor];
             t.used = true;
             t.need16 = t.need16 || vec;
         }
         auto chunk_of = [side](const Tile& t) { return side == 0 ? t.dst_buf : t.src_buf; };
         auto class_of = [](const Tile& t) { return (t.flags & TILE_KIND_MASK) == TILE_KIND_VEC ? 0u : 1u; };
-        std::stable_sort(tiles.begin(), tiles.end(), [&](const Tile& a, const Tile& b) {
+        std::vector<uint32_t> order(tiles.size());
+        for (size_t i = 0; i < order.size(); ++i) order[i] = (uint32_t)i;
+        std::stable_sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) {
+            const Tile &a = tiles[x], &b = tiles[y];
             return class_of(a) != class_of(b) ? class_of(a) < class_of(b) : chunk_of(a) < chunk_of(b);
         });
+        m.tiles[side].resize(tiles.size());
+        m.tile_base[side].resize(tiles.size());
+        for (size_t i = 0; i < order.size(); ++i) {
+            m.tiles[side][i] = tiles[order[i]];
+            m.tile_base[side][i] = base[order[i]];
+        }
         uint64_t n_class[2] = {0, 0};
         for (const Tile& t : tiles) n_class[class_of(t)]++;
         for (unsigned k = 0; k < 2; ++k) {

@@ -88,19 +88,49 @@ def exec_tiles(plan, side, src_bufs, dst_bufs, chunk_range=None):
             col = 0
 
 
+def tile_checksums(plan, side, wire_chunks, n_src_tensors):
+    """Per-tensor (A, B) computed the way the device does: per tile, terms with positions counted
+    from the tile's wire-side byte offset, then shifted by the tile's run_unit_base and added up."""
+    mask = (1 << 64) - 1
+    sums = [[0, 0] for _ in range(n_src_tensors)]
+    for i in range(plan.num_tiles(side)):
+        t = plan.tile(side, i)
+        if side == 0:
+            chunk, off, stride, es = t.dst_buf, t.dst_byte_off, t.dst_byte_stride, t.elem_bytes_dst
+        else:
+            chunk, off, stride, es = t.src_buf, t.src_byte_off, t.src_byte_stride, t.elem_bytes_src
+        buf = wire_chunks[chunk]
+        a = b = 0
+        left, col, row = int(t.count), int(t.first_col), 0
+        while left:
+            n = min(int(t.row_len) - col, left)
+            rel = row * stride + col * es              # bytes from the tile's wire-side offset
+            h = buf[off + rel: off + rel + n * es].view("<u2").astype(object)
+            k0 = rel // 2
+            a += int(sum(h))
+            b += int(sum((k0 + j + 1) * int(v) for j, v in enumerate(h)))
+            left -= n
+            row += 1
+            col = 0
+        sums[t.src_tensor][0] = (sums[t.src_tensor][0] + a) & mask
+        sums[t.src_tensor][1] = (sums[t.src_tensor][1] + b + int(t.run_unit_base) * a) & mask
+    return np.array(sums, dtype=np.uint64)
+
+
 @contextlib.contextmanager
 def tile_sizes(tile_bytes):
     """Plans created inside the block use `tile_bytes` for every tile kind (None: library defaults)."""
     import paper_2604_09107_amd as th
-    old = th.th_config_get(th.TH_CFG_TILE_BYTES), th.th_config_get(th.TH_CFG_TILE_BYTES_ANY)
+    keys = (th.TH_CFG_TILE_BYTES, th.TH_CFG_TILE_BYTES_ANY, th.TH_CFG_TILE_BYTES_CHECKSUM)
+    old = [th.th_config_get(k) for k in keys]
     try:
         if tile_bytes:
-            th.th_config_set(th.TH_CFG_TILE_BYTES, tile_bytes)
-            th.th_config_set(th.TH_CFG_TILE_BYTES_ANY, tile_bytes)
+            for k in keys:
+                th.th_config_set(k, tile_bytes)
         yield
     finally:
-        th.th_config_set(th.TH_CFG_TILE_BYTES, old[0])
-        th.th_config_set(th.TH_CFG_TILE_BYTES_ANY, old[1])
+        for k, v in zip(keys, old):
+            th.th_config_set(k, v)
 
 
 def flat_u8(arrs):

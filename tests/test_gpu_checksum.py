@@ -1,0 +1,126 @@
+"""GPU parity of the fused per-tensor wire checksums (th_pack_checksum / th_unpack_checksum)
+against the checksum oracle, bit for bit, plus the property the checksum exists for: a corrupted
+wire is detected on the reader side, for exactly the tensor that was hit."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+import paper_2604_09107_amd as th
+from paper_2604_09107_amd import device as dev
+from oracle import checksum, layouts, reshard, segments
+from helpers import holder_tensors_cpu, tile_sizes
+from test_planner_manifest import scatter_segments
+
+pytestmark = pytest.mark.gpu
+
+
+def sums_dev(n):
+    return torch.zeros(2 * n, dtype=torch.int64, device="cuda")
+
+
+def sums_host(t):
+    return t.cpu().numpy().view(np.uint64).reshape(-1, 2)
+
+
+@pytest.mark.parametrize("tile_bytes", [4096, None])
+@pytest.mark.parametrize("name", ["cfg1_tiny_tp2_to_tp1", "small_dense_tp1_to_tp4", "small_dense_tp4_to_tp2",
+                                  "small_moe_ep4_to_tp2"])
+def test_model_checksums_bit_exact(name, tile_bytes):
+    w = synth.workload(name)
+    model, dst = w["model"], w["reader"]
+    stream = dev.current_stream()
+    for src in w["holders"]:
+        tensors = holder_tensors_cpu(model, src, w["seed"])
+        wire = reshard.pack(model, src, dst, tensors)
+        want = checksum.model_checksums(model, src, dst, wire, len(tensors))
+        with tile_sizes(tile_bytes):
+            plan = th.th_plan_create(model, src, dst, 64 * 1024, th.TH_FLAG_CHECKSUM)
+        src_dev = [synth.from_bits(t.reshape(-1), "cuda") for t in tensors]
+        dst_dev = dev.alloc_tensors(plan, 1, fill_bits=0)
+        wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=0xEE)
+        ps, us = sums_dev(len(tensors)), sums_dev(len(tensors))
+        n = plan.num_chunks
+        # whole range in one call for pack, chunk by chunk (backwards) for unpack: both must add up
+        th.th_pack_checksum(plan, dev.ptrs(src_dev), wptrs, 0, n, ps.data_ptr(), stream)
+        for c in range(n - 1, -1, -1):
+            th.th_unpack_checksum(plan, wptrs[c:c + 1], c, 1, dev.ptrs(dst_dev), us.data_ptr(), stream)
+        torch.cuda.synchronize()
+        assert np.array_equal(wire_dev.cpu().numpy()[:plan.wire_bytes], wire)
+        assert np.array_equal(sums_host(ps), want), "pack-side checksums"
+        assert np.array_equal(sums_host(us), want), "unpack-side checksums"
+        # the data path is unchanged by the checksum variant
+        want_dst = reshard.empty_tensors(model, dst, fill=0)
+        reshard.unpack(model, src, dst, wire, want_dst)
+        for g, x in zip(dst_dev, want_dst):
+            assert np.array_equal(synth.to_bits(g), x.reshape(-1))
+        plan.destroy()
+
+
+@pytest.mark.parametrize("tile_bytes", [4096, None])
+def test_scattered_checksums_bit_exact(tile_bytes):
+    n = 300
+    d = synth.scatter_description(n, 71, min_bytes=256, max_bytes=1 << 17)
+    pool_dev = synth.scatter_values(d["pool_elems"] + 3, 71, "cuda", 0.05)[1:]
+    pool = synth.to_bits(pool_dev[:d["pool_elems"]])
+    srcs = [pool[o:o + m] for o, m in zip(d["pool_off"], d["n_elems"])]
+    osegs = dict(src_tensor=d["seg_src_tensor"], dst_tensor=np.zeros(n, dtype=np.int64),
+                 src_off=d["seg_src_off"], src_stride=d["seg_src_stride"], dst_off=d["seg_dst_off"],
+                 dst_stride=d["seg_dst_stride"], nrows=d["seg_nrows"], row_len=d["seg_row_len"])
+    wire = segments.pack(osegs, srcs, "f32", "bf16")
+    offs, _ = segments.wire_offsets(osegs, "bf16")
+    want = checksum.segment_checksums(osegs, offs, "bf16", wire, n)
+    with tile_sizes(tile_bytes):
+        plan = th.th_plan_create_from_segments(scatter_segments(d), d["n_elems"], [d["arena_elems"] + 8], 256 * 1024,
+                                               th.TH_FLAG_CHECKSUM)
+    arena_dev = torch.zeros(d["arena_elems"] + 9, dtype=torch.bfloat16, device="cuda")
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=0xEE)
+    src_ptrs = pool_dev.data_ptr() + d["pool_off"].astype(np.uint64) * np.uint64(4)
+    ps, us = sums_dev(n), sums_dev(n)
+    stream = dev.current_stream()
+    th.th_pack_checksum(plan, src_ptrs, wptrs, 0, plan.num_chunks, ps.data_ptr(), stream)
+    th.th_unpack_checksum(plan, wptrs, 0, plan.num_chunks, [arena_dev.data_ptr() + 2], us.data_ptr(), stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(wire_dev.cpu().numpy()[:plan.wire_bytes], wire)
+    assert np.array_equal(sums_host(ps), want)
+    assert np.array_equal(sums_host(us), want)
+    plan.destroy()
+
+
+def test_corrupted_wire_is_detected_for_the_tensor_that_was_hit():
+    w = synth.workload("small_dense_tp1_to_tp4")
+    model, src, dst = w["model"], w["holders"][0], w["reader"]
+    tensors = holder_tensors_cpu(model, src, 9)
+    plan = th.th_plan_create(model, src, dst, w["chunk_bytes"], th.TH_FLAG_CHECKSUM)
+    src_dev = [synth.from_bits(t.reshape(-1), "cuda") for t in tensors]
+    dst_dev = dev.alloc_tensors(plan, 1, fill_bits=0)
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=0)
+    ps, us = sums_dev(len(tensors)), sums_dev(len(tensors))
+    stream = dev.current_stream()
+    th.th_pack_checksum(plan, dev.ptrs(src_dev), wptrs, 0, plan.num_chunks, ps.data_ptr(), stream)
+    torch.cuda.synchronize()
+    items = list(reshard.plan_items(model, src, dst))
+    victim = max(items, key=lambda it: len(it["src_r"]) * len(it["src_c"]))  # a run of many KB
+    assert len(victim["src_r"]) * len(victim["src_c"]) * 2 > 8192
+    wire_dev[victim["wire_off"] + 1000] ^= 0x04       # one flipped bit "in transit"
+    a, b = victim["wire_off"] + 2000, victim["wire_off"] + 4000  # and two swapped 16-bit units
+    tmp = wire_dev[a:a + 2].clone()
+    wire_dev[a:a + 2] = wire_dev[b:b + 2]
+    wire_dev[b:b + 2] = tmp
+    th.th_unpack_checksum(plan, wptrs, 0, plan.num_chunks, dev.ptrs(dst_dev), us.data_ptr(), stream)
+    torch.cuda.synchronize()
+    differs = np.nonzero((sums_host(ps) != sums_host(us)).any(axis=1))[0]
+    assert list(differs) == [victim["src_id"]]
+    plan.destroy()
+
+
+def test_checksum_calls_need_the_flag():
+    w = synth.workload("cfg1_tiny_tp2_to_tp1")
+    plan = th.th_plan_create(w["model"], w["holders"][0], w["reader"], w["chunk_bytes"])
+    src_dev = dev.alloc_tensors(plan, 0)
+    wire_dev, wptrs = dev.alloc_wire(plan)
+    s = sums_dev(plan.num_tensors(0))
+    with pytest.raises(th.ThError) as e:
+        th.th_pack_checksum(plan, dev.ptrs(src_dev), wptrs, 0, plan.num_chunks, s.data_ptr())
+    assert e.value.code == -1 and "CHECKSUM" in str(e.value)
+    plan.destroy()

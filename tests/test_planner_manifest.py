@@ -10,8 +10,9 @@ import pytest
 
 import synth
 import paper_2604_09107_amd as th
-from oracle import layouts, reshard, segments
-from helpers import (exec_runs_pack, exec_runs_unpack, exec_tiles, flat_u8, holder_tensors_cpu)
+from oracle import checksum, layouts, reshard, segments
+from helpers import (exec_runs_pack, exec_runs_unpack, exec_tiles, flat_u8, holder_tensors_cpu, tile_checksums,
+                     tile_sizes)
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HOST = th.TH_FLAG_HOST_ONLY
@@ -114,6 +115,39 @@ def test_direct_list_equals_the_wire_free_definition(name):
         plan.destroy()
     for g, x in zip(got, want):
         assert np.array_equal(g, x)
+
+
+@pytest.mark.parametrize("tile_bytes", [4096, None])
+def test_tile_checksum_bases_reproduce_the_oracle_checksums(tile_bytes):
+    """The per-tile position bases of the work list, used the way the device uses them, give the
+    oracle's per-tensor checksums - on both directions, for model and explicit-segment plans."""
+    w = synth.workload("small_moe_ep4_to_tp2")
+    model, src, dst = w["model"], w["holders"][0], w["reader"]
+    tensors = holder_tensors_cpu(model, src, 5)
+    wire = reshard.pack(model, src, dst, tensors)
+    want = checksum.model_checksums(model, src, dst, wire, len(tensors))
+    with tile_sizes(tile_bytes):
+        plan = th.th_plan_create(model, src, dst, 64 * 1024, HOST)
+    chunks = reshard.chunks(wire, 64 * 1024)
+    for side in (0, 1):
+        assert np.array_equal(tile_checksums(plan, side, chunks, len(tensors)), want), side
+    plan.destroy()
+
+    d = synth.scatter_description(80, 23, min_bytes=256, max_bytes=16384)
+    pool = synth.to_bits(synth.scatter_values(d["pool_elems"], 23))
+    srcs = [pool[o:o + m] for o, m in zip(d["pool_off"], d["n_elems"])]
+    osegs = dict(src_tensor=d["seg_src_tensor"], dst_tensor=np.zeros(80, dtype=np.int64),
+                 src_off=d["seg_src_off"], src_stride=d["seg_src_stride"], dst_off=d["seg_dst_off"],
+                 dst_stride=d["seg_dst_stride"], nrows=d["seg_nrows"], row_len=d["seg_row_len"])
+    wire = segments.pack(osegs, srcs, "f32", "bf16")
+    offs, _ = segments.wire_offsets(osegs, "bf16")
+    want = checksum.segment_checksums(osegs, offs, "bf16", wire, 80)
+    with tile_sizes(tile_bytes):
+        plan = th.th_plan_create_from_segments(scatter_segments(d), d["n_elems"], [d["arena_elems"]], 8192, HOST)
+    chunks = reshard.chunks(wire, 8192)
+    for side in (0, 1):
+        assert np.array_equal(tile_checksums(plan, side, chunks, 80), want), side
+    plan.destroy()
 
 
 def test_chunks_are_self_contained():
