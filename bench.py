@@ -161,6 +161,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2_8b_tp1_to_tp4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--offload", action="store_true",
+                    help="also time th_pack into / th_unpack out of pinned host memory (up to 2 GiB of chunks)")
     ap.add_argument("--tile-bytes", type=int, default=0, help="override the vector-path tile size")
     ap.add_argument("--no-specialize", action="store_true", help="always launch the all-paths kernel")
     ap.add_argument("--tile-bytes-any", type=int, default=0, help="override the any-alignment tile size")
@@ -291,6 +293,29 @@ def main():
     checksum_ms = c0.elapsed_time(c1) / 10
     checksums_agree = all(bool((ps == us).all()) for ps, us in sums)
 
+    # offload replica: wire chunks in pinned host memory, written / read over the host link
+    offload = None
+    if args.offload:
+        j = jobs[0]
+        plan = j["plan"]
+        nck = max(1, min(plan.num_chunks, (2 << 30) // plan.chunk_bytes(0)))
+        nbytes = sum(plan.chunk_bytes(c) for c in range(nck))
+        host = torch.empty(nbytes + 16, dtype=torch.uint8, pin_memory=True)
+        hptrs = dev.chunk_ptrs(plan, host)[:nck]
+        res = {}
+        for name, call in (("th_pack", lambda: th.th_pack(plan, j["src_ptrs"], hptrs, 0, nck, stream)),
+                           ("th_unpack", lambda: th.th_unpack(plan, hptrs, 0, nck, dst_ptrs, stream))):
+            call()
+            torch.cuda.synchronize()
+            c0.record()
+            for _ in range(3):
+                call()
+            c1.record()
+            torch.cuda.synchronize()
+            ms = c0.elapsed_time(c1) / 3
+            res[name] = {"ms": round(ms, 3), "host_link_GB/s": round(nbytes / (ms * 1e-3) / 1e9, 2)}
+        offload = {"chunks": nck, "bytes": nbytes, **res}
+
     value = sweep_bytes / (ms_per_step * 1e-3) / 1e9
     out = {
         "metric": "reshard pack+unpack effective HBM GB/s",
@@ -314,6 +339,8 @@ def main():
                      "unit": "GB/s", "frac": round(dom[1] / HBM_PEAK_GBPS, 4),
                      "traffic": measured_traffic(args.workload, dom[0])},
     }
+    if offload:
+        out["offload_pinned_host"] = offload
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = (cpu_baseline_scatter if w["kind"] == "scatter" else cpu_baseline)(synth, w, jobs)
     print(json.dumps(out))

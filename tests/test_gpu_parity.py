@@ -384,3 +384,30 @@ def test_pointer_tables_may_change_between_calls():
         torch.cuda.synchronize()
         assert np.array_equal(wire_dev.cpu().numpy()[:plan.wire_bytes], reshard.pack(model, src, dst, tensors))
     plan.destroy()
+
+
+def test_wire_chunks_in_pinned_host_memory():
+    """Offload replica: the wire chunks live in pinned host memory (device-accessible), the kernels
+    write / read them over the host link; results are the oracle's, bit for bit."""
+    w = synth.workload("small_dense_tp1_to_tp4")
+    model, src, dst = w["model"], w["holders"][0], w["reader"]
+    tensors = holder_tensors_cpu(model, src, 77)
+    wire = reshard.pack(model, src, dst, tensors)
+    plan = th.th_plan_create(model, src, dst, 256 * 1024)
+    host_wire = torch.empty(plan.wire_bytes + 16, dtype=torch.uint8, pin_memory=True)
+    host_wire.fill_(0xEE)
+    wptrs = dev.chunk_ptrs(plan, host_wire)
+    assert wptrs[0] % 16 == 0
+    src_dev = [to_dev(t) for t in tensors]
+    dst_dev = dev.alloc_tensors(plan, 1, fill_bits=SENT16)
+    stream = dev.current_stream()
+    th.th_pack(plan, dev.ptrs(src_dev), wptrs, 0, plan.num_chunks, stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_wire.numpy()[:plan.wire_bytes], wire)
+    assert np.all(host_wire.numpy()[plan.wire_bytes:] == 0xEE)
+    th.th_unpack(plan, wptrs, 0, plan.num_chunks, dev.ptrs(dst_dev), stream)
+    torch.cuda.synchronize()
+    want = reshard.empty_tensors(model, dst, fill=SENT16)
+    reshard.unpack(model, src, dst, wire, want)
+    assert_same([synth.to_bits(t) for t in dst_dev], [x.reshape(-1) for x in want])
+    plan.destroy()
