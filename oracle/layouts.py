@@ -9,7 +9,12 @@ a reading, not the paper's text:
   * column-parallel (split rows):   lm_head;  vocab-parallel: embed_tokens;
   * row-parallel (split columns):   o_proj, down_proj, expert/shared w2;
   * fused QKV, global rows [Q heads | K heads | V heads]; rank r keeps its
-    contiguous range of Q heads and of K/V heads, stored as [Q_r; K_r; V_r];
+    contiguous range of Q heads and of K/V heads, stored as [Q_r; K_r; V_r],
+    or - "grouped", the trainer-side convention - per KV head g of the rank as
+    [Q heads of group g; K_g; V_g], group after group;
+  * a side may pad the vocabulary of embed_tokens / lm_head to a larger size
+    before splitting it; padding rows exist in the rank's tensor but belong to
+    no logical weight: they are never sent and never written;
   * fused gate_up (and expert/shared w13), global rows [gate | up]; rank r keeps
     [gate_r; up_r];
   * replicated: norms, MoE router;
@@ -87,8 +92,12 @@ def shard_index(model, lt, lay):
     if part == "repl":
         pass
     elif part in ("col", "vocab"):
-        n = _split(R, T, lt["name"] + " rows")
+        padded = lay.get("padded_vocab", 0) or R
+        if padded < R:
+            raise ValueError("padded vocabulary %d is smaller than the vocabulary %d" % (padded, R))
+        n = _split(padded, T, lt["name"] + " rows")
         rows = np.arange(r * n, (r + 1) * n)
+        rows = rows[rows < R]  # the rest of the rank's n rows is padding
     elif part == "row":
         n = _split(C, T, lt["name"] + " cols")
         cols = np.arange(r * n, (r + 1) * n)
@@ -97,10 +106,19 @@ def shard_index(model, lt, lay):
         nq, nkv = model["n_q_heads"], model["n_kv_heads"]
         q = _split(nq, T, "n_q_heads")
         kv = _split(nkv, T, "n_kv_heads")
-        q_rows = np.arange(r * q * hd, (r + 1) * q * hd)
-        k_rows = nq * hd + np.arange(r * kv * hd, (r + 1) * kv * hd)
-        v_rows = (nq + nkv) * hd + np.arange(r * kv * hd, (r + 1) * kv * hd)
-        rows = np.concatenate([q_rows, k_rows, v_rows])
+        if lay.get("qkv_grouped", 0):
+            per = nq // nkv  # query heads per KV head
+            pieces = []
+            for g in range(r * kv, (r + 1) * kv):  # the rank's KV heads
+                pieces.append(np.arange(g * per * hd, (g + 1) * per * hd))
+                pieces.append(nq * hd + np.arange(g * hd, (g + 1) * hd))
+                pieces.append((nq + nkv) * hd + np.arange(g * hd, (g + 1) * hd))
+            rows = np.concatenate(pieces)
+        else:
+            q_rows = np.arange(r * q * hd, (r + 1) * q * hd)
+            k_rows = nq * hd + np.arange(r * kv * hd, (r + 1) * kv * hd)
+            v_rows = (nq + nkv) * hd + np.arange(r * kv * hd, (r + 1) * kv * hd)
+            rows = np.concatenate([q_rows, k_rows, v_rows])
     elif part == "gate_up":
         F = R // 2
         n = _split(F, T, lt["name"] + " ffn")
@@ -109,6 +127,15 @@ def shard_index(model, lt, lay):
     else:
         raise ValueError(part)
     return rows, cols
+
+
+def storage_rows(model, lt, lay):
+    """Rows the rank's tensor has for this logical weight: the kept rows, plus padding rows for a
+    padded vocabulary (they follow the kept rows)."""
+    rows, _ = shard_index(model, lt, lay)
+    if lt["part"] in ("col", "vocab") and lay.get("padded_vocab", 0):
+        return lay["padded_vocab"] // lay["tp_size"]
+    return len(rows)
 
 
 def storage_dtype(model, lt, lay):
@@ -141,7 +168,8 @@ def registered_tensors(model, lay):
             t["parts"].append((i, t["rows"]))
             t["rows"] += len(rows)
         else:
-            out.append(dict(name=lt["name"], dtype=dt, rows=len(rows), cols=len(cols), parts=[(i, 0)]))
+            out.append(dict(name=lt["name"], dtype=dt, rows=storage_rows(model, lt, lay), cols=len(cols),
+                            parts=[(i, 0)]))
     return out
 
 

@@ -10,15 +10,21 @@ library's planner.
 MiB = 1 << 20
 
 
-def layout(tp_size=1, tp_rank=0, ep_size=1, ep_rank=0, experts_stacked=0, f32_store="f32"):
+def layout(tp_size=1, tp_rank=0, ep_size=1, ep_rank=0, experts_stacked=0, f32_store="f32",
+           qkv_grouped=0, padded_vocab=0):
     """One worker's place in a model-parallel group.
 
     f32_store: dtype in which this side keeps tensors whose model dtype is
     fp32 ("f32" keeps them, "bf16" narrows them: the inference-ready format).
+    qkv_grouped: the fused QKV tensor is stored per KV group (trainer style)
+    instead of all Q, then all K, then all V.
+    padded_vocab: vocabulary size the embedding / output tables are padded to
+    on this side before they are split over ranks (0 = not padded).
     """
     assert f32_store in ("f32", "bf16")
     return dict(tp_size=tp_size, tp_rank=tp_rank, ep_size=ep_size, ep_rank=ep_rank,
-                experts_stacked=experts_stacked, f32_store=f32_store)
+                experts_stacked=experts_stacked, f32_store=f32_store, qkv_grouped=qkv_grouped,
+                padded_vocab=padded_vocab)
 
 
 def _dense(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, tied):
@@ -41,6 +47,7 @@ MODELS = {
                 expert_ffn=1408, weight_dtype="bf16", norm_dtype="f32"),
     # reduced shapes of the same families, for CPU tests and quick GPU parity
     "dense_small": _dense(3, 512, 8, 4, 64, 1536, 4096, 0),
+    "dense_small_v4000": _dense(2, 512, 8, 4, 64, 1536, 4000, 0),
     "moe_small": dict(kind="moe", n_layers=2, hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64,
                       ffn=0, vocab=2048, tied_embeddings=0, n_experts=16, n_shared_experts=2,
                       expert_ffn=176, weight_dtype="bf16", norm_dtype="f32"),
@@ -81,6 +88,21 @@ WORKLOADS = {
         model="dense_small", seed=13, chunk_bytes=256 * 1024,
         holders=[layout(4, 2), layout(4, 3)],
         reader=layout(2, 1, f32_store="bf16")),
+    # trainer-style source: group-interleaved QKV, vocabulary 4000 padded to 4096 over 4 ranks
+    "small_dense_trainer_to_rollout": dict(
+        model="dense_small_v4000", seed=16, chunk_bytes=256 * 1024,
+        holders=[layout(4, 2, qkv_grouped=1, padded_vocab=4096), layout(4, 3, qkv_grouped=1, padded_vocab=4096)],
+        reader=layout(2, 1, f32_store="bf16")),
+    # and back: rollout-style source into a trainer-style reader (fp32 norms kept)
+    "small_dense_rollout_to_trainer": dict(
+        model="dense_small_v4000", seed=17, chunk_bytes=512 * 1024,
+        holders=[layout(1, 0)],
+        reader=layout(4, 3, qkv_grouped=1, padded_vocab=4096)),
+    # stacked experts at the source, per-expert tensors at the reader
+    "small_moe_stacked_to_per_expert": dict(
+        model="moe_small", seed=18, chunk_bytes=128 * 1024,
+        holders=[layout(2, 1, experts_stacked=1)],
+        reader=layout(1, 0, ep_size=2, ep_rank=1, f32_store="bf16")),
     "small_moe_ep4_to_tp2": dict(
         model="moe_small", seed=14, chunk_bytes=128 * 1024,
         holders=[layout(1, 0, ep_size=4, ep_rank=1)],

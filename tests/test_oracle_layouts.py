@@ -37,7 +37,8 @@ def full_weights(model, seed=0):
 
 
 def shard_of(model, lay, full):
-    """Registered tensors of a rank cut from the full weights with the oracle's index vectors."""
+    """Registered tensors of a rank cut from the full weights with the oracle's index vectors
+    (padding rows of a padded vocabulary are filled with a marker)."""
     lts = layouts.logical_tensors(model)
     out = []
     for t in layouts.registered_tensors(model, lay):
@@ -45,7 +46,10 @@ def shard_of(model, lay, full):
         for li, _ in t["parts"]:
             rows, cols = layouts.shard_index(model, lts[li], lay)
             parts.append(full[li][np.ix_(rows, cols)])
-        out.append(np.concatenate(parts, axis=0))
+        a = np.concatenate(parts, axis=0)
+        if a.shape[0] < t["rows"]:
+            a = np.concatenate([a, np.full((t["rows"] - a.shape[0], a.shape[1]), 0xDEAD, dtype=a.dtype)], axis=0)
+        out.append(a)
         assert out[-1].shape == (t["rows"], t["cols"])
     return out
 
@@ -94,6 +98,76 @@ def test_shards_match_numpy_split_small_dense(T):
         for r in range(T):
             rows, cols = layouts.shard_index(model, lt, L(T, r))
             assert np.array_equal(W[np.ix_(rows, cols)], split_reference(model, lt["name"], W, T, r))
+
+
+@pytest.mark.parametrize("T", [1, 2, 4])
+def test_grouped_qkv_matches_numpy_reference(T):
+    """Trainer-style fused QKV: per KV head of the rank, its query heads, then its K, then its V."""
+    model = synth.MODELS["dense_small"]  # 8 query heads, 4 KV heads, head_dim 64
+    hd, nq, nkv = model["head_dim"], model["n_q_heads"], model["n_kv_heads"]
+    qkv = [t for t in layouts.logical_tensors(model) if t["part"] == "qkv"][0]
+    W = np.random.default_rng(7).integers(0, 1 << 16, size=(qkv["rows"], qkv["cols"]), dtype=np.uint16)
+    q, k, v = np.split(W, [nq * hd, (nq + nkv) * hd], axis=0)
+    q_groups = np.split(q, nkv, axis=0)      # query heads of KV head g
+    k_heads, v_heads = np.split(k, nkv, axis=0), np.split(v, nkv, axis=0)
+    for r in range(T):
+        mine = range(r * nkv // T, (r + 1) * nkv // T)
+        want = np.concatenate([x for g in mine for x in (q_groups[g], k_heads[g], v_heads[g])], axis=0)
+        rows, cols = layouts.shard_index(model, qkv, L(T, r, qkv_grouped=1))
+        assert np.array_equal(W[np.ix_(rows, cols)], want)
+        # same set of rows as the concatenated convention, different order
+        rows_c, _ = layouts.shard_index(model, qkv, L(T, r))
+        assert sorted(rows) == sorted(rows_c) and (T == nkv or not np.array_equal(rows, rows_c))
+
+
+@pytest.mark.parametrize("T,padded", [(4, 4096), (2, 4096), (8, 4096), (1, 4000)])
+def test_padded_vocabulary_matches_numpy_pad_then_split(T, padded):
+    model = synth.MODELS["dense_small_v4000"]
+    lts = layouts.logical_tensors(model)
+    rng = np.random.default_rng(8)
+    for li in (0, len(lts) - 1):  # embed_tokens, lm_head
+        lt = lts[li]
+        W = rng.integers(1, 1 << 16, size=(lt["rows"], lt["cols"]), dtype=np.uint16)
+        Wp = np.pad(W, ((0, padded - lt["rows"]), (0, 0)))  # zero rows = padding
+        for r in range(T):
+            lay = L(T, r, padded_vocab=padded)
+            want = np.split(Wp, T, axis=0)[r]
+            rows, cols = layouts.shard_index(model, lt, lay)
+            assert layouts.storage_rows(model, lt, lay) == want.shape[0] == padded // T
+            n_real = len(rows)
+            assert np.array_equal(W[np.ix_(rows, cols)], want[:n_real])
+            assert not want[n_real:].any()  # what is left of the rank's tensor is padding
+    with pytest.raises(ValueError):
+        layouts.shard_index(model, lts[0], L(2, 0, padded_vocab=3000))
+    with pytest.raises(ValueError):
+        layouts.shard_index(model, lts[0], L(3, 0, padded_vocab=4096))
+
+
+def test_trainer_to_rollout_and_back_is_the_identity():
+    """Grouped QKV + padded vocabulary TP=4 -> plain TP=2 -> grouped + padded TP=4: every rank gets
+    its tensors back, padding rows untouched."""
+    model = synth.MODELS["dense_small_v4000"]
+    full = full_weights(dict(model, weight_dtype="f32"))
+    model = dict(model, weight_dtype="f32")
+    trainer = [L(4, r, qkv_grouped=1, padded_vocab=4096) for r in range(4)]
+    rollout = [L(2, r) for r in range(2)]
+    t_shards = [shard_of(model, lay, full) for lay in trainer]
+    r_shards = []
+    for d in rollout:
+        out = reshard.empty_tensors(model, d, fill=0)
+        counts = [np.zeros(t.shape, dtype=np.int32) for t in out]
+        for lay, ts in zip(trainer, t_shards):
+            reshard.unpack(model, lay, d, reshard.pack(model, lay, d, ts), out, counts)
+        assert all(np.all(c == 1) for c in counts)
+        for o, wnt in zip(out, shard_of(model, d, full)):
+            assert np.array_equal(o, wnt)
+        r_shards.append(out)
+    for lay, ts in zip(trainer, t_shards):
+        back = reshard.empty_tensors(model, lay, fill=0xDEAD)
+        for d, rs in zip(rollout, r_shards):
+            reshard.unpack(model, d, lay, reshard.pack(model, d, lay, rs), back)
+        for b, t in zip(back, ts):
+            assert np.array_equal(b, t)
 
 
 def test_gqa_grouping_kept_on_one_rank():
@@ -315,7 +389,9 @@ def test_moe_expert_parallel_to_stacked_tensor_parallel():
 
 def test_wire_equals_definition_without_wire():
     """pack -> unpack lands exactly what the wire-free result definition gives, incl. narrowing of norms."""
-    for name in ("small_dense_tp1_to_tp4", "small_dense_tp4_to_tp2", "small_moe_ep4_to_tp2"):
+    for name in ("small_dense_tp1_to_tp4", "small_dense_tp4_to_tp2", "small_moe_ep4_to_tp2",
+                 "small_dense_trainer_to_rollout", "small_dense_rollout_to_trainer",
+                 "small_moe_stacked_to_per_expert"):
         w = synth.workload(name)
         model, dst = w["model"], w["reader"]
         rng = np.random.default_rng(w["seed"])
