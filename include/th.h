@@ -119,6 +119,11 @@ typedef struct th_layout {
     int tp_size, tp_rank, ep_size, ep_rank;
     int experts_stacked;
     int f32_store;
+    int qkv_grouped;  /* nonzero: fused QKV is stored per KV head g of the rank as [query heads of
+                         group g; K_g; V_g], group after group (trainer side), not [Q_r; K_r; V_r] */
+    int padded_vocab; /* 0, or the vocabulary size embed_tokens / lm_head are padded to on this side
+                         before they are split over tp_size ranks (>= vocab, divisible by tp_size).
+                         Padding rows are part of the rank's tensor but are never sent or written */
 } th_layout;
 
 /* Build the plan for holder layout `src` -> reader layout `dst` (all host

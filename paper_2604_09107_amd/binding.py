@@ -46,7 +46,8 @@ class _ModelDesc(C.Structure):
 
 
 class _Layout(C.Structure):
-    _fields_ = [(n, C.c_int) for n in ("tp_size", "tp_rank", "ep_size", "ep_rank", "experts_stacked", "f32_store")]
+    _fields_ = [(n, C.c_int) for n in ("tp_size", "tp_rank", "ep_size", "ep_rank", "experts_stacked", "f32_store",
+                                       "qkv_grouped", "padded_vocab")]
 
 
 class _Segment(C.Structure):
@@ -147,7 +148,8 @@ def _model_struct(m):
 
 def _layout_struct(l):
     return _Layout(tp_size=l["tp_size"], tp_rank=l["tp_rank"], ep_size=l["ep_size"], ep_rank=l["ep_rank"],
-                   experts_stacked=int(l["experts_stacked"]), f32_store=_DTYPE[l["f32_store"]])
+                   experts_stacked=int(l["experts_stacked"]), f32_store=_DTYPE[l["f32_store"]],
+                   qkv_grouped=int(l.get("qkv_grouped", 0)), padded_vocab=int(l.get("padded_vocab", 0)))
 
 
 class Plan:

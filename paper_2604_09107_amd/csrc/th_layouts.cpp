@@ -16,7 +16,7 @@
 namespace th {
 namespace {
 
-enum Part { P_REPL, P_SPLIT_ROWS, P_SPLIT_COLS, P_QKV, P_GATE_UP };
+enum Part { P_REPL, P_SPLIT_ROWS, P_SPLIT_COLS, P_QKV, P_GATE_UP, P_VOCAB_ROWS };
 
 struct Logical {
     std::string name;
@@ -44,7 +44,7 @@ std::vector<Logical> build_logicals(const th_model_desc& m) {
     auto add = [&](std::string name, int64_t r, int64_t c, Part p, bool norm = false, int e = -1) {
         v.push_back(Logical{std::move(name), r, c, p, norm, e});
     };
-    add("embed_tokens", m.vocab, H, P_SPLIT_ROWS);
+    add("embed_tokens", m.vocab, H, P_VOCAB_ROWS);
     for (int l = 0; l < m.n_layers; ++l) {
         const std::string p = "layers." + std::to_string(l) + ".";
         add(p + "input_norm", 1, H, P_REPL, true);
@@ -70,7 +70,7 @@ std::vector<Logical> build_logicals(const th_model_desc& m) {
         }
     }
     add("final_norm", 1, H, P_REPL, true);
-    if (!m.tied_embeddings) add("lm_head", m.vocab, H, P_SPLIT_ROWS);
+    if (!m.tied_embeddings) add("lm_head", m.vocab, H, P_VOCAB_ROWS);
     return v;
 }
 
@@ -84,11 +84,15 @@ int check_div(int64_t n, int64_t parts, const std::string& what) {
 }
 
 // Global rectangles that tensor-parallel rank r of T keeps of `lt`, top to bottom in local order.
-int shard_rects(const th_model_desc& m, const Logical& lt, int T, int r,
-                std::vector<std::array<int64_t, 4>>& out) {
+// *storage_rows receives the rows of the rank's tensor (more than the rectangles' rows when the
+// vocabulary is padded: the padding rows follow the kept ones).
+int shard_rects(const th_model_desc& m, const Logical& lt, const th_layout& lay,
+                std::vector<std::array<int64_t, 4>>& out, int64_t* storage_rows) {
     out.clear();
+    const int T = lay.tp_size, r = lay.tp_rank;
     const int64_t R = lt.rows, C = lt.cols;
     int rc;
+    *storage_rows = -1;
     switch (lt.part) {
         case P_REPL:
             out.push_back({0, 0, R, C});
@@ -97,6 +101,18 @@ int shard_rects(const th_model_desc& m, const Logical& lt, int T, int r,
             if ((rc = check_div(R, T, lt.name + " rows"))) return rc;
             out.push_back({r * (R / T), 0, R / T, C});
             break;
+        case P_VOCAB_ROWS: {
+            const int64_t padded = lay.padded_vocab ? lay.padded_vocab : R;
+            if (padded < R) {
+                set_error("padded_vocab %lld is smaller than the vocabulary %lld", (long long)padded, (long long)R);
+                return TH_ERR_ARG;
+            }
+            if ((rc = check_div(padded, T, lt.name + " (padded) rows"))) return rc;
+            const int64_t n = padded / T, lo = r * n, hi = std::min<int64_t>(R, lo + n);
+            if (hi > lo) out.push_back({lo, 0, hi - lo, C});
+            *storage_rows = n;
+            break;
+        }
         case P_SPLIT_COLS:
             if ((rc = check_div(C, T, lt.name + " columns"))) return rc;
             out.push_back({0, r * (C / T), R, C / T});
@@ -111,9 +127,20 @@ int shard_rects(const th_model_desc& m, const Logical& lt, int T, int r,
             const int64_t hd = m.head_dim;
             const int64_t q = (int64_t)m.n_q_heads / T * hd, kv = (int64_t)m.n_kv_heads / T * hd;
             const int64_t k_base = (int64_t)m.n_q_heads * hd, v_base = k_base + (int64_t)m.n_kv_heads * hd;
-            out.push_back({r * q, 0, q, C});
-            out.push_back({k_base + r * kv, 0, kv, C});
-            out.push_back({v_base + r * kv, 0, kv, C});
+            if (lay.qkv_grouped) {
+                // per KV head of the rank: its query heads, its K head, its V head
+                const int64_t per = (int64_t)(m.n_q_heads / m.n_kv_heads) * hd;
+                const int64_t g0 = (int64_t)r * (m.n_kv_heads / T), g1 = g0 + m.n_kv_heads / T;
+                for (int64_t g = g0; g < g1; ++g) {
+                    out.push_back({g * per, 0, per, C});
+                    out.push_back({k_base + g * hd, 0, hd, C});
+                    out.push_back({v_base + g * hd, 0, hd, C});
+                }
+            } else {
+                out.push_back({r * q, 0, q, C});
+                out.push_back({k_base + r * kv, 0, kv, C});
+                out.push_back({v_base + r * kv, 0, kv, C});
+            }
             break;
         }
         case P_GATE_UP: {
@@ -146,8 +173,10 @@ int build_regs(const th_model_desc& m, const std::vector<Logical>& lts, const th
     for (size_t i = 0; i < lts.size(); ++i) {
         const Logical& lt = lts[i];
         if (lt.expert >= 0 && lt.expert / experts_per_rank != lay.ep_rank) continue;
-        if (int rc = shard_rects(m, lt, lay.tp_size, lay.tp_rank, rects)) return rc;
+        int64_t storage_rows = -1;
+        if (int rc = shard_rects(m, lt, lay, rects, &storage_rows)) return rc;
         const int dt = storage_dtype(m, lt, lay);
+        const uint64_t cols = lt.part == P_SPLIT_COLS ? (uint64_t)(lt.cols / lay.tp_size) : (uint64_t)lt.cols;
         Reg* reg;
         if (lt.expert >= 0 && lay.experts_stacked) {
             // "layers.L.experts.E.w13" -> "layers.L.experts.w13"
@@ -160,7 +189,7 @@ int build_regs(const th_model_desc& m, const std::vector<Logical>& lts, const th
                 regs.emplace_back();
                 regs.back().info.name = name;
                 regs.back().info.dtype = dt;
-                regs.back().info.cols = (uint64_t)rects[0][3];
+                regs.back().info.cols = cols;
             }
             reg = &regs[it->second];
         } else {
@@ -168,12 +197,14 @@ int build_regs(const th_model_desc& m, const std::vector<Logical>& lts, const th
             reg = &regs.back();
             reg->info.name = lt.name;
             reg->info.dtype = dt;
-            reg->info.cols = (uint64_t)rects[0][3];
+            reg->info.cols = cols;
         }
+        const uint64_t rows_before = reg->info.rows;
         for (const auto& q : rects) {
             reg->blocks.push_back(Block{(int)i, q[0], q[1], q[2], q[3], (int64_t)reg->info.rows, 0});
             reg->info.rows += (uint64_t)q[2];
         }
+        if (storage_rows >= 0) reg->info.rows = rows_before + (uint64_t)storage_rows;  // padding rows follow
     }
     return TH_OK;
 }
@@ -189,8 +220,8 @@ bool supplies(const Logical& lt, const th_layout& src, const th_layout& dst) {
 
 int check_layout(const th_layout& l, const char* who) {
     if (l.tp_size < 1 || l.ep_size < 1 || l.tp_rank < 0 || l.tp_rank >= l.tp_size || l.ep_rank < 0 ||
-        l.ep_rank >= l.ep_size || (l.f32_store != TH_BF16 && l.f32_store != TH_F32)) {
-        set_error("%s layout: bad parallel size / rank / f32_store", who);
+        l.ep_rank >= l.ep_size || (l.f32_store != TH_BF16 && l.f32_store != TH_F32) || l.padded_vocab < 0) {
+        set_error("%s layout: bad parallel size / rank / f32_store / padded_vocab", who);
         return TH_ERR_ARG;
     }
     return TH_OK;

@@ -16,7 +16,9 @@ from helpers import (exec_runs_pack, exec_runs_unpack, exec_tiles, flat_u8, hold
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HOST = th.TH_FLAG_HOST_ONLY
-MODEL_WORKLOADS = ["cfg1_tiny_tp2_to_tp1", "small_dense_tp1_to_tp4", "small_dense_tp4_to_tp2", "small_moe_ep4_to_tp2"]
+MODEL_WORKLOADS = ["cfg1_tiny_tp2_to_tp1", "small_dense_tp1_to_tp4", "small_dense_tp4_to_tp2", "small_moe_ep4_to_tp2",
+                   "small_dense_trainer_to_rollout", "small_dense_rollout_to_trainer",
+                   "small_moe_stacked_to_per_expert"]
 
 
 def test_library_exports_every_declared_symbol():
@@ -247,6 +249,12 @@ def test_error_paths():
     with pytest.raises(th.ThError) as e:  # reader keeps fp32 norms but holder stores bf16: widening
         th.th_plan_create(model, synth.layout(2, 0, f32_store="bf16"), synth.layout(1, 0, f32_store="f32"), 1 << 20, HOST)
     assert e.value.code == -3
+    with pytest.raises(th.ThError) as e:  # padding smaller than the vocabulary
+        th.th_plan_create(model, synth.layout(2, 0, padded_vocab=512), dst, 1 << 20, HOST)
+    assert e.value.code == -1
+    with pytest.raises(th.ThError) as e:  # padded size not divisible by the ranks
+        th.th_plan_create(model, synth.layout(2, 0, padded_vocab=1001), dst, 1 << 20, HOST)
+    assert e.value.code == -2
     plan = th.th_plan_create(model, src, dst, 1 << 20, HOST)
     with pytest.raises(th.ThError) as e:
         th.th_pack(plan, [0] * plan.num_tensors(0), [0], 0, 1)
