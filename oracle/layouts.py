@@ -11,7 +11,9 @@ a reading, not the paper's text:
   * fused QKV, global rows [Q heads | K heads | V heads]; rank r keeps its
     contiguous range of Q heads and of K/V heads, stored as [Q_r; K_r; V_r],
     or - "grouped", the trainer-side convention - per KV head g of the rank as
-    [Q heads of group g; K_g; V_g], group after group;
+    [Q heads of group g; K_g; V_g], group after group; with more ranks than KV
+    heads (T a multiple of n_kv) rank r keeps its Q heads and a copy of the one
+    KV head they use, head r // (T / n_kv);
   * a side may pad the vocabulary of embed_tokens / lm_head to a larger size
     before splitting it; padding rows exist in the rank's tensor but belong to
     no logical weight: they are never sent and never written;
@@ -105,6 +107,14 @@ def shard_index(model, lt, lay):
         hd = model["head_dim"]
         nq, nkv = model["n_q_heads"], model["n_kv_heads"]
         q = _split(nq, T, "n_q_heads")
+        if T > nkv:
+            # KV heads are replicated: T / n_kv consecutive ranks share one
+            rep = _split(T, nkv, "tp_size over n_kv_heads")
+            g = r // rep
+            rows = np.concatenate([np.arange(r * q * hd, (r + 1) * q * hd),
+                                   nq * hd + np.arange(g * hd, (g + 1) * hd),
+                                   (nq + nkv) * hd + np.arange(g * hd, (g + 1) * hd)])
+            return rows, cols
         kv = _split(nkv, T, "n_kv_heads")
         if lay.get("qkv_grouped", 0):
             per = nq // nkv  # query heads per KV head
@@ -171,6 +181,24 @@ def registered_tensors(model, lay):
             out.append(dict(name=lt["name"], dtype=dt, rows=storage_rows(model, lt, lay), cols=len(cols),
                             parts=[(i, 0)]))
     return out
+
+
+def row_supply_mask(model, lt, src, dst):
+    """For data that only some of the holder ranks replicate - K/V heads when the holders have
+    more ranks than KV heads - which of this holder's rows it sends to reader `dst`: of the rep_s
+    holders that keep a head, reader number j of the rep_d readers that want it (rep_d = 1 if the
+    readers do not replicate) pulls from copy floor(j * rep_s / rep_d)."""
+    rows, _ = shard_index(model, lt, src)
+    mask = np.ones(len(rows), dtype=bool)
+    nkv = model["n_kv_heads"]
+    if lt["part"] == "qkv" and src["tp_size"] > nkv:
+        rep_s = src["tp_size"] // nkv
+        rep_d = max(1, dst["tp_size"] // nkv)
+        mine = src["tp_rank"] % rep_s
+        wanted = ((dst["tp_rank"] % rep_d) * rep_s) // rep_d
+        is_kv = rows >= model["n_q_heads"] * model["head_dim"]
+        mask[is_kv] = mine == wanted
+    return mask
 
 
 def supplies(model, lt, src, dst):

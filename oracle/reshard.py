@@ -60,7 +60,7 @@ def plan_items(model, src, dst):
             did, drow0 = where_dst[li]
             s_rows, s_cols = layouts.shard_index(model, lt, src)
             d_rows, d_cols = layouts.shard_index(model, lt, dst)
-            r_need = np.isin(s_rows, d_rows)
+            r_need = np.isin(s_rows, d_rows) & layouts.row_supply_mask(model, lt, src, dst)
             c_need = np.isin(s_cols, d_cols)
             if not r_need.any() or not c_need.any():
                 continue
@@ -163,10 +163,11 @@ def reshard_by_definition(model, holders, holder_tensors, dst):
                     continue
                 sid, srow0, sdt = _find_part(layouts.registered_tensors(model, lay), li)
                 rows, cols = layouts.shard_index(model, lt, lay)
+                sends = layouts.row_supply_mask(model, lt, lay, dst)  # partly replicated rows: one sender
                 if full is None:
                     full = np.zeros((lt["rows"], lt["cols"]), dtype=NPBITS[sdt])
-                full[np.ix_(rows, cols)] = tensors[sid][srow0:srow0 + len(rows), :]
-                have[np.ix_(rows, cols)] += 1
+                full[np.ix_(rows[sends], cols)] = tensors[sid][srow0:srow0 + len(rows), :][sends]
+                have[np.ix_(rows[sends], cols)] += 1
             if full is None:
                 continue
             assert have.max() <= 1, "two holders supplied the same element"

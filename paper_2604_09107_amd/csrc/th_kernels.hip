@@ -173,6 +173,21 @@ template <int SUM>
 __device__ __forceinline__ void copy_vec(gsrc_t src, gdst_t dst, uint64_t ss, uint64_t ds, uint32_t count,
                                          uint32_t vpr, uint32_t col0, uint32_t magic, Sum& acc) {
     const uint32_t tid = threadIdx.x;
+    if (count <= kBlockThreads) {
+        // the default tile: one vector per thread, nothing else
+        if (tid < count) {
+            const uint32_t x = col0 + tid;
+            const uint32_t row = div_rows(x, vpr, magic);
+            const uint32_t col = x - row * vpr;
+            const u32x4 v = ld16(src + (size_t)row * ss + (size_t)col * 16);
+            st16(dst + (size_t)row * ds + (size_t)col * 16, v);
+            if (SUM) {
+                const uint64_t rel = (uint64_t)row * (SUM == 1 ? ds : ss) + (uint64_t)col * 16;
+                sum_halves(acc, v, 0, 8, (int64_t)(rel / 2));
+            }
+        }
+        return;
+    }
     constexpr uint32_t kStep = kBlockThreads * kUnroll;
     for (uint32_t base = 0; base < count; base += kStep) {
         u32x4 v[kUnroll];

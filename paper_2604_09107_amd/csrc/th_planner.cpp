@@ -318,6 +318,9 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
     for (int side = 0; side < 2; ++side) {
         std::vector<Tile> tiles;
         std::vector<uint64_t> base;
+        const size_t guess = (size_t)(m.payload_bytes / std::min(tune.tile_bytes, tune.tile_bytes_any)) + 2 * m.runs.size();
+        tiles.reserve(guess);
+        base.reserve(guess);
         for (size_t ri = 0; ri < m.runs.size(); ++ri) {
             const th_run& r = m.runs[ri];
             const unsigned es_s = esize(r.src_dtype), es_w = esize(r.dst_dtype);
@@ -344,18 +347,7 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
         }
         auto chunk_of = [side](const Tile& t) { return side == 0 ? t.dst_buf : t.src_buf; };
         auto class_of = [](const Tile& t) { return (t.flags & TILE_KIND_MASK) == TILE_KIND_VEC ? 0u : 1u; };
-        std::vector<uint32_t> order(tiles.size());
-        for (size_t i = 0; i < order.size(); ++i) order[i] = (uint32_t)i;
-        std::stable_sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) {
-            const Tile &a = tiles[x], &b = tiles[y];
-            return class_of(a) != class_of(b) ? class_of(a) < class_of(b) : chunk_of(a) < chunk_of(b);
-        });
-        m.tiles[side].resize(tiles.size());
-        m.tile_base[side].resize(tiles.size());
-        for (size_t i = 0; i < order.size(); ++i) {
-            m.tiles[side][i] = tiles[order[i]];
-            m.tile_base[side][i] = base[order[i]];
-        }
+        // counting sort by (class, chunk): stable, one pass
         uint64_t n_class[2] = {0, 0};
         for (const Tile& t : tiles) n_class[class_of(t)]++;
         for (unsigned k = 0; k < 2; ++k) {
@@ -366,11 +358,20 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
             first[0] = k == 0 ? 0 : n_class[0];
             for (size_t c = 0; c < m.n_chunks; ++c) first[c + 1] += first[c];
         }
+        std::vector<uint64_t> cursor[2] = {m.chunk_tile0[side][0], m.chunk_tile0[side][1]};
+        m.tiles[side].resize(tiles.size());
+        m.tile_base[side].resize(tiles.size());
+        for (size_t i = 0; i < tiles.size(); ++i) {
+            const uint64_t pos = cursor[class_of(tiles[i])][chunk_of(tiles[i])]++;
+            m.tiles[side][pos] = tiles[i];
+            m.tile_base[side][pos] = base[i];
+        }
     }
 
     // ---- direct list: holder tensors -> reader tensors without the wire, one pass over the segments ----
     {
         std::vector<Tile>& tiles = m.tiles[2];
+        tiles.reserve((size_t)(m.payload_bytes / std::min(tune.tile_bytes, tune.tile_bytes_any)) + 2 * m.segments.size());
         for (const Segment& g : m.segments) {
             const unsigned es_s = esize(g.src_dtype), es_d = esize(g.dst_dtype);
             const Side S{g.src_tensor, g.src_off * es_s, g.src_stride * es_s, es_s};

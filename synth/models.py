@@ -48,6 +48,7 @@ MODELS = {
     # reduced shapes of the same families, for CPU tests and quick GPU parity
     "dense_small": _dense(3, 512, 8, 4, 64, 1536, 4096, 0),
     "dense_small_v4000": _dense(2, 512, 8, 4, 64, 1536, 4000, 0),
+    "dense_small_kv": _dense(2, 512, 16, 4, 32, 1024, 2048, 0),  # 16 query heads over 4 KV heads
     "moe_small": dict(kind="moe", n_layers=2, hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64,
                       ffn=0, vocab=2048, tied_embeddings=0, n_experts=16, n_shared_experts=2,
                       expert_ffn=176, weight_dtype="bf16", norm_dtype="f32"),
@@ -98,6 +99,16 @@ WORKLOADS = {
         model="dense_small_v4000", seed=17, chunk_bytes=512 * 1024,
         holders=[layout(1, 0)],
         reader=layout(4, 3, qkv_grouped=1, padded_vocab=4096)),
+    # more ranks than KV heads on the holder side (each KV head kept by two ranks)
+    "small_dense_kvrep_tp8_to_tp2": dict(
+        model="dense_small_kv", seed=19, chunk_bytes=128 * 1024,
+        holders=[layout(8, 4), layout(8, 5), layout(8, 6), layout(8, 7)],
+        reader=layout(2, 1, f32_store="bf16")),
+    # ... and on the reader side
+    "small_dense_kvrep_tp2_to_tp16": dict(
+        model="dense_small_kv", seed=20, chunk_bytes=128 * 1024,
+        holders=[layout(2, 1)],
+        reader=layout(16, 13, f32_store="bf16")),
     # stacked experts at the source, per-expert tensors at the reader
     "small_moe_stacked_to_per_expert": dict(
         model="moe_small", seed=18, chunk_bytes=128 * 1024,

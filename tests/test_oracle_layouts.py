@@ -189,8 +189,49 @@ def test_indivisible_split_is_an_error():
     emb = layouts.logical_tensors(model)[0]
     with pytest.raises(ValueError):
         layouts.shard_index(model, emb, L(2, 0))
-    with pytest.raises(ValueError):  # 4 ranks, 2 kv heads: would need KV replication
-        layouts.shard_index(tiny_model(), layouts.logical_tensors(tiny_model())[2], L(4, 0))
+    with pytest.raises(ValueError):  # 3 ranks over 2 KV heads / 4 query heads
+        layouts.shard_index(tiny_model(), layouts.logical_tensors(tiny_model())[2], L(3, 0))
+
+
+@pytest.mark.parametrize("T", [8, 16])
+def test_replicated_kv_heads_match_numpy_reference(T):
+    """More ranks than KV heads: every rank keeps its query heads and a copy of their KV head."""
+    model = synth.MODELS["dense_small_kv"]  # 16 query heads, 4 KV heads
+    hd, nq, nkv = model["head_dim"], model["n_q_heads"], model["n_kv_heads"]
+    qkv = [t for t in layouts.logical_tensors(model) if t["part"] == "qkv"][0]
+    W = np.random.default_rng(9).integers(0, 1 << 16, size=(qkv["rows"], qkv["cols"]), dtype=np.uint16)
+    q, k, v = np.split(W, [nq * hd, (nq + nkv) * hd], axis=0)
+    for r in range(T):
+        g = r * nkv // T
+        want = np.concatenate([np.split(q, T, 0)[r], np.split(k, nkv, 0)[g], np.split(v, nkv, 0)[g]], 0)
+        rows, cols = layouts.shard_index(model, qkv, L(T, r))
+        assert np.array_equal(W[np.ix_(rows, cols)], want)
+        # the rank's query heads all use the KV head it keeps
+        q_heads = set(rows[rows < nq * hd] // hd)
+        assert {h // (nq // nkv) for h in q_heads} == {g}
+
+
+@pytest.mark.parametrize("S,D", [(8, 2), (8, 4), (8, 16), (16, 8), (2, 8), (8, 8), (16, 1)])
+def test_replicated_kv_every_reader_element_written_exactly_once(S, D):
+    model = dict(synth.MODELS["dense_small_kv"], n_layers=1, weight_dtype="f32")
+    full = full_weights(model)
+    for d in range(D):
+        dst, out, counts, payload = run_reader(model, S, D, d, full)
+        want = shard_of(model, dst, full)
+        for o, wnt, c in zip(out, want, counts):
+            assert np.all(c == 1)
+            assert np.array_equal(o, wnt)
+        assert payload == sum(o.size * 4 for o in out)
+    # the copies of a KV head are pulled evenly: with S = 16 holders, D = 8 readers the two readers
+    # that share KV head 0 use different holder copies
+    if (S, D) == (16, 8):
+        qkv = [t for t in layouts.logical_tensors(model) if t["part"] == "qkv"][0]
+        senders = {d: [s for s in range(S) if (layouts.row_supply_mask(model, qkv, L(S, s), L(D, d))
+                                                & np.isin(layouts.shard_index(model, qkv, L(S, s))[0],
+                                                          layouts.shard_index(model, qkv, L(D, d))[0])
+                                                & (layouts.shard_index(model, qkv, L(S, s))[0] >= 16 * 32)).any()]
+                   for d in (0, 1)}
+        assert len(senders[0]) == 1 and len(senders[1]) == 1 and senders[0] != senders[1]
 
 
 def test_registration_order_and_names():
@@ -391,7 +432,8 @@ def test_wire_equals_definition_without_wire():
     """pack -> unpack lands exactly what the wire-free result definition gives, incl. narrowing of norms."""
     for name in ("small_dense_tp1_to_tp4", "small_dense_tp4_to_tp2", "small_moe_ep4_to_tp2",
                  "small_dense_trainer_to_rollout", "small_dense_rollout_to_trainer",
-                 "small_moe_stacked_to_per_expert"):
+                 "small_moe_stacked_to_per_expert", "small_dense_kvrep_tp8_to_tp2",
+                 "small_dense_kvrep_tp2_to_tp16"):
         w = synth.workload(name)
         model, dst = w["model"], w["reader"]
         rng = np.random.default_rng(w["seed"])
