@@ -104,7 +104,9 @@ typedef struct th_model_desc {
  *   vocab-parallel embed_tokens split rows, row-parallel o_proj / down_proj / w2
  *   split columns, norms and router are replicated.  Fused QKV is [Q heads | K
  *   heads | V heads] globally and [Q_r; K_r; V_r] locally with contiguous head
- *   ranges (needs tp_size | n_kv_heads); fused gate_up is [gate | up] globally
+ *   ranges; tp_size must divide n_kv_heads, or be a multiple of it, in which
+ *   case tp_size / n_kv_heads consecutive ranks each keep a copy of one KV head
+ *   next to their own query heads.  Fused gate_up is [gate | up] globally
  *   and [gate_r; up_r] locally.
  *   expert parallel: rank p keeps routed experts [p*E/P, (p+1)*E/P) whole.
  *   experts_stacked: the rank's routed experts live in one tensor per layer and

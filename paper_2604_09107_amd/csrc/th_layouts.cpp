@@ -31,6 +31,7 @@ struct Logical {
 struct Block {
     int logical;
     int64_t g_r0, g_c0, nr, nc, l_r0, l_c0;
+    int rep_index = 0, rep_count = 1;  // this rank's copy number among the ranks that keep the block
 };
 
 struct Reg {
@@ -84,11 +85,13 @@ int check_div(int64_t n, int64_t parts, const std::string& what) {
 }
 
 // Global rectangles that tensor-parallel rank r of T keeps of `lt`, top to bottom in local order.
+// *kv_rep: > 1 when the rectangles after the first are K/V heads that kv_rep ranks keep copies of.
 // *storage_rows receives the rows of the rank's tensor (more than the rectangles' rows when the
 // vocabulary is padded: the padding rows follow the kept ones).
 int shard_rects(const th_model_desc& m, const Logical& lt, const th_layout& lay,
-                std::vector<std::array<int64_t, 4>>& out, int64_t* storage_rows) {
+                std::vector<std::array<int64_t, 4>>& out, int64_t* storage_rows, int* kv_rep) {
     out.clear();
+    *kv_rep = 1;
     const int T = lay.tp_size, r = lay.tp_rank;
     const int64_t R = lt.rows, C = lt.cols;
     int rc;
@@ -119,12 +122,25 @@ int shard_rects(const th_model_desc& m, const Logical& lt, const th_layout& lay,
             break;
         case P_QKV: {
             if ((rc = check_div(m.n_q_heads, T, "n_q_heads"))) return rc;
+            const int64_t hd = m.head_dim;
+            if (T > m.n_kv_heads) {
+                // more ranks than KV heads: T / n_kv consecutive ranks keep copies of one KV head
+                if (T % m.n_kv_heads) {
+                    set_error("tp_size %d is neither a divisor nor a multiple of n_kv_heads %d", T, m.n_kv_heads);
+                    return TH_ERR_UNSUPPORTED;
+                }
+                const int rep = T / m.n_kv_heads;
+                const int64_t g = r / rep, qrows = (int64_t)m.n_q_heads / T * hd;
+                out.push_back({r * qrows, 0, qrows, C});
+                out.push_back({(int64_t)m.n_q_heads * hd + g * hd, 0, hd, C});
+                out.push_back({(int64_t)(m.n_q_heads + m.n_kv_heads) * hd + g * hd, 0, hd, C});
+                *kv_rep = rep;
+                break;
+            }
             if (m.n_kv_heads % T) {
-                set_error("tp_size %d does not divide n_kv_heads %d (KV-head replication is not supported)",
-                          T, m.n_kv_heads);
+                set_error("tp_size %d is neither a divisor nor a multiple of n_kv_heads %d", T, m.n_kv_heads);
                 return TH_ERR_UNSUPPORTED;
             }
-            const int64_t hd = m.head_dim;
             const int64_t q = (int64_t)m.n_q_heads / T * hd, kv = (int64_t)m.n_kv_heads / T * hd;
             const int64_t k_base = (int64_t)m.n_q_heads * hd, v_base = k_base + (int64_t)m.n_kv_heads * hd;
             if (lay.qkv_grouped) {
@@ -174,7 +190,8 @@ int build_regs(const th_model_desc& m, const std::vector<Logical>& lts, const th
         const Logical& lt = lts[i];
         if (lt.expert >= 0 && lt.expert / experts_per_rank != lay.ep_rank) continue;
         int64_t storage_rows = -1;
-        if (int rc = shard_rects(m, lt, lay, rects, &storage_rows)) return rc;
+        int kv_rep = 1;
+        if (int rc = shard_rects(m, lt, lay, rects, &storage_rows, &kv_rep)) return rc;
         const int dt = storage_dtype(m, lt, lay);
         const uint64_t cols = lt.part == P_SPLIT_COLS ? (uint64_t)(lt.cols / lay.tp_size) : (uint64_t)lt.cols;
         Reg* reg;
@@ -200,8 +217,14 @@ int build_regs(const th_model_desc& m, const std::vector<Logical>& lts, const th
             reg->info.cols = cols;
         }
         const uint64_t rows_before = reg->info.rows;
-        for (const auto& q : rects) {
-            reg->blocks.push_back(Block{(int)i, q[0], q[1], q[2], q[3], (int64_t)reg->info.rows, 0});
+        for (size_t k = 0; k < rects.size(); ++k) {
+            const auto& q = rects[k];
+            Block b{(int)i, q[0], q[1], q[2], q[3], (int64_t)reg->info.rows, 0};
+            if (kv_rep > 1 && k > 0) {
+                b.rep_index = lay.tp_rank % kv_rep;
+                b.rep_count = kv_rep;
+            }
+            reg->blocks.push_back(b);
             reg->info.rows += (uint64_t)q[2];
         }
         if (storage_rows >= 0) reg->info.rows = rows_before + (uint64_t)storage_rows;  // padding rows follow
@@ -278,6 +301,12 @@ int build_model_segments(const th_model_desc& m, const th_layout& src, const th_
         pieces.clear();
         for (const Block& b : sr.blocks) {
             if (!supplies(lts[b.logical], src, dst)) continue;
+            if (b.rep_count > 1) {
+                // of the holders that keep a copy, reader number j of the rep_d readers that want the
+                // block pulls from copy floor(j * rep_s / rep_d)
+                const int rep_d = std::max(1, dst.tp_size / m.n_kv_heads);
+                if (b.rep_index != (dst.tp_rank % rep_d) * b.rep_count / rep_d) continue;
+            }
             for (const auto& db : dst_of[b.logical]) {
                 const Block& d = db.second;
                 const int64_t r0 = std::max(b.g_r0, d.g_r0), r1 = std::min(b.g_r0 + b.nr, d.g_r0 + d.nr);

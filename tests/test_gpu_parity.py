@@ -67,7 +67,8 @@ def assert_same(got, want, names=None):
 @pytest.mark.parametrize("pattern", [False, True])
 @pytest.mark.parametrize("name", ["cfg1_tiny_tp2_to_tp1", "small_dense_tp1_to_tp4", "small_dense_tp4_to_tp2",
                                   "small_moe_ep4_to_tp2", "small_dense_trainer_to_rollout",
-                                  "small_dense_rollout_to_trainer", "small_moe_stacked_to_per_expert"])
+                                  "small_dense_rollout_to_trainer", "small_moe_stacked_to_per_expert",
+                                  "small_dense_kvrep_tp8_to_tp2", "small_dense_kvrep_tp2_to_tp16"])
 def test_model_workloads_bit_exact(name, pattern):
     w = synth.workload(name)
     got, want = run_model_workload(w, pattern)
@@ -303,7 +304,8 @@ def test_aligned_rows_of_one_to_five_vectors():
 
 @pytest.mark.parametrize("name", ["cfg1_tiny_tp2_to_tp1", "small_dense_tp1_to_tp4", "small_dense_tp4_to_tp2",
                                   "small_moe_ep4_to_tp2", "small_dense_trainer_to_rollout",
-                                  "small_dense_rollout_to_trainer", "small_moe_stacked_to_per_expert"])
+                                  "small_dense_rollout_to_trainer", "small_moe_stacked_to_per_expert",
+                                  "small_dense_kvrep_tp8_to_tp2", "small_dense_kvrep_tp2_to_tp16"])
 def test_direct_reshard_matches_wire_free_definition(name):
     """th_reshard (no wire) against the oracle's result definition, untouched elements keep the sentinel."""
     w = synth.workload(name)

@@ -18,7 +18,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HOST = th.TH_FLAG_HOST_ONLY
 MODEL_WORKLOADS = ["cfg1_tiny_tp2_to_tp1", "small_dense_tp1_to_tp4", "small_dense_tp4_to_tp2", "small_moe_ep4_to_tp2",
                    "small_dense_trainer_to_rollout", "small_dense_rollout_to_trainer",
-                   "small_moe_stacked_to_per_expert"]
+                   "small_moe_stacked_to_per_expert", "small_dense_kvrep_tp8_to_tp2", "small_dense_kvrep_tp2_to_tp16"]
 
 
 def test_library_exports_every_declared_symbol():
@@ -237,8 +237,8 @@ def test_error_paths():
     with pytest.raises(th.ThError) as e:
         th.th_plan_create(dict(model, vocab=1001), src, dst, 1 << 20, HOST)
     assert e.value.code == -2 and "vocab" in str(e.value) or "embed" in str(e.value)
-    with pytest.raises(th.ThError) as e:  # 4 ranks, 2 KV heads
-        th.th_plan_create(model, synth.layout(4, 0), dst, 1 << 20, HOST)
+    with pytest.raises(th.ThError) as e:  # 3 ranks over 6 query / 2 KV heads: neither divisor nor multiple
+        th.th_plan_create(dict(model, n_q_heads=6, hidden=384, vocab=999), synth.layout(3, 0), dst, 1 << 20, HOST)
     assert e.value.code == -3
     with pytest.raises(th.ThError) as e:
         th.th_plan_create(model, src, dst, 1000, HOST)  # not a multiple of 16
