@@ -293,6 +293,23 @@ def main():
     checksum_ms = c0.elapsed_time(c1) / 10
     checksums_agree = all(bool((ps == us).all()) for ps, us in sums)
 
+    # streaming use: one call per chunk (a reader consuming the prefix that has arrived)
+    def per_chunk_sweep():
+        for j in jobs:
+            for c in range(j["plan"].num_chunks):
+                th.th_pack(j["plan"], j["src_ptrs"], j["wptrs"][c:c + 1], c, 1, stream)
+        for j in jobs:
+            for c in range(j["plan"].num_chunks):
+                th.th_unpack(j["plan"], j["wptrs"][c:c + 1], c, 1, dst_ptrs, stream)
+
+    per_chunk_sweep()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(3):
+        per_chunk_sweep()
+    torch.cuda.synchronize()
+    per_chunk_ms = (time.perf_counter() - t0) / 3 * 1e3
+
     # offload replica: wire chunks in pinned host memory, written / read over the host link
     offload = None
     if args.offload:
@@ -333,6 +350,8 @@ def main():
                     "th_unpack": {"ms": round(unpack_ms, 4), "GB/s": round(k_unpack, 1)}},
         "checksum_sweep": {"ms": round(checksum_ms, 4), "GB/s": round(sweep_bytes / (checksum_ms * 1e-3) / 1e9, 1),
                            "pack_and_unpack_sums_agree": checksums_agree},
+        "per_chunk_calls_sweep": {"ms": round(per_chunk_ms, 4), "calls": 2 * sum(j["plan"].num_chunks for j in jobs),
+                                  "GB/s": round(sweep_bytes / (per_chunk_ms * 1e-3) / 1e9, 1)},
         "th_reshard_direct": {"ms": round(direct_ms, 4), "GB/s": round(direct_bytes / (direct_ms * 1e-3) / 1e9, 1)},
         "d2d_copy_GB/s": {"torch_copy_": round(copy_gbps, 1), "th_reference_copy": round(ref_gbps, 1)},
         "roofline": {"bound": "hbm", "kernel": dom[0], "achieved": round(dom[1], 1), "peak": HBM_PEAK_GBPS,

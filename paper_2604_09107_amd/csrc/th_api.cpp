@@ -251,26 +251,36 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
     }
     if (ntiles[0] + ntiles[1] == 0) return TH_OK;
 
-    std::vector<uintptr_t> wkey((size_t)chunk_count + 1);
-    wkey[0] = chunk_first;  // entry 0 of the uploaded table is skipped by the kernel's indexing
-    for (uint32_t i = 0; i < chunk_count; ++i) wkey[i + 1] = reinterpret_cast<uintptr_t>(wire_ptrs[i]);
-
+    for (uint32_t i = 0; i < chunk_count; ++i) {
+        const uintptr_t a = reinterpret_cast<uintptr_t>(wire_ptrs[i]);
+        if (a == 0 || a % 16) {
+            set_error("wire pointer %u is NULL or not 16-byte aligned", i);
+            return TH_ERR_ARG;
+        }
+    }
     std::lock_guard<std::mutex> lk(p->mu);
     PtrSlot* ts = nullptr;
     if (int rc = tensor_table(p, side, tensor_ptrs, n_tensors, &ts)) return rc;
-    bool fresh = false;
-    PtrSlot* ws = p->wire_cache[side].get(wkey, fresh);
-    if (!ws) return TH_ERR_HIP;
-    if (fresh) {
-        for (uint32_t i = 0; i < chunk_count; ++i)
-            if (wkey[i + 1] == 0 || wkey[i + 1] % 16) {
-                ws->host.clear();
-                set_error("wire pointer %u is NULL or not 16-byte aligned", i);
-                return TH_ERR_ARG;
-            }
+    // Short chunk ranges carry their wire pointers in the kernel arguments; longer ones use a
+    // cached device table whose entry 0 is skipped by the kernel's indexing.
+    InlineWire inl;
+    std::memset(&inl, 0, sizeof inl);
+    PtrSlot* ws = nullptr;
+    const void* const* wire_tab = nullptr;
+    if (chunk_count <= kInlineChunks) {
+        inl.n = chunk_count;
+        for (uint32_t i = 0; i < chunk_count; ++i) inl.p[i] = const_cast<void*>(wire_ptrs[i]);
+    } else {
+        std::vector<uintptr_t> wkey((size_t)chunk_count + 1);
+        wkey[0] = chunk_first;
+        for (uint32_t i = 0; i < chunk_count; ++i) wkey[i + 1] = reinterpret_cast<uintptr_t>(wire_ptrs[i]);
+        bool fresh = false;
+        ws = p->wire_cache[side].get(wkey, fresh);
+        if (!ws) return TH_ERR_HIP;
+        wire_tab = reinterpret_cast<const void* const*>(ws->dev + 1);
     }
-    const void* const* wire_tab = reinterpret_cast<const void* const*>(ws->dev + 1);
     const void* const* tens_tab = reinterpret_cast<const void* const*>(ts->dev);
+    if (!wire_tab) wire_tab = tens_tab;  // never read in inline mode, but keep it a valid device address
     int rc = TH_OK;
     for (int k = 0; k < 2 && rc == TH_OK; ++k) {
         if (!ntiles[k]) continue;
@@ -278,16 +288,17 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
         uint64_t* partials = want_sums ? p->d_partials[side] : nullptr;
         if (side == 0)
             rc = launch_tiles(MODE_PACK, vec_only, p->d_tiles[0], tile0[k], ntiles[k], tens_tab,
-                              const_cast<void* const*>(wire_tab), chunk_first, partials, stream);
+                              const_cast<void* const*>(wire_tab), chunk_first, inl, partials, stream);
         else
             rc = launch_tiles(MODE_UNPACK, vec_only, p->d_tiles[1], tile0[k], ntiles[k], wire_tab,
-                              const_cast<void* const*>(tens_tab), chunk_first, partials, stream);
+                              const_cast<void* const*>(tens_tab), chunk_first, inl, partials, stream);
         if (rc == TH_OK && want_sums)
             rc = launch_checksum_finalize(p->d_tiles[side], p->d_partials[side], p->d_tile_base[side], tile0[k],
                                           ntiles[k], sums, stream);
     }
     if (rc != TH_OK) return rc;
     for (PtrSlot* s : {ts, ws}) {
+        if (!s) continue;
         hipError_t e = hipEventRecord(s->used, static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return hip_fail(e, "hipEventRecord");
         s->recorded = true;
@@ -408,13 +419,15 @@ int th_reshard(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, vo
     if (int rc = tensor_table(p, 1, const_cast<const void* const*>(dst_ptrs), n_dst, &ds)) return rc;
     const void* const* stab = reinterpret_cast<const void* const*>(ss->dev);
     void* const* dtab = reinterpret_cast<void* const*>(ds->dev);
+    InlineWire no_inline;
+    std::memset(&no_inline, 0, sizeof no_inline);
     int rc = TH_OK;
     if (m.direct_n_vec)
-        rc = launch_tiles(MODE_DIRECT, p->specialize, p->d_tiles[2], 0, m.direct_n_vec, stab, dtab, 0, nullptr,
-                          hip_stream);
+        rc = launch_tiles(MODE_DIRECT, p->specialize, p->d_tiles[2], 0, m.direct_n_vec, stab, dtab, 0, no_inline,
+                          nullptr, hip_stream);
     if (rc == TH_OK && total > m.direct_n_vec)
         rc = launch_tiles(MODE_DIRECT, false, p->d_tiles[2], m.direct_n_vec, total - m.direct_n_vec, stab, dtab, 0,
-                          nullptr, hip_stream);
+                          no_inline, nullptr, hip_stream);
     if (rc != TH_OK) return rc;
     for (PtrSlot* s : {ss, ds}) {
         hipError_t e = hipEventRecord(s->used, static_cast<hipStream_t>(hip_stream));

@@ -123,11 +123,18 @@ inline unsigned esize(int dtype) { return dtype == TH_F32 ? 4u : 2u; }
 // direct: neither).  wire_first: chunk index that entry 0 of the wire pointer table stands for.
 // vec_only: every tile of the range is KIND_VEC (selects the kernel without the other paths).
 enum TileMode { MODE_PACK = 0, MODE_UNPACK = 1, MODE_DIRECT = 2 };
+// Wire chunk pointers of a short chunk range travel in the kernel arguments instead of a device
+// table, so that chunk-by-chunk calls (a reader consuming a prefix) upload nothing.
+constexpr uint32_t kInlineChunks = 8;
+struct InlineWire {
+    void* p[kInlineChunks];
+    uint32_t n;  // 0: use the device table
+};
 // partials: nullptr, or device array of 2 x uint64 per tile of `tiles` (same indexing) that receives
 // each tile's checksum terms (A, B with tile-local positions).
 int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first,
-                 uint64_t* partials, void* stream);
+                 const InlineWire& inl, uint64_t* partials, void* stream);
 // Adds the per-tile terms of tiles [tile0, tile0 + ntiles) into sums[2 * src_tensor + {0, 1}].
 int launch_checksum_finalize(const Tile* tiles, const uint64_t* partials, const uint64_t* tile_base,
                              uint64_t tile0, uint64_t ntiles, uint64_t* sums, void* stream);

@@ -37,6 +37,11 @@ typedef TH_GLOBAL char* gdst_t;
 struct __attribute__((packed, aligned(2))) Unaligned2 { u32x4 v; };
 struct __attribute__((packed, aligned(4))) Unaligned4 { u32x4 v; };
 
+// Two workgroups of 1024 threads per compute unit = 8 wavefronts per SIMD, which caps a wavefront
+// at 64 vector registers.
+#ifndef TH_MIN_WAVES_PER_EU
+#define TH_MIN_WAVES_PER_EU 8
+#endif
 #ifndef TH_UNROLL
 #define TH_UNROLL 4
 #endif
@@ -415,10 +420,10 @@ __device__ __forceinline__ void copy_any(gsrc_t src, gdst_t dst, uint64_t ss, ui
 }
 
 template <int MODE, bool VEC_ONLY, bool CHECKSUM>
-__global__ __launch_bounds__(kBlockThreads) void th_tiles_kernel(const Tile* __restrict__ tiles,
+__global__ __launch_bounds__(kBlockThreads, TH_MIN_WAVES_PER_EU) void th_tiles_kernel(const Tile* __restrict__ tiles,
                                                                   const void* const* __restrict__ src_table,
                                                                   void* const* __restrict__ dst_table,
-                                                                  uint32_t wire_first,
+                                                                  uint32_t wire_first, InlineWire inl,
                                                                   uint64_t* __restrict__ partials) {
     // Workgroups are dealt to the 8 XCDs round-robin (workgroup b runs on XCD b mod 8).  Give
     // each XCD one contiguous eighth of the tile list so that it streams through its own
@@ -435,8 +440,10 @@ __global__ __launch_bounds__(kBlockThreads) void th_tiles_kernel(const Tile* __r
     constexpr int SUM = !CHECKSUM ? 0 : (PACK ? 1 : 2);
     const uint32_t sb = MODE == MODE_UNPACK ? t.src_buf - wire_first : t.src_buf;
     const uint32_t db = MODE == MODE_PACK ? t.dst_buf - wire_first : t.dst_buf;
-    gsrc_t src = (gsrc_t)(static_cast<const char*>(src_table[sb]) + t.src_off);
-    gdst_t dst = (gdst_t)(static_cast<char*>(dst_table[db]) + t.dst_off);
+    const void* sbase = (MODE == MODE_UNPACK && inl.n) ? inl.p[sb] : src_table[sb];
+    void* dbase = (MODE == MODE_PACK && inl.n) ? inl.p[db] : dst_table[db];
+    gsrc_t src = (gsrc_t)(static_cast<const char*>(sbase) + t.src_off);
+    gdst_t dst = (gdst_t)(static_cast<char*>(dbase) + t.dst_off);
     const uint32_t kind = VEC_ONLY ? (uint32_t)TILE_KIND_VEC : (flags & TILE_KIND_MASK);
     Sum acc;
 
@@ -531,11 +538,11 @@ __global__ __launch_bounds__(kBlockThreads) void th_reference_copy_kernel(const 
 }  // namespace
 
 int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
-                 const void* const* src_table, void* const* dst_table, uint32_t wire_first, uint64_t* partials,
-                 void* stream) {
+                 const void* const* src_table, void* const* dst_table, uint32_t wire_first, const InlineWire& inl,
+                 uint64_t* partials, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     constexpr uint64_t kMaxGrid = 1u << 30;
-    typedef void (*kernel_t)(const Tile*, const void* const*, void* const*, uint32_t, uint64_t*);
+    typedef void (*kernel_t)(const Tile*, const void* const*, void* const*, uint32_t, InlineWire, uint64_t*);
     static const kernel_t kernels[3][2][2] = {
         {{th_tiles_kernel<MODE_PACK, false, false>, th_tiles_kernel<MODE_PACK, false, true>},
          {th_tiles_kernel<MODE_PACK, true, false>, th_tiles_kernel<MODE_PACK, true, true>}},
@@ -550,7 +557,7 @@ int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uin
     while (ntiles) {
         const uint64_t n = ntiles < kMaxGrid ? ntiles : kMaxGrid;
         hipLaunchKernelGGL(kernel, dim3((uint32_t)n), dim3(kBlockThreads), 0, st, tiles + tile0, src_table,
-                           dst_table, wire_first, partials ? partials + 2 * tile0 : nullptr);
+                           dst_table, wire_first, inl, partials ? partials + 2 * tile0 : nullptr);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) {
             set_error("kernel launch failed: %s", hipGetErrorString(e));

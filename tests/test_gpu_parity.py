@@ -415,3 +415,65 @@ def test_wire_chunks_in_pinned_host_memory():
     reshard.unpack(model, src, dst, wire, want)
     assert_same([synth.to_bits(t) for t in dst_dev], [x.reshape(-1) for x in want])
     plan.destroy()
+
+
+def test_pipelined_chunks_on_two_streams_and_two_threads():
+    """Prefix consumption: chunk c is unpacked on a second stream as soon as its pack has finished,
+    while later chunks are still being packed; then the same plan is driven from two host threads at
+    once.  Results must be the oracle's either way."""
+    import threading
+    w = synth.workload("small_dense_tp1_to_tp4")
+    model, src, dst = w["model"], w["holders"][0], w["reader"]
+    tensors = holder_tensors_cpu(model, src, 88)
+    wire = reshard.pack(model, src, dst, tensors)
+    want = reshard.empty_tensors(model, dst, fill=SENT16)
+    reshard.unpack(model, src, dst, wire, want)
+    plan = th.th_plan_create(model, src, dst, 64 * 1024)
+    n = plan.num_chunks
+    assert n > 16
+    src_dev = [to_dev(t) for t in tensors]
+    sp = dev.ptrs(src_dev)
+
+    # (1) two streams, one event per chunk
+    s_pack, s_unpack = torch.cuda.Stream(), torch.cuda.Stream()
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=SENT8)
+    dst_dev = dev.alloc_tensors(plan, 1, fill_bits=SENT16)
+    dp = dev.ptrs(dst_dev)
+    torch.cuda.synchronize()
+    for c in range(n):
+        th.th_pack(plan, sp, wptrs[c:c + 1], c, 1, s_pack.cuda_stream)
+        ev = torch.cuda.Event()
+        ev.record(s_pack)
+        s_unpack.wait_event(ev)
+        th.th_unpack(plan, wptrs[c:c + 1], c, 1, dp, s_unpack.cuda_stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(wire_dev.cpu().numpy()[:plan.wire_bytes], wire)
+    assert_same([synth.to_bits(t) for t in dst_dev], [x.reshape(-1) for x in want])
+
+    # (2) two host threads, each with its own stream, wire buffer and destination tensors
+    results, errors = {}, []
+
+    def worker(k):
+        try:
+            st = torch.cuda.Stream()
+            wd, wp = dev.alloc_wire(plan, fill_byte=SENT8)
+            dd = dev.alloc_tensors(plan, 1, fill_bits=SENT16)
+            for rep in range(20):
+                th.th_pack(plan, sp, wp, 0, n, st.cuda_stream)
+                th.th_unpack(plan, wp, 0, n, dev.ptrs(dd), st.cuda_stream)
+            st.synchronize()
+            results[k] = (wd, dd)
+        except Exception as e:  # noqa: BLE001
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for k in range(2):
+        wd, dd = results[k]
+        assert np.array_equal(wd.cpu().numpy()[:plan.wire_bytes], wire)
+        assert_same([synth.to_bits(t) for t in dd], [x.reshape(-1) for x in want])
+    plan.destroy()
