@@ -1,10 +1,12 @@
 """Benchmark of the reshard hot path on one MI355X.
 
 One step = th_pack of every chunk + th_unpack of every chunk of the workload's
-plan(s), inputs resident in HBM.  Prints one JSON line (see the design notes for
-the byte accounting).  The plan (host planner + one table upload) is created
-once per (holder, reader, model) and reused for every weight version, so it is
-timed separately and reported as plan_ms.
+plan(s), inputs resident in HBM.  Prints one JSON line.  Byte accounting: a
+bf16 element costs 2 bytes read + 2 written per direction (8 per sweep), a
+narrowed fp32 element 4 + 2 at pack and 2 + 2 at unpack (10 per sweep).  The
+plan (host planner + one table upload) is created once per (holder, reader,
+model) and reused for every weight version, so it is timed separately and
+reported as plan_ms.
 """
 import argparse
 import json

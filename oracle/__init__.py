@@ -16,7 +16,7 @@ contiguous buffers which the receiver unpacks into their slices (Sec. 4.3.2,
 (Sec. 4.3.3).  It prints no layout math, no wire format and no worked example
 for this path.  The conventions implemented here (standard tensor-parallel /
 expert-parallel shard shapes, wire order, 16-byte tensor alignment, NaN rule)
-are readings, each listed in the design notes; their pins are mathematical:
+are readings, each stated in the module that implements it; their pins are mathematical:
 round trips, exactly-once coverage, byte conservation, brute force on tiny
 shapes, agreement with numpy.split, exhaustive RNE checks.
 """
