@@ -33,12 +33,12 @@ def run_checksum(run_bytes):
     return a & MASK, b & MASK
 
 
-def model_checksums(model, src, dst, wire, n_src_tensors):
+def model_checksums(model, src, dst, wire, n_src_tensors, narrow_at="pack"):
     """(A, B) per holder tensor for the stream `wire` of the pair (src, dst)."""
     out = np.zeros((n_src_tensors, 2), dtype=np.uint64)
     spans = {}
-    for it in reshard.plan_items(model, src, dst):
-        n = len(it["src_r"]) * len(it["src_c"]) * reshard.ESIZE[it["dst_dtype"]]
+    for it in reshard.plan_items(model, src, dst, narrow_at):
+        n = len(it["src_r"]) * len(it["src_c"]) * reshard.ESIZE[it["wire_dtype"]]
         lo, hi = spans.get(it["src_id"], (it["wire_off"], it["wire_off"]))
         spans[it["src_id"]] = (min(lo, it["wire_off"]), max(hi, it["wire_off"] + n))
     for t, (lo, hi) in spans.items():

@@ -9,9 +9,11 @@ Wire (a reading motivated by "compacts ... into contiguous buffers" and by the
 tensor-ordered prefix a reader may fetch, Sec. 4.3.2 / 4.3.3).  For one
 (holder, reader) pair the stream is, for each of the holder's registered
 tensors in registration order, the elements of that tensor the reader needs,
-in the tensor's row-major order, already converted to the reader's dtype.
-Each tensor's run starts at the next 16-byte boundary, the gap is zero bytes,
-tensors that contribute nothing take no space.  Chunk c is stream bytes
+in the tensor's row-major order, already converted to the reader's dtype
+(narrow_at="pack", the default: the wire carries the narrow type) or still in
+the holder's dtype (narrow_at="unpack": the reader converts).  Each tensor's run
+starts at the next 16-byte boundary, the gap is zero bytes, tensors that
+contribute nothing take no space.  Chunk c is stream bytes
 [c*CB, min((c+1)*CB, total)).
 
 Everything is done with index vectors and numpy fancy indexing: membership of
@@ -30,7 +32,7 @@ def _align16(n):
     return (n + 15) // 16 * 16
 
 
-def plan_items(model, src, dst):
+def plan_items(model, src, dst, narrow_at="pack"):
     """What moves for the pair (holder layout src, reader layout dst).
 
     Yields, in wire order, one item per (holder tensor, logical tensor in it)
@@ -39,7 +41,7 @@ def plan_items(model, src, dst):
       src_r, src_c          local row / col indices (holder tensor) of the needed
                             elements; needed set = src_r x src_c, row-major
       dst_r, dst_c          local row / col indices (reader tensor) where they land
-      src_dtype, dst_dtype
+      src_dtype, dst_dtype, wire_dtype
       wire_off              byte offset of the item's first element in the stream
     and finally the total stream length via StopIteration-free helper wire_bytes().
     """
@@ -70,37 +72,38 @@ def plan_items(model, src, dst):
             pos_c = np.full(lt["cols"], -1, dtype=np.int64)
             pos_c[d_cols] = np.arange(len(d_cols))
             ddt = dst_regs[did]["dtype"]
+            wdt = ddt if narrow_at == "pack" else t["dtype"]
             if first_of_tensor:
                 off = _align16(off)
                 first_of_tensor = False
             item = dict(src_id=sid, dst_id=did,
                         src_r=srow0 + np.nonzero(r_need)[0], src_c=np.nonzero(c_need)[0],
                         dst_r=drow0 + pos_r[s_rows[r_need]], dst_c=pos_c[s_cols[c_need]],
-                        src_dtype=t["dtype"], dst_dtype=ddt, wire_off=off, logical=li)
-            off += len(item["src_r"]) * len(item["src_c"]) * ESIZE[ddt]
+                        src_dtype=t["dtype"], dst_dtype=ddt, wire_dtype=wdt, wire_off=off, logical=li)
+            off += len(item["src_r"]) * len(item["src_c"]) * ESIZE[wdt]
             yield item
 
 
-def wire_bytes(model, src, dst):
+def wire_bytes(model, src, dst, narrow_at="pack"):
     total = 0
-    for it in plan_items(model, src, dst):
-        total = it["wire_off"] + len(it["src_r"]) * len(it["src_c"]) * ESIZE[it["dst_dtype"]]
+    for it in plan_items(model, src, dst, narrow_at):
+        total = it["wire_off"] + len(it["src_r"]) * len(it["src_c"]) * ESIZE[it["wire_dtype"]]
     return total
 
 
 def item_wire(it, src_tensor):
     """The item's elements as they appear on the wire (1-D bit-pattern array)."""
     sel = src_tensor[np.ix_(it["src_r"], it["src_c"])]
-    return rne.convert(sel, it["src_dtype"], it["dst_dtype"]).reshape(-1)
+    return rne.convert(sel, it["src_dtype"], it["wire_dtype"]).reshape(-1)
 
 
-def pack(model, src, dst, src_tensors):
+def pack(model, src, dst, src_tensors, narrow_at="pack"):
     """Wire stream (uint8 array) of holder `src` for reader `dst`.
     src_tensors: the holder's registered tensors as 2-D bit-pattern arrays."""
-    items = list(plan_items(model, src, dst))
+    items = list(plan_items(model, src, dst, narrow_at))
     total = 0
     for it in items:
-        total = it["wire_off"] + len(it["src_r"]) * len(it["src_c"]) * ESIZE[it["dst_dtype"]]
+        total = it["wire_off"] + len(it["src_r"]) * len(it["src_c"]) * ESIZE[it["wire_dtype"]]
     wire = np.zeros(total, dtype=np.uint8)
     for it in items:
         w = item_wire(it, src_tensors[it["src_id"]])
@@ -108,13 +111,14 @@ def pack(model, src, dst, src_tensors):
     return wire
 
 
-def unpack(model, src, dst, wire, dst_tensors, counts=None):
+def unpack(model, src, dst, wire, dst_tensors, counts=None, narrow_at="pack"):
     """Scatter a received stream into the reader's registered tensors (in place).
     counts (optional, same shapes, integer): incremented once per written element."""
-    for it in plan_items(model, src, dst):
+    for it in plan_items(model, src, dst, narrow_at):
         nr, nc = len(it["src_r"]), len(it["src_c"])
-        nb = nr * nc * ESIZE[it["dst_dtype"]]
-        vals = wire[it["wire_off"]:it["wire_off"] + nb].view(NPBITS[it["dst_dtype"]]).reshape(nr, nc)
+        nb = nr * nc * ESIZE[it["wire_dtype"]]
+        vals = wire[it["wire_off"]:it["wire_off"] + nb].view(NPBITS[it["wire_dtype"]]).reshape(nr, nc)
+        vals = rne.convert(vals, it["wire_dtype"], it["dst_dtype"])
         ix = np.ix_(it["dst_r"], it["dst_c"])
         dst_tensors[it["dst_id"]][ix] = vals
         if counts is not None:

@@ -488,6 +488,35 @@ def test_stream_length_closed_form_moe():
     assert reshard.wire_bytes(w["model"], w["holders"][0], w["reader"]) == elems * 2
 
 
+def test_narrowing_at_unpack_gives_the_same_reader_tensors_over_a_wider_wire():
+    """The wire carries fp32 for the norms and the reader narrows: same destination bits, and the
+    stream is longer by exactly 2 bytes per narrowed element."""
+    for name in ("small_dense_tp1_to_tp4", "small_dense_trainer_to_rollout"):
+        w = synth.workload(name)
+        model, dst = w["model"], w["reader"]
+        rng = np.random.default_rng(3)
+        for src in w["holders"]:
+            ts = []
+            for t in layouts.registered_tensors(model, src):
+                hi = 1 << (32 if t["dtype"] == "f32" else 16)
+                ts.append(rng.integers(0, hi, size=(t["rows"], t["cols"]), dtype=np.uint64).astype(reshard.NPBITS[t["dtype"]]))
+            a = reshard.empty_tensors(model, dst, fill=0)
+            b = reshard.empty_tensors(model, dst, fill=0)
+            w_pack = reshard.pack(model, src, dst, ts)
+            w_unpack = reshard.pack(model, src, dst, ts, narrow_at="unpack")
+            reshard.unpack(model, src, dst, w_pack, a)
+            reshard.unpack(model, src, dst, w_unpack, b, narrow_at="unpack")
+            for x, y in zip(a, b):
+                assert np.array_equal(x, y)
+            narrowed = sum(len(it["src_r"]) * len(it["src_c"]) for it in reshard.plan_items(model, src, dst)
+                           if it["src_dtype"] != it["dst_dtype"])
+            if narrowed:
+                assert len(w_unpack) > len(w_pack)
+                # runs stay 16-byte aligned, so the difference is the extra payload up to alignment gaps
+                assert 0 <= len(w_unpack) - len(w_pack) - 2 * narrowed < 16 * len(ts)
+            assert len(w_unpack) == reshard.wire_bytes(model, src, dst, narrow_at="unpack")
+
+
 def test_chunks_tile_the_stream():
     wire = np.arange(1000, dtype=np.uint8)
     cs = reshard.chunks(wire, 256)
