@@ -76,6 +76,9 @@ enum {
     TH_FLAG_PTRS_ALIGNED16 = 1u << 1, /* th_plan_create_from_segments: caller promises that every
                                          tensor base pointer is 16-byte aligned (model plans always
                                          require it) */
+    TH_FLAG_NARROW_AT_UNPACK = 1u << 3, /* the wire carries the holder's dtype and th_unpack narrows
+                                           (default: th_pack narrows, the wire carries the reader's
+                                           dtype: fewer bytes to transfer) */
     TH_FLAG_CHECKSUM = 1u << 2        /* allocate what th_pack_checksum / th_unpack_checksum need
                                          (24 bytes of device memory per tile) and use the larger
                                          checksum tile size; plain th_pack / th_unpack on such a plan
@@ -146,7 +149,7 @@ typedef struct th_segment {
     uint64_t src_elem_off, dst_elem_off;
     uint64_t src_row_stride, dst_row_stride;
     uint64_t nrows, row_len;
-    uint8_t src_dtype, dst_dtype; /* th_dtype; wire dtype = dst_dtype */
+    uint8_t src_dtype, dst_dtype; /* th_dtype; wire dtype = dst_dtype unless TH_FLAG_NARROW_AT_UNPACK */
     uint8_t reserved[6];
 } th_segment;
 
@@ -251,7 +254,8 @@ typedef struct th_run {
     uint64_t nrows, row_len;
     uint8_t src_dtype, dst_dtype;
     uint8_t pad_bytes; /* zero bytes that follow the run's last element on the wire */
-    uint8_t reserved2[5];
+    uint8_t wire_dtype; /* dtype of the run's elements on the wire */
+    uint8_t reserved2[4];
 } th_run;
 size_t th_plan_num_runs(const th_plan* plan);
 int th_plan_get_run(const th_plan* plan, size_t i, th_run* out);

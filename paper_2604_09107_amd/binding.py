@@ -12,7 +12,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libtensorhub_reshard.so")
 
 TH_BF16, TH_F32 = 1, 2
-TH_FLAG_HOST_ONLY, TH_FLAG_PTRS_ALIGNED16, TH_FLAG_CHECKSUM = 1, 2, 4
+TH_FLAG_HOST_ONLY, TH_FLAG_PTRS_ALIGNED16, TH_FLAG_CHECKSUM, TH_FLAG_NARROW_AT_UNPACK = 1, 2, 4, 8
 TH_CFG_TILE_BYTES = 1
 TH_CFG_TILE_BYTES_ANY = 2
 TH_CFG_SPECIALIZE = 3
@@ -73,7 +73,7 @@ class Run(C.Structure):
                 ("chunk_byte_off", C.c_uint64), ("wire_byte_stride", C.c_uint64),
                 ("nrows", C.c_uint64), ("row_len", C.c_uint64),
                 ("src_dtype", C.c_uint8), ("dst_dtype", C.c_uint8), ("pad_bytes", C.c_uint8),
-                ("reserved2", C.c_uint8 * 5)]
+                ("wire_dtype", C.c_uint8), ("reserved2", C.c_uint8 * 4)]
 
 
 class TileInfo(C.Structure):

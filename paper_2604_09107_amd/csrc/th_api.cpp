@@ -326,7 +326,7 @@ int th_plan_create(const th_model_desc* model, const th_layout* src, const th_la
         return TH_ERR_NOMEM;
     }
     try {
-        int rc = build_model_segments(*model, *src, *dst, p->m);
+        int rc = build_model_segments(*model, *src, *dst, (flags & TH_FLAG_NARROW_AT_UNPACK) != 0, p->m);
         if (rc != TH_OK) {
             delete p;
             return rc;
@@ -353,7 +353,8 @@ int th_plan_create_from_segments(const th_segment* segs, size_t n, const uint64_
         return TH_ERR_NOMEM;
     }
     try {
-        int rc = segments_from_user(segs, n, src_tensor_elems, n_src, dst_tensor_elems, n_dst, p->m);
+        int rc = segments_from_user(segs, n, src_tensor_elems, n_src, dst_tensor_elems, n_dst,
+                                    (flags & TH_FLAG_NARROW_AT_UNPACK) != 0, p->m);
         if (rc != TH_OK) {
             delete p;
             return rc;

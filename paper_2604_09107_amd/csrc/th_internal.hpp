@@ -30,6 +30,7 @@ struct Segment {
     uint64_t nrows = 0, row_len = 0;
     uint64_t wire_off = 0, wire_stride = 0;  // bytes
     uint8_t src_dtype = 0, dst_dtype = 0;
+    uint8_t wire_dtype = 0;  // dtype on the wire: dst_dtype (narrow at pack) or src_dtype (narrow at unpack)
     uint8_t pad_after = 0;  // zero bytes after the segment's last element (wire alignment gap)
     uint64_t run_start = 0;  // wire byte offset where the run of this segment's source tensor begins
 };
@@ -109,10 +110,10 @@ void set_error(const char* fmt, ...);
 
 // th_layouts.cpp: registered tensors of both ranks and the rectangles that move between them.
 int build_model_segments(const th_model_desc& model, const th_layout& src, const th_layout& dst,
-                         Manifest& m);
+                         bool narrow_at_unpack, Manifest& m);
 // th_planner.cpp
 int segments_from_user(const th_segment* segs, size_t n, const uint64_t* src_elems, uint32_t n_src,
-                       const uint64_t* dst_elems, uint32_t n_dst, Manifest& m);
+                       const uint64_t* dst_elems, uint32_t n_dst, bool narrow_at_unpack, Manifest& m);
 int finish_manifest(Manifest& m, uint64_t chunk_bytes, bool ptrs_aligned16, const Tuning& tune);
 
 inline unsigned esize(int dtype) { return dtype == TH_F32 ? 4u : 2u; }

@@ -270,6 +270,24 @@ __device__ __forceinline__ u32x4 load_slot(gsrc_t s) {
     }
 }
 
+// The same, and with SUM == 2 (the wire is the source) the checksum terms of the source bytes that
+// were read, which sit rel bytes after the tile's wire base.
+template <int SES, int DES, int SUM>
+__device__ __forceinline__ u32x4 load_slot_sum(gsrc_t s, uint64_t rel, Sum& acc) {
+    if (SUM == 2 && SES != DES) {  // fp32 on the wire, narrowed here
+        const u32x4 a = reinterpret_cast<const TH_GLOBAL Unaligned4*>(s)->v;
+        sum_halves(acc, a, 0, 8, (int64_t)(rel / 2));
+        u32x4 o;
+        o.x = narrow_pair(a.x, a.y);
+        o.y = narrow_pair(a.z, a.w);
+        o.z = o.w = 0;
+        return o;
+    }
+    const u32x4 o = load_slot<SES, DES>(s);
+    if (SUM == 2) sum_halves(acc, o, 0, SlotBytes<SES, DES>::value / 2, (int64_t)(rel / 2));
+    return o;
+}
+
 template <int DES, int EPV>
 __device__ __forceinline__ u32x4 pack_slot(const uint32_t (&v)[EPV]) {
     u32x4 o;
@@ -295,9 +313,11 @@ struct Slot {
 // Gather the elements [first, last) of a slot from a rectangle (rows of nc elements, ss bytes
 // apart), starting at (row, col) and walking over row ends, converting on the way.  All loads are
 // issued before the first use, so a slot costs one memory latency.  FULL: first = 0, last = EPV.
+// rel0: byte offset of `src` from the tile's wire base (positions of checksum terms when the wire
+// is the source).
 template <int SES, int DES, int SUM, bool FULL>
 __device__ __forceinline__ u32x4 gather_slot(gsrc_t src, uint64_t ss, uint32_t nc, uint32_t row, uint32_t col,
-                                             int first, int last, Sum& acc) {
+                                             int first, int last, uint64_t rel0, Sum& acc) {
     constexpr int EPV = SlotBytes<SES, DES>::value / DES;
     uint32_t v[EPV];
 #pragma unroll
@@ -306,7 +326,7 @@ __device__ __forceinline__ u32x4 gather_slot(gsrc_t src, uint64_t ss, uint32_t n
         if (FULL || (j >= first && j < last)) {
             const uint64_t rel = (uint64_t)row * ss + (uint64_t)col * SES;
             v[j] = load_elem<SES>(src + rel);
-            if (SUM == 2) sum_elem<SES>(acc, v[j], rel);
+            if (SUM == 2) sum_elem<SES>(acc, v[j], rel0 + rel);
             const bool wrap = ++col == nc;
             col = wrap ? 0u : col;
             row += wrap ? 1u : 0u;
@@ -369,12 +389,11 @@ __device__ __forceinline__ Slot<DES> fetch_slot(gsrc_t src, gdst_t dst, uint64_t
     const bool full = s.first == 0 && s.last == EPV;
     if (full && col + EPV <= nc) {
         const uint64_t rel = (uint64_t)row * ss + (uint64_t)col * SES;
-        s.o = load_slot<SES, DES>(src + rel);
-        if (SUM == 2) sum_halves(acc, s.o, 0, SlotBytes<SES, DES>::value / 2, (int64_t)(rel / 2));
+        s.o = load_slot_sum<SES, DES, SUM>(src + rel, rel, acc);
     } else if (full) {
-        s.o = gather_slot<SES, DES, SUM, true>(src, ss, nc, row, col, 0, EPV, acc);
+        s.o = gather_slot<SES, DES, SUM, true>(src, ss, nc, row, col, 0, EPV, 0, acc);
     } else {
-        s.o = gather_slot<SES, DES, SUM, false>(src, ss, nc, row, col, s.first, s.last, acc);
+        s.o = gather_slot<SES, DES, SUM, false>(src, ss, nc, row, col, s.first, s.last, 0, acc);
     }
     return s;
 }
@@ -429,15 +448,14 @@ __device__ __forceinline__ void copy_any(gsrc_t src, gdst_t dst, uint64_t ss, ui
             q.first = e0 < 0 ? -e0 : 0;
             q.last = (uint32_t)(e0 + EPV) <= ncols ? EPV : (int)(ncols - (uint32_t)e0);
             q.d = d + (ptrdiff_t)e0 * DES;
+            const uint64_t row_rel = (uint64_t)r * ss;  // the source row's offset from the tile's base
             if (q.first == 0 && q.last == EPV)
-                q.o = load_slot<SES, DES>(s + (size_t)e0 * SES);
+                q.o = load_slot_sum<SES, DES, SUM>(s + (size_t)e0 * SES, row_rel + (uint64_t)e0 * SES, acc);
             else
-                q.o = gather_slot<SES, DES, 0, false>(s, 0, 0xFFFFFFFFu, 0, (uint32_t)(e0 + q.first), q.first,
-                                                      q.last, acc);
-            // the slot is contiguous on both sides: its element 0 sits at row offset e0 on either
-            const int64_t rel = (int64_t)r * (int64_t)(SUM == 1 ? ds : ss) + (int64_t)e0 * (SUM == 1 ? DES : SES);
-            if (SUM == 2) sum_halves(acc, q.o, q.first * DES / 2, q.last * DES / 2, rel / 2);
-            commit_slot<DES, SLOT, SUM>(q, rel, acc);
+                q.o = gather_slot<SES, DES, SUM, false>(s, 0, 0xFFFFFFFFu, 0, (uint32_t)(e0 + q.first), q.first,
+                                                        q.last, row_rel, acc);
+            // wire = destination: the slot's element 0 sits e0 elements into the destination row
+            commit_slot<DES, SLOT, SUM>(q, (int64_t)r * (int64_t)ds + (int64_t)e0 * DES, acc);
         }
     }
 }
@@ -479,7 +497,7 @@ __global__ __launch_bounds__(kBlockThreads, TH_MIN_WAVES_PER_EU) void th_tiles_k
             copy_dense<4, 4, SUM>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok, acc);
             des = 4;
         } else if (flags & TILE_SRC_F32) {
-            copy_dense<4, 2, SUM == 2 ? 0 : SUM>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok, acc);
+            copy_dense<4, 2, SUM>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok, acc);
         } else {
             copy_dense<2, 2, SUM>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok, acc);
         }
@@ -496,7 +514,7 @@ __global__ __launch_bounds__(kBlockThreads, TH_MIN_WAVES_PER_EU) void th_tiles_k
             copy_any<4, 4, SUM>(src, dst, ss, ds, count, ncols, lg, acc);
             des = 4;
         } else if (flags & TILE_SRC_F32) {
-            copy_any<4, 2, SUM == 2 ? 0 : SUM>(src, dst, ss, ds, count, ncols, lg, acc);
+            copy_any<4, 2, SUM>(src, dst, ss, ds, count, ncols, lg, acc);
         } else {
             copy_any<2, 2, SUM>(src, dst, ss, ds, count, ncols, lg, acc);
         }

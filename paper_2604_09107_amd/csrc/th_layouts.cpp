@@ -259,7 +259,7 @@ struct Piece {  // a needed rectangle in holder-tensor coordinates and where it 
 }  // namespace
 
 int build_model_segments(const th_model_desc& m, const th_layout& src, const th_layout& dst,
-                         Manifest& man) {
+                         bool narrow_at_unpack, Manifest& man) {
     if ((m.kind != TH_MODEL_DENSE && m.kind != TH_MODEL_MOE) || m.n_layers < 0 || m.hidden < 1 ||
         m.n_q_heads < 1 || m.n_kv_heads < 1 || m.head_dim < 1 || m.vocab < 1 ||
         (m.weight_dtype != TH_BF16 && m.weight_dtype != TH_F32) ||
@@ -351,7 +351,8 @@ int build_model_segments(const th_model_desc& m, const th_layout& src, const th_
             for (size_t j = 0; j < band.size(); ++j) {
                 const Piece& p = *band[j];
                 const TensorInfo& dt = man.tensors[1][p.dst_tensor];
-                const unsigned es = esize(dt.dtype);
+                const int wire_dtype = narrow_at_unpack ? sr.info.dtype : dt.dtype;
+                const unsigned es = esize(wire_dtype);
                 if (sr.info.dtype == TH_BF16 && dt.dtype == TH_F32) {
                     set_error("tensor %s: bf16 -> fp32 widening is not supported", sr.info.name.c_str());
                     return TH_ERR_UNSUPPORTED;
@@ -369,6 +370,7 @@ int build_model_segments(const th_model_desc& m, const th_layout& src, const th_
                 g.wire_stride = width * es;
                 g.src_dtype = (uint8_t)sr.info.dtype;
                 g.dst_dtype = (uint8_t)dt.dtype;
+                g.wire_dtype = (uint8_t)wire_dtype;
                 g.run_start = run_start;
                 prefix += (uint64_t)p.nc;
                 // continue the segment of the previous band if this one extends it downwards
@@ -392,14 +394,15 @@ int build_model_segments(const th_model_desc& m, const th_layout& src, const th_
             }
             open.swap(now);
             // all pieces of one holder tensor land in tensors of one dtype, so one element size per band
-            wire += (uint64_t)(b - a) * width * esize(man.tensors[1][band[0]->dst_tensor].dtype);
+            wire += (uint64_t)(b - a) * width *
+                    esize(narrow_at_unpack ? sr.info.dtype : man.tensors[1][band[0]->dst_tensor].dtype);
         }
         // the alignment gap that follows this tensor's run is written by whoever holds its last element
         const uint64_t gap = (16 - wire % 16) % 16;
         if (gap) {
             for (size_t i = first_seg; i < man.segments.size(); ++i) {
                 Segment& g = man.segments[i];
-                const uint64_t end = g.wire_off + (g.nrows - 1) * g.wire_stride + g.row_len * esize(g.dst_dtype);
+                const uint64_t end = g.wire_off + (g.nrows - 1) * g.wire_stride + g.row_len * esize(g.wire_dtype);
                 if (end == wire) g.pad_after = (uint8_t)gap;
             }
         }
@@ -407,9 +410,9 @@ int build_model_segments(const th_model_desc& m, const th_layout& src, const th_
     // no gap is owed after the last run of the stream
     uint64_t last_end = 0;
     for (const Segment& g : man.segments)
-        last_end = std::max(last_end, g.wire_off + (g.nrows - 1) * g.wire_stride + g.row_len * esize(g.dst_dtype));
+        last_end = std::max(last_end, g.wire_off + (g.nrows - 1) * g.wire_stride + g.row_len * esize(g.wire_dtype));
     for (Segment& g : man.segments)
-        if (g.wire_off + (g.nrows - 1) * g.wire_stride + g.row_len * esize(g.dst_dtype) == last_end) g.pad_after = 0;
+        if (g.wire_off + (g.nrows - 1) * g.wire_stride + g.row_len * esize(g.wire_dtype) == last_end) g.pad_after = 0;
     return TH_OK;
 }
 

@@ -11,7 +11,7 @@ namespace {
 typedef unsigned __int128 u128;
 
 uint64_t seg_wire_end(const Segment& g) {
-    return g.wire_off + (g.nrows - 1) * g.wire_stride + g.row_len * esize(g.dst_dtype);
+    return g.wire_off + (g.nrows - 1) * g.wire_stride + g.row_len * esize(g.wire_dtype);
 }
 
 unsigned ceil_log2(uint64_t v) {
@@ -165,7 +165,7 @@ void tile_run(std::vector<Tile>& out, Side S, Side D, uint64_t nrows, uint64_t n
 }  // namespace
 
 int segments_from_user(const th_segment* segs, size_t n, const uint64_t* src_elems, uint32_t n_src,
-                       const uint64_t* dst_elems, uint32_t n_dst, Manifest& m) {
+                       const uint64_t* dst_elems, uint32_t n_dst, bool narrow_at_unpack, Manifest& m) {
     if ((n && !segs) || (n_src && !src_elems) || (n_dst && !dst_elems)) {
         set_error("null segment or tensor-size array");
         return TH_ERR_ARG;
@@ -238,11 +238,12 @@ int segments_from_user(const th_segment* segs, size_t n, const uint64_t* src_ele
         g.row_len = u.row_len;
         g.src_dtype = u.src_dtype;
         g.dst_dtype = u.dst_dtype;
+        g.wire_dtype = narrow_at_unpack ? u.src_dtype : u.dst_dtype;
         g.wire_off = wire;
         g.run_start = run_start;
-        g.wire_stride = u.row_len * esize(u.dst_dtype);
+        g.wire_stride = u.row_len * esize(g.wire_dtype);
         m.segments.push_back(g);
-        wire += u.nrows * u.row_len * esize(u.dst_dtype);
+        wire += u.nrows * u.row_len * esize(g.wire_dtype);
     }
     return TH_OK;
 }
@@ -256,7 +257,7 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
     m.wire_bytes = m.payload_bytes = m.src_read_bytes = 0;
     for (const Segment& g : m.segments) {
         m.wire_bytes = std::max(m.wire_bytes, seg_wire_end(g));
-        m.payload_bytes += g.nrows * g.row_len * esize(g.dst_dtype);
+        m.payload_bytes += g.nrows * g.row_len * esize(g.wire_dtype);
         m.src_read_bytes += g.nrows * g.row_len * esize(g.src_dtype);
     }
     const uint64_t nchunks = (m.wire_bytes + CB - 1) / CB;
@@ -268,7 +269,7 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
 
     // ---- runs: every segment cut so that each piece lies inside one chunk ----
     for (const Segment& g : m.segments) {
-        const unsigned es_s = esize(g.src_dtype), es_w = esize(g.dst_dtype);
+        const unsigned es_s = esize(g.src_dtype), es_w = esize(g.wire_dtype), es_d = esize(g.dst_dtype);
         const uint64_t row_bytes = g.row_len * es_w;
         auto emit = [&](uint64_t r0, uint64_t nr, uint64_t c0, uint64_t nc, uint64_t wire_pos) {
             th_run r;
@@ -278,14 +279,15 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
             r.chunk = (uint32_t)(wire_pos / CB);
             r.src_byte_off = (g.src_off + r0 * g.src_stride + c0) * es_s;
             r.src_byte_stride = g.src_stride * es_s;
-            r.dst_byte_off = (g.dst_off + r0 * g.dst_stride + c0) * es_w;
-            r.dst_byte_stride = g.dst_stride * es_w;
+            r.dst_byte_off = (g.dst_off + r0 * g.dst_stride + c0) * es_d;
+            r.dst_byte_stride = g.dst_stride * es_d;
             r.chunk_byte_off = wire_pos % CB;
             r.wire_byte_stride = g.wire_stride;
             r.nrows = nr;
             r.row_len = nc;
             r.src_dtype = g.src_dtype;
             r.dst_dtype = g.dst_dtype;
+            r.wire_dtype = g.wire_dtype;
             if (r0 + nr == g.nrows && c0 + nc == g.row_len) r.pad_bytes = g.pad_after;
             m.runs.push_back(r);
             m.run_starts.push_back(g.run_start);
@@ -323,14 +325,14 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
         base.reserve(guess);
         for (size_t ri = 0; ri < m.runs.size(); ++ri) {
             const th_run& r = m.runs[ri];
-            const unsigned es_s = esize(r.src_dtype), es_w = esize(r.dst_dtype);
+            const unsigned es_s = esize(r.src_dtype), es_w = esize(r.wire_dtype), es_d = esize(r.dst_dtype);
             Side S, D;
             if (side == 0) {
                 S = Side{r.src_tensor, r.src_byte_off, r.src_byte_stride, es_s};
                 D = Side{r.chunk, r.chunk_byte_off, r.wire_byte_stride, es_w};
             } else {
                 S = Side{r.chunk, r.chunk_byte_off, r.wire_byte_stride, es_w};
-                D = Side{r.dst_tensor, r.dst_byte_off, r.dst_byte_stride, es_w};
+                D = Side{r.dst_tensor, r.dst_byte_off, r.dst_byte_stride, es_d};
             }
             bool vec = false;
             const size_t before = tiles.size();

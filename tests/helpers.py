@@ -54,16 +54,16 @@ def exec_runs_pack(plan, src_flat, fill=0xEE):
         r = plan.run(i)
         exec_copy(src_flat[r.src_tensor], chunks[r.chunk], r.src_byte_off, r.src_byte_stride,
                   r.chunk_byte_off, r.wire_byte_stride, r.nrows, r.row_len,
-                  4 if r.src_dtype == 2 else 2, 4 if r.dst_dtype == 2 else 2, r.pad_bytes)
+                  4 if r.src_dtype == 2 else 2, 4 if r.wire_dtype == 2 else 2, r.pad_bytes)
     return chunks
 
 
 def exec_runs_unpack(plan, chunks, dst_flat):
     for i in range(plan.num_runs):
         r = plan.run(i)
-        es = 4 if r.dst_dtype == 2 else 2
         exec_copy(chunks[r.chunk], dst_flat[r.dst_tensor], r.chunk_byte_off, r.wire_byte_stride,
-                  r.dst_byte_off, r.dst_byte_stride, r.nrows, r.row_len, es, es)
+                  r.dst_byte_off, r.dst_byte_stride, r.nrows, r.row_len,
+                  4 if r.wire_dtype == 2 else 2, 4 if r.dst_dtype == 2 else 2)
 
 
 def exec_tiles(plan, side, src_bufs, dst_bufs, chunk_range=None):

@@ -87,6 +87,66 @@ def test_scattered_checksums_bit_exact(tile_bytes):
     plan.destroy()
 
 
+@pytest.mark.parametrize("tile_bytes", [4096, None])
+def test_narrowing_at_unpack_bit_exact_with_checksums(tile_bytes):
+    """The wire carries fp32 and th_unpack narrows: wire, reader tensors and both checksum arrays
+    against the oracle, for a model plan (fp32 norms) and the scattered fp32 -> bf16 workload."""
+    flags = th.TH_FLAG_CHECKSUM | th.TH_FLAG_NARROW_AT_UNPACK
+    stream = dev.current_stream()
+    w = synth.workload("small_dense_trainer_to_rollout")
+    model, dst = w["model"], w["reader"]
+    want_dst = reshard.empty_tensors(model, dst, fill=0)
+    dst_dev = None
+    for src in w["holders"]:
+        tensors = holder_tensors_cpu(model, src, w["seed"])
+        wire = reshard.pack(model, src, dst, tensors, narrow_at="unpack")
+        reshard.unpack(model, src, dst, wire, want_dst, narrow_at="unpack")
+        want = checksum.model_checksums(model, src, dst, wire, len(tensors), narrow_at="unpack")
+        with tile_sizes(tile_bytes):
+            plan = th.th_plan_create(model, src, dst, 64 * 1024, flags)
+        src_dev = [synth.from_bits(t.reshape(-1), "cuda") for t in tensors]
+        if dst_dev is None:
+            dst_dev = dev.alloc_tensors(plan, 1, fill_bits=0)
+        wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=0xEE)
+        ps, us = sums_dev(len(tensors)), sums_dev(len(tensors))
+        th.th_pack_checksum(plan, dev.ptrs(src_dev), wptrs, 0, plan.num_chunks, ps.data_ptr(), stream)
+        th.th_unpack_checksum(plan, wptrs, 0, plan.num_chunks, dev.ptrs(dst_dev), us.data_ptr(), stream)
+        torch.cuda.synchronize()
+        assert np.array_equal(wire_dev.cpu().numpy()[:plan.wire_bytes], wire)
+        assert np.array_equal(sums_host(ps), want) and np.array_equal(sums_host(us), want)
+        plan.destroy()
+    for g, x in zip(dst_dev, want_dst):
+        assert np.array_equal(synth.to_bits(g), x.reshape(-1))
+
+    n = 200
+    d = synth.scatter_description(n, 72, min_bytes=256, max_bytes=1 << 16)
+    pool_dev = synth.scatter_values(d["pool_elems"] + 3, 72, "cuda", 0.05)[1:]
+    pool = synth.to_bits(pool_dev[:d["pool_elems"]])
+    srcs = [pool[o:o + m] for o, m in zip(d["pool_off"], d["n_elems"])]
+    osegs = dict(src_tensor=d["seg_src_tensor"], dst_tensor=np.zeros(n, dtype=np.int64),
+                 src_off=d["seg_src_off"], src_stride=d["seg_src_stride"], dst_off=d["seg_dst_off"],
+                 dst_stride=d["seg_dst_stride"], nrows=d["seg_nrows"], row_len=d["seg_row_len"])
+    wire = segments.pack(osegs, srcs, "f32", "bf16", narrow_at="unpack")
+    offs, _ = segments.wire_offsets(osegs, "f32")
+    want = checksum.segment_checksums(osegs, offs, "f32", wire, n)
+    arena = np.full(d["arena_elems"] + 8, 0x7777, dtype=np.uint16)
+    segments.unpack(osegs, wire, [arena], "bf16", wire_dtype="f32")
+    with tile_sizes(tile_bytes):
+        plan = th.th_plan_create_from_segments(scatter_segments(d), d["n_elems"], [len(arena)], 128 * 1024, flags)
+    assert plan.wire_bytes == len(wire)
+    arena_dev = synth.from_bits(np.full(len(arena) + 1, 0x7777, dtype=np.uint16), "cuda")
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=0xEE)
+    src_ptrs = pool_dev.data_ptr() + d["pool_off"].astype(np.uint64) * np.uint64(4)
+    ps, us = sums_dev(n), sums_dev(n)
+    th.th_pack_checksum(plan, src_ptrs, wptrs, 0, plan.num_chunks, ps.data_ptr(), stream)
+    th.th_unpack_checksum(plan, wptrs, 0, plan.num_chunks, [arena_dev.data_ptr() + 2], us.data_ptr(), stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(wire_dev.cpu().numpy()[:plan.wire_bytes], wire)
+    assert np.array_equal(synth.to_bits(arena_dev)[1:], arena)
+    assert np.array_equal(sums_host(ps), want) and np.array_equal(sums_host(us), want)
+    plan.destroy()
+
+
 def test_corrupted_wire_is_detected_for_the_tensor_that_was_hit():
     w = synth.workload("small_dense_tp1_to_tp4")
     model, src, dst = w["model"], w["holders"][0], w["reader"]

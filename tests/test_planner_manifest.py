@@ -152,6 +152,39 @@ def test_tile_checksum_bases_reproduce_the_oracle_checksums(tile_bytes):
     plan.destroy()
 
 
+@pytest.mark.parametrize("name", ["small_dense_tp1_to_tp4", "small_dense_trainer_to_rollout", "small_moe_ep4_to_tp2"])
+def test_narrowing_at_unpack_manifest(name):
+    """TH_FLAG_NARROW_AT_UNPACK: the wire carries the holder's dtype; runs, tiles and checksum bases
+    reproduce the oracle's wider stream and the same reader tensors."""
+    w = synth.workload(name)
+    model, dst = w["model"], w["reader"]
+    flags = HOST | th.TH_FLAG_NARROW_AT_UNPACK
+    want = reshard.empty_tensors(model, dst, fill=0x5A5A)
+    got = reshard.empty_tensors(model, dst, fill=0x5A5A)
+    direct = reshard.empty_tensors(model, dst, fill=0x5A5A)
+    for src in w["holders"]:
+        tensors = holder_tensors_cpu(model, src, w["seed"], pattern=True)
+        wire = reshard.pack(model, src, dst, tensors, narrow_at="unpack")
+        reshard.unpack(model, src, dst, wire, want, narrow_at="unpack")
+        with tile_sizes(4096):
+            plan = th.th_plan_create(model, src, dst, 32 * 1024, flags)
+        assert plan.wire_bytes == len(wire) and plan.payload_bytes <= plan.src_read_bytes
+        want_chunks = reshard.chunks(wire, 32 * 1024)
+        chunks = exec_runs_pack(plan, flat_u8(tensors))
+        tchunks = [np.full(len(c), 0xEE, dtype=np.uint8) for c in want_chunks]
+        exec_tiles(plan, 0, flat_u8(tensors), tchunks)
+        for a, b, x in zip(chunks, tchunks, want_chunks):
+            assert np.array_equal(a, x) and np.array_equal(b, x)
+        exec_tiles(plan, 1, tchunks, flat_u8(got))
+        exec_tiles(plan, 2, flat_u8(tensors), flat_u8(direct))
+        cs = checksum.model_checksums(model, src, dst, wire, len(tensors), narrow_at="unpack")
+        for side in (0, 1):
+            assert np.array_equal(tile_checksums(plan, side, want_chunks, len(tensors)), cs)
+        plan.destroy()
+    for g, d, x in zip(got, direct, want):
+        assert np.array_equal(g, x) and np.array_equal(d, x)
+
+
 def test_chunks_are_self_contained():
     """Unpacking any subset of chunks, in any order, touches only that subset's elements."""
     w = synth.workload("small_dense_tp1_to_tp4")

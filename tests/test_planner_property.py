@@ -55,19 +55,21 @@ def cases(draw):
         pass  # whole model narrowed
     chunk = 16 * draw(st.integers(1, 64))
     tile = draw(st.sampled_from([4096, 8192]))
-    return model, src, dst, chunk, tile
+    narrow_at = draw(st.sampled_from(["pack", "unpack"]))
+    return model, src, dst, chunk, tile, narrow_at
 
 
 @settings(max_examples=300, deadline=None, suppress_health_check=[HealthCheck.too_slow, HealthCheck.data_too_large])
 @given(cases())
 def test_manifest_matches_oracle_on_random_shapes(case):
-    model, src, dst, chunk, tile = case
+    model, src, dst, chunk, tile, narrow_at = case
     tensors = holder_tensors_cpu(model, src, 1, pattern=True)
-    wire = reshard.pack(model, src, dst, tensors)
+    wire = reshard.pack(model, src, dst, tensors, narrow_at=narrow_at)
     want = reshard.empty_tensors(model, dst, fill=0x5A5A)
-    reshard.unpack(model, src, dst, wire, want)
+    reshard.unpack(model, src, dst, wire, want, narrow_at=narrow_at)
     with tile_sizes(tile):
-        plan = th.th_plan_create(model, src, dst, chunk, HOST)
+        plan = th.th_plan_create(model, src, dst, chunk,
+                                 HOST | (th.TH_FLAG_NARROW_AT_UNPACK if narrow_at == "unpack" else 0))
     try:
         assert plan.wire_bytes == len(wire)
         want_chunks = reshard.chunks(wire, chunk) if len(wire) else []
@@ -83,7 +85,7 @@ def test_manifest_matches_oracle_on_random_shapes(case):
         for g, d, x in zip(got, direct, want):
             assert np.array_equal(g, x) and np.array_equal(d, x)
         if len(wire):
-            cs = checksum.model_checksums(model, src, dst, wire, len(tensors))
+            cs = checksum.model_checksums(model, src, dst, wire, len(tensors), narrow_at=narrow_at)
             for side in (0, 1):
                 assert np.array_equal(tile_checksums(plan, side, want_chunks, len(tensors)), cs)
     finally:
