@@ -214,6 +214,18 @@ int th_unpack_checksum(const th_plan* plan, const void* const* wire_ptrs, uint32
                        uint32_t chunk_count, void* const* dst_ptrs, uint32_t n_dst, uint64_t* sums,
                        void* hip_stream);
 
+/* Progress counter (Sec. 4.3.3: a replicating worker tracks how many tensors of
+ * the version it has received; a reader reads the counter and fetches that
+ * prefix).  th_signal enqueues, after all work already in hip_stream, a store of
+ * `value` to *flag (device memory or pinned host memory, 8-byte aligned) that is
+ * visible to the host and to other devices once it lands - e.g. the number of
+ * chunks unpacked so far, published without any host synchronisation.
+ * th_plan_tensors_complete converts chunks into the paper's unit: the number of
+ * leading source tensors (registration order; tensors that send nothing count
+ * as complete) whose whole wire run lies inside the first n_chunks_done chunks. */
+int th_signal(uint64_t* flag, uint64_t value, void* hip_stream);
+uint32_t th_plan_tensors_complete(const th_plan* plan, uint32_t n_chunks_done);
+
 /* Co-located holder and reader (trainer and rollout time-sharing one GPU, Sec.
  * 2.1): move what the reader needs straight from the holder's registered tensors
  * into the reader's, with the same narrowing, without a wire in between - half

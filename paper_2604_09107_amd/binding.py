@@ -117,6 +117,8 @@ _get_run = _sig("th_plan_get_run", C.c_int, _P, C.c_size_t, C.POINTER(Run))
 _num_tiles = _sig("th_plan_num_tiles", C.c_size_t, _P, C.c_int)
 _get_tile = _sig("th_plan_get_tile", C.c_int, _P, C.c_int, C.c_size_t, C.POINTER(TileInfo))
 _chunk_first_tile = _sig("th_plan_chunk_first_tile", C.c_size_t, _P, C.c_int, C.c_int, C.c_uint32)
+_signal = _sig("th_signal", C.c_int, _P, C.c_uint64, _P)
+_tensors_complete = _sig("th_plan_tensors_complete", C.c_uint32, _P, C.c_uint32)
 _reference_copy = _sig("th_reference_copy", C.c_int, _P, _P, C.c_size_t, _P)
 _config_set = _sig("th_config_set", C.c_int, C.c_int, C.c_uint64)
 _config_get = _sig("th_config_get", C.c_uint64, C.c_int)
@@ -201,6 +203,9 @@ class Plan:
     def chunk_first_tile(self, side, path_class, chunk):
         return _chunk_first_tile(self.handle, side, path_class, chunk)
 
+    def tensors_complete(self, n_chunks_done):
+        return _tensors_complete(self.handle, n_chunks_done)
+
     def destroy(self):
         if self._h is not None:
             _check(_destroy(self._h))
@@ -267,6 +272,10 @@ def th_reshard(plan, src_ptrs, dst_ptrs, stream=0):
 
 def th_plan_destroy(plan):
     plan.destroy()
+
+
+def th_signal(flag_ptr, value, stream=0):
+    _check(_signal(flag_ptr, value, stream))
 
 
 def th_reference_copy(dst_ptr, src_ptr, nbytes, stream=0):

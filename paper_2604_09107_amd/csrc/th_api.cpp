@@ -559,6 +559,23 @@ size_t th_plan_chunk_first_tile(const th_plan* p, int side, int path_class, uint
     return (size_t)p->m.chunk_tile0[side][path_class][chunk];
 }
 
+int th_signal(uint64_t* flag, uint64_t value, void* hip_stream) {
+    if (!flag || reinterpret_cast<uintptr_t>(flag) % 8) {
+        set_error("flag pointer is NULL or not 8-byte aligned");
+        return TH_ERR_ARG;
+    }
+    return launch_signal(flag, value, hip_stream);
+}
+
+uint32_t th_plan_tensors_complete(const th_plan* p, uint32_t n_chunks_done) {
+    if (!p) return 0;
+    const Manifest& m = p->m;
+    const uint64_t done = std::min<uint64_t>((uint64_t)n_chunks_done * m.chunk_bytes, m.wire_bytes);
+    uint32_t n = 0;
+    while (n < m.tensor_wire_end.size() && m.tensor_wire_end[n] <= done) ++n;
+    return n;
+}
+
 int th_reference_copy(void* dst, const void* src, size_t nbytes, void* hip_stream) {
     if ((nbytes && (!dst || !src)) || nbytes % 16 || reinterpret_cast<uintptr_t>(dst) % 16 ||
         reinterpret_cast<uintptr_t>(src) % 16) {

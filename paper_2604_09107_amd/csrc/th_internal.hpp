@@ -89,6 +89,7 @@ struct Manifest {
     // the vector-path range can be launched with the kernel that holds only that path.
     std::vector<Tile> tiles[3];               // [2]: direct holder tensor -> reader tensor list (no wire)
     std::vector<uint64_t> chunk_tile0[2][2];  // [side][class]: first tile of each chunk (+ end of the sub-list)
+    std::vector<uint64_t> tensor_wire_end;    // per source tensor: end of its last run on the wire (0: sends nothing)
     uint64_t direct_n_vec = 0;                // KIND_VEC tiles at the front of tiles[2]
     std::vector<uint64_t> run_starts;         // per run: Segment::run_start of the segment it was cut from
     // per pack / unpack tile: 16-bit units between the start of its tensor's wire run and the tile's
@@ -141,5 +142,6 @@ int launch_checksum_finalize(const Tile* tiles, const uint64_t* partials, const 
                              uint64_t tile0, uint64_t ntiles, uint64_t* sums, void* stream);
 
 int launch_reference_copy(void* dst, const void* src, uint64_t nbytes, void* stream);
+int launch_signal(uint64_t* flag, uint64_t value, void* stream);
 
 }  // namespace th

@@ -576,7 +576,22 @@ __global__ __launch_bounds__(kBlockThreads) void th_reference_copy_kernel(const 
     if (i < nvec) st16((gdst_t)(dst + i), ld16((gsrc_t)(src + i)));
 }
 
+// Progress counter store: ordered after everything earlier in the stream, visible system-wide.
+__global__ void th_signal_kernel(uint64_t* flag, uint64_t value) {
+    __atomic_store_n(flag, value, __ATOMIC_RELEASE);  // system scope: host and peers may poll it
+}
+
 }  // namespace
+
+int launch_signal(uint64_t* flag, uint64_t value, void* stream) {
+    hipLaunchKernelGGL(th_signal_kernel, dim3(1), dim3(1), 0, static_cast<hipStream_t>(stream), flag, value);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("kernel launch failed: %s", hipGetErrorString(e));
+        return TH_ERR_HIP;
+    }
+    return TH_OK;
+}
 
 int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first, const InlineWire& inl,

@@ -255,8 +255,10 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
     }
     m.chunk_bytes = CB;
     m.wire_bytes = m.payload_bytes = m.src_read_bytes = 0;
+    m.tensor_wire_end.assign(m.tensors[0].size(), 0);
     for (const Segment& g : m.segments) {
         m.wire_bytes = std::max(m.wire_bytes, seg_wire_end(g));
+        m.tensor_wire_end[g.src_tensor] = std::max(m.tensor_wire_end[g.src_tensor], seg_wire_end(g));
         m.payload_bytes += g.nrows * g.row_len * esize(g.wire_dtype);
         m.src_read_bytes += g.nrows * g.row_len * esize(g.src_dtype);
     }

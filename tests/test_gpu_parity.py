@@ -477,3 +477,46 @@ def test_pipelined_chunks_on_two_streams_and_two_threads():
         assert np.array_equal(wd.cpu().numpy()[:plan.wire_bytes], wire)
         assert_same([synth.to_bits(t) for t in dd], [x.reshape(-1) for x in want])
     plan.destroy()
+
+
+def test_progress_counter_in_pinned_host_memory():
+    """th_signal after each unpacked chunk: a polling host thread sees a monotone counter that ends
+    at the chunk count, without any host synchronisation in between."""
+    import threading
+    import time
+    w = synth.workload("small_dense_tp1_to_tp4")
+    model, src, dst = w["model"], w["holders"][0], w["reader"]
+    tensors = holder_tensors_cpu(model, src, 91)
+    plan = th.th_plan_create(model, src, dst, 64 * 1024)
+    n = plan.num_chunks
+    src_dev = [to_dev(t) for t in tensors]
+    dst_dev = dev.alloc_tensors(plan, 1, fill_bits=SENT16)
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=SENT8)
+    counter = torch.zeros(1, dtype=torch.int64, pin_memory=True)
+    seen = []
+    stop = threading.Event()
+
+    def poll():
+        while not stop.is_set():
+            seen.append(int(counter[0]))
+            time.sleep(0.0002)
+
+    t = threading.Thread(target=poll)
+    t.start()
+    stream = dev.current_stream()
+    for c in range(n):
+        th.th_pack(plan, dev.ptrs(src_dev), wptrs[c:c + 1], c, 1, stream)
+        th.th_unpack(plan, wptrs[c:c + 1], c, 1, dev.ptrs(dst_dev), stream)
+        th.th_signal(counter.data_ptr(), c + 1, stream)
+    torch.cuda.synchronize()
+    stop.set()
+    t.join()
+    assert int(counter[0]) == n
+    assert seen == sorted(seen) and seen[-1] <= n
+    assert plan.tensors_complete(int(counter[0])) == plan.num_tensors(0)
+    want = reshard.empty_tensors(model, dst, fill=SENT16)
+    reshard.unpack(model, src, dst, reshard.pack(model, src, dst, tensors), want)
+    assert_same([synth.to_bits(x) for x in dst_dev], [x.reshape(-1) for x in want])
+    with pytest.raises(th.ThError):
+        th.th_signal(counter.data_ptr() + 4, 1, stream)
+    plan.destroy()

@@ -185,6 +185,32 @@ def test_narrowing_at_unpack_manifest(name):
         assert np.array_equal(g, x) and np.array_equal(d, x)
 
 
+def test_tensors_complete_matches_the_oracle_prefix():
+    """Chunks done -> leading source tensors whose run has fully arrived (the paper's progress unit)."""
+    for name in ("small_dense_tp1_to_tp4", "small_moe_ep4_to_tp2", "small_dense_tp4_to_tp2"):
+        w = synth.workload(name)
+        model, dst = w["model"], w["reader"]
+        for src in w["holders"]:
+            cb = 64 * 1024
+            plan = th.th_plan_create(model, src, dst, cb, HOST)
+            n_src = plan.num_tensors(0)
+            end = np.zeros(n_src, dtype=np.int64)
+            for it in reshard.plan_items(model, src, dst):
+                n = len(it["src_r"]) * len(it["src_c"]) * reshard.ESIZE[it["wire_dtype"]]
+                end[it["src_id"]] = max(end[it["src_id"]], it["wire_off"] + n)
+            prev = 0
+            for c in range(plan.num_chunks + 1):
+                done = min(c * cb, plan.wire_bytes)
+                want = 0
+                while want < n_src and end[want] <= done:
+                    want += 1
+                got = plan.tensors_complete(c)
+                assert got == want and got >= prev
+                prev = got
+            assert plan.tensors_complete(plan.num_chunks) == n_src
+            plan.destroy()
+
+
 def test_chunks_are_self_contained():
     """Unpacking any subset of chunks, in any order, touches only that subset's elements."""
     w = synth.workload("small_dense_tp1_to_tp4")
