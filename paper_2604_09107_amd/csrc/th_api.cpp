@@ -186,6 +186,18 @@ int finish_plan(th_plan* p, size_t chunk_bytes, unsigned flags, bool aligned16, 
     return TH_OK;
 }
 
+// A plan's tables live on the device that was current when it was created.
+int check_device(const th_plan* p) {
+    int dev = -1;
+    const hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev != p->device) {
+        set_error("plan belongs to device %d but device %d is current", p->device, dev);
+        return TH_ERR_ARG;
+    }
+    return TH_OK;
+}
+
 // Looks up / uploads the device table of the tensor base pointers of one side (0 = source tensors,
 // 1 = destination tensors) and validates a table that was not seen before.  Caller holds p->mu.
 int tensor_table(const th_plan* p, int side, const void* const* ptrs, uint32_t n, PtrSlot** out) {
@@ -250,6 +262,7 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
         ntiles[k] = m.chunk_tile0[side][k][chunk_first + chunk_count] - tile0[k];
     }
     if (ntiles[0] + ntiles[1] == 0) return TH_OK;
+    if (int rc = check_device(p)) return rc;
 
     for (uint32_t i = 0; i < chunk_count; ++i) {
         const uintptr_t a = reinterpret_cast<uintptr_t>(wire_ptrs[i]);
@@ -414,6 +427,7 @@ int th_reshard(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, vo
         set_error("null pointer array");
         return TH_ERR_ARG;
     }
+    if (int rc = check_device(p)) return rc;
     std::lock_guard<std::mutex> lk(p->mu);
     PtrSlot *ss = nullptr, *ds = nullptr;
     if (int rc = tensor_table(p, 0, src_ptrs, n_src, &ss)) return rc;

@@ -460,7 +460,8 @@ __device__ __forceinline__ void copy_any(gsrc_t src, gdst_t dst, uint64_t ss, ui
     }
 }
 
-template <int MODE, bool VEC_ONLY, bool CHECKSUM>
+// INLINE: the wire pointers come from the kernel arguments (short chunk ranges) instead of the table.
+template <int MODE, bool VEC_ONLY, bool CHECKSUM, bool INLINE>
 __global__ __launch_bounds__(kBlockThreads, TH_MIN_WAVES_PER_EU) void th_tiles_kernel(const Tile* __restrict__ tiles,
                                                                   const void* const* __restrict__ src_table,
                                                                   void* const* __restrict__ dst_table,
@@ -481,8 +482,8 @@ __global__ __launch_bounds__(kBlockThreads, TH_MIN_WAVES_PER_EU) void th_tiles_k
     constexpr int SUM = !CHECKSUM ? 0 : (PACK ? 1 : 2);
     const uint32_t sb = MODE == MODE_UNPACK ? t.src_buf - wire_first : t.src_buf;
     const uint32_t db = MODE == MODE_PACK ? t.dst_buf - wire_first : t.dst_buf;
-    const void* sbase = (MODE == MODE_UNPACK && inl.n) ? inl.p[sb] : src_table[sb];
-    void* dbase = (MODE == MODE_PACK && inl.n) ? inl.p[db] : dst_table[db];
+    const void* sbase = (MODE == MODE_UNPACK && INLINE) ? inl.p[sb] : src_table[sb];
+    void* dbase = (MODE == MODE_PACK && INLINE) ? inl.p[db] : dst_table[db];
     gsrc_t src = (gsrc_t)(static_cast<const char*>(sbase) + t.src_off);
     gdst_t dst = (gdst_t)(static_cast<char*>(dbase) + t.dst_off);
     const uint32_t kind = VEC_ONLY ? (uint32_t)TILE_KIND_VEC : (flags & TILE_KIND_MASK);
@@ -599,15 +600,21 @@ int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uin
     hipStream_t st = static_cast<hipStream_t>(stream);
     constexpr uint64_t kMaxGrid = 1u << 30;
     typedef void (*kernel_t)(const Tile*, const void* const*, void* const*, uint32_t, InlineWire, uint64_t*);
-    static const kernel_t kernels[3][2][2] = {
-        {{th_tiles_kernel<MODE_PACK, false, false>, th_tiles_kernel<MODE_PACK, false, true>},
-         {th_tiles_kernel<MODE_PACK, true, false>, th_tiles_kernel<MODE_PACK, true, true>}},
-        {{th_tiles_kernel<MODE_UNPACK, false, false>, th_tiles_kernel<MODE_UNPACK, false, true>},
-         {th_tiles_kernel<MODE_UNPACK, true, false>, th_tiles_kernel<MODE_UNPACK, true, true>}},
-        {{th_tiles_kernel<MODE_DIRECT, false, false>, nullptr}, {th_tiles_kernel<MODE_DIRECT, true, false>, nullptr}}};
-    const kernel_t kernel = kernels[mode][vec_only ? 1 : 0][partials ? 1 : 0];
+    // [mode][vector-only][checksum][inline wire pointers]
+    static const kernel_t kernels[3][2][2][2] = {
+        {{{th_tiles_kernel<MODE_PACK, false, false, false>, th_tiles_kernel<MODE_PACK, false, false, true>},
+          {th_tiles_kernel<MODE_PACK, false, true, false>, th_tiles_kernel<MODE_PACK, false, true, true>}},
+         {{th_tiles_kernel<MODE_PACK, true, false, false>, th_tiles_kernel<MODE_PACK, true, false, true>},
+          {th_tiles_kernel<MODE_PACK, true, true, false>, th_tiles_kernel<MODE_PACK, true, true, true>}}},
+        {{{th_tiles_kernel<MODE_UNPACK, false, false, false>, th_tiles_kernel<MODE_UNPACK, false, false, true>},
+          {th_tiles_kernel<MODE_UNPACK, false, true, false>, th_tiles_kernel<MODE_UNPACK, false, true, true>}},
+         {{th_tiles_kernel<MODE_UNPACK, true, false, false>, th_tiles_kernel<MODE_UNPACK, true, false, true>},
+          {th_tiles_kernel<MODE_UNPACK, true, true, false>, th_tiles_kernel<MODE_UNPACK, true, true, true>}}},
+        {{{th_tiles_kernel<MODE_DIRECT, false, false, false>, nullptr}, {nullptr, nullptr}},
+         {{th_tiles_kernel<MODE_DIRECT, true, false, false>, nullptr}, {nullptr, nullptr}}}};
+    const kernel_t kernel = kernels[mode][vec_only ? 1 : 0][partials ? 1 : 0][inl.n ? 1 : 0];
     if (!kernel) {
-        set_error("no checksum variant of this kernel");
+        set_error("no such variant of the tile kernel");
         return TH_ERR_ARG;
     }
     while (ntiles) {
