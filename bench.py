@@ -24,12 +24,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # the counter reads for th_reference_copy of known size; summaries under profiles/).  Valid only for
 # the kernel sources they were taken with: bench.py reports null once those files have changed.
 TRAFFIC_SOURCES = ("th_kernels.hip", "th_planner.cpp", "th_internal.hpp")
-TRAFFIC_SHA256 = "3d568fd7109a1553450de6abf274393100afb992038524e196843de505f0f85c"
+TRAFFIC_SHA256 = "3bd39a68aa43e97a23c270e2ff5e32004da41cc78bcd583162f0d06acb0bc4b8"
 TRAFFIC_BYTES = {
-    "cfg2_8b_tp1_to_tp4": {"th_pack": 8063029000, "th_unpack": 8062360000},
-    "cfg3_70b_tp8_to_tp4": {"th_pack": 35421357000, "th_unpack": 35416100000},
-    "cfg4_moe_ep8_to_tp2": {"th_pack": 5832600000, "th_unpack": 5832200000},
-    "cfg5_scatter_fp32_to_bf16": {"th_pack": 36895500000, "th_unpack": 22646600000},
+    "cfg2_8b_tp1_to_tp4": {"th_pack": 8062894619, "th_unpack": 8062271709},
+    "cfg3_70b_tp8_to_tp4": {"th_pack": 35420331854, "th_unpack": 35414952856},
+    "cfg4_moe_ep8_to_tp2": {"th_pack": 5832457756, "th_unpack": 5832146398},
+    "cfg5_scatter_fp32_to_bf16": {"th_pack": 37172418306, "th_unpack": 22633059596},
 }
 
 
