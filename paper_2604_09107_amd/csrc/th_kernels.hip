@@ -45,6 +45,9 @@ struct __attribute__((packed, aligned(4))) Unaligned4 { u32x4 v; };
 #ifndef TH_UNROLL
 #define TH_UNROLL 4
 #endif
+#ifndef TH_DENSE_IN_FLIGHT
+#define TH_DENSE_IN_FLIGHT 2
+#endif
 constexpr int kUnroll = TH_UNROLL;  // 128-bit accesses in flight per lane on the vector path
 
 // Streaming accesses: every byte is touched once, so mark them non-temporal.
@@ -63,8 +66,13 @@ __device__ __forceinline__ uint32_t narrow_rne(uint32_t u) {
     const uint32_t quiet = (u >> 16) | 0x0040u;
     return ((u & 0x7FFFFFFFu) > 0x7F800000u) ? quiet : rounded;
 }
+// Two at a time: the hardware pair conversion rounds to nearest even, keeps subnormals and quiets a
+// NaN the same way (it agrees with narrow_rne on all 2^32 inputs in the default float mode).
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t narrow_pair(uint32_t lo, uint32_t hi) {
-    return narrow_rne(lo) | (narrow_rne(hi) << 16);
+    const f32x2 v = {__builtin_bit_cast(float, lo), __builtin_bit_cast(float, hi)};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 // x / d for the linear position x of a tile element in a rectangle with d units per row.
@@ -242,50 +250,87 @@ __device__ __forceinline__ uint32_t load_elem(gsrc_t p) {
     return *reinterpret_cast<const TH_GLOBAL uint16_t*>(p);
 }
 
-// One 16-byte destination slot from element-aligned, contiguous source data.
-template <int SES, int DES>
-__device__ __forceinline__ u32x4 load_slot(gsrc_t s) {
-    if (SES == DES) {
-        if (SES == 2 && (reinterpret_cast<uintptr_t>(s) & 2u)) {
-            // A 16-byte load that is not even dword-aligned costs ~10 % of the bandwidth here.
-            // Read the five aligned dwords that contain the slot instead (they contain valid bytes,
-            // so they lie in the same pages) and shift by 16 bits.
-            const u32x4 q = reinterpret_cast<const TH_GLOBAL Unaligned4*>(s - 2)->v;
-            const uint32_t e = *reinterpret_cast<const TH_GLOBAL uint32_t*>(s + 14);
-            u32x4 o;
-            o.x = __builtin_amdgcn_alignbit(q.y, q.x, 16);
-            o.y = __builtin_amdgcn_alignbit(q.z, q.y, 16);
-            o.z = __builtin_amdgcn_alignbit(q.w, q.z, 16);
-            o.w = __builtin_amdgcn_alignbit(e, q.w, 16);
-            return o;
-        }
-        return reinterpret_cast<const TH_GLOBAL Unaligned4*>(s)->v;
-    } else {  // 4 fp32 -> 4 bf16 (an 8-byte slot in the low half)
-        const u32x4 a = reinterpret_cast<const TH_GLOBAL Unaligned4*>(s)->v;
-        u32x4 o;
-        o.x = narrow_pair(a.x, a.y);
-        o.y = narrow_pair(a.z, a.w);
-        o.z = o.w = 0;
-        return o;
+// 16 source bytes at an element-aligned address, in two steps so that several can be in flight:
+// issue16 starts the loads, settle16 (first use of the data) puts the bytes in place.  A 16-byte
+// load that is not even dword-aligned costs ~10 % of the bandwidth here, so for 2-byte elements at
+// an odd halfword the five aligned dwords that contain the slot are read instead (they contain
+// valid bytes, so they lie in the same pages) and shifted by 16 bits.
+template <int SES>
+struct Raw16 {
+    u32x4 q;
+    uint32_t e;
+};
+template <int SES>
+__device__ __forceinline__ void issue16(Raw16<SES>& r, gsrc_t p) {
+    if (SES == 4) {
+        r.q = reinterpret_cast<const TH_GLOBAL Unaligned4*>(p)->v;
+    } else {
+        const uint32_t odd = (uint32_t)reinterpret_cast<uintptr_t>(p) & 2u;
+        r.q = reinterpret_cast<const TH_GLOBAL Unaligned4*>(p - odd)->v;
+        r.e = 0;
+        if (odd) r.e = *reinterpret_cast<const TH_GLOBAL uint32_t*>(p + 14);
     }
 }
+template <int SES>
+__device__ __forceinline__ uint32_t odd_half(gsrc_t p) {  // 2 when p is not dword-aligned
+    return SES == 4 ? 0u : (uint32_t)reinterpret_cast<uintptr_t>(p) & 2u;
+}
+template <int SES>
+__device__ __forceinline__ u32x4 settle16(const Raw16<SES>& r, uint32_t odd) {
+    if (SES == 4) return r.q;
+    const uint32_t sh = odd * 8u;
+    u32x4 o;
+    o.x = __builtin_amdgcn_alignbit(r.q.y, r.q.x, sh);
+    o.y = __builtin_amdgcn_alignbit(r.q.z, r.q.y, sh);
+    o.z = __builtin_amdgcn_alignbit(r.q.w, r.q.z, sh);
+    o.w = __builtin_amdgcn_alignbit(r.e, r.q.w, sh);
+    return o;
+}
 
-// The same, and with SUM == 2 (the wire is the source) the checksum terms of the source bytes that
-// were read, which sit rel bytes after the tile's wire base.
+// The 16 bytes that start `over` elements of ES bytes into the 32 bytes a || b (over * ES < 16).
+// Written with selects on named values: an indexed array here ends up in scratch memory.
+template <int ES>
+__device__ __forceinline__ u32x4 shift_in(u32x4 a, u32x4 b, uint32_t over) {
+    const uint32_t sd = ES == 4 ? over : over >> 1;  // whole dwords
+    const bool s1 = (sd & 1u) != 0, s2 = (sd & 2u) != 0;
+    const uint32_t u0 = s1 ? a.y : a.x, u1 = s1 ? a.z : a.y, u2 = s1 ? a.w : a.z, u3 = s1 ? b.x : a.w;
+    const uint32_t u4 = s1 ? b.y : b.x, u5 = s1 ? b.z : b.y, u6 = s1 ? b.w : b.z;
+    const uint32_t t0 = s2 ? u2 : u0, t1 = s2 ? u3 : u1, t2 = s2 ? u4 : u2, t3 = s2 ? u5 : u3;
+    u32x4 o;
+    if (ES == 4) {
+        o.x = t0, o.y = t1, o.z = t2, o.w = t3;
+    } else {
+        const uint32_t t4 = s2 ? u6 : u4;
+        const uint32_t sh = (over & 1u) * 16u;
+        o.x = __builtin_amdgcn_alignbit(t1, t0, sh);
+        o.y = __builtin_amdgcn_alignbit(t2, t1, sh);
+        o.z = __builtin_amdgcn_alignbit(t3, t2, sh);
+        o.w = __builtin_amdgcn_alignbit(t4, t3, sh);
+    }
+    return o;
+}
+
+// 16 source bytes -> the destination slot's bytes (4 fp32 -> 4 bf16 in the low half when narrowing).
+template <int SES, int DES>
+__device__ __forceinline__ u32x4 convert_slot(u32x4 a) {
+    if (SES == DES) return a;
+    u32x4 o;
+    o.x = narrow_pair(a.x, a.y);
+    o.y = narrow_pair(a.z, a.w);
+    o.z = o.w = 0;
+    return o;
+}
+
+// One destination slot from element-aligned, contiguous source data; with SUM == 2 (the wire is
+// the source) also the checksum terms of the source bytes, which sit rel bytes after the tile's
+// wire base.
 template <int SES, int DES, int SUM>
 __device__ __forceinline__ u32x4 load_slot_sum(gsrc_t s, uint64_t rel, Sum& acc) {
-    if (SUM == 2 && SES != DES) {  // fp32 on the wire, narrowed here
-        const u32x4 a = reinterpret_cast<const TH_GLOBAL Unaligned4*>(s)->v;
-        sum_halves(acc, a, 0, 8, (int64_t)(rel / 2));
-        u32x4 o;
-        o.x = narrow_pair(a.x, a.y);
-        o.y = narrow_pair(a.z, a.w);
-        o.z = o.w = 0;
-        return o;
-    }
-    const u32x4 o = load_slot<SES, DES>(s);
-    if (SUM == 2) sum_halves(acc, o, 0, SlotBytes<SES, DES>::value / 2, (int64_t)(rel / 2));
-    return o;
+    Raw16<SES> r;
+    issue16<SES>(r, s);
+    const u32x4 a = settle16<SES>(r, odd_half<SES>(s));
+    if (SUM == 2) sum_halves(acc, a, 0, 8, (int64_t)(rel / 2));
+    return convert_slot<SES, DES>(a);
 }
 
 template <int DES, int EPV>
@@ -366,63 +411,113 @@ __device__ __forceinline__ void commit_slot(const Slot<DES>& s, int64_t rel, Sum
     }
 }
 
-// Contiguous destination: each thread owns one aligned 16-byte slot of the tile's destination
+// Contiguous destination: each thread owns one aligned destination slot of the tile's destination
 // bytes and gathers its elements from the source rectangle, whose rows hold nc elements and lie
 // ss bytes apart; element e of the tile sits at linear position x = col0 + e of that rectangle.
 // A slot that straddles the boundary between two tiles of one run is written whole by the
 // earlier tile (tail_ok) and skipped by the later one (head_skip), so inside a run every store
-// is one 128-bit store whatever the alignment of the base pointer; only a run's first and last
+// is one full-slot store whatever the alignment of the base pointer; only a run's first and last
 // slot can be partial.  Division as on the vector path (magic == 0: at most one wrap per tile).
-template <int SES, int DES, int SUM>
-__device__ __forceinline__ Slot<DES> fetch_slot(gsrc_t src, gdst_t dst, uint64_t ss, uint32_t nc, uint32_t col0,
-                                                uint32_t magic, uint32_t lead, uint32_t limit, uint32_t t,
-                                                Sum& acc) {
-    constexpr int EPV = SlotBytes<SES, DES>::value / DES;
-    Slot<DES> s;
-    const int32_t e0 = (int32_t)(t * EPV) - (int32_t)lead;
-    s.first = e0 < 0 ? -e0 : 0;
-    s.last = (uint32_t)(e0 + EPV) <= limit ? EPV : (int)(limit - (uint32_t)e0);
-    s.d = dst + (ptrdiff_t)e0 * DES;
-    const uint32_t x = col0 + (uint32_t)(e0 + s.first);
-    const uint32_t row = div_rows(x, nc, magic);
-    const uint32_t col = x - row * nc;
-    const bool full = s.first == 0 && s.last == EPV;
-    if (full && col + EPV <= nc) {
-        const uint64_t rel = (uint64_t)row * ss + (uint64_t)col * SES;
-        s.o = load_slot_sum<SES, DES, SUM>(src + rel, rel, acc);
-    } else if (full) {
-        s.o = gather_slot<SES, DES, SUM, true>(src, ss, nc, row, col, 0, EPV, 0, acc);
-    } else {
-        s.o = gather_slot<SES, DES, SUM, false>(src, ss, nc, row, col, s.first, s.last, 0, acc);
-    }
-    return s;
-}
-
+//
+// A full slot whose elements lie in one source row is one 16-byte load.  A full slot that runs
+// over a row end takes two: the last 16 bytes of its row and the first 16 bytes of the next row
+// (both inside the rectangle when a row holds at least a slot's elements), and picks its bytes
+// out of the 32.  kInFlight slots per thread and pass: all their loads are issued before the
+// first use, so a pass costs one memory latency.  Rows shorter than a slot, and wrapping slots
+// whose source bytes enter a checksum, take the general loop; the run's partial first and last
+// slot are gathered element by element by one thread each.
 template <int SES, int DES, int SUM>
 __device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, uint32_t count, uint32_t nc,
                                            uint32_t col0, uint32_t magic, bool head_skip, bool tail_ok, Sum& acc) {
     constexpr int SLOT = SlotBytes<SES, DES>::value;
     constexpr int EPV = SLOT / DES;
+    static_assert(EPV * SES == 16, "a slot's source elements fill one 16-byte load");
     const uint32_t lead = (uint32_t)(reinterpret_cast<uintptr_t>(dst) & (uint32_t)(SLOT - 1)) / DES;
     const uint32_t nslots = (lead + count + EPV - 1) / EPV;
     const uint32_t limit = tail_ok ? count + EPV : count;  // elements this tile may write
-    // two slots per thread and pass, both fetched before either is stored (four in flight measured
-    // slower: register pressure, and the path is not latency-bound)
-    constexpr int kInFlight = 2;
-    for (uint32_t t = threadIdx.x + ((head_skip && lead) ? 1u : 0u); t < nslots; t += kInFlight * kBlockThreads) {
-        Slot<DES> q[kInFlight];
+    // slots [lo, hi) are full; slot 0 is partial when the tile starts inside it (and is another
+    // tile's when head_skip), the last slot when the tile ends inside it
+    const uint32_t lo = lead ? 1u : 0u;
+    const uint32_t full_end = (lead + limit) / EPV;
+    const uint32_t hi = full_end < nslots ? full_end : nslots;
+    const uint32_t tid = threadIdx.x;
+    // element e0 = slot * EPV - lead of the tile -> its row and column in the source rectangle
+    auto locate = [&](uint32_t slot, uint32_t skip, uint32_t& row, uint32_t& col) {
+        const uint32_t x = col0 + slot * EPV - lead + skip;
+        row = div_rows(x, nc, magic);
+        col = x - row * nc;
+    };
+
+    if (nc >= (uint32_t)EPV && (SUM != 2 || col0 + limit <= nc)) {
+        constexpr int kInFlight = TH_DENSE_IN_FLIGHT;
+        for (uint32_t t = lo + tid; t < hi; t += kInFlight * kBlockThreads) {
+            Raw16<SES> ra[kInFlight], rb[kInFlight];
+            uint32_t over[kInFlight], odd_a[kInFlight], odd_b[kInFlight];
+            uint64_t rel[kInFlight];
 #pragma unroll
-        for (int i = 0; i < kInFlight; ++i) {
-            const uint32_t ti = t + i * kBlockThreads;
-            if (i == 0 || ti < nslots)
-                q[i] = fetch_slot<SES, DES, SUM>(src, dst, ss, nc, col0, magic, lead, limit, ti, acc);
-        }
-        const int64_t rel0 = ((int64_t)t * EPV - (int64_t)lead) * DES;
+            for (int i = 0; i < kInFlight; ++i) {
+                const uint32_t ti = t + i * kBlockThreads;
+                over[i] = 0;
+                if (i == 0 || ti < hi) {
+                    uint32_t row, col;
+                    locate(ti, 0, row, col);
+                    over[i] = col + EPV <= nc ? 0u : col + EPV - nc;  // elements that lie in the next row
+                    rel[i] = (uint64_t)row * ss + (uint64_t)col * SES;
+                    gsrc_t pa = src + rel[i] - (uint64_t)over[i] * SES;
+                    odd_a[i] = odd_half<SES>(pa);
+                    issue16<SES>(ra[i], pa);
+                    if (over[i]) {
+                        gsrc_t pb = src + (uint64_t)(row + 1) * ss;
+                        odd_b[i] = odd_half<SES>(pb);
+                        issue16<SES>(rb[i], pb);
+                    }
+                }
+            }
 #pragma unroll
-        for (int i = 0; i < kInFlight; ++i) {
-            const uint32_t ti = t + i * kBlockThreads;
-            if (i == 0 || ti < nslots) commit_slot<DES, SLOT, SUM>(q[i], rel0 + (int64_t)i * kBlockThreads * SLOT, acc);
+            for (int i = 0; i < kInFlight; ++i) {
+                const uint32_t ti = t + i * kBlockThreads;
+                if (i == 0 || ti < hi) {
+                    u32x4 a = settle16<SES>(ra[i], odd_a[i]);
+                    if (over[i]) a = shift_in<SES>(a, settle16<SES>(rb[i], odd_b[i]), over[i]);
+                    if (SUM == 2) sum_halves(acc, a, 0, 8, (int64_t)(rel[i] / 2));
+                    Slot<DES> s;
+                    s.o = convert_slot<SES, DES>(a);
+                    s.d = dst + ((ptrdiff_t)ti * EPV - (ptrdiff_t)lead) * DES;
+                    s.first = 0, s.last = EPV;
+                    commit_slot<DES, SLOT, SUM>(s, ((int64_t)ti * EPV - (int64_t)lead) * DES, acc);
+                }
+            }
         }
+    } else {
+        for (uint32_t t = lo + tid; t < hi; t += kBlockThreads) {
+            uint32_t row, col;
+            locate(t, 0, row, col);
+            Slot<DES> s;
+            if (col + EPV <= nc) {
+                const uint64_t rel = (uint64_t)row * ss + (uint64_t)col * SES;
+                s.o = load_slot_sum<SES, DES, SUM>(src + rel, rel, acc);
+            } else {
+                s.o = gather_slot<SES, DES, SUM, true>(src, ss, nc, row, col, 0, EPV, 0, acc);
+            }
+            s.d = dst + ((ptrdiff_t)t * EPV - (ptrdiff_t)lead) * DES;
+            s.first = 0, s.last = EPV;
+            commit_slot<DES, SLOT, SUM>(s, ((int64_t)t * EPV - (int64_t)lead) * DES, acc);
+        }
+    }
+
+    // partial slots: thread 0 takes the first, a thread of another wavefront the last
+    const bool head = lead && !head_skip, tail = hi < nslots && (nslots > 1 || !lead);
+    if ((head && tid == 0) || (tail && tid == 64)) {
+        const uint32_t t = tid == 0 ? 0u : nslots - 1;
+        Slot<DES> s;
+        const int32_t e0 = (int32_t)(t * EPV) - (int32_t)lead;
+        s.first = e0 < 0 ? -e0 : 0;
+        s.last = (uint32_t)(e0 + EPV) <= limit ? EPV : (int)(limit - (uint32_t)e0);
+        s.d = dst + (ptrdiff_t)e0 * DES;
+        uint32_t row, col;
+        locate(t, (uint32_t)s.first, row, col);
+        s.o = gather_slot<SES, DES, SUM, false>(src, ss, nc, row, col, s.first, s.last, 0, acc);
+        commit_slot<DES, SLOT, SUM>(s, (int64_t)e0 * DES, acc);
     }
 }
 
