@@ -78,7 +78,13 @@ enum : uint32_t {
 #ifndef TH_BLOCK_THREADS
 #define TH_BLOCK_THREADS 1024
 #endif
-constexpr int kBlockThreads = TH_BLOCK_THREADS;  // threads per workgroup (one tile each)
+constexpr int kBlockThreads = TH_BLOCK_THREADS;  // threads per workgroup (one tile each), vector-path kernel
+// The kernel that holds every path runs smaller workgroups: its tiles are often short (a tile never
+// spans two runs), and a compute unit refills sooner when it waits for 8 free wavefront slots, not 16.
+#ifndef TH_BLOCK_THREADS_ANY
+#define TH_BLOCK_THREADS_ANY 512
+#endif
+constexpr int kBlockThreadsAny = TH_BLOCK_THREADS_ANY;
 
 struct Manifest {
     std::vector<TensorInfo> tensors[2];  // 0 = source side, 1 = destination side
@@ -101,7 +107,7 @@ struct Manifest {
 
 struct Tuning {
     uint64_t tile_bytes = 16384;      // vector path: one 128-bit vector per thread of a workgroup
-    uint64_t tile_bytes_any = 32768;  // any-alignment paths: two destination slots per thread
+    uint64_t tile_bytes_any = 12288;  // any-alignment paths (measured best with 512-thread workgroups on short runs)
     uint64_t tile_bytes_checksum = 65536;  // both paths in plans with checksums: amortises the workgroup reduction
     bool specialize = true;           // launch vector-path tiles with the kernel that holds only that path
 };
@@ -134,7 +140,8 @@ struct InlineWire {
 };
 // partials: nullptr, or device array of 2 x uint64 per tile of `tiles` (same indexing) that receives
 // each tile's checksum terms (A, B with tile-local positions).
-int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
+// list_tiles: length of the whole list `tiles` (decides whether tile records are prefetched).
+int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles, uint64_t list_tiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first,
                  const InlineWire& inl, uint64_t* partials, void* stream);
 // Adds the per-tile terms of tiles [tile0, tile0 + ntiles) into sums[2 * src_tensor + {0, 1}].

@@ -150,8 +150,9 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
 // The 64-bit B is reduced as three limbs of 21 + 21 + 22 bits so that a wavefront's limb sums fit
 // 32 bits; A is below 2^24 per thread (at most 32 slots of 8 halves).  One thread adds the
 // wavefronts' results in 64-bit arithmetic.
+template <int BT>
 __device__ __forceinline__ void block_sum_store(const Sum& s, uint64_t* out) {
-    constexpr uint32_t kWaves = kBlockThreads / 64;
+    constexpr uint32_t kWaves = BT / 64;
     __shared__ uint32_t part[4 * kWaves];
     const uint32_t a = wave_sum_u32(s.a);
     const uint32_t b0 = wave_sum_u32((uint32_t)(s.b & 0x1FFFFFu));
@@ -182,11 +183,11 @@ __device__ __forceinline__ void block_sum_store(const Sum& s, uint64_t* out) {
 // x = col0 + i: row x / vpr, column x % vpr.  magic != 0: vpr < 2^15 and x < 2^16, so the
 // multiply-high division is exact; magic == 0: vpr is at least the tile's capacity, so x < 2*vpr
 // and the quotient is 0 or 1.
-template <int SUM>
+template <int BT, int SUM>
 __device__ __forceinline__ void copy_vec(gsrc_t src, gdst_t dst, uint64_t ss, uint64_t ds, uint32_t count,
                                          uint32_t vpr, uint32_t col0, uint32_t magic, Sum& acc) {
     const uint32_t tid = threadIdx.x;
-    if (count <= kBlockThreads) {
+    if (count <= BT) {
         // the default tile: one vector per thread, nothing else
         if (tid < count) {
             const uint32_t x = col0 + tid;
@@ -201,13 +202,13 @@ __device__ __forceinline__ void copy_vec(gsrc_t src, gdst_t dst, uint64_t ss, ui
         }
         return;
     }
-    constexpr uint32_t kStep = kBlockThreads * kUnroll;
+    constexpr uint32_t kStep = BT * kUnroll;
     for (uint32_t base = 0; base < count; base += kStep) {
         u32x4 v[kUnroll];
         uint32_t row[kUnroll], col[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const uint32_t i = base + u * kBlockThreads + tid;
+            const uint32_t i = base + u * BT + tid;
             const uint32_t x = col0 + i;
             row[u] = div_rows(x, vpr, magic);
             col[u] = x - row[u] * vpr;
@@ -215,7 +216,7 @@ __device__ __forceinline__ void copy_vec(gsrc_t src, gdst_t dst, uint64_t ss, ui
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const uint32_t i = base + u * kBlockThreads + tid;
+            const uint32_t i = base + u * BT + tid;
             if (i < count) {
                 st16(dst + (size_t)row[u] * ds + (size_t)col[u] * 16, v[u]);
                 if (SUM) {
@@ -426,7 +427,7 @@ __device__ __forceinline__ void commit_slot(const Slot<DES>& s, int64_t rel, Sum
 // first use, so a pass costs one memory latency.  Rows shorter than a slot, and wrapping slots
 // whose source bytes enter a checksum, take the general loop; the run's partial first and last
 // slot are gathered element by element by one thread each.
-template <int SES, int DES, int SUM>
+template <int BT, int SES, int DES, int SUM>
 __device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, uint32_t count, uint32_t nc,
                                            uint32_t col0, uint32_t magic, bool head_skip, bool tail_ok, Sum& acc) {
     constexpr int SLOT = SlotBytes<SES, DES>::value;
@@ -450,13 +451,13 @@ __device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, 
 
     if (nc >= (uint32_t)EPV && (SUM != 2 || col0 + limit <= nc)) {
         constexpr int kInFlight = TH_DENSE_IN_FLIGHT;
-        for (uint32_t t = lo + tid; t < hi; t += kInFlight * kBlockThreads) {
+        for (uint32_t t = lo + tid; t < hi; t += kInFlight * BT) {
             Raw16<SES> ra[kInFlight], rb[kInFlight];
             uint32_t over[kInFlight], odd_a[kInFlight], odd_b[kInFlight];
             uint64_t rel[kInFlight];
 #pragma unroll
             for (int i = 0; i < kInFlight; ++i) {
-                const uint32_t ti = t + i * kBlockThreads;
+                const uint32_t ti = t + i * BT;
                 over[i] = 0;
                 if (i == 0 || ti < hi) {
                     uint32_t row, col;
@@ -475,7 +476,7 @@ __device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, 
             }
 #pragma unroll
             for (int i = 0; i < kInFlight; ++i) {
-                const uint32_t ti = t + i * kBlockThreads;
+                const uint32_t ti = t + i * BT;
                 if (i == 0 || ti < hi) {
                     u32x4 a = settle16<SES>(ra[i], odd_a[i]);
                     if (over[i]) a = shift_in<SES>(a, settle16<SES>(rb[i], odd_b[i]), over[i]);
@@ -489,7 +490,7 @@ __device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, 
             }
         }
     } else {
-        for (uint32_t t = lo + tid; t < hi; t += kBlockThreads) {
+        for (uint32_t t = lo + tid; t < hi; t += BT) {
             uint32_t row, col;
             locate(t, 0, row, col);
             Slot<DES> s;
@@ -522,16 +523,17 @@ __device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, 
 }
 
 // Strided destination: each destination row is cut into aligned 16-byte slots of its own.
-template <int SES, int DES, int SUM>
+template <int BT, int SES, int DES, int SUM>
 __device__ __forceinline__ void copy_any(gsrc_t src, gdst_t dst, uint64_t ss, uint64_t ds, uint32_t nrows,
                                          uint32_t ncols, uint32_t lg, Sum& acc) {
     constexpr int SLOT = SlotBytes<SES, DES>::value;
     constexpr int EPV = SLOT / DES;  // elements per destination slot
     const uint32_t tid = threadIdx.x;
-    const uint32_t lanes = 1u << lg;             // threads that share a row
-    const uint32_t groups = kBlockThreads >> lg;  // rows in flight
+    const uint32_t lgc = min(lg, (uint32_t)__builtin_ctz(BT));
+    const uint32_t lanes = 1u << lgc;   // threads that share a row
+    const uint32_t groups = BT >> lgc;  // rows in flight
     const uint32_t lane = tid & (lanes - 1);
-    for (uint32_t r = tid >> lg; r < nrows; r += groups) {
+    for (uint32_t r = tid >> lgc; r < nrows; r += groups) {
         gsrc_t s = src + (size_t)r * ss;
         gdst_t d = dst + (size_t)r * ds;
         // elements between the previous 16-byte boundary and the row start
@@ -557,17 +559,27 @@ __device__ __forceinline__ void copy_any(gsrc_t src, gdst_t dst, uint64_t ss, ui
 
 // INLINE: the wire pointers come from the kernel arguments (short chunk ranges) instead of the table.
 template <int MODE, bool VEC_ONLY, bool CHECKSUM, bool INLINE>
-__global__ __launch_bounds__(kBlockThreads, TH_MIN_WAVES_PER_EU) void th_tiles_kernel(const Tile* __restrict__ tiles,
+__global__ __launch_bounds__(VEC_ONLY ? kBlockThreads : kBlockThreadsAny, TH_MIN_WAVES_PER_EU) void th_tiles_kernel(const Tile* __restrict__ tiles,
                                                                   const void* const* __restrict__ src_table,
                                                                   void* const* __restrict__ dst_table,
-                                                                  uint32_t wire_first, InlineWire inl,
-                                                                  uint64_t* __restrict__ partials) {
+                                                                  uint32_t wire_first, uint32_t records_ahead,
+                                                                  InlineWire inl, uint64_t* __restrict__ partials) {
     // Workgroups are dealt to the 8 XCDs round-robin (workgroup b runs on XCD b mod 8).  Give
     // each XCD one contiguous eighth of the tile list so that it streams through its own
     // address range instead of every 8th tile.
+    constexpr int BT = VEC_ONLY ? kBlockThreads : kBlockThreadsAny;
     uint32_t b = blockIdx.x;
     const uint32_t per_xcd = gridDim.x >> 3;
     if (b < per_xcd * 8) b = (b & 7) * per_xcd + (b >> 3);
+
+    // records_ahead != 0: pull the record of a tile this XCD reaches a few microseconds from now
+    // into its L2.  A record costs a workgroup one exposed memory latency before its first data
+    // load; the list of a small plan stays in the memory-side cache between launches, that of a
+    // large plan does not.  One lane, vector side of the memory system (a scalar load would be
+    // waited for together with this tile's own record).
+    uint32_t ahead = 0;
+    const bool prefetch = records_ahead && threadIdx.x == 0 && b + records_ahead < gridDim.x;
+    if (prefetch) ahead = *(const TH_GLOBAL uint32_t*)(tiles + b + records_ahead);
 
     const Tile& t = tiles[b];  // uniform: fetched by the scalar unit
     const uint32_t flags = t.flags;
@@ -585,17 +597,17 @@ __global__ __launch_bounds__(kBlockThreads, TH_MIN_WAVES_PER_EU) void th_tiles_k
     Sum acc;
 
     if (kind == TILE_KIND_VEC) {
-        copy_vec<SUM>(src, dst, ss, ds, count, ncols, t.col0, t.magic, acc);
+        copy_vec<BT, SUM>(src, dst, ss, ds, count, ncols, t.col0, t.magic, acc);
     } else if (kind == TILE_KIND_DENSE) {
         const bool head_skip = (flags & TILE_HEAD_SKIP) != 0, tail_ok = (flags & TILE_TAIL_OK) != 0;
         unsigned des = 2;
         if (flags & TILE_DST_F32) {
-            copy_dense<4, 4, SUM>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok, acc);
+            copy_dense<BT, 4, 4, SUM>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok, acc);
             des = 4;
         } else if (flags & TILE_SRC_F32) {
-            copy_dense<4, 2, SUM>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok, acc);
+            copy_dense<BT, 4, 2, SUM>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok, acc);
         } else {
-            copy_dense<2, 2, SUM>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok, acc);
+            copy_dense<BT, 2, 2, SUM>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok, acc);
         }
         if (PACK) {
             // zero the alignment gap that follows a tensor's last element on the wire
@@ -607,12 +619,12 @@ __global__ __launch_bounds__(kBlockThreads, TH_MIN_WAVES_PER_EU) void th_tiles_k
         const uint32_t lg = (flags & TILE_LG_LANES_MASK) >> TILE_LG_LANES_SHIFT;
         unsigned des = 2;
         if (flags & TILE_DST_F32) {
-            copy_any<4, 4, SUM>(src, dst, ss, ds, count, ncols, lg, acc);
+            copy_any<BT, 4, 4, SUM>(src, dst, ss, ds, count, ncols, lg, acc);
             des = 4;
         } else if (flags & TILE_SRC_F32) {
-            copy_any<4, 2, SUM>(src, dst, ss, ds, count, ncols, lg, acc);
+            copy_any<BT, 4, 2, SUM>(src, dst, ss, ds, count, ncols, lg, acc);
         } else {
-            copy_any<2, 2, SUM>(src, dst, ss, ds, count, ncols, lg, acc);
+            copy_any<BT, 2, 2, SUM>(src, dst, ss, ds, count, ncols, lg, acc);
         }
         if (PACK) {
             const uint32_t pad = (flags & TILE_PAD_MASK) >> TILE_PAD_SHIFT;
@@ -622,7 +634,8 @@ __global__ __launch_bounds__(kBlockThreads, TH_MIN_WAVES_PER_EU) void th_tiles_k
             }
         }
     }
-    if (CHECKSUM) block_sum_store(acc, partials + 2 * (size_t)b);
+    if (CHECKSUM) block_sum_store<BT>(acc, partials + 2 * (size_t)b);
+    if (prefetch) asm volatile("" ::"v"(ahead));  // keeps the load; its value is not used
 }
 
 // One thread per tile: shift the tile's pair to positions counted from the start of its tensor's
@@ -689,12 +702,16 @@ int launch_signal(uint64_t* flag, uint64_t value, void* stream) {
     return TH_OK;
 }
 
-int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
+int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles, uint64_t list_tiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first, const InlineWire& inl,
                  uint64_t* partials, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     constexpr uint64_t kMaxGrid = 1u << 30;
-    typedef void (*kernel_t)(const Tile*, const void* const*, void* const*, uint32_t, InlineWire, uint64_t*);
+    // a tile list of 32 MiB or more is taken not to stay in the memory-side cache from one launch
+    // to the next: prefetch its records
+    constexpr uint64_t kPrefetchMinTiles = 1u << 19;
+    const uint32_t records_ahead = list_tiles >= kPrefetchMinTiles ? 256u : 0u;
+    typedef void (*kernel_t)(const Tile*, const void* const*, void* const*, uint32_t, uint32_t, InlineWire, uint64_t*);
     // [mode][vector-only][checksum][inline wire pointers]
     static const kernel_t kernels[3][2][2][2] = {
         {{{th_tiles_kernel<MODE_PACK, false, false, false>, th_tiles_kernel<MODE_PACK, false, false, true>},
@@ -714,8 +731,9 @@ int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uin
     }
     while (ntiles) {
         const uint64_t n = ntiles < kMaxGrid ? ntiles : kMaxGrid;
-        hipLaunchKernelGGL(kernel, dim3((uint32_t)n), dim3(kBlockThreads), 0, st, tiles + tile0, src_table,
-                           dst_table, wire_first, inl, partials ? partials + 2 * tile0 : nullptr);
+        hipLaunchKernelGGL(kernel, dim3((uint32_t)n), dim3(vec_only ? kBlockThreads : kBlockThreadsAny), 0, st,
+                           tiles + tile0, src_table, dst_table, wire_first, records_ahead, inl,
+                           partials ? partials + 2 * tile0 : nullptr);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) {
             set_error("kernel launch failed: %s", hipGetErrorString(e));

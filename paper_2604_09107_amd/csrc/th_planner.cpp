@@ -140,7 +140,8 @@ void tile_run(std::vector<Tile>& out, Side S, Side D, uint64_t nrows, uint64_t n
         t.ncols = (uint32_t)nu;
         t.flags = flags;
         const uint64_t slots = (nu * D.es + 15) / 16 + 1;  // 16-byte destination slots a row can touch
-        t.flags |= std::min(10u, ceil_log2(slots)) << TILE_LG_LANES_SHIFT;
+        // threads that share a row: a power of two, at most the workgroup of the kernel that runs these tiles
+        t.flags |= std::min(ceil_log2((uint64_t)kBlockThreadsAny), ceil_log2(slots)) << TILE_LG_LANES_SHIFT;
         if (last && pad) t.flags |= (uint32_t)pad << TILE_PAD_SHIFT;
         out.push_back(t);
     };
