@@ -24,12 +24,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # the counter reads for th_reference_copy of known size; summaries under profiles/).  Valid only for
 # the kernel sources they were taken with: bench.py reports null once those files have changed.
 TRAFFIC_SOURCES = ("th_kernels.hip", "th_planner.cpp", "th_internal.hpp")
-TRAFFIC_SHA256 = "3bd39a68aa43e97a23c270e2ff5e32004da41cc78bcd583162f0d06acb0bc4b8"
+TRAFFIC_SHA256 = "e6540c546444e1bb0c12b5447df2daf057c1076be938f0f04b134366280e05a2"
 TRAFFIC_BYTES = {
-    "cfg2_8b_tp1_to_tp4": {"th_pack": 8062894619, "th_unpack": 8062271709},
-    "cfg3_70b_tp8_to_tp4": {"th_pack": 35420331854, "th_unpack": 35414952856},
-    "cfg4_moe_ep8_to_tp2": {"th_pack": 5832457756, "th_unpack": 5832146398},
-    "cfg5_scatter_fp32_to_bf16": {"th_pack": 37172418306, "th_unpack": 22633059596},
+    "cfg2_8b_tp1_to_tp4": {"th_pack": 8062863255, "th_unpack": 8062224856},
+    "cfg3_70b_tp8_to_tp4": {"th_pack": 35420888402, "th_unpack": 35415446251},
+    "cfg4_moe_ep8_to_tp2": {"th_pack": 5832497074, "th_unpack": 5832154900},
+    "cfg5_scatter_fp32_to_bf16": {"th_pack": 37187144201, "th_unpack": 22790162665},
 }
 
 

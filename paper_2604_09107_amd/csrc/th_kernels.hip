@@ -1,17 +1,18 @@
 // gfx950 kernels of the reshard path: one launch moves every tile of a chunk range.
 //
-// Pure data movement, bound by HBM bandwidth: no matrix cores.  One workgroup of
-// kBlockThreads threads (wavefronts of 64) takes one 64-byte tile record, which
-// the scalar unit fetches once for the whole workgroup, resolves its two base
-// pointers through the pointer tables, and copies a sub-rectangle:
+// Pure data movement, bound by HBM bandwidth: no matrix cores.  One workgroup
+// (kBlockThreads threads in the instance that holds only the vector path,
+// kBlockThreadsAny in the one that holds every path; wavefronts of 64) takes one
+// 64-byte tile record, which the scalar unit fetches once for the whole workgroup,
+// resolves its two base pointers through the pointer tables, and copies a sub-rectangle:
 //
 //   vector path  every address is a multiple of 16 bytes: 128-bit loads and stores,
-//                kUnroll of them in flight per lane before the first store;
+//                one per thread in the default tile size;
 //   dense path   element-aligned addresses and/or fp32 -> bf16 narrowing into a
 //                contiguous destination (every wire run of an explicit-segment plan):
-//                each thread owns one aligned 16-byte destination slot and gathers its
-//                elements from the source rows with unaligned vector loads, so every
-//                interior store is 128-bit even when rows are a few elements long;
+//                each thread owns one aligned destination slot and gathers its elements
+//                from the source rows with unaligned 16-byte loads, so every interior
+//                store is a full slot even when rows are a few elements long;
 //   any path     the same for a strided destination: each destination row is cut into
 //                aligned 16-byte slots; row-edge slots fall back to per-element accesses.
 //

@@ -161,6 +161,41 @@ def test_all_special_values_narrowed_like_the_oracle():
     run_scatter(100, 34, 1 << 18, 1 << 18, special_rate=1.0)
 
 
+def test_narrowing_every_high_half_at_the_rounding_boundaries():
+    """fp32 -> bf16 through th_pack on every sign / exponent / kept-mantissa combination (all 2^16
+    high halves) at the low halves where rounding decides (0, 1, just below / at / just above the
+    midpoint, all ones), plus 2^24 random bit patterns: the kernel's conversion against the
+    oracle's definition of round-to-nearest-even (subnormals kept, NaN quieted)."""
+    from oracle import rne
+    hi = np.arange(1 << 16, dtype=np.uint32) << 16
+    lows = np.array([0x0000, 0x0001, 0x7FFF, 0x8000, 0x8001, 0xFFFF], dtype=np.uint32)
+    grid = (hi[:, None] | lows[None, :]).reshape(-1)
+    rnd = np.random.default_rng(77).integers(0, 1 << 32, size=1 << 24, dtype=np.uint64).astype(np.uint32)
+    src = np.concatenate([grid, rnd])
+    n = len(src)
+    want = rne.narrow(src)
+    S = th.binding.SEGMENT_NP
+    # three segments so that fp32 sources start at every 4-byte phase of a 16-byte line
+    cuts = [0, 100003, 393216 + 5, n]
+    segs = np.zeros(3, dtype=S)
+    for k in range(3):
+        segs[k]["src_elem_off"] = segs[k]["dst_elem_off"] = cuts[k]
+        segs[k]["nrows"], segs[k]["row_len"] = 1, cuts[k + 1] - cuts[k]
+        segs[k]["src_row_stride"] = segs[k]["dst_row_stride"] = cuts[k + 1] - cuts[k]
+    segs["src_dtype"], segs["dst_dtype"] = th.TH_F32, th.TH_BF16
+    plan = th.th_plan_create_from_segments(segs, [n], [n], 1 << 22)
+    src_dev = synth.from_bits(src, "cuda")
+    dst_dev = synth.from_bits(np.zeros(n, dtype=np.uint16), "cuda")
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=SENT8)
+    th.th_pack(plan, [src_dev.data_ptr()], wptrs, 0, plan.num_chunks, dev.current_stream())
+    th.th_unpack(plan, wptrs, 0, plan.num_chunks, [dst_dev.data_ptr()], dev.current_stream())
+    torch.cuda.synchronize()
+    got = synth.to_bits(dst_dev)
+    bad = np.nonzero(got != want)[0]
+    assert bad.size == 0, "input %08x -> %04x, oracle %04x (%d differ)" % (src[bad[0]], got[bad[0]], want[bad[0]], bad.size)
+    plan.destroy()
+
+
 def test_same_dtype_any_alignment_and_fp32_passthrough():
     """Explicit segments with bf16 -> bf16 at odd element offsets and fp32 -> fp32 copies."""
     rng = np.random.default_rng(40)
