@@ -300,10 +300,10 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
         const bool vec_only = k == 0 && p->specialize;
         uint64_t* partials = want_sums ? p->d_partials[side] : nullptr;
         if (side == 0)
-            rc = launch_tiles(MODE_PACK, vec_only, p->d_tiles[0], tile0[k], ntiles[k], p->m.tiles[0].size(), tens_tab,
+            rc = launch_tiles(MODE_PACK, vec_only, p->d_tiles[0], tile0[k], ntiles[k], tens_tab,
                               const_cast<void* const*>(wire_tab), chunk_first, inl, partials, stream);
         else
-            rc = launch_tiles(MODE_UNPACK, vec_only, p->d_tiles[1], tile0[k], ntiles[k], p->m.tiles[1].size(), wire_tab,
+            rc = launch_tiles(MODE_UNPACK, vec_only, p->d_tiles[1], tile0[k], ntiles[k], wire_tab,
                               const_cast<void* const*>(tens_tab), chunk_first, inl, partials, stream);
         if (rc == TH_OK && want_sums)
             rc = launch_checksum_finalize(p->d_tiles[side], p->d_partials[side], p->d_tile_base[side], tile0[k],
@@ -438,10 +438,10 @@ int th_reshard(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, vo
     std::memset(&no_inline, 0, sizeof no_inline);
     int rc = TH_OK;
     if (m.direct_n_vec)
-        rc = launch_tiles(MODE_DIRECT, p->specialize, p->d_tiles[2], 0, m.direct_n_vec, total, stab, dtab, 0, no_inline,
+        rc = launch_tiles(MODE_DIRECT, p->specialize, p->d_tiles[2], 0, m.direct_n_vec, stab, dtab, 0, no_inline,
                           nullptr, hip_stream);
     if (rc == TH_OK && total > m.direct_n_vec)
-        rc = launch_tiles(MODE_DIRECT, false, p->d_tiles[2], m.direct_n_vec, total - m.direct_n_vec, total, stab, dtab, 0,
+        rc = launch_tiles(MODE_DIRECT, false, p->d_tiles[2], m.direct_n_vec, total - m.direct_n_vec, stab, dtab, 0,
                           no_inline, nullptr, hip_stream);
     if (rc != TH_OK) return rc;
     for (PtrSlot* s : {ss, ds}) {

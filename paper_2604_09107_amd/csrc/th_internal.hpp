@@ -140,8 +140,7 @@ struct InlineWire {
 };
 // partials: nullptr, or device array of 2 x uint64 per tile of `tiles` (same indexing) that receives
 // each tile's checksum terms (A, B with tile-local positions).
-// list_tiles: length of the whole list `tiles` (decides whether tile records are prefetched).
-int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles, uint64_t list_tiles,
+int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first,
                  const InlineWire& inl, uint64_t* partials, void* stream);
 // Adds the per-tile terms of tiles [tile0, tile0 + ntiles) into sums[2 * src_tensor + {0, 1}].

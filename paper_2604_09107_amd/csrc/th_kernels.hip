@@ -46,6 +46,7 @@ struct __attribute__((packed, aligned(4))) Unaligned4 { u32x4 v; };
 #ifndef TH_UNROLL
 #define TH_UNROLL 4
 #endif
+constexpr uint32_t kRecordsAhead = 256;  // tile records between a workgroup's own and the one it prefetches
 #ifndef TH_DENSE_IN_FLIGHT
 #define TH_DENSE_IN_FLIGHT 2
 #endif
@@ -572,8 +573,8 @@ template <int MODE, bool VEC_ONLY, bool CHECKSUM, bool INLINE>
 __global__ __launch_bounds__(VEC_ONLY ? kBlockThreads : kBlockThreadsAny, TH_MIN_WAVES_PER_EU) void th_tiles_kernel(const Tile* __restrict__ tiles,
                                                                   const void* const* __restrict__ src_table,
                                                                   void* const* __restrict__ dst_table,
-                                                                  uint32_t wire_first, uint32_t records_ahead,
-                                                                  InlineWire inl, uint64_t* __restrict__ partials) {
+                                                                  uint32_t wire_first, InlineWire inl,
+                                                                  uint64_t* __restrict__ partials) {
     // Workgroups are dealt to the 8 XCDs round-robin (workgroup b runs on XCD b mod 8).  Give
     // each XCD one contiguous eighth of the tile list so that it streams through its own
     // address range instead of every 8th tile.
@@ -582,18 +583,9 @@ __global__ __launch_bounds__(VEC_ONLY ? kBlockThreads : kBlockThreadsAny, TH_MIN
     const uint32_t per_xcd = gridDim.x >> 3;
     if (b < per_xcd * 8) b = (b & 7) * per_xcd + (b >> 3);
 
-    // records_ahead != 0: pull the record of a tile this XCD reaches a few microseconds from now
-    // into its L2.  A record costs a workgroup one exposed memory latency before its first data
-    // load; the list of a small plan stays in the memory-side cache between launches, that of a
-    // large plan does not.  One lane, vector side of the memory system (a scalar load would be
-    // waited for together with this tile's own record).
-    uint32_t ahead = 0;
-    const bool prefetch = records_ahead && threadIdx.x == 0 && b + records_ahead < gridDim.x;
-    if (prefetch) ahead = *(const TH_GLOBAL uint32_t*)(tiles + b + records_ahead);
-
     const Tile& t = tiles[b];  // uniform: fetched by the scalar unit
     const uint32_t flags = t.flags;
-    const uint32_t count = t.count, ncols = t.ncols;
+    const uint32_t count = t.count, ncols = t.ncols, col0 = t.col0, magic = t.magic;
     const uint64_t ss = t.src_stride, ds = t.dst_stride;
     constexpr bool PACK = MODE == MODE_PACK;
     constexpr int SUM = !CHECKSUM ? 0 : (PACK ? 1 : 2);
@@ -606,18 +598,33 @@ __global__ __launch_bounds__(VEC_ONLY ? kBlockThreads : kBlockThreadsAny, TH_MIN
     const uint32_t kind = VEC_ONLY ? (uint32_t)TILE_KIND_VEC : (flags & TILE_KIND_MASK);
     Sum acc;
 
+    // Pull the record of a tile this XCD reaches a few microseconds from now into its L2.  A record
+    // costs a workgroup one exposed memory latency before its first data load; the list of a small
+    // plan stays in the memory-side cache between launches, that of a large plan does not (the
+    // 70B-shaped reshard gains 5-7 %, nothing loses).  One lane issues a vector load and nobody
+    // waits for it: written as asm because the compiler would turn this uniform load into a scalar
+    // load and wait for it on the spot.  It comes after this tile's own uniform loads, which the
+    // compiler keeps on the scalar unit only while no asm statement precedes them.  The register
+    // it returns into stays reserved until the end of the kernel.
+    uint32_t ahead = 0;
+    const bool prefetch = threadIdx.x == 0 && b + kRecordsAhead < gridDim.x;
+    if (prefetch) {
+        const TH_GLOBAL uint32_t* next = (const TH_GLOBAL uint32_t*)(tiles + b + kRecordsAhead);
+        asm volatile("global_load_dword %0, %1, off" : "=v"(ahead) : "v"(next));
+    }
+
     if (kind == TILE_KIND_VEC) {
-        copy_vec<BT, SUM>(src, dst, ss, ds, count, ncols, t.col0, t.magic, acc);
+        copy_vec<BT, SUM>(src, dst, ss, ds, count, ncols, col0, magic, acc);
     } else if (kind == TILE_KIND_DENSE) {
         const bool head_skip = (flags & TILE_HEAD_SKIP) != 0, tail_ok = (flags & TILE_TAIL_OK) != 0;
         unsigned des = 2;
         if (flags & TILE_DST_F32) {
-            copy_dense<BT, 4, 4, SUM>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok, acc);
+            copy_dense<BT, 4, 4, SUM>(src, dst, ss, count, ncols, col0, magic, head_skip, tail_ok, acc);
             des = 4;
         } else if (flags & TILE_SRC_F32) {
-            copy_dense<BT, 4, 2, SUM>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok, acc);
+            copy_dense<BT, 4, 2, SUM>(src, dst, ss, count, ncols, col0, magic, head_skip, tail_ok, acc);
         } else {
-            copy_dense<BT, 2, 2, SUM>(src, dst, ss, count, ncols, t.col0, t.magic, head_skip, tail_ok, acc);
+            copy_dense<BT, 2, 2, SUM>(src, dst, ss, count, ncols, col0, magic, head_skip, tail_ok, acc);
         }
         if (PACK) {
             // zero the alignment gap that follows a tensor's last element on the wire
@@ -712,16 +719,12 @@ int launch_signal(uint64_t* flag, uint64_t value, void* stream) {
     return TH_OK;
 }
 
-int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles, uint64_t list_tiles,
+int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first, const InlineWire& inl,
                  uint64_t* partials, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     constexpr uint64_t kMaxGrid = 1u << 30;
-    // a tile list of 32 MiB or more is taken not to stay in the memory-side cache from one launch
-    // to the next: prefetch its records
-    constexpr uint64_t kPrefetchMinTiles = 1u << 19;
-    const uint32_t records_ahead = list_tiles >= kPrefetchMinTiles ? 256u : 0u;
-    typedef void (*kernel_t)(const Tile*, const void* const*, void* const*, uint32_t, uint32_t, InlineWire, uint64_t*);
+    typedef void (*kernel_t)(const Tile*, const void* const*, void* const*, uint32_t, InlineWire, uint64_t*);
     // [mode][vector-only][checksum][inline wire pointers]
     static const kernel_t kernels[3][2][2][2] = {
         {{{th_tiles_kernel<MODE_PACK, false, false, false>, th_tiles_kernel<MODE_PACK, false, false, true>},
@@ -742,7 +745,7 @@ int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uin
     while (ntiles) {
         const uint64_t n = ntiles < kMaxGrid ? ntiles : kMaxGrid;
         hipLaunchKernelGGL(kernel, dim3((uint32_t)n), dim3(vec_only ? kBlockThreads : kBlockThreadsAny), 0, st,
-                           tiles + tile0, src_table, dst_table, wire_first, records_ahead, inl,
+                           tiles + tile0, src_table, dst_table, wire_first, inl,
                            partials ? partials + 2 * tile0 : nullptr);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) {
