@@ -30,6 +30,14 @@ if not os.path.exists(_LIB_PATH):
     raise ImportError(
         "%s is missing: build it with `python -m paper_2604_09107_amd.build` "
         "(the reshard path has no non-HIP fallback)" % _LIB_PATH)
+# PyTorch for ROCm ships its own copy of the HIP runtime, and a process must hold one runtime only
+# (torch owns the buffers and streams that this library is handed).  Let torch load first when it
+# is installed; the library then binds to the runtime that is already in the process.  Loading in
+# the other order ends in "no ROCm-capable device" at the first plan.
+try:
+    import torch  # noqa: F401
+except ImportError:
+    pass
 _lib = C.CDLL(_LIB_PATH)
 
 

@@ -156,7 +156,8 @@ int upload_tables(th_plan* p) {
         e = hipMemcpy(p->d_tiles[side], t.data(), t.size() * sizeof(Tile), hipMemcpyHostToDevice);
         if (e != hipSuccess) return hip_fail(e, "hipMemcpy(tile table)");
         if (p->checksum && side < 2) {
-            e = hipMalloc(reinterpret_cast<void**>(&p->d_partials[side]), t.size() * 2 * sizeof(uint64_t));
+            e = hipMalloc(reinterpret_cast<void**>(&p->d_partials[side]),
+                          t.size() * kPartialsPerTile * 2 * sizeof(uint64_t));
             if (e != hipSuccess) return hip_fail(e, "hipMalloc(checksum partials)");
             e = hipMalloc(reinterpret_cast<void**>(&p->d_tile_base[side]), t.size() * sizeof(uint64_t));
             if (e != hipSuccess) return hip_fail(e, "hipMalloc(checksum bases)");
@@ -171,7 +172,7 @@ int upload_tables(th_plan* p) {
 int finish_plan(th_plan* p, size_t chunk_bytes, unsigned flags, bool aligned16, th_plan** out) {
     Tuning tune = current_tuning();
     p->specialize = tune.specialize;
-    if (flags & TH_FLAG_CHECKSUM) tune.tile_bytes = tune.tile_bytes_any = tune.tile_bytes_checksum;
+    if (flags & TH_FLAG_CHECKSUM) tune.tile_bytes = tune.tile_bytes_checksum;
     int rc = finish_manifest(p->m, chunk_bytes, aligned16, tune);
     if (rc == TH_OK) {
         p->host_only = (flags & TH_FLAG_HOST_ONLY) != 0;
@@ -307,7 +308,7 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
                               const_cast<void* const*>(tens_tab), chunk_first, inl, partials, stream);
         if (rc == TH_OK && want_sums)
             rc = launch_checksum_finalize(p->d_tiles[side], p->d_partials[side], p->d_tile_base[side], tile0[k],
-                                          ntiles[k], sums, stream);
+                                          ntiles[k], vec_only, sums, stream);
     }
     if (rc != TH_OK) return rc;
     for (PtrSlot* s : {ts, ws}) {

@@ -85,6 +85,8 @@ constexpr int kBlockThreads = TH_BLOCK_THREADS;  // threads per workgroup (one t
 #define TH_BLOCK_THREADS_ANY 512
 #endif
 constexpr int kBlockThreadsAny = TH_BLOCK_THREADS_ANY;
+static_assert(kBlockThreadsAny <= kBlockThreads && kBlockThreads % 64 == 0 && kBlockThreadsAny % 64 == 0, "workgroup sizes");
+constexpr int kPartialsPerTile = kBlockThreads / 64;  // checksum pairs reserved per tile: one per wavefront
 
 struct Manifest {
     std::vector<TensorInfo> tensors[2];  // 0 = source side, 1 = destination side
@@ -108,7 +110,8 @@ struct Manifest {
 struct Tuning {
     uint64_t tile_bytes = 16384;      // vector path: one 128-bit vector per thread of a workgroup
     uint64_t tile_bytes_any = 12288;  // any-alignment paths (measured best with 512-thread workgroups on short runs)
-    uint64_t tile_bytes_checksum = 65536;  // both paths in plans with checksums: amortises the workgroup reduction
+    uint64_t tile_bytes_checksum = 32768;  // vector path in plans with checksums: two vectors per thread amortise
+                                           // the per-wavefront reduction
     bool specialize = true;           // launch vector-path tiles with the kernel that holds only that path
 };
 Tuning current_tuning();
@@ -138,14 +141,16 @@ struct InlineWire {
     void* p[kInlineChunks];
     uint32_t n;  // 0: use the device table
 };
-// partials: nullptr, or device array of 2 x uint64 per tile of `tiles` (same indexing) that receives
-// each tile's checksum terms (A, B with tile-local positions).
+// partials: nullptr, or device array of kPartialsPerTile pairs of uint64 per tile of `tiles` (same
+// indexing): wavefront w of the workgroup that runs a tile writes the checksum terms (A, B with
+// tile-local positions) of what it moved into pair w.
 int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first,
                  const InlineWire& inl, uint64_t* partials, void* stream);
 // Adds the per-tile terms of tiles [tile0, tile0 + ntiles) into sums[2 * src_tensor + {0, 1}].
+// vec_only: as in the launch_tiles call that filled the pairs (it fixes the wavefronts per tile).
 int launch_checksum_finalize(const Tile* tiles, const uint64_t* partials, const uint64_t* tile_base,
-                             uint64_t tile0, uint64_t ntiles, uint64_t* sums, void* stream);
+                             uint64_t tile0, uint64_t ntiles, bool vec_only, uint64_t* sums, void* stream);
 
 int launch_reference_copy(void* dst, const void* src, uint64_t nbytes, void* stream);
 int launch_signal(uint64_t* flag, uint64_t value, void* stream);

@@ -157,33 +157,19 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
     return v;
 }
 
-// Workgroup total of the per-thread terms -> out[0..1].  Every thread of the workgroup calls it.
-// The 64-bit B is reduced as three limbs of 21 + 21 + 22 bits so that a wavefront's limb sums fit
-// 32 bits; A is below 2^24 per thread (at most 32 slots of 8 halves).  One thread adds the
-// wavefronts' results in 64-bit arithmetic.
-template <int BT>
-__device__ __forceinline__ void block_sum_store(const Sum& s, uint64_t* out) {
-    constexpr uint32_t kWaves = BT / 64;
-    __shared__ uint32_t part[4 * kWaves];
+// Wavefront total of the per-thread terms -> out[0..1]; every thread of the wavefront calls it.
+// One pair per wavefront and no workgroup-level reduction: a barrier would hold every wavefront of
+// the workgroup until the slowest load has returned.  The 64-bit B is reduced as three limbs of
+// 21 + 21 + 22 bits so that a wavefront's limb sums fit 32 bits; A is below 2^24 per thread (at
+// most 32 slots of 8 halves).
+__device__ __forceinline__ void wave_sum_store(const Sum& s, uint64_t* out) {
     const uint32_t a = wave_sum_u32(s.a);
     const uint32_t b0 = wave_sum_u32((uint32_t)(s.b & 0x1FFFFFu));
     const uint32_t b1 = wave_sum_u32((uint32_t)((s.b >> 21) & 0x1FFFFFu));
     const uint32_t b2 = wave_sum_u32((uint32_t)(s.b >> 42));
-    const uint32_t tid = threadIdx.x;
-    if ((tid & 63) == 63) {
-        uint32_t* p = part + 4 * (tid >> 6);
-        p[0] = a, p[1] = b0, p[2] = b1, p[3] = b2;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        uint64_t ta = 0, tb = 0;
-#pragma unroll
-        for (uint32_t w = 0; w < kWaves; ++w) {
-            ta += part[4 * w];
-            tb += (uint64_t)part[4 * w + 1] + ((uint64_t)part[4 * w + 2] << 21) + ((uint64_t)part[4 * w + 3] << 42);
-        }
-        out[0] = ta;
-        out[1] = tb;
+    if ((threadIdx.x & 63) == 63) {
+        out[0] = a;
+        out[1] = (uint64_t)b0 + ((uint64_t)b1 << 21) + ((uint64_t)b2 << 42);
     }
 }
 
@@ -651,25 +637,31 @@ __global__ __launch_bounds__(VEC_ONLY ? kBlockThreads : kBlockThreadsAny, TH_MIN
             }
         }
     }
-    if (CHECKSUM) block_sum_store<BT>(acc, partials + 2 * (size_t)b);
+    if (CHECKSUM) wave_sum_store(acc, partials + 2 * ((size_t)b * kPartialsPerTile + (threadIdx.x >> 6)));
     if (prefetch) asm volatile("" ::"v"(ahead));  // keeps the load; its value is not used
 }
 
-// One thread per tile: shift the tile's pair to positions counted from the start of its tensor's
-// run (B += base * A) and add it to the tensor's sums.  Tiles of one tensor are neighbours in the
-// list, so a wavefront usually holds one tensor and issues one pair of atomics.
+// One thread per tile: add up the pairs of the tile's wavefronts, shift the result to positions
+// counted from the start of its tensor's run (B += base * A) and add it to the tensor's sums.
+// Tiles of one tensor are neighbours in the list, so a wavefront usually holds one tensor and
+// issues one pair of atomics.
 __global__ __launch_bounds__(256) void th_checksum_finalize_kernel(const Tile* __restrict__ tiles,
                                                                    const uint64_t* __restrict__ partials,
                                                                    const uint64_t* __restrict__ tile_base,
-                                                                   uint64_t n, uint64_t* __restrict__ sums) {
+                                                                   uint64_t n, uint32_t waves,
+                                                                   uint64_t* __restrict__ sums) {
     const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
     const bool active = i < n;
     uint32_t tensor = 0xFFFFFFFFu;
     uint64_t a = 0, bsum = 0;
     if (active) {
         tensor = tiles[i].src_tensor;
-        a = partials[2 * i];
-        bsum = partials[2 * i + 1] + tile_base[i] * a;
+        const uint64_t* pair = partials + 2 * i * kPartialsPerTile;
+        for (uint32_t w = 0; w < waves; ++w) {
+            a += pair[2 * w];
+            bsum += pair[2 * w + 1];
+        }
+        bsum += tile_base[i] * a;
     }
     const uint32_t lead_tensor = __shfl(tensor, 0);
     const bool same = __all(!active || tensor == lead_tensor);
@@ -746,7 +738,7 @@ int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uin
         const uint64_t n = ntiles < kMaxGrid ? ntiles : kMaxGrid;
         hipLaunchKernelGGL(kernel, dim3((uint32_t)n), dim3(vec_only ? kBlockThreads : kBlockThreadsAny), 0, st,
                            tiles + tile0, src_table, dst_table, wire_first, inl,
-                           partials ? partials + 2 * tile0 : nullptr);
+                           partials ? partials + 2 * kPartialsPerTile * tile0 : nullptr);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) {
             set_error("kernel launch failed: %s", hipGetErrorString(e));
@@ -759,12 +751,13 @@ int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uin
 }
 
 int launch_checksum_finalize(const Tile* tiles, const uint64_t* partials, const uint64_t* tile_base, uint64_t tile0,
-                             uint64_t ntiles, uint64_t* sums, void* stream) {
+                             uint64_t ntiles, bool vec_only, uint64_t* sums, void* stream) {
     if (!ntiles) return TH_OK;
     const uint64_t grid = (ntiles + 255) / 256;
+    const uint32_t waves = (vec_only ? kBlockThreads : kBlockThreadsAny) / 64;  // of the kernel that ran these tiles
     hipLaunchKernelGGL(th_checksum_finalize_kernel, dim3((uint32_t)grid), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), tiles + tile0, partials + 2 * tile0, tile_base + tile0,
-                       ntiles, sums);
+                       static_cast<hipStream_t>(stream), tiles + tile0, partials + 2 * kPartialsPerTile * tile0,
+                       tile_base + tile0, ntiles, waves, sums);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         set_error("kernel launch failed: %s", hipGetErrorString(e));
