@@ -131,6 +131,7 @@ struct th_plan {
     th::Manifest m;
     bool host_only = false;
     bool specialize = true;
+    int vec_instance = th::VEC_ANY;  // vector-only kernel instance that fits this plan's tile size
     int device = -1;
     th::Tile* d_tiles[3] = {nullptr, nullptr, nullptr};
     // checksum support (TH_FLAG_CHECKSUM): per-tile (A, B) pairs and per-tile position bases
@@ -173,6 +174,7 @@ int finish_plan(th_plan* p, size_t chunk_bytes, unsigned flags, bool aligned16, 
     Tuning tune = current_tuning();
     p->specialize = tune.specialize;
     if (flags & TH_FLAG_CHECKSUM) tune.tile_bytes = tune.tile_bytes_checksum;
+    p->vec_instance = vector_instance(tune.tile_bytes);
     int rc = finish_manifest(p->m, chunk_bytes, aligned16, tune);
     if (rc == TH_OK) {
         p->host_only = (flags & TH_FLAG_HOST_ONLY) != 0;
@@ -299,12 +301,13 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
     for (int k = 0; k < 2 && rc == TH_OK; ++k) {
         if (!ntiles[k]) continue;
         const bool vec_only = k == 0 && p->specialize;
+        const int instance = vec_only ? p->vec_instance : (int)VEC_ALL_PATHS;
         uint64_t* partials = want_sums ? p->d_partials[side] : nullptr;
         if (side == 0)
-            rc = launch_tiles(MODE_PACK, vec_only, p->d_tiles[0], tile0[k], ntiles[k], tens_tab,
+            rc = launch_tiles(MODE_PACK, instance, p->d_tiles[0], tile0[k], ntiles[k], tens_tab,
                               const_cast<void* const*>(wire_tab), chunk_first, inl, partials, stream);
         else
-            rc = launch_tiles(MODE_UNPACK, vec_only, p->d_tiles[1], tile0[k], ntiles[k], wire_tab,
+            rc = launch_tiles(MODE_UNPACK, instance, p->d_tiles[1], tile0[k], ntiles[k], wire_tab,
                               const_cast<void* const*>(tens_tab), chunk_first, inl, partials, stream);
         if (rc == TH_OK && want_sums)
             rc = launch_checksum_finalize(p->d_tiles[side], p->d_partials[side], p->d_tile_base[side], tile0[k],
@@ -439,10 +442,10 @@ int th_reshard(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, vo
     std::memset(&no_inline, 0, sizeof no_inline);
     int rc = TH_OK;
     if (m.direct_n_vec)
-        rc = launch_tiles(MODE_DIRECT, p->specialize, p->d_tiles[2], 0, m.direct_n_vec, stab, dtab, 0, no_inline,
+        rc = launch_tiles(MODE_DIRECT, p->specialize ? p->vec_instance : (int)VEC_ALL_PATHS, p->d_tiles[2], 0, m.direct_n_vec, stab, dtab, 0, no_inline,
                           nullptr, hip_stream);
     if (rc == TH_OK && total > m.direct_n_vec)
-        rc = launch_tiles(MODE_DIRECT, false, p->d_tiles[2], m.direct_n_vec, total - m.direct_n_vec, stab, dtab, 0,
+        rc = launch_tiles(MODE_DIRECT, VEC_ALL_PATHS, p->d_tiles[2], m.direct_n_vec, total - m.direct_n_vec, stab, dtab, 0,
                           no_inline, nullptr, hip_stream);
     if (rc != TH_OK) return rc;
     for (PtrSlot* s : {ss, ds}) {

@@ -132,8 +132,16 @@ inline unsigned esize(int dtype) { return dtype == TH_F32 ? 4u : 2u; }
 // Launches one kernel over tiles [tile0, tile0 + ntiles) of `tiles` (device pointer).
 // mode: which of the two pointer tables is indexed by chunk (pack: destination, unpack: source,
 // direct: neither).  wire_first: chunk index that entry 0 of the wire pointer table stands for.
-// vec_only: every tile of the range is KIND_VEC (selects the kernel without the other paths).
+// instance: which build of the kernel runs the range.  VEC_ALL_PATHS holds every path; the others
+// hold the vector path only (every tile of the range must be KIND_VEC) for tiles of at most one,
+// at most two, or any number of vectors per thread of a kBlockThreads workgroup.
 enum TileMode { MODE_PACK = 0, MODE_UNPACK = 1, MODE_DIRECT = 2 };
+enum TileInstance { VEC_ALL_PATHS = 0, VEC_ONE = 1, VEC_TWO = 2, VEC_ANY = 3 };
+// The vector-only instance for tiles of up to tile_bytes.
+inline int vector_instance(uint64_t tile_bytes) {
+    const uint64_t vectors = tile_bytes / 16;
+    return vectors <= (uint64_t)kBlockThreads ? VEC_ONE : vectors <= 2 * (uint64_t)kBlockThreads ? VEC_TWO : VEC_ANY;
+}
 // Wire chunk pointers of a short chunk range travel in the kernel arguments instead of a device
 // table, so that chunk-by-chunk calls (a reader consuming a prefix) upload nothing.
 constexpr uint32_t kInlineChunks = 8;
@@ -144,11 +152,12 @@ struct InlineWire {
 // partials: nullptr, or device array of kPartialsPerTile pairs of uint64 per tile of `tiles` (same
 // indexing): wavefront w of the workgroup that runs a tile writes the checksum terms (A, B with
 // tile-local positions) of what it moved into pair w.
-int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
+int launch_tiles(int mode, int instance, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first,
                  const InlineWire& inl, uint64_t* partials, void* stream);
 // Adds the per-tile terms of tiles [tile0, tile0 + ntiles) into sums[2 * src_tensor + {0, 1}].
-// vec_only: as in the launch_tiles call that filled the pairs (it fixes the wavefronts per tile).
+// vec_only: whether the launch_tiles call that filled the pairs ran a vector-only instance (it fixes
+// the wavefronts per tile).
 int launch_checksum_finalize(const Tile* tiles, const uint64_t* partials, const uint64_t* tile_base,
                              uint64_t tile0, uint64_t ntiles, bool vec_only, uint64_t* sums, void* stream);
 

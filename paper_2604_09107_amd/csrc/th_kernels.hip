@@ -59,15 +59,31 @@ __device__ __forceinline__ u32x4 ld16(gsrc_t p) {
 __device__ __forceinline__ void st16(gdst_t p, u32x4 v) {
     __builtin_nontemporal_store(v, reinterpret_cast<TH_GLOBAL u32x4*>(p));
 }
-// The vector path's stores: non-temporal at agent scope (written through instead of held in this
-// XCD's L2).  Measured inside this kernel against plain non-temporal stores: +1.5 to 3 % on the
-// 8B-shaped reshard, +1 % on the 70B-shaped one.  Not for the any-alignment paths, whose wavefronts
-// also write parts of cache lines (there it cost 8 %); agent scope alone or system scope cost 9 %.
-// The compiler has no builtin for a 128-bit store with these bits, hence the one-instruction asm;
-// a store needs no wait before the wavefront ends.
+// Stores of the vector-path kernels with one or two vectors per thread: non-temporal at agent scope
+// (written through instead of held in this XCD's L2).  Measured inside this kernel against plain
+// non-temporal stores: +1.5 to 3 % on the 8B-shaped reshard, +1 % on the 70B-shaped one.  Not for
+// the any-alignment paths, whose wavefronts also write parts of cache lines (there it cost 8 %);
+// agent scope alone or system scope cost 9 %.
+//
+// The compiler has no builtin for a 128-bit store with these bits, so it is one asm instruction,
+// and the compiler does not know that it is a store: the memory system reads a store's data
+// registers some time after the instruction has issued, and the compiler protects only the stores
+// it knows from a later instruction that reuses those registers.  (A checksum computed after such
+// a store, in place over the stored registers, corrupted what arrived in memory.)  Hence the rule
+// for this function: it is called only from the tail of the kernel, after every other instruction
+// that writes a vector register, and the stored values are kept live up to the end of the kernel
+// (hold_live), so that no register of theirs can be handed out again.
 __device__ __forceinline__ void st16_through(gdst_t p, u32x4 v) {
     asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
 }
+__device__ __forceinline__ void hold_live(u32x4 v) { asm volatile("" ::"v"(v)); }
+
+// What a one- or two-vector tile still has to store when its copy routine returns.
+struct LateStores {
+    gdst_t p[2];
+    u32x4 v[2];
+    bool on[2] = {false, false};
+};
 
 // fp32 bits -> bf16 bits, round to nearest even in integer arithmetic.  No flush of
 // subnormals; overflow carries into infinity; a NaN keeps its sign and top payload bits
@@ -180,48 +196,76 @@ __device__ __forceinline__ void wave_sum_store(const Sum& s, uint64_t* out) {
 // x = col0 + i: row x / vpr, column x % vpr.  magic != 0: vpr < 2^15 and x < 2^16, so the
 // multiply-high division is exact; magic == 0: vpr is at least the tile's capacity, so x < 2*vpr
 // and the quotient is 0 or 1.
-template <int BT, int SUM>
-__device__ __forceinline__ void copy_vec(gsrc_t src, gdst_t dst, uint64_t ss, uint64_t ds, uint32_t count,
-                                         uint32_t vpr, uint32_t col0, uint32_t magic, Sum& acc) {
+// U vectors per thread, vectors [base, base + U * BT) of the tile: every load is issued before the
+// first store, in straight-line code.  Threads past the end load the tile's last vector again and
+// store nothing: a load inside a conditional block costs a wait for every load issued before it
+// (the block's address arithmetic reuses registers of loads in flight), which serialises them.
+template <int BT, int SUM, int U>
+__device__ __forceinline__ void copy_vec_pass(gsrc_t src, gdst_t dst, uint64_t ss, uint64_t ds, uint32_t base,
+                                              uint32_t count, uint32_t vpr, uint32_t col0, uint32_t magic,
+                                              Sum& acc) {
     const uint32_t tid = threadIdx.x;
-    if (count <= BT) {
-        // the default tile: one vector per thread, nothing else
-        if (tid < count) {
-            const uint32_t x = col0 + tid;
-            const uint32_t row = div_rows(x, vpr, magic);
-            const uint32_t col = x - row * vpr;
-            const u32x4 v = ld16(src + (size_t)row * ss + (size_t)col * 16);
-            st16_through(dst + (size_t)row * ds + (size_t)col * 16, v);
+    u32x4 v[U];
+    uint32_t row[U], col[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t i = base + u * BT + tid;
+        const uint32_t x = col0 + (i < count ? i : count - 1);
+        row[u] = div_rows(x, vpr, magic);
+        col[u] = x - row[u] * vpr;
+        v[u] = ld16(src + (size_t)row[u] * ss + (size_t)col[u] * 16);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t i = base + u * BT + tid;
+        if (i < count) {
+            st16(dst + (size_t)row[u] * ds + (size_t)col[u] * 16, v[u]);
             if (SUM) {
-                const uint64_t rel = (uint64_t)row * (SUM == 1 ? ds : ss) + (uint64_t)col * 16;
-                sum_halves(acc, v, 0, 8, (int64_t)(rel / 2));
+                const uint64_t rel = (uint64_t)row[u] * (SUM == 1 ? ds : ss) + (uint64_t)col[u] * 16;
+                sum_halves(acc, v[u], 0, 8, (int64_t)(rel / 2));
             }
         }
-        return;
     }
-    constexpr uint32_t kStep = BT * kUnroll;
-    for (uint32_t base = 0; base < count; base += kStep) {
-        u32x4 v[kUnroll];
-        uint32_t row[kUnroll], col[kUnroll];
+}
+
+// VPT: vectors per thread the tiles of this kernel instance can need (their count is at most
+// VPT * BT); 0 = any count.  The default tile size gives VPT = 1: one load, one store, nothing else.
+// With VPT = 1 or 2 the stores are left to the caller (late), which issues them as its last
+// instructions; all loads are issued before anything else, in straight-line code (threads past the
+// end load the tile's last vector again and store nothing).
+template <int BT, int SUM, int VPT>
+__device__ __forceinline__ void copy_vec(gsrc_t src, gdst_t dst, uint64_t ss, uint64_t ds, uint32_t count,
+                                         uint32_t vpr, uint32_t col0, uint32_t magic, Sum& acc, LateStores& late) {
+    if (VPT == 1 || VPT == 2) {
+        const uint32_t tid = threadIdx.x;
+        constexpr int N = VPT ? VPT : 1;  // (VPT == 0 never gets here)
+        uint32_t row[N], col[N];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const uint32_t i = base + u * BT + tid;
-            const uint32_t x = col0 + i;
+        for (int u = 0; u < N; ++u) {
+            const uint32_t i = u * BT + tid;
+            late.on[u] = i < count;
+            const uint32_t x = col0 + (late.on[u] ? i : count - 1);
             row[u] = div_rows(x, vpr, magic);
             col[u] = x - row[u] * vpr;
-            if (i < count) v[u] = ld16(src + (size_t)row[u] * ss + (size_t)col[u] * 16);
+            late.v[u] = ld16(src + (size_t)row[u] * ss + (size_t)col[u] * 16);
+            late.p[u] = dst + (size_t)row[u] * ds + (size_t)col[u] * 16;
         }
+        if (SUM) {
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const uint32_t i = base + u * BT + tid;
-            if (i < count) {
-                st16_through(dst + (size_t)row[u] * ds + (size_t)col[u] * 16, v[u]);
-                if (SUM) {
+            for (int u = 0; u < N; ++u) {
+                if (late.on[u]) {
                     const uint64_t rel = (uint64_t)row[u] * (SUM == 1 ? ds : ss) + (uint64_t)col[u] * 16;
-                    sum_halves(acc, v[u], 0, 8, (int64_t)(rel / 2));
+                    sum_halves(acc, late.v[u], 0, 8, (int64_t)(rel / 2));
                 }
             }
         }
+    } else if (count <= BT) {
+        copy_vec_pass<BT, SUM, 1>(src, dst, ss, ds, 0, count, vpr, col0, magic, acc);
+    } else if (count <= 2 * BT) {
+        copy_vec_pass<BT, SUM, 2>(src, dst, ss, ds, 0, count, vpr, col0, magic, acc);
+    } else {
+        for (uint32_t base = 0; base < count; base += BT * kUnroll)
+            copy_vec_pass<BT, SUM, kUnroll>(src, dst, ss, ds, base, count, vpr, col0, magic, acc);
     }
 }
 
@@ -267,6 +311,20 @@ __device__ __forceinline__ void issue16(Raw16<SES>& r, gsrc_t p) {
         r.q = reinterpret_cast<const TH_GLOBAL Unaligned4*>(p - odd)->v;
         r.e = 0;
         if (odd) r.e = *reinterpret_cast<const TH_GLOBAL uint32_t*>(p + 14);
+    }
+}
+// The start of the row after a slot's own: a slot of 4-byte elements can need 3 elements of it at
+// most, so 12 bytes are loaded.  (A register that is loaded but never read is handed out again at
+// once, and whatever writes it next has to wait for the load: that serialised the slots in flight.)
+typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+struct __attribute__((packed, aligned(4))) Unaligned4x3 { u32x3 v; };
+template <int SES>
+__device__ __forceinline__ void issue_row_start(Raw16<SES>& r, gsrc_t p) {
+    if (SES == 4) {
+        const u32x3 h = reinterpret_cast<const TH_GLOBAL Unaligned4x3*>(p)->v;
+        r.q.x = h.x, r.q.y = h.y, r.q.z = h.z;
+    } else {
+        issue16<SES>(r, p);
     }
 }
 template <int SES>
@@ -467,7 +525,7 @@ __device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, 
                     if (over[i]) {
                         gsrc_t pb = src + (uint64_t)(row + 1) * ss;
                         odd_b[i] = odd_half<SES>(pb);
-                        issue16<SES>(rb[i], pb);
+                        issue_row_start<SES>(rb[i], pb);
                     }
                 }
             }
@@ -555,8 +613,8 @@ __device__ __forceinline__ void copy_any(gsrc_t src, gdst_t dst, uint64_t ss, ui
 }
 
 // INLINE: the wire pointers come from the kernel arguments (short chunk ranges) instead of the table.
-template <int MODE, bool VEC_ONLY, bool CHECKSUM, bool INLINE>
-__global__ __launch_bounds__(VEC_ONLY ? kBlockThreads : kBlockThreadsAny, TH_MIN_WAVES_PER_EU) void th_tiles_kernel(const Tile* __restrict__ tiles,
+template <int MODE, int VEC, bool CHECKSUM, bool INLINE>
+__global__ __launch_bounds__(VEC ? kBlockThreads : kBlockThreadsAny, TH_MIN_WAVES_PER_EU) void th_tiles_kernel(const Tile* __restrict__ tiles,
                                                                   const void* const* __restrict__ src_table,
                                                                   void* const* __restrict__ dst_table,
                                                                   uint32_t wire_first, InlineWire inl,
@@ -564,7 +622,9 @@ __global__ __launch_bounds__(VEC_ONLY ? kBlockThreads : kBlockThreadsAny, TH_MIN
     // Workgroups are dealt to the 8 XCDs round-robin (workgroup b runs on XCD b mod 8).  Give
     // each XCD one contiguous eighth of the tile list so that it streams through its own
     // address range instead of every 8th tile.
+    constexpr bool VEC_ONLY = VEC != VEC_ALL_PATHS;
     constexpr int BT = VEC_ONLY ? kBlockThreads : kBlockThreadsAny;
+    constexpr int VPT = VEC == VEC_ONE ? 1 : VEC == VEC_TWO ? 2 : 0;
     uint32_t b = blockIdx.x;
     const uint32_t per_xcd = gridDim.x >> 3;
     if (b < per_xcd * 8) b = (b & 7) * per_xcd + (b >> 3);
@@ -583,24 +643,27 @@ __global__ __launch_bounds__(VEC_ONLY ? kBlockThreads : kBlockThreadsAny, TH_MIN
     gdst_t dst = (gdst_t)(static_cast<char*>(dbase) + t.dst_off);
     const uint32_t kind = VEC_ONLY ? (uint32_t)TILE_KIND_VEC : (flags & TILE_KIND_MASK);
     Sum acc;
+    LateStores late;
 
     // Pull the record of a tile this XCD reaches a few microseconds from now into its L2.  A record
     // costs a workgroup one exposed memory latency before its first data load; the list of a small
     // plan stays in the memory-side cache between launches, that of a large plan does not (the
-    // 70B-shaped reshard gains 5-7 %, nothing loses).  One lane issues a vector load and nobody
-    // waits for it: written as asm because the compiler would turn this uniform load into a scalar
-    // load and wait for it on the spot.  It comes after this tile's own uniform loads, which the
-    // compiler keeps on the scalar unit only while no asm statement precedes them.  The register
-    // it returns into stays reserved until the end of the kernel.
+    // 70B-shaped reshard gains 5-7 %, nothing loses).  One lane issues a vector load whose result is
+    // only "used" at the end of the kernel, so nobody waits for it.  The address gets a zero that
+    // the compiler cannot see through: a load from a provably uniform address would go to the scalar
+    // unit and be waited for, together with the next tile-record or pointer-table load.  This comes
+    // after the tile's own uniform loads, which stay scalar only while no asm statement precedes them.
     uint32_t ahead = 0;
     const bool prefetch = threadIdx.x == 0 && b + kRecordsAhead < gridDim.x;
     if (prefetch) {
-        const TH_GLOBAL uint32_t* next = (const TH_GLOBAL uint32_t*)(tiles + b + kRecordsAhead);
-        asm volatile("global_load_dword %0, %1, off" : "=v"(ahead) : "v"(next));
+        uint32_t opaque_zero;
+        asm("v_mov_b32 %0, 0" : "=v"(opaque_zero));
+        const TH_GLOBAL char* next = (const TH_GLOBAL char*)(tiles + b + kRecordsAhead) + opaque_zero;
+        ahead = *(const TH_GLOBAL uint32_t*)next;
     }
 
     if (kind == TILE_KIND_VEC) {
-        copy_vec<BT, SUM>(src, dst, ss, ds, count, ncols, col0, magic, acc);
+        copy_vec<BT, SUM, VPT>(src, dst, ss, ds, count, ncols, col0, magic, acc, late);
     } else if (kind == TILE_KIND_DENSE) {
         const bool head_skip = (flags & TILE_HEAD_SKIP) != 0, tail_ok = (flags & TILE_TAIL_OK) != 0;
         unsigned des = 2;
@@ -638,7 +701,20 @@ __global__ __launch_bounds__(VEC_ONLY ? kBlockThreads : kBlockThreadsAny, TH_MIN
         }
     }
     if (CHECKSUM) wave_sum_store(acc, partials + 2 * ((size_t)b * kPartialsPerTile + (threadIdx.x >> 6)));
-    if (prefetch) asm volatile("" ::"v"(ahead));  // keeps the load; its value is not used
+    if (prefetch) asm volatile("" ::"v"(ahead));  // keeps the prefetch load alive; its value is not used
+    if (VPT) {
+        // the tile's data stores: the last instructions of the kernel (see st16_through).  The first
+        // hold_live makes every lane's loads land before the branches, so that the one after the
+        // stores needs no wait (which would also wait for the stores to complete).
+#pragma unroll
+        for (int u = 0; u < (VPT ? VPT : 1); ++u) hold_live(late.v[u]);
+#pragma unroll
+        for (int u = 0; u < (VPT ? VPT : 1); ++u) {
+            if (late.on[u]) st16_through(late.p[u], late.v[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < (VPT ? VPT : 1); ++u) hold_live(late.v[u]);
+    }
 }
 
 // One thread per tile: add up the pairs of the tile's wavefronts, shift the result to positions
@@ -691,7 +767,11 @@ __global__ __launch_bounds__(kBlockThreads) void th_reference_copy_kernel(const 
     const uint32_t per_xcd = gridDim.x >> 3;
     if (b < per_xcd * 8) b = (b & 7) * per_xcd + (b >> 3);
     const uint64_t i = (uint64_t)b * kBlockThreads + threadIdx.x;
-    if (i < nvec) st16_through((gdst_t)(dst + i), ld16((gsrc_t)(src + i)));
+    if (i < nvec) {
+        const u32x4 v = ld16((gsrc_t)(src + i));
+        st16_through((gdst_t)(dst + i), v);  // last instruction, and the value stays live: see st16_through
+        hold_live(v);
+    }
 }
 
 // Progress counter store: ordered after everything earlier in the stream, visible system-wide.
@@ -711,25 +791,29 @@ int launch_signal(uint64_t* flag, uint64_t value, void* stream) {
     return TH_OK;
 }
 
-int launch_tiles(int mode, bool vec_only, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
+int launch_tiles(int mode, int instance, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first, const InlineWire& inl,
                  uint64_t* partials, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     constexpr uint64_t kMaxGrid = 1u << 30;
     typedef void (*kernel_t)(const Tile*, const void* const*, void* const*, uint32_t, InlineWire, uint64_t*);
-    // [mode][vector-only][checksum][inline wire pointers]
-    static const kernel_t kernels[3][2][2][2] = {
-        {{{th_tiles_kernel<MODE_PACK, false, false, false>, th_tiles_kernel<MODE_PACK, false, false, true>},
-          {th_tiles_kernel<MODE_PACK, false, true, false>, th_tiles_kernel<MODE_PACK, false, true, true>}},
-         {{th_tiles_kernel<MODE_PACK, true, false, false>, th_tiles_kernel<MODE_PACK, true, false, true>},
-          {th_tiles_kernel<MODE_PACK, true, true, false>, th_tiles_kernel<MODE_PACK, true, true, true>}}},
-        {{{th_tiles_kernel<MODE_UNPACK, false, false, false>, th_tiles_kernel<MODE_UNPACK, false, false, true>},
-          {th_tiles_kernel<MODE_UNPACK, false, true, false>, th_tiles_kernel<MODE_UNPACK, false, true, true>}},
-         {{th_tiles_kernel<MODE_UNPACK, true, false, false>, th_tiles_kernel<MODE_UNPACK, true, false, true>},
-          {th_tiles_kernel<MODE_UNPACK, true, true, false>, th_tiles_kernel<MODE_UNPACK, true, true, true>}}},
-        {{{th_tiles_kernel<MODE_DIRECT, false, false, false>, nullptr}, {nullptr, nullptr}},
-         {{th_tiles_kernel<MODE_DIRECT, true, false, false>, nullptr}, {nullptr, nullptr}}}};
-    const kernel_t kernel = kernels[mode][vec_only ? 1 : 0][partials ? 1 : 0][inl.n ? 1 : 0];
+    // [mode][instance][checksum][inline wire pointers]
+#define TH_K(M, V) {{th_tiles_kernel<M, V, false, false>, th_tiles_kernel<M, V, false, true>}, \
+                    {th_tiles_kernel<M, V, true, false>, th_tiles_kernel<M, V, true, true>}}
+#define TH_KD(V) {{th_tiles_kernel<MODE_DIRECT, V, false, false>, nullptr}, {nullptr, nullptr}}
+    static const kernel_t kernels[3][4][2][2] = {
+        {TH_K(MODE_PACK, VEC_ALL_PATHS), TH_K(MODE_PACK, VEC_ONE), TH_K(MODE_PACK, VEC_TWO), TH_K(MODE_PACK, VEC_ANY)},
+        {TH_K(MODE_UNPACK, VEC_ALL_PATHS), TH_K(MODE_UNPACK, VEC_ONE), TH_K(MODE_UNPACK, VEC_TWO),
+         TH_K(MODE_UNPACK, VEC_ANY)},
+        {TH_KD(VEC_ALL_PATHS), TH_KD(VEC_ONE), TH_KD(VEC_TWO), TH_KD(VEC_ANY)}};
+#undef TH_K
+#undef TH_KD
+    if (instance < 0 || instance > VEC_ANY) {
+        set_error("no such instance of the tile kernel");
+        return TH_ERR_ARG;
+    }
+    const bool vec_only = instance != VEC_ALL_PATHS;
+    const kernel_t kernel = kernels[mode][instance][partials ? 1 : 0][inl.n ? 1 : 0];
     if (!kernel) {
         set_error("no such variant of the tile kernel");
         return TH_ERR_ARG;
