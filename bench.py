@@ -24,12 +24,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # the counter reads for th_reference_copy of known size; summaries under profiles/).  Valid only for
 # the kernel sources they were taken with: bench.py reports null once those files have changed.
 TRAFFIC_SOURCES = ("th_kernels.hip", "th_planner.cpp", "th_internal.hpp")
-TRAFFIC_SHA256 = "67c2be52e5b610cdaaa8904a11c13f289c1c3ebb72cebee1766e0c9d0b1ae5a6"
+TRAFFIC_SHA256 = "288dc3acbc1fac9c831863a679accdaa332fc23a772f0627a294a2560120ff9c"
 TRAFFIC_BYTES = {
-    "cfg2_8b_tp1_to_tp4": {"th_pack": 8047728428, "th_unpack": 8047045165},
-    "cfg3_70b_tp8_to_tp4": {"th_pack": 35353567460, "th_unpack": 35348095374},
-    "cfg4_moe_ep8_to_tp2": {"th_pack": 5821569418, "th_unpack": 5821207978},
-    "cfg5_scatter_fp32_to_bf16": {"th_pack": 37151859014, "th_unpack": 22677722420},
+    "cfg2_8b_tp1_to_tp4": {"th_pack": 8047677891, "th_unpack": 8047012806},
+    "cfg3_70b_tp8_to_tp4": {"th_pack": 35353502948, "th_unpack": 35348055049},
+    "cfg4_moe_ep8_to_tp2": {"th_pack": 5821515392, "th_unpack": 5821174371},
+    "cfg5_scatter_fp32_to_bf16": {"th_pack": 37134103245, "th_unpack": 22679281384},
 }
 
 
