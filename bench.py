@@ -174,6 +174,7 @@ def main():
               "independent plan); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
+    import numpy as np
     import torch
     import synth
     import paper_2604_09107_amd as th
@@ -227,8 +228,10 @@ def main():
     # Per-launch durations from events recorded around every launch, on the launch stream, inside
     # the timed region (one kernel launch per th_pack / th_unpack call).
     n_launch = len(events[0])
-    pack_ms = sum(a.elapsed_time(b) for a, b in events[0]) / n_launch
-    unpack_ms = sum(a.elapsed_time(b) for a, b in events[1]) / n_launch
+    pack_all = sorted(a.elapsed_time(b) for a, b in events[0])
+    unpack_all = sorted(a.elapsed_time(b) for a, b in events[1])
+    pack_ms = sum(pack_all) / n_launch
+    unpack_ms = sum(unpack_all) / n_launch
     k_pack = pack_bytes / len(jobs) / (pack_ms * 1e-3) / 1e9      # algorithmic bytes of an average launch
     k_unpack = unpack_bytes / len(jobs) / (unpack_ms * 1e-3) / 1e9
     dom = ("th_pack", k_pack, pack_ms) if pack_ms >= unpack_ms else ("th_unpack", k_unpack, unpack_ms)
@@ -312,6 +315,29 @@ def main():
     torch.cuda.synchronize()
     per_chunk_ms = (time.perf_counter() - t0) / 3 * 1e3
 
+    # chunk ring: two wire buffers reused round-robin, unpack(c) right after pack(c), so a chunk is
+    # read back while it still sits in the memory-side cache (what a co-located pipeline would see)
+    ring_ms = None
+    cb_max = max(j["plan"].chunk_bytes(0) for j in jobs if j["plan"].num_chunks)
+    if 2 * cb_max <= (192 << 20):
+        ring = torch.empty(2 * cb_max, dtype=torch.uint8, device="cuda")
+        rp = [np.array([ring.data_ptr() + k * cb_max], dtype=np.uint64) for k in range(2)]
+
+        def ring_sweep():
+            for j in jobs:
+                for c in range(j["plan"].num_chunks):
+                    th.th_pack(j["plan"], j["src_ptrs"], rp[c & 1], c, 1, stream)
+                    th.th_unpack(j["plan"], rp[c & 1], c, 1, dst_ptrs, stream)
+
+        ring_sweep()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            ring_sweep()
+        torch.cuda.synchronize()
+        ring_ms = (time.perf_counter() - t0) / 3 * 1e3
+        del ring
+
     # offload replica: wire chunks in pinned host memory, written / read over the host link
     offload = None
     if args.offload:
@@ -348,12 +374,17 @@ def main():
                    "tile_bytes_any": th.th_config_get(th.TH_CFG_TILE_BYTES_ANY)},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "plan_ms": round(plan_ms, 3),
-        "kernels": {"th_pack": {"ms": round(pack_ms, 4), "GB/s": round(k_pack, 1)},
-                    "th_unpack": {"ms": round(unpack_ms, 4), "GB/s": round(k_unpack, 1)}},
+        "kernels": {"th_pack": {"ms": round(pack_ms, 4), "GB/s": round(k_pack, 1),
+                                "median_ms": round(pack_all[n_launch // 2], 4), "min_ms": round(pack_all[0], 4)},
+                    "th_unpack": {"ms": round(unpack_ms, 4), "GB/s": round(k_unpack, 1),
+                                  "median_ms": round(unpack_all[n_launch // 2], 4),
+                                  "min_ms": round(unpack_all[0], 4)}},
         "checksum_sweep": {"ms": round(checksum_ms, 4), "GB/s": round(sweep_bytes / (checksum_ms * 1e-3) / 1e9, 1),
                            "pack_and_unpack_sums_agree": checksums_agree},
         "per_chunk_calls_sweep": {"ms": round(per_chunk_ms, 4), "calls": 2 * sum(j["plan"].num_chunks for j in jobs),
                                   "GB/s": round(sweep_bytes / (per_chunk_ms * 1e-3) / 1e9, 1)},
+        "chunk_ring_sweep": None if ring_ms is None else {
+            "ms": round(ring_ms, 4), "ring_chunks": 2, "GB/s": round(sweep_bytes / (ring_ms * 1e-3) / 1e9, 1)},
         "th_reshard_direct": {"ms": round(direct_ms, 4), "GB/s": round(direct_bytes / (direct_ms * 1e-3) / 1e9, 1)},
         "d2d_copy_GB/s": {"torch_copy_": round(copy_gbps, 1), "th_reference_copy": round(ref_gbps, 1)},
         "roofline": {"bound": "hbm", "kernel": dom[0], "achieved": round(dom[1], 1), "peak": HBM_PEAK_GBPS,

@@ -23,7 +23,7 @@ def sums_host(t):
     return t.cpu().numpy().view(np.uint64).reshape(-1, 2)
 
 
-@pytest.mark.parametrize("tile_bytes", [4096, None])
+@pytest.mark.parametrize("tile_bytes", [4096, None, 131072])
 @pytest.mark.parametrize("name", ["cfg1_tiny_tp2_to_tp1", "small_dense_tp1_to_tp4", "small_dense_tp4_to_tp2",
                                   "small_moe_ep4_to_tp2"])
 def test_model_checksums_bit_exact(name, tile_bytes):
@@ -57,7 +57,7 @@ def test_model_checksums_bit_exact(name, tile_bytes):
         plan.destroy()
 
 
-@pytest.mark.parametrize("tile_bytes", [4096, None])
+@pytest.mark.parametrize("tile_bytes", [4096, None, 131072])
 def test_scattered_checksums_bit_exact(tile_bytes):
     n = 300
     d = synth.scatter_description(n, 71, min_bytes=256, max_bytes=1 << 17)

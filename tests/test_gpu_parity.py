@@ -75,7 +75,7 @@ def test_model_workloads_bit_exact(name, pattern):
     assert_same(got, want, [t["name"] for t in layouts.registered_tensors(w["model"], w["reader"])])
 
 
-@pytest.mark.parametrize("tile_bytes", [4096, 16384, 262144])
+@pytest.mark.parametrize("tile_bytes", [4096, 16384, 32768, 262144])
 def test_tile_sizes(tile_bytes):
     w = synth.workload("small_dense_tp1_to_tp4")
     got, want = run_model_workload(w, True, tile_bytes=tile_bytes)
