@@ -168,6 +168,7 @@ def main():
     ap.add_argument("--tile-bytes", type=int, default=0, help="override the vector-path tile size")
     ap.add_argument("--no-specialize", action="store_true", help="always launch the all-paths kernel")
     ap.add_argument("--tile-bytes-any", type=int, default=0, help="override the any-alignment tile size")
+    ap.add_argument("--tile-bytes-narrow", type=int, default=0, help="override the tile size of narrowing copies")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the reshard path has no cross-GPU step (every holder/reader pair is an "
@@ -188,6 +189,8 @@ def main():
         th.th_config_set(th.TH_CFG_SPECIALIZE, 0)
     if args.tile_bytes_any:
         th.th_config_set(th.TH_CFG_TILE_BYTES_ANY, args.tile_bytes_any)
+    if args.tile_bytes_narrow:
+        th.th_config_set(th.TH_CFG_TILE_BYTES_NARROW, args.tile_bytes_narrow)
     w = synth.workload(args.workload)
     if w["kind"] == "scatter":
         jobs, dst_dev, dst_ptrs, plan_ms = build_scatter_inputs(th, dev, synth, w, torch)
@@ -371,7 +374,8 @@ def main():
                    "holders": len(jobs), "payload_bytes": sum(j["plan"].payload_bytes for j in jobs),
                    "sweep_bytes": sweep_bytes, "chunks": sum(j["plan"].num_chunks for j in jobs),
                    "tile_bytes": th.th_config_get(th.TH_CFG_TILE_BYTES),
-                   "tile_bytes_any": th.th_config_get(th.TH_CFG_TILE_BYTES_ANY)},
+                   "tile_bytes_any": th.th_config_get(th.TH_CFG_TILE_BYTES_ANY),
+                   "tile_bytes_narrow": th.th_config_get(th.TH_CFG_TILE_BYTES_NARROW)},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "plan_ms": round(plan_ms, 3),
         "kernels": {"th_pack": {"ms": round(pack_ms, 4), "GB/s": round(k_pack, 1),

@@ -318,6 +318,8 @@ enum {
     TH_CFG_TILE_BYTES = 1,    /* destination bytes per tile (one workgroup's share) on the 16-byte
                                  vector path; multiple of 4096 in [4096, 524288]; default 16384 */
     TH_CFG_TILE_BYTES_ANY = 2, /* same for the any-alignment paths; default 12288 */
+    TH_CFG_TILE_BYTES_NARROW = 5, /* same for the any-alignment paths when the copy narrows fp32 to
+                                     bf16; default 8192 */
     TH_CFG_TILE_BYTES_CHECKSUM = 4, /* vector-path tile size in plans created with TH_FLAG_CHECKSUM;
                                        default 32768 (amortises the per-wavefront reduction) */
     TH_CFG_SPECIALIZE = 3      /* nonzero (default): vector-path tiles are launched with a kernel that

@@ -630,6 +630,13 @@ int th_config_set(int key, uint64_t value) {
             }
             g_tuning.tile_bytes_any = value;
             return TH_OK;
+        case TH_CFG_TILE_BYTES_NARROW:
+            if (value < 4096 || value > 524288 || value % 4096) {
+                set_error("tile bytes must be a multiple of 4096 in [4096, 524288]");
+                return TH_ERR_ARG;
+            }
+            g_tuning.tile_bytes_narrow = value;
+            return TH_OK;
     }
     set_error("unknown configuration key %d", key);
     return TH_ERR_ARG;
@@ -639,7 +646,8 @@ uint64_t th_config_get(int key) {
     std::lock_guard<std::mutex> lk(g_cfg_mu);
     return key == TH_CFG_TILE_BYTES ? g_tuning.tile_bytes : key == TH_CFG_TILE_BYTES_ANY ? g_tuning.tile_bytes_any
            : key == TH_CFG_SPECIALIZE ? (uint64_t)g_tuning.specialize
-           : key == TH_CFG_TILE_BYTES_CHECKSUM ? g_tuning.tile_bytes_checksum : 0;
+           : key == TH_CFG_TILE_BYTES_CHECKSUM ? g_tuning.tile_bytes_checksum
+           : key == TH_CFG_TILE_BYTES_NARROW ? g_tuning.tile_bytes_narrow : 0;
 }
 
 const char* th_last_error(void) { return g_err; }

@@ -110,6 +110,7 @@ struct Manifest {
 struct Tuning {
     uint64_t tile_bytes = 16384;      // vector path: one 128-bit vector per thread of a workgroup
     uint64_t tile_bytes_any = 12288;  // any-alignment paths (measured best with 512-thread workgroups on short runs)
+    uint64_t tile_bytes_narrow = 8192;  // any-alignment paths when the copy narrows fp32 to bf16 (8-byte slots)
     uint64_t tile_bytes_checksum = 32768;  // vector path in plans with checksums: two vectors per thread amortise
                                            // the per-wavefront reduction
     bool specialize = true;           // launch vector-path tiles with the kernel that holds only that path

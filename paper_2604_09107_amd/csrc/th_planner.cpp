@@ -37,7 +37,8 @@ void tile_run(std::vector<Tile>& out, Side S, Side D, uint64_t nrows, uint64_t n
     const bool vec = bases_aligned16 && pad == 0 && S.es == D.es && S.off % 16 == 0 && D.off % 16 == 0 &&
                      (ncols * D.es) % 16 == 0 && (nrows == 1 || (S.stride % 16 == 0 && D.stride % 16 == 0));
     used_vec = vec;
-    const uint64_t tile_bytes = vec ? tune.tile_bytes : tune.tile_bytes_any;
+    const bool narrows = S.es == 4 && D.es == 2;
+    const uint64_t tile_bytes = vec ? tune.tile_bytes : narrows ? tune.tile_bytes_narrow : tune.tile_bytes_any;
     uint32_t flags = vec ? TILE_KIND_VEC : TILE_KIND_ANY;
     if (S.es == 4) flags |= TILE_SRC_F32;
     if (D.es == 4) flags |= TILE_DST_F32;
@@ -323,7 +324,7 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
     for (int side = 0; side < 2; ++side) {
         std::vector<Tile> tiles;
         std::vector<uint64_t> base;
-        const size_t guess = (size_t)(m.payload_bytes / std::min(tune.tile_bytes, tune.tile_bytes_any)) + 2 * m.runs.size();
+        const size_t guess = (size_t)(m.payload_bytes / std::min({tune.tile_bytes, tune.tile_bytes_any, tune.tile_bytes_narrow})) + 2 * m.runs.size();
         tiles.reserve(guess);
         base.reserve(guess);
         for (size_t ri = 0; ri < m.runs.size(); ++ri) {
@@ -376,7 +377,7 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
     // ---- direct list: holder tensors -> reader tensors without the wire, one pass over the segments ----
     {
         std::vector<Tile>& tiles = m.tiles[2];
-        tiles.reserve((size_t)(m.payload_bytes / std::min(tune.tile_bytes, tune.tile_bytes_any)) + 2 * m.segments.size());
+        tiles.reserve((size_t)(m.payload_bytes / std::min({tune.tile_bytes, tune.tile_bytes_any, tune.tile_bytes_narrow})) + 2 * m.segments.size());
         for (const Segment& g : m.segments) {
             const unsigned es_s = esize(g.src_dtype), es_d = esize(g.dst_dtype);
             const Side S{g.src_tensor, g.src_off * es_s, g.src_stride * es_s, es_s};

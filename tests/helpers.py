@@ -121,7 +121,7 @@ def tile_checksums(plan, side, wire_chunks, n_src_tensors):
 def tile_sizes(tile_bytes):
     """Plans created inside the block use `tile_bytes` for every tile kind (None: library defaults)."""
     import paper_2604_09107_amd as th
-    keys = (th.TH_CFG_TILE_BYTES, th.TH_CFG_TILE_BYTES_ANY, th.TH_CFG_TILE_BYTES_CHECKSUM)
+    keys = (th.TH_CFG_TILE_BYTES, th.TH_CFG_TILE_BYTES_ANY, th.TH_CFG_TILE_BYTES_CHECKSUM, th.TH_CFG_TILE_BYTES_NARROW)
     old = [th.th_config_get(k) for k in keys]
     try:
         if tile_bytes:
