@@ -24,12 +24,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # the counter reads for th_reference_copy of known size; summaries under profiles/).  Valid only for
 # the kernel sources they were taken with: bench.py reports null once those files have changed.
 TRAFFIC_SOURCES = ("th_kernels.hip", "th_planner.cpp", "th_internal.hpp")
-TRAFFIC_SHA256 = "288dc3acbc1fac9c831863a679accdaa332fc23a772f0627a294a2560120ff9c"
+TRAFFIC_SHA256 = "b250516662995b554f68ee5a5f61c0984ea57eb62bfbde4a0165cb4d83d0b585"
 TRAFFIC_BYTES = {
-    "cfg2_8b_tp1_to_tp4": {"th_pack": 8047677891, "th_unpack": 8047012806},
-    "cfg3_70b_tp8_to_tp4": {"th_pack": 35353502948, "th_unpack": 35348055049},
-    "cfg4_moe_ep8_to_tp2": {"th_pack": 5821515392, "th_unpack": 5821174371},
-    "cfg5_scatter_fp32_to_bf16": {"th_pack": 37134103245, "th_unpack": 22679281384},
+    "cfg2_8b_tp1_to_tp4": {"th_pack": 8047686422, "th_unpack": 8047011994},
+    "cfg3_70b_tp8_to_tp4": {"th_pack": 35353551952, "th_unpack": 35348057813},
+    "cfg4_moe_ep8_to_tp2": {"th_pack": 5821513152, "th_unpack": 5821175075},
+    "cfg5_scatter_fp32_to_bf16": {"th_pack": 37155837097, "th_unpack": 22679808770},
 }
 
 
