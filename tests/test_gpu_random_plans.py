@@ -3,7 +3,7 @@
 Each seed draws one plan: dtype pair, alignment regime (everything a multiple of 16 bytes, so the
 vector path runs, or element-aligned offsets with misaligned base pointers), segment shapes from
 single elements to rows of a few thousand, strided or dense destinations, chunk and tile sizes,
-checksums on or off.  Checked bit for bit: the wire, the destination tensors (with sentinels in
+checksums on or off, narrowing at pack or at unpack.  Checked bit for bit: the wire, the destination tensors (with sentinels in
 every byte the plan does not own), both checksum arrays, and th_reshard into a second copy.
 """
 import numpy as np
@@ -62,7 +62,8 @@ def draw_plan(rng):
     return dict(src_dt=src_dt, dst_dt=dst_dt, aligned=aligned, segs=segs, src_len=src_len, dst_len=dst_len,
                 chunk_bytes=int([256, 4096, 65536, 1 << 20][int(rng.integers(0, 4))]),
                 tile_bytes=int([4096, 8192, 16384, 32768, 131072][int(rng.integers(0, 5))]),
-                checksum=bool(rng.integers(0, 2)))
+                checksum=bool(rng.integers(0, 2)),
+                narrow_at_unpack=bool(rng.integers(0, 2)) and src_dt != dst_dt)
 
 
 def device_tensor(bits, shift_elems):
@@ -82,11 +83,13 @@ def test_random_segment_plan(seed):
                 for i, n in enumerate(p["src_len"])]
     else:
         srcs = [rng.integers(0, 1 << 16, size=n).astype(np.uint16) for n in p["src_len"]]
-    wire = segments.pack(segs, srcs, src_dt, dst_dt)
+    late = p["narrow_at_unpack"]  # the wire carries the source dtype and th_unpack narrows
+    wire_dt = src_dt if late else dst_dt
+    wire = segments.pack(segs, srcs, src_dt, dst_dt, narrow_at="unpack" if late else "pack")
     want = [np.full(n, SENT[dst_dt], dtype=NP[dst_dt]) for n in p["dst_len"]]
-    segments.unpack(segs, wire, want, dst_dt)
-    offs, _ = segments.wire_offsets(segs, dst_dt)
-    want_sums = checksum.segment_checksums(segs, offs, dst_dt, wire, len(srcs))
+    segments.unpack(segs, wire, want, dst_dt, wire_dtype=wire_dt)
+    offs, _ = segments.wire_offsets(segs, wire_dt)
+    want_sums = checksum.segment_checksums(segs, offs, wire_dt, wire, len(srcs))
 
     S = th.binding.SEGMENT_NP
     csegs = np.zeros(n_seg, dtype=S)
@@ -95,7 +98,8 @@ def test_random_segment_plan(seed):
     csegs["dst_elem_off"], csegs["dst_row_stride"] = segs["dst_off"], segs["dst_stride"]
     csegs["nrows"], csegs["row_len"] = segs["nrows"], segs["row_len"]
     csegs["src_dtype"], csegs["dst_dtype"] = TH[src_dt], TH[dst_dt]
-    flags = (th.TH_FLAG_CHECKSUM if p["checksum"] else 0) | (th.TH_FLAG_PTRS_ALIGNED16 if p["aligned"] else 0)
+    flags = ((th.TH_FLAG_CHECKSUM if p["checksum"] else 0) | (th.TH_FLAG_PTRS_ALIGNED16 if p["aligned"] else 0) |
+             (th.TH_FLAG_NARROW_AT_UNPACK if late else 0))
     with tile_sizes(p["tile_bytes"]):
         plan = th.th_plan_create_from_segments(csegs, p["src_len"], p["dst_len"], p["chunk_bytes"], flags)
     assert plan.wire_bytes == len(wire)
@@ -132,7 +136,8 @@ def test_random_segment_plan(seed):
     th.th_reshard(plan, src_ptrs, dir_ptrs, stream)
     torch.cuda.synchronize()
 
-    what = "seed %d: %s" % (seed, {k: p[k] for k in ("src_dt", "dst_dt", "aligned", "chunk_bytes", "tile_bytes", "checksum")})
+    what = "seed %d: %s" % (seed, {k: p[k] for k in ("src_dt", "dst_dt", "aligned", "chunk_bytes", "tile_bytes", "checksum",
+                                                        "narrow_at_unpack")})
     got_wire = wire_dev.cpu().numpy()[:plan.wire_bytes]
     bad = np.nonzero(got_wire != wire)[0]
     assert bad.size == 0, "%s: wire differs first at byte %d (%d differ)" % (what, bad[0], bad.size)
