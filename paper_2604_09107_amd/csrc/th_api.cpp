@@ -548,7 +548,7 @@ int th_plan_get_tile(const th_plan* p, int side, size_t i, th_tile_info* out) {
     const bool vec = (t.flags & TILE_KIND_MASK) == TILE_KIND_VEC;
     out->elem_bytes_src = (t.flags & TILE_SRC_F32) ? 4 : 2;
     out->elem_bytes_dst = (t.flags & TILE_DST_F32) ? 4 : 2;
-    const uint64_t per_vec = 16 / out->elem_bytes_dst;
+    const uint64_t per_vec = 16 / out->elem_bytes_src;  // elements per unit of the vector path
     if (vec) {
         out->first_col = (uint64_t)t.col0 * per_vec;
         out->row_len = (uint64_t)t.ncols * per_vec;

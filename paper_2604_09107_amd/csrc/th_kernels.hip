@@ -59,6 +59,12 @@ __device__ __forceinline__ u32x4 ld16(gsrc_t p) {
 __device__ __forceinline__ void st16(gdst_t p, u32x4 v) {
     __builtin_nontemporal_store(v, reinterpret_cast<TH_GLOBAL u32x4*>(p));
 }
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void st8(gdst_t p, uint32_t lo, uint32_t hi) {
+    u32x2 v;
+    v.x = lo, v.y = hi;
+    __builtin_nontemporal_store(v, reinterpret_cast<TH_GLOBAL u32x2*>(p));
+}
 // Stores of the vector-path kernels with one or two vectors per thread: non-temporal at agent scope
 // (written through instead of held in this XCD's L2).  Measured inside this kernel against plain
 // non-temporal stores: +1.5 to 3 % on the 8B-shaped reshard, +1 % on the 70B-shaped one.  Not for
@@ -76,13 +82,19 @@ __device__ __forceinline__ void st16(gdst_t p, u32x4 v) {
 __device__ __forceinline__ void st16_through(gdst_t p, u32x4 v) {
     asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
 }
+__device__ __forceinline__ void st8_through(gdst_t p, uint32_t lo, uint32_t hi) {  // same rule
+    u32x2 v;
+    v.x = lo, v.y = hi;
+    asm volatile("global_store_dwordx2 %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
+}
 __device__ __forceinline__ void hold_live(u32x4 v) { asm volatile("" ::"v"(v)); }
 
 // What a one- or two-vector tile still has to store when its copy routine returns.
 struct LateStores {
     gdst_t p[2];
-    u32x4 v[2];
+    u32x4 v[2];  // narrow: the 8 bytes to store are v.x, v.y
     bool on[2] = {false, false};
+    bool narrow = false;
 };
 
 // fp32 bits -> bf16 bits, round to nearest even in integer arithmetic.  No flush of
@@ -100,6 +112,17 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t narrow_pair(uint32_t lo, uint32_t hi) {
     const f32x2 v = {__builtin_bit_cast(float, lo), __builtin_bit_cast(float, hi)};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// 16 source bytes -> the destination slot's bytes (4 fp32 -> 4 bf16 in the low half when narrowing).
+template <int SES, int DES>
+__device__ __forceinline__ u32x4 convert_slot(u32x4 a) {
+    if (SES == DES) return a;
+    u32x4 o;
+    o.x = narrow_pair(a.x, a.y);
+    o.y = narrow_pair(a.z, a.w);
+    o.z = o.w = 0;
+    return o;
 }
 
 // x / d for the linear position x of a tile element in a rectangle with d units per row.
@@ -203,8 +226,9 @@ __device__ __forceinline__ void wave_sum_store(const Sum& s, uint64_t* out) {
 template <int BT, int SUM, int U>
 __device__ __forceinline__ void copy_vec_pass(gsrc_t src, gdst_t dst, uint64_t ss, uint64_t ds, uint32_t base,
                                               uint32_t count, uint32_t vpr, uint32_t col0, uint32_t magic,
-                                              Sum& acc) {
+                                              bool narrow, Sum& acc) {
     const uint32_t tid = threadIdx.x;
+    const uint32_t du = narrow ? 8u : 16u;  // destination bytes per unit
     u32x4 v[U];
     uint32_t row[U], col[U];
 #pragma unroll
@@ -219,11 +243,16 @@ __device__ __forceinline__ void copy_vec_pass(gsrc_t src, gdst_t dst, uint64_t s
     for (int u = 0; u < U; ++u) {
         const uint32_t i = base + u * BT + tid;
         if (i < count) {
-            st16(dst + (size_t)row[u] * ds + (size_t)col[u] * 16, v[u]);
-            if (SUM) {
-                const uint64_t rel = (uint64_t)row[u] * (SUM == 1 ? ds : ss) + (uint64_t)col[u] * 16;
-                sum_halves(acc, v[u], 0, 8, (int64_t)(rel / 2));
+            if (SUM == 2) sum_halves(acc, v[u], 0, 8, (int64_t)(((uint64_t)row[u] * ss + (uint64_t)col[u] * 16) / 2));
+            gdst_t d = dst + (size_t)row[u] * ds + (size_t)col[u] * du;
+            if (narrow) {
+                v[u] = convert_slot<4, 2>(v[u]);
+                st8(d, v[u].x, v[u].y);
+            } else {
+                st16(d, v[u]);
             }
+            if (SUM == 1)
+                sum_halves(acc, v[u], 0, narrow ? 4 : 8, (int64_t)(((uint64_t)row[u] * ds + (uint64_t)col[u] * du) / 2));
         }
     }
 }
@@ -235,11 +264,14 @@ __device__ __forceinline__ void copy_vec_pass(gsrc_t src, gdst_t dst, uint64_t s
 // end load the tile's last vector again and store nothing).
 template <int BT, int SUM, int VPT>
 __device__ __forceinline__ void copy_vec(gsrc_t src, gdst_t dst, uint64_t ss, uint64_t ds, uint32_t count,
-                                         uint32_t vpr, uint32_t col0, uint32_t magic, Sum& acc, LateStores& late) {
+                                         uint32_t vpr, uint32_t col0, uint32_t magic, bool narrow, Sum& acc,
+                                         LateStores& late) {
     if (VPT == 1 || VPT == 2) {
-        const uint32_t tid = threadIdx.x;
         constexpr int N = VPT ? VPT : 1;  // (VPT == 0 never gets here)
+        const uint32_t tid = threadIdx.x;
+        const uint32_t du = narrow ? 8u : 16u;  // destination bytes per unit
         uint32_t row[N], col[N];
+        late.narrow = narrow;
 #pragma unroll
         for (int u = 0; u < N; ++u) {
             const uint32_t i = u * BT + tid;
@@ -248,24 +280,24 @@ __device__ __forceinline__ void copy_vec(gsrc_t src, gdst_t dst, uint64_t ss, ui
             row[u] = div_rows(x, vpr, magic);
             col[u] = x - row[u] * vpr;
             late.v[u] = ld16(src + (size_t)row[u] * ss + (size_t)col[u] * 16);
-            late.p[u] = dst + (size_t)row[u] * ds + (size_t)col[u] * 16;
+            late.p[u] = dst + (size_t)row[u] * ds + (size_t)col[u] * du;
         }
-        if (SUM) {
 #pragma unroll
-            for (int u = 0; u < N; ++u) {
-                if (late.on[u]) {
-                    const uint64_t rel = (uint64_t)row[u] * (SUM == 1 ? ds : ss) + (uint64_t)col[u] * 16;
-                    sum_halves(acc, late.v[u], 0, 8, (int64_t)(rel / 2));
-                }
-            }
+        for (int u = 0; u < N; ++u) {
+            if (SUM == 2 && late.on[u])
+                sum_halves(acc, late.v[u], 0, 8, (int64_t)(((uint64_t)row[u] * ss + (uint64_t)col[u] * 16) / 2));
+            if (narrow) late.v[u] = convert_slot<4, 2>(late.v[u]);
+            if (SUM == 1 && late.on[u])
+                sum_halves(acc, late.v[u], 0, narrow ? 4 : 8,
+                           (int64_t)(((uint64_t)row[u] * ds + (uint64_t)col[u] * du) / 2));
         }
     } else if (count <= BT) {
-        copy_vec_pass<BT, SUM, 1>(src, dst, ss, ds, 0, count, vpr, col0, magic, acc);
+        copy_vec_pass<BT, SUM, 1>(src, dst, ss, ds, 0, count, vpr, col0, magic, narrow, acc);
     } else if (count <= 2 * BT) {
-        copy_vec_pass<BT, SUM, 2>(src, dst, ss, ds, 0, count, vpr, col0, magic, acc);
+        copy_vec_pass<BT, SUM, 2>(src, dst, ss, ds, 0, count, vpr, col0, magic, narrow, acc);
     } else {
         for (uint32_t base = 0; base < count; base += BT * kUnroll)
-            copy_vec_pass<BT, SUM, kUnroll>(src, dst, ss, ds, base, count, vpr, col0, magic, acc);
+            copy_vec_pass<BT, SUM, kUnroll>(src, dst, ss, ds, base, count, vpr, col0, magic, narrow, acc);
     }
 }
 
@@ -279,12 +311,6 @@ struct SlotBytes {
     static constexpr int value = (SES == 4 && DES == 2) ? 8 : 16;
 };
 
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ void st8(gdst_t p, uint32_t lo, uint32_t hi) {
-    u32x2 v;
-    v.x = lo, v.y = hi;
-    __builtin_nontemporal_store(v, reinterpret_cast<TH_GLOBAL u32x2*>(p));
-}
 
 template <int SES>
 __device__ __forceinline__ uint32_t load_elem(gsrc_t p) {
@@ -363,17 +389,6 @@ __device__ __forceinline__ u32x4 shift_in(u32x4 a, u32x4 b, uint32_t over) {
         o.z = __builtin_amdgcn_alignbit(t3, t2, sh);
         o.w = __builtin_amdgcn_alignbit(t4, t3, sh);
     }
-    return o;
-}
-
-// 16 source bytes -> the destination slot's bytes (4 fp32 -> 4 bf16 in the low half when narrowing).
-template <int SES, int DES>
-__device__ __forceinline__ u32x4 convert_slot(u32x4 a) {
-    if (SES == DES) return a;
-    u32x4 o;
-    o.x = narrow_pair(a.x, a.y);
-    o.y = narrow_pair(a.z, a.w);
-    o.z = o.w = 0;
     return o;
 }
 
@@ -663,7 +678,8 @@ __global__ __launch_bounds__(VEC ? kBlockThreads : kBlockThreadsAny, TH_MIN_WAVE
     }
 
     if (kind == TILE_KIND_VEC) {
-        copy_vec<BT, SUM, VPT>(src, dst, ss, ds, count, ncols, col0, magic, acc, late);
+        const bool narrow = (flags & TILE_SRC_F32) && !(flags & TILE_DST_F32);
+        copy_vec<BT, SUM, VPT>(src, dst, ss, ds, count, ncols, col0, magic, narrow, acc, late);
     } else if (kind == TILE_KIND_DENSE) {
         const bool head_skip = (flags & TILE_HEAD_SKIP) != 0, tail_ok = (flags & TILE_TAIL_OK) != 0;
         unsigned des = 2;
@@ -710,7 +726,12 @@ __global__ __launch_bounds__(VEC ? kBlockThreads : kBlockThreadsAny, TH_MIN_WAVE
         for (int u = 0; u < (VPT ? VPT : 1); ++u) hold_live(late.v[u]);
 #pragma unroll
         for (int u = 0; u < (VPT ? VPT : 1); ++u) {
-            if (late.on[u]) st16_through(late.p[u], late.v[u]);
+            if (late.on[u]) {
+                if (late.narrow)
+                    st8_through(late.p[u], late.v[u].x, late.v[u].y);
+                else
+                    st16_through(late.p[u], late.v[u]);
+            }
         }
 #pragma unroll
         for (int u = 0; u < (VPT ? VPT : 1); ++u) hold_live(late.v[u]);

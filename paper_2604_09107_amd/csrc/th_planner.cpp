@@ -34,31 +34,36 @@ void tile_run(std::vector<Tile>& out, Side S, Side D, uint64_t nrows, uint64_t n
         ncols *= nrows;
         nrows = 1;
     }
-    const bool vec = bases_aligned16 && pad == 0 && S.es == D.es && S.off % 16 == 0 && D.off % 16 == 0 &&
-                     (ncols * D.es) % 16 == 0 && (nrows == 1 || (S.stride % 16 == 0 && D.stride % 16 == 0));
-    used_vec = vec;
     const bool narrows = S.es == 4 && D.es == 2;
+    // Vector path: every address a multiple of 16 bytes on both sides and the same dtype; or, when
+    // narrowing, 16 bytes of source (four elements) for every 8 bytes of destination.
+    const uint64_t unit_elems = 16 / S.es;  // elements per column unit of the vector path
+    const uint64_t vs = 16, vd = unit_elems * D.es;  // unit bytes on either side: 16 / 16, or 16 / 8
+    const bool vec = bases_aligned16 && pad == 0 && (S.es == D.es || narrows) && S.off % vs == 0 &&
+                     D.off % vd == 0 && ncols % unit_elems == 0 &&
+                     (nrows == 1 || (S.stride % vs == 0 && D.stride % vd == 0));
+    used_vec = vec;
     const uint64_t tile_bytes = vec ? tune.tile_bytes : narrows ? tune.tile_bytes_narrow : tune.tile_bytes_any;
     uint32_t flags = vec ? TILE_KIND_VEC : TILE_KIND_ANY;
     if (S.es == 4) flags |= TILE_SRC_F32;
     if (D.es == 4) flags |= TILE_DST_F32;
-    const uint64_t unit_d = vec ? 16 : D.es, unit_s = vec ? 16 : S.es;  // bytes per column unit
+    const uint64_t unit_d = vec ? vd : D.es, unit_s = vec ? vs : S.es;  // bytes per column unit
     const uint64_t units = ncols * D.es / unit_d;                        // column units per row
     const uint64_t row_bytes = ncols * D.es;
 
     if (vec) {
         // Cut the rectangle's vectors, taken in row-major order, into equal runs: every tile is
         // full whatever the row length; a tile may start mid-row and wrap over row ends.
-        const uint64_t cap = tile_bytes / 16;  // vectors per tile
+        const uint64_t cap = tile_bytes / 16;  // units per tile: one per thread at the default size
         const uint64_t total = nrows * units;
         for (uint64_t v0 = 0; v0 < total; v0 += cap) {
             Tile t;
             std::memset(&t, 0, sizeof t);
             const uint64_t row0 = nrows == 1 ? 0 : v0 / units;
             const uint64_t col0 = nrows == 1 ? 0 : v0 % units;
-            const uint64_t lin = nrows == 1 ? v0 * 16 : 0;  // a single row needs no wrapping
-            t.src_off = S.off + row0 * S.stride + lin;
-            t.dst_off = D.off + row0 * D.stride + lin;
+            // a single row needs no wrapping: the tile starts v0 units into it
+            t.src_off = S.off + row0 * S.stride + (nrows == 1 ? v0 * vs : 0);
+            t.dst_off = D.off + row0 * D.stride + (nrows == 1 ? v0 * vd : 0);
             t.src_stride = S.stride;
             t.dst_stride = D.stride;
             t.src_buf = S.buf;
