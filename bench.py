@@ -24,12 +24,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # the counter reads for th_reference_copy of known size; summaries under profiles/).  Valid only for
 # the kernel sources they were taken with: bench.py reports null once those files have changed.
 TRAFFIC_SOURCES = ("th_kernels.hip", "th_planner.cpp", "th_internal.hpp")
-TRAFFIC_SHA256 = "b250516662995b554f68ee5a5f61c0984ea57eb62bfbde4a0165cb4d83d0b585"
+TRAFFIC_SHA256 = "b2985a67100a07c9989f08f41480870d7735d5d108fe39594b5b310898c1262a"
 TRAFFIC_BYTES = {
-    "cfg2_8b_tp1_to_tp4": {"th_pack": 8047686422, "th_unpack": 8047011994},
-    "cfg3_70b_tp8_to_tp4": {"th_pack": 35353551952, "th_unpack": 35348057813},
-    "cfg4_moe_ep8_to_tp2": {"th_pack": 5821513152, "th_unpack": 5821175075},
-    "cfg5_scatter_fp32_to_bf16": {"th_pack": 37155837097, "th_unpack": 22679808770},
+    "cfg2_8b_tp1_to_tp4": {"th_pack": 8047563821, "th_unpack": 8047013392},
+    "cfg3_70b_tp8_to_tp4": {"th_pack": 35349367683, "th_unpack": 35348058853},
+    "cfg4_moe_ep8_to_tp2": {"th_pack": 5821398859, "th_unpack": 5821176301},
+    "cfg5_scatter_fp32_to_bf16": {"th_pack": 37138964390, "th_unpack": 22674080841},
 }
 
 
