@@ -305,13 +305,13 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
         uint64_t* partials = want_sums ? p->d_partials[side] : nullptr;
         if (side == 0)
             rc = launch_tiles(MODE_PACK, instance, p->d_tiles[0], tile0[k], ntiles[k], tens_tab,
-                              const_cast<void* const*>(wire_tab), chunk_first, inl, partials, stream);
+                              const_cast<void* const*>(wire_tab), chunk_first, inl, partials, p->m.tiles[0].size(), stream);
         else
             rc = launch_tiles(MODE_UNPACK, instance, p->d_tiles[1], tile0[k], ntiles[k], wire_tab,
-                              const_cast<void* const*>(tens_tab), chunk_first, inl, partials, stream);
+                              const_cast<void* const*>(tens_tab), chunk_first, inl, partials, p->m.tiles[1].size(), stream);
         if (rc == TH_OK && want_sums)
             rc = launch_checksum_finalize(p->d_tiles[side], p->d_partials[side], p->d_tile_base[side], tile0[k],
-                                          ntiles[k], vec_only, sums, stream);
+                                          ntiles[k], p->m.tiles[side].size(), vec_only, sums, stream);
     }
     if (rc != TH_OK) return rc;
     for (PtrSlot* s : {ts, ws}) {
@@ -443,10 +443,10 @@ int th_reshard(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, vo
     int rc = TH_OK;
     if (m.direct_n_vec)
         rc = launch_tiles(MODE_DIRECT, p->specialize ? p->vec_instance : (int)VEC_ALL_PATHS, p->d_tiles[2], 0, m.direct_n_vec, stab, dtab, 0, no_inline,
-                          nullptr, hip_stream);
+                          nullptr, 0, hip_stream);
     if (rc == TH_OK && total > m.direct_n_vec)
         rc = launch_tiles(MODE_DIRECT, VEC_ALL_PATHS, p->d_tiles[2], m.direct_n_vec, total - m.direct_n_vec, stab, dtab, 0,
-                          no_inline, nullptr, hip_stream);
+                          no_inline, nullptr, 0, hip_stream);
     if (rc != TH_OK) return rc;
     for (PtrSlot* s : {ss, ds}) {
         hipError_t e = hipEventRecord(s->used, static_cast<hipStream_t>(hip_stream));

@@ -150,17 +150,18 @@ struct InlineWire {
     void* p[kInlineChunks];
     uint32_t n;  // 0: use the device table
 };
-// partials: nullptr, or device array of kPartialsPerTile pairs of uint64 per tile of `tiles` (same
-// indexing): wavefront w of the workgroup that runs a tile writes the checksum terms (A, B with
-// tile-local positions) of what it moved into pair w.
+// partials: nullptr, or device array of kPartialsPerTile x list_tiles pairs of uint64, list_tiles
+// being the length of the whole list `tiles`: wavefront w of the workgroup that runs tile i writes
+// the checksum terms (A, B with tile-local positions) of what it moved into pair [w][i].
 int launch_tiles(int mode, int instance, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first,
-                 const InlineWire& inl, uint64_t* partials, void* stream);
+                 const InlineWire& inl, uint64_t* partials, uint64_t list_tiles, void* stream);
 // Adds the per-tile terms of tiles [tile0, tile0 + ntiles) into sums[2 * src_tensor + {0, 1}].
 // vec_only: whether the launch_tiles call that filled the pairs ran a vector-only instance (it fixes
 // the wavefronts per tile).
 int launch_checksum_finalize(const Tile* tiles, const uint64_t* partials, const uint64_t* tile_base,
-                             uint64_t tile0, uint64_t ntiles, bool vec_only, uint64_t* sums, void* stream);
+                             uint64_t tile0, uint64_t ntiles, uint64_t list_tiles, bool vec_only, uint64_t* sums,
+                             void* stream);
 
 int launch_reference_copy(void* dst, const void* src, uint64_t nbytes, void* stream);
 int launch_signal(uint64_t* flag, uint64_t value, void* stream);

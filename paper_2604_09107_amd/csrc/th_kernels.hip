@@ -632,8 +632,8 @@ template <int MODE, int VEC, bool CHECKSUM, bool INLINE>
 __global__ __launch_bounds__(VEC ? kBlockThreads : kBlockThreadsAny, TH_MIN_WAVES_PER_EU) void th_tiles_kernel(const Tile* __restrict__ tiles,
                                                                   const void* const* __restrict__ src_table,
                                                                   void* const* __restrict__ dst_table,
-                                                                  uint32_t wire_first, InlineWire inl,
-                                                                  uint64_t* __restrict__ partials) {
+                                                                  uint32_t wire_first, uint32_t partial_stride,
+                                                                  InlineWire inl, uint64_t* __restrict__ partials) {
     // Workgroups are dealt to the 8 XCDs round-robin (workgroup b runs on XCD b mod 8).  Give
     // each XCD one contiguous eighth of the tile list so that it streams through its own
     // address range instead of every 8th tile.
@@ -716,7 +716,9 @@ __global__ __launch_bounds__(VEC ? kBlockThreads : kBlockThreadsAny, TH_MIN_WAVE
             }
         }
     }
-    if (CHECKSUM) wave_sum_store(acc, partials + 2 * ((size_t)b * kPartialsPerTile + (threadIdx.x >> 6)));
+    // pair of wavefront w of the launch's tile b: [w][b], so that the finalize kernel, one thread per
+    // tile, reads neighbouring pairs
+    if (CHECKSUM) wave_sum_store(acc, partials + 2 * ((size_t)(threadIdx.x >> 6) * partial_stride + b));
     if (prefetch) asm volatile("" ::"v"(ahead));  // keeps the prefetch load alive; its value is not used
     if (VPT) {
         // the tile's data stores: the last instructions of the kernel (see st16_through).  The first
@@ -746,6 +748,7 @@ __global__ __launch_bounds__(256) void th_checksum_finalize_kernel(const Tile* _
                                                                    const uint64_t* __restrict__ partials,
                                                                    const uint64_t* __restrict__ tile_base,
                                                                    uint64_t n, uint32_t waves,
+                                                                   uint32_t partial_stride,
                                                                    uint64_t* __restrict__ sums) {
     const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
     const bool active = i < n;
@@ -753,10 +756,10 @@ __global__ __launch_bounds__(256) void th_checksum_finalize_kernel(const Tile* _
     uint64_t a = 0, bsum = 0;
     if (active) {
         tensor = tiles[i].src_tensor;
-        const uint64_t* pair = partials + 2 * i * kPartialsPerTile;
         for (uint32_t w = 0; w < waves; ++w) {
-            a += pair[2 * w];
-            bsum += pair[2 * w + 1];
+            const uint64_t* pair = partials + 2 * ((size_t)w * partial_stride + i);
+            a += pair[0];
+            bsum += pair[1];
         }
         bsum += tile_base[i] * a;
     }
@@ -814,10 +817,10 @@ int launch_signal(uint64_t* flag, uint64_t value, void* stream) {
 
 int launch_tiles(int mode, int instance, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first, const InlineWire& inl,
-                 uint64_t* partials, void* stream) {
+                 uint64_t* partials, uint64_t list_tiles, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     constexpr uint64_t kMaxGrid = 1u << 30;
-    typedef void (*kernel_t)(const Tile*, const void* const*, void* const*, uint32_t, InlineWire, uint64_t*);
+    typedef void (*kernel_t)(const Tile*, const void* const*, void* const*, uint32_t, uint32_t, InlineWire, uint64_t*);
     // [mode][instance][checksum][inline wire pointers]
 #define TH_K(M, V) {{th_tiles_kernel<M, V, false, false>, th_tiles_kernel<M, V, false, true>}, \
                     {th_tiles_kernel<M, V, true, false>, th_tiles_kernel<M, V, true, true>}}
@@ -842,8 +845,8 @@ int launch_tiles(int mode, int instance, const Tile* tiles, uint64_t tile0, uint
     while (ntiles) {
         const uint64_t n = ntiles < kMaxGrid ? ntiles : kMaxGrid;
         hipLaunchKernelGGL(kernel, dim3((uint32_t)n), dim3(vec_only ? kBlockThreads : kBlockThreadsAny), 0, st,
-                           tiles + tile0, src_table, dst_table, wire_first, inl,
-                           partials ? partials + 2 * kPartialsPerTile * tile0 : nullptr);
+                           tiles + tile0, src_table, dst_table, wire_first, (uint32_t)list_tiles, inl,
+                           partials ? partials + 2 * tile0 : nullptr);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) {
             set_error("kernel launch failed: %s", hipGetErrorString(e));
@@ -856,13 +859,13 @@ int launch_tiles(int mode, int instance, const Tile* tiles, uint64_t tile0, uint
 }
 
 int launch_checksum_finalize(const Tile* tiles, const uint64_t* partials, const uint64_t* tile_base, uint64_t tile0,
-                             uint64_t ntiles, bool vec_only, uint64_t* sums, void* stream) {
+                             uint64_t ntiles, uint64_t list_tiles, bool vec_only, uint64_t* sums, void* stream) {
     if (!ntiles) return TH_OK;
     const uint64_t grid = (ntiles + 255) / 256;
     const uint32_t waves = (vec_only ? kBlockThreads : kBlockThreadsAny) / 64;  // of the kernel that ran these tiles
     hipLaunchKernelGGL(th_checksum_finalize_kernel, dim3((uint32_t)grid), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), tiles + tile0, partials + 2 * kPartialsPerTile * tile0,
-                       tile_base + tile0, ntiles, waves, sums);
+                       static_cast<hipStream_t>(stream), tiles + tile0, partials + 2 * tile0, tile_base + tile0,
+                       ntiles, waves, (uint32_t)list_tiles, sums);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         set_error("kernel launch failed: %s", hipGetErrorString(e));
