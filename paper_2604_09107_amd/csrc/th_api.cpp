@@ -36,33 +36,41 @@ int hip_fail(hipError_t e, const char* what) {
     return TH_ERR_HIP;
 }
 
-// A pointer table that lives on the device, with the host copy it was uploaded from and an
-// event marking the last kernel that reads it.
+// A pointer table that lives on the device, with the host copy it was uploaded from.
 struct PtrSlot {
     std::vector<uintptr_t> host;
     void** dev = nullptr;
     size_t cap = 0;  // entries allocated on the device
-    hipEvent_t used = nullptr;
-    bool recorded = false;
     uint64_t stamp = 0;
 };
 
 // Small cache of uploaded pointer tables: callers usually pass the same registered
 // tensors and the same wire buffers version after version (tensors are registered once
-// and reused, Sec. 4.2), so steady-state calls upload nothing.
+// and reused, Sec. 4.2), so steady-state calls upload nothing and make no HIP call besides
+// the kernel launch.  A device table is never overwritten: a kernel that was handed it may
+// still be running.  When a slot gets a new key, its old device table is retired and freed
+// later, after a device synchronisation (once per kRetireBatch retirements) or with the plan.
 struct PtrCache {
     static constexpr size_t kSlots = 8;
+    static constexpr size_t kRetireBatch = 32;
     std::vector<PtrSlot> slots;
+    std::vector<void**> retired;
     uint64_t clock = 0;
 
-    // Returns the slot holding exactly `key` (uploading it if new), or nullptr on error.
-    PtrSlot* get(const std::vector<uintptr_t>& key, bool& fresh) {
-        fresh = false;
+    // The slot whose host copy equals key[0..n), or nullptr.
+    PtrSlot* find(const uintptr_t* key, size_t n) {
         for (PtrSlot& s : slots)
-            if (s.host == key) {
+            if (s.host.size() == n && (n == 0 || std::memcmp(s.host.data(), key, n * sizeof(uintptr_t)) == 0)) {
                 s.stamp = ++clock;
                 return &s;
             }
+        return nullptr;
+    }
+
+    // Returns the slot holding exactly key[0..n) (uploading it if new), or nullptr on error.
+    PtrSlot* get(const uintptr_t* key, size_t n, bool& fresh) {
+        fresh = false;
+        if (PtrSlot* hit = find(key, n)) return hit;
         PtrSlot* s;
         if (slots.size() < kSlots) {
             slots.emplace_back();
@@ -71,56 +79,50 @@ struct PtrCache {
             s = &slots[0];
             for (PtrSlot& c : slots)
                 if (c.stamp < s->stamp) s = &c;
-            // a kernel that was handed this table may still be running
-            if (s->recorded) {
-                hipError_t e = hipEventSynchronize(s->used);
-                if (e != hipSuccess) {
-                    hip_fail(e, "hipEventSynchronize");
-                    return nullptr;
-                }
-            }
         }
-        if (!s->used) {
-            hipError_t e = hipEventCreateWithFlags(&s->used, hipEventDisableTiming);
-            if (e != hipSuccess) {
-                hip_fail(e, "hipEventCreate");
-                return nullptr;
-            }
-        }
-        const size_t n = key.size() ? key.size() : 1;
-        if (s->cap < n) {
-            if (s->dev) (void)hipFree(s->dev);
+        s->host.clear();
+        if (s->dev) {
+            retired.push_back(s->dev);
             s->dev = nullptr;
             s->cap = 0;
-            hipError_t e = hipMalloc(reinterpret_cast<void**>(&s->dev), n * sizeof(void*));
-            if (e != hipSuccess) {
-                s->host.clear();
-                hip_fail(e, "hipMalloc(pointer table)");
-                return nullptr;
+            if (retired.size() >= kRetireBatch) {
+                const hipError_t e = hipDeviceSynchronize();
+                if (e != hipSuccess) {
+                    hip_fail(e, "hipDeviceSynchronize");
+                    return nullptr;
+                }
+                for (void** d : retired) (void)hipFree(d);
+                retired.clear();
             }
-            s->cap = n;
         }
-        if (!key.empty()) {
-            hipError_t e = hipMemcpy(s->dev, key.data(), key.size() * sizeof(void*), hipMemcpyHostToDevice);
+        const size_t cap = n ? n : 1;
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&s->dev), cap * sizeof(void*));
+        if (e != hipSuccess) {
+            s->dev = nullptr;
+            hip_fail(e, "hipMalloc(pointer table)");
+            return nullptr;
+        }
+        s->cap = cap;
+        if (n) {
+            e = hipMemcpy(s->dev, key, n * sizeof(void*), hipMemcpyHostToDevice);
             if (e != hipSuccess) {
-                s->host.clear();
                 hip_fail(e, "hipMemcpy(pointer table)");
                 return nullptr;
             }
         }
-        s->host = key;
-        s->recorded = false;
+        s->host.assign(key, key + n);
         s->stamp = ++clock;
         fresh = true;
         return s;
     }
 
+    // The plan is being destroyed: the caller has synchronised the streams that used it.
     void release() {
-        for (PtrSlot& s : slots) {
+        for (PtrSlot& s : slots)
             if (s.dev) (void)hipFree(s.dev);
-            if (s.used) (void)hipEventDestroy(s.used);
-        }
+        for (void** d : retired) (void)hipFree(d);
         slots.clear();
+        retired.clear();
     }
 };
 
@@ -205,10 +207,10 @@ int check_device(const th_plan* p) {
 // 1 = destination tensors) and validates a table that was not seen before.  Caller holds p->mu.
 int tensor_table(const th_plan* p, int side, const void* const* ptrs, uint32_t n, PtrSlot** out) {
     const Manifest& m = p->m;
-    std::vector<uintptr_t> key(n);
-    for (uint32_t i = 0; i < n; ++i) key[i] = reinterpret_cast<uintptr_t>(ptrs[i]);
+    static_assert(sizeof(uintptr_t) == sizeof(void*), "pointer tables are compared as integers");
+    const uintptr_t* key = reinterpret_cast<const uintptr_t*>(ptrs);
     bool fresh = false;
-    PtrSlot* ts = p->tensor_cache[side].get(key, fresh);
+    PtrSlot* ts = p->tensor_cache[side].get(key, n, fresh);
     *out = ts;
     if (!ts) return TH_ERR_HIP;
     if (!fresh) return TH_OK;
@@ -291,7 +293,7 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
         wkey[0] = chunk_first;
         for (uint32_t i = 0; i < chunk_count; ++i) wkey[i + 1] = reinterpret_cast<uintptr_t>(wire_ptrs[i]);
         bool fresh = false;
-        ws = p->wire_cache[side].get(wkey, fresh);
+        ws = p->wire_cache[side].get(wkey.data(), wkey.size(), fresh);
         if (!ws) return TH_ERR_HIP;
         wire_tab = reinterpret_cast<const void* const*>(ws->dev + 1);
     }
@@ -313,14 +315,7 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
             rc = launch_checksum_finalize(p->d_tiles[side], p->d_partials[side], p->d_tile_base[side], tile0[k],
                                           ntiles[k], p->m.tiles[side].size(), vec_only, sums, stream);
     }
-    if (rc != TH_OK) return rc;
-    for (PtrSlot* s : {ts, ws}) {
-        if (!s) continue;
-        hipError_t e = hipEventRecord(s->used, static_cast<hipStream_t>(stream));
-        if (e != hipSuccess) return hip_fail(e, "hipEventRecord");
-        s->recorded = true;
-    }
-    return TH_OK;
+    return rc;
 }
 
 }  // namespace
@@ -447,13 +442,7 @@ int th_reshard(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, vo
     if (rc == TH_OK && total > m.direct_n_vec)
         rc = launch_tiles(MODE_DIRECT, VEC_ALL_PATHS, p->d_tiles[2], m.direct_n_vec, total - m.direct_n_vec, stab, dtab, 0,
                           no_inline, nullptr, 0, hip_stream);
-    if (rc != TH_OK) return rc;
-    for (PtrSlot* s : {ss, ds}) {
-        hipError_t e = hipEventRecord(s->used, static_cast<hipStream_t>(hip_stream));
-        if (e != hipSuccess) return hip_fail(e, "hipEventRecord");
-        s->recorded = true;
-    }
-    return TH_OK;
+    return rc;
 }
 
 int th_plan_destroy(th_plan* p) {
