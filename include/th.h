@@ -178,7 +178,11 @@ int th_plan_create_from_segments(const th_segment* segs, size_t n,
  *              th_plan_chunk_bytes(plan, chunk_first+i) bytes.  Every byte of the
  *              chunk is written (payload and zero gaps).
  * The host arrays are read before the call returns.  Pointer tables are kept on
- * the device and re-uploaded only when their contents change.
+ * the device and re-uploaded only when their contents change (the call that
+ * brings a table not seen before allocates and copies synchronously, and every
+ * 32nd such call synchronises the device to free replaced tables; a call with
+ * tables seen before, or with at most 8 chunks and known tensor pointers, only
+ * launches).
  * Errors (synchronous): TH_ERR_ARG, TH_ERR_RANGE, TH_ERR_HIP.  Device-side
  * faults surface at the caller's next synchronisation. */
 int th_pack(const th_plan* plan, const void* const* src_ptrs, uint32_t n_src,
