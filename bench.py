@@ -24,12 +24,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # the counter reads for th_reference_copy of known size; summaries under profiles/).  Valid only for
 # the kernel sources they were taken with: bench.py reports null once those files have changed.
 TRAFFIC_SOURCES = ("th_kernels.hip", "th_planner.cpp", "th_internal.hpp")
-TRAFFIC_SHA256 = "b2985a67100a07c9989f08f41480870d7735d5d108fe39594b5b310898c1262a"
+TRAFFIC_SHA256 = "aa23b083292ba27b140c550a6d6f7ef5ebd3b95c3859fc9d475b3fe3e152a839"
 TRAFFIC_BYTES = {
-    "cfg2_8b_tp1_to_tp4": {"th_pack": 8047563821, "th_unpack": 8047013392},
-    "cfg3_70b_tp8_to_tp4": {"th_pack": 35349367683, "th_unpack": 35348058853},
-    "cfg4_moe_ep8_to_tp2": {"th_pack": 5821398859, "th_unpack": 5821176301},
-    "cfg5_scatter_fp32_to_bf16": {"th_pack": 37138964390, "th_unpack": 22674080841},
+    "cfg2_8b_tp1_to_tp4": {"th_pack": 8047561889, "th_unpack": 8047001220},
+    "cfg3_70b_tp8_to_tp4": {"th_pack": 35349367824, "th_unpack": 35348045937},
+    "cfg4_moe_ep8_to_tp2": {"th_pack": 5821397869, "th_unpack": 5821163279},
+    "cfg5_scatter_fp32_to_bf16": {"th_pack": 37146686722, "th_unpack": 22673702227},
 }
 
 
