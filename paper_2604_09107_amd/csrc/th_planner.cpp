@@ -2,6 +2,7 @@
 // device work list (tiles).  Integer arithmetic only.
 #include <algorithm>
 #include <cstring>
+#include <thread>
 
 #include "th_internal.hpp"
 
@@ -27,7 +28,8 @@ struct Side {  // one end of a copy, in bytes
 };
 
 // Append the tiles of one run, seen as a copy S -> D of nrows x ncols elements.
-void tile_run(std::vector<Tile>& out, Side S, Side D, uint64_t nrows, uint64_t ncols, unsigned pad,
+// outs[0] receives vector-path tiles, outs[1] all others; a run's tiles are all of one class.
+void tile_run(std::vector<Tile>* outs, Side S, Side D, uint64_t nrows, uint64_t ncols, unsigned pad,
               bool bases_aligned16, const Tuning& tune, bool& used_vec) {
     // rows that follow each other without a gap on both ends are one long row
     if (nrows > 1 && S.stride == ncols * S.es && D.stride == ncols * D.es) {
@@ -43,6 +45,7 @@ void tile_run(std::vector<Tile>& out, Side S, Side D, uint64_t nrows, uint64_t n
                      D.off % vd == 0 && ncols % unit_elems == 0 &&
                      (nrows == 1 || (S.stride % vs == 0 && D.stride % vd == 0));
     used_vec = vec;
+    std::vector<Tile>& out = outs[vec ? 0 : 1];
     const uint64_t tile_bytes = vec ? tune.tile_bytes : narrows ? tune.tile_bytes_narrow : tune.tile_bytes_any;
     uint32_t flags = vec ? TILE_KIND_VEC : TILE_KIND_ANY;
     if (S.es == 4) flags |= TILE_SRC_F32;
@@ -325,13 +328,28 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
         }
     }
 
-    // ---- tiles, one list per direction: vector-path tiles first, each sub-list grouped by chunk ----
-    for (int side = 0; side < 2; ++side) {
-        std::vector<Tile> tiles;
-        std::vector<uint64_t> base;
-        const size_t guess = (size_t)(m.payload_bytes / std::min({tune.tile_bytes, tune.tile_bytes_any, tune.tile_bytes_narrow})) + 2 * m.runs.size();
-        tiles.reserve(guess);
-        base.reserve(guess);
+    // ---- tiles: one list per direction and the wire-free list, built by three threads (the lists
+    // are independent; what they learn about the tensors is merged afterwards) ----
+    struct Seen {
+        std::vector<uint8_t> used, need16;
+    };
+    Seen seen[3][2];  // [list][tensor side]
+    for (int l = 0; l < 3; ++l)
+        for (int s = 0; s < 2; ++s) {
+            seen[l][s].used.assign(m.tensors[s].size(), 0);
+            seen[l][s].need16.assign(m.tensors[s].size(), 0);
+        }
+    const size_t guess = (size_t)(m.payload_bytes / std::min({tune.tile_bytes, tune.tile_bytes_any, tune.tile_bytes_narrow}));
+
+    // One list per direction: vector-path tiles first, each sub-list grouped by chunk.  Runs come in
+    // wire order, so within a class the tiles are generated in chunk order already: the two classes
+    // are collected separately and joined, nothing is sorted or copied twice.
+    auto build_side = [&](int side) {
+        std::vector<Tile> tiles[2];
+        std::vector<uint64_t> base[2];
+        bool reserved[2] = {false, false};
+        Seen& mine = seen[side][side];  // pack learns about source tensors, unpack about destination tensors
+        for (unsigned k = 0; k < 2; ++k) m.chunk_tile0[side][k].assign((size_t)m.n_chunks + 1, 0);
         for (size_t ri = 0; ri < m.runs.size(); ++ri) {
             const th_run& r = m.runs[ri];
             const unsigned es_s = esize(r.src_dtype), es_w = esize(r.wire_dtype), es_d = esize(r.dst_dtype);
@@ -344,57 +362,82 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
                 D = Side{r.dst_tensor, r.dst_byte_off, r.dst_byte_stride, es_d};
             }
             bool vec = false;
-            const size_t before = tiles.size();
+            const size_t before[2] = {tiles[0].size(), tiles[1].size()};
             tile_run(tiles, S, D, r.nrows, r.row_len, side == 0 ? r.pad_bytes : 0, ptrs_aligned16, tune, vec);
-            for (size_t i = before; i < tiles.size(); ++i) {
-                Tile& t = tiles[i];
+            const unsigned k = vec ? 0 : 1;
+            if (!reserved[k]) {  // first run of this class (most plans use one class only)
+                reserved[k] = true;
+                tiles[k].reserve(guess + 2 * m.runs.size());
+                base[k].reserve(guess + 2 * m.runs.size());
+            }
+            for (size_t i = before[k]; i < tiles[k].size(); ++i) {
+                Tile& t = tiles[k][i];
                 t.src_tensor = r.src_tensor;
                 const uint64_t wire_off = (uint64_t)r.chunk * CB + (side == 0 ? t.dst_off : t.src_off);
-                base.push_back((wire_off - m.run_starts[ri]) / 2);
+                base[k].push_back((wire_off - m.run_starts[ri]) / 2);
             }
-            TensorInfo& t = side == 0 ? m.tensors[0][r.src_tensor] : m.tensors[1][r.dst_tensor];
-            t.used = true;
-            t.need16 = t.need16 || vec;
+            m.chunk_tile0[side][k][r.chunk + 1] += tiles[k].size() - before[k];
+            const uint32_t tensor = side == 0 ? r.src_tensor : r.dst_tensor;
+            mine.used[tensor] = 1;
+            if (vec) mine.need16[tensor] = 1;
         }
-        auto chunk_of = [side](const Tile& t) { return side == 0 ? t.dst_buf : t.src_buf; };
-        auto class_of = [](const Tile& t) { return (t.flags & TILE_KIND_MASK) == TILE_KIND_VEC ? 0u : 1u; };
-        // counting sort by (class, chunk): stable, one pass
-        uint64_t n_class[2] = {0, 0};
-        for (const Tile& t : tiles) n_class[class_of(t)]++;
         for (unsigned k = 0; k < 2; ++k) {
             std::vector<uint64_t>& first = m.chunk_tile0[side][k];
-            first.assign((size_t)m.n_chunks + 1, 0);
-            for (const Tile& t : tiles)
-                if (class_of(t) == k) first[chunk_of(t) + 1]++;
-            first[0] = k == 0 ? 0 : n_class[0];
+            first[0] = k == 0 ? 0 : tiles[0].size();
             for (size_t c = 0; c < m.n_chunks; ++c) first[c + 1] += first[c];
         }
-        std::vector<uint64_t> cursor[2] = {m.chunk_tile0[side][0], m.chunk_tile0[side][1]};
-        m.tiles[side].resize(tiles.size());
-        m.tile_base[side].resize(tiles.size());
-        for (size_t i = 0; i < tiles.size(); ++i) {
-            const uint64_t pos = cursor[class_of(tiles[i])][chunk_of(tiles[i])]++;
-            m.tiles[side][pos] = tiles[i];
-            m.tile_base[side][pos] = base[i];
+        if (tiles[0].empty()) {
+            m.tiles[side] = std::move(tiles[1]);
+            m.tile_base[side] = std::move(base[1]);
+        } else {
+            m.tiles[side] = std::move(tiles[0]);
+            m.tile_base[side] = std::move(base[0]);
+            m.tiles[side].insert(m.tiles[side].end(), tiles[1].begin(), tiles[1].end());
+            m.tile_base[side].insert(m.tile_base[side].end(), base[1].begin(), base[1].end());
         }
-    }
+    };
 
-    // ---- direct list: holder tensors -> reader tensors without the wire, one pass over the segments ----
-    {
-        std::vector<Tile>& tiles = m.tiles[2];
-        tiles.reserve((size_t)(m.payload_bytes / std::min({tune.tile_bytes, tune.tile_bytes_any, tune.tile_bytes_narrow})) + 2 * m.segments.size());
+    // direct list: holder tensors -> reader tensors without the wire, one pass over the segments
+    auto build_direct = [&]() {
+        std::vector<Tile> tiles[2];
+        bool reserved[2] = {false, false};
         for (const Segment& g : m.segments) {
             const unsigned es_s = esize(g.src_dtype), es_d = esize(g.dst_dtype);
             const Side S{g.src_tensor, g.src_off * es_s, g.src_stride * es_s, es_s};
             const Side D{g.dst_tensor, g.dst_off * es_d, g.dst_stride * es_d, es_d};
             bool vec = false;
             tile_run(tiles, S, D, g.nrows, g.row_len, 0, ptrs_aligned16, tune, vec);
-            if (vec) m.tensors[0][g.src_tensor].need16 = m.tensors[1][g.dst_tensor].need16 = true;
+            if (!reserved[vec ? 0 : 1]) {
+                reserved[vec ? 0 : 1] = true;
+                tiles[vec ? 0 : 1].reserve(guess + 2 * m.segments.size());
+            }
+            if (vec) seen[2][0].need16[g.src_tensor] = seen[2][1].need16[g.dst_tensor] = 1;
         }
-        auto is_vec = [](const Tile& t) { return (t.flags & TILE_KIND_MASK) == TILE_KIND_VEC; };
-        std::stable_partition(tiles.begin(), tiles.end(), is_vec);
-        m.direct_n_vec = (uint64_t)std::count_if(tiles.begin(), tiles.end(), is_vec);
+        m.direct_n_vec = tiles[0].size();
+        if (tiles[0].empty()) {
+            m.tiles[2] = std::move(tiles[1]);
+        } else {
+            m.tiles[2] = std::move(tiles[0]);
+            m.tiles[2].insert(m.tiles[2].end(), tiles[1].begin(), tiles[1].end());
+        }
+    };
+
+    if (guess < 4096) {  // small plans: not worth two threads
+        build_side(0);
+        build_side(1);
+        build_direct();
+    } else {
+        std::thread t0(build_side, 0), t1(build_side, 1);
+        build_direct();
+        t0.join();
+        t1.join();
     }
+    for (int l = 0; l < 3; ++l)
+        for (int s = 0; s < 2; ++s)
+            for (size_t i = 0; i < m.tensors[s].size(); ++i) {
+                if (seen[l][s].used[i]) m.tensors[s][i].used = true;
+                if (seen[l][s].need16[i]) m.tensors[s][i].need16 = true;
+            }
     return TH_OK;
 }
 
