@@ -24,12 +24,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # the counter reads for th_reference_copy of known size; summaries under profiles/).  Valid only for
 # the kernel sources they were taken with: bench.py reports null once those files have changed.
 TRAFFIC_SOURCES = ("th_kernels.hip", "th_planner.cpp", "th_internal.hpp")
-TRAFFIC_SHA256 = "aa23b083292ba27b140c550a6d6f7ef5ebd3b95c3859fc9d475b3fe3e152a839"
+TRAFFIC_SHA256 = "2a121dede828590ec3a36e17a2a6ed9d97dcc7d03b9996af3675c1bb34c3a49a"
 TRAFFIC_BYTES = {
-    "cfg2_8b_tp1_to_tp4": {"th_pack": 8047561889, "th_unpack": 8047001220},
-    "cfg3_70b_tp8_to_tp4": {"th_pack": 35349367824, "th_unpack": 35348045937},
-    "cfg4_moe_ep8_to_tp2": {"th_pack": 5821397869, "th_unpack": 5821163279},
-    "cfg5_scatter_fp32_to_bf16": {"th_pack": 37146686722, "th_unpack": 22673702227},
+    "cfg2_8b_tp1_to_tp4": {"th_pack": 8047563341, "th_unpack": 8046999728},
+    "cfg3_70b_tp8_to_tp4": {"th_pack": 35349366699, "th_unpack": 35348044028},
+    "cfg4_moe_ep8_to_tp2": {"th_pack": 5821401099, "th_unpack": 5821162381},
+    "cfg5_scatter_fp32_to_bf16": {"th_pack": 37140380236, "th_unpack": 22673869394},
 }
 
 
