@@ -78,7 +78,8 @@ __device__ __forceinline__ void st8(gdst_t p, uint32_t lo, uint32_t hi) {
 // a store, in place over the stored registers, corrupted what arrived in memory.)  Hence the rule
 // for this function: it is called only from the tail of the kernel, after every other instruction
 // that writes a vector register, and the stored values are kept live up to the end of the kernel
-// (hold_live), so that no register of theirs can be handed out again.
+// (hold_live), so that no register of theirs can be handed out again.  tests/test_kernel_tail.py
+// checks this on the compiled code of every kernel instance.
 __device__ __forceinline__ void st16_through(gdst_t p, u32x4 v) {
     asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
 }
