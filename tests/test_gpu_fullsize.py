@@ -12,7 +12,7 @@ import torch
 import synth
 import paper_2604_09107_amd as th
 from paper_2604_09107_amd import device as dev
-from oracle import layouts, reshard, segments
+from oracle import checksum, layouts, reshard, segments
 from test_planner_manifest import scatter_segments
 
 pytestmark = pytest.mark.gpu
@@ -169,4 +169,108 @@ def test_scattered_sweep_full_size():
     assert int16_sum(arena[:d["arena_elems"]]) == int16_sum(wire_dev[:plan.wire_bytes])
     g = synth.to_bits(arena_dev)
     assert g[0] == 0x7FA5 and np.all(g[d["arena_elems"] + 1:] == 0x7FA5)
+    plan.destroy()
+
+
+def sums_host(t):
+    return t.cpu().numpy().view(np.uint64).reshape(-1, 2)
+
+
+@pytest.mark.parametrize("name,layers", [("cfg2_8b_tp1_to_tp4", {0, 17, 31}), ("cfg4_moe_ep8_to_tp2", {0, 23})])
+def test_model_checksums_full_size(name, layers):
+    """Fused checksums in the configuration the benchmark's checksum sweep times: both sides agree
+    for every holder tensor, the oracle (from the source bits alone) on a sample of them, and the
+    reader tensors equal those of the plain calls."""
+    w = synth.workload(name)
+    model, src, dst = w["model"], w["holders"][0], w["reader"]
+    lts = layouts.logical_tensors(model)
+    regs = layouts.registered_tensors(model, src)
+    stream = dev.current_stream()
+    plan = th.th_plan_create(model, src, dst, w["chunk_bytes"], th.TH_FLAG_CHECKSUM)
+    plain = th.th_plan_create(model, src, dst, w["chunk_bytes"])
+    src_dev = [synth.weight_values(t["rows"] * t["cols"], t["dtype"], w["seed"] * 16, i, "cuda",
+                                   is_norm=lts[t["parts"][0][0]]["role"] == "norm")
+               for i, t in enumerate(regs)]
+    dst_dev = dev.alloc_tensors(plan, 1, fill_bits=0x7FA5)
+    ref_dev = dev.alloc_tensors(plain, 1, fill_bits=0x7FA5)
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=0xEE)
+    ps = torch.zeros(2 * len(regs), dtype=torch.int64, device="cuda")
+    us = torch.zeros_like(ps)
+    log("%s: %d tensors, wire %.2f GB, %d tiles" % (name, len(regs), plan.wire_bytes / 1e9, plan.num_tiles(0)))
+    th.th_pack_checksum(plan, dev.ptrs(src_dev), wptrs, 0, plan.num_chunks, ps.data_ptr(), stream)
+    th.th_unpack_checksum(plan, wptrs, 0, plan.num_chunks, dev.ptrs(dst_dev), us.data_ptr(), stream)
+    torch.cuda.synchronize()
+    log("packed + unpacked with checksums")
+    got_p, got_u = sums_host(ps), sums_host(us)
+    assert np.array_equal(got_p, got_u)
+    sample = set(layer_sample(regs, layers))
+    runs = {}
+    for it in reshard.plan_items(model, src, dst):
+        if it["src_id"] in sample:
+            reg = regs[it["src_id"]]
+            bits = synth.to_bits(src_dev[it["src_id"]]).reshape(reg["rows"], reg["cols"])
+            runs.setdefault(it["src_id"], []).append((it["wire_off"], reshard.item_wire(it, bits).view(np.uint8)))
+    for t, parts in runs.items():
+        lo = min(o for o, _ in parts)
+        run = np.zeros(max(o + len(b) for o, b in parts) - lo, dtype=np.uint8)
+        for o, b in parts:
+            run[o - lo:o - lo + len(b)] = b
+        assert tuple(int(v) for v in got_p[t]) == checksum.run_checksum(run), regs[t]["name"]
+    sends = {it["src_id"] for it in reshard.plan_items(model, src, dst)}
+    for t in range(len(regs)):
+        if t not in sends:
+            assert not got_p[t].any(), regs[t]["name"]
+    log("oracle agreed on the checksums of %d sampled tensors" % len(runs))
+    assert len(runs) >= 10
+    # the checksum variant moves the same data as the plain calls
+    th.th_pack(plain, dev.ptrs(src_dev), wptrs, 0, plain.num_chunks, stream)
+    th.th_unpack(plain, wptrs, 0, plain.num_chunks, dev.ptrs(ref_dev), stream)
+    torch.cuda.synchronize()
+    for a, b in zip(dst_dev, ref_dev):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    plan.destroy()
+    plain.destroy()
+
+
+def test_scattered_checksums_full_size():
+    """Checksums of the 100,000-tensor narrowing sweep: equal on both sides for every tensor, equal
+    to the oracle's for a sample (each tensor is one segment, so its run is that segment's wire)."""
+    n, seed, chunk = 100_000, 5, 16 << 20
+    d = synth.scatter_description(n, seed)
+    pool_dev = synth.scatter_values(d["pool_elems"] + 3, seed, "cuda")[1:]
+    arena_dev = torch.empty(d["arena_elems"] + 9, dtype=torch.bfloat16, device="cuda")
+    arena = arena_dev[1:]
+    plan = th.th_plan_create_from_segments(scatter_segments(d), d["n_elems"], [d["arena_elems"] + 8], chunk,
+                                           th.TH_FLAG_CHECKSUM)
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=0xEE)
+    src_ptrs = pool_dev.data_ptr() + d["pool_off"].astype(np.uint64) * np.uint64(4)
+    ps = torch.zeros(2 * n, dtype=torch.int64, device="cuda")
+    us = torch.zeros_like(ps)
+    stream = dev.current_stream()
+    th.th_pack_checksum(plan, src_ptrs, wptrs, 0, plan.num_chunks, ps.data_ptr(), stream)
+    th.th_unpack_checksum(plan, wptrs, 0, plan.num_chunks, [arena.data_ptr()], us.data_ptr(), stream)
+    torch.cuda.synchronize()
+    log("scattered sweep packed + unpacked with checksums")
+    got_p, got_u = sums_host(ps), sums_host(us)
+    assert np.array_equal(got_p, got_u)
+    assert np.array_equal(np.sort(d["seg_src_tensor"]), np.arange(n))   # one segment per tensor, wire order shuffled
+    osegs = dict(src_tensor=d["seg_src_tensor"], dst_tensor=np.zeros(n, dtype=np.int64),
+                 src_off=d["seg_src_off"], src_stride=d["seg_src_stride"], dst_off=d["seg_dst_off"],
+                 dst_stride=d["seg_dst_stride"], nrows=d["seg_nrows"], row_len=d["seg_row_len"])
+    rng = np.random.default_rng(seed + 1)
+    size = d["seg_nrows"] * d["seg_row_len"]
+    order = np.argsort(size)
+    ks = set(rng.choice(n, 800, replace=False).tolist()) | set(order[:100].tolist()) | set(order[-8:].tolist())
+    ks |= {0, n - 1}
+
+    class Lazy:
+        def __getitem__(self, t):
+            o, m = int(d["pool_off"][t]), int(d["n_elems"][t])
+            return synth.to_bits(pool_dev[o:o + m])
+
+    for k in sorted(ks):
+        want = segments.segment_wire(osegs, k, Lazy(), "f32", "bf16")
+        t = int(d["seg_src_tensor"][k])
+        assert tuple(int(v) for v in got_p[t]) == checksum.run_checksum(want.view(np.uint8)), "tensor %d" % t
+    log("oracle agreed on the checksums of %d sampled tensors" % len(ks))
     plan.destroy()
