@@ -46,26 +46,33 @@ def measured_traffic(workload, kernel):
 def build_inputs(th, dev, synth, w, torch):
     """Plans, resident source tensors, wire buffers and destination tensors of a model workload."""
     from oracle import layouts  # only for tensor roles of the synthetic values (norm vs weight)
-    model, dst = w["model"], w["reader"]
+    model = w["model"]
     lts = layouts.logical_tensors(model)
     jobs = []
-    dst_dev = None
+    resident = {}          # holder layout -> its tensors in HBM (a holder feeding several readers is resident once)
     plan_ms = 0.0
-    for h, src in enumerate(w["holders"]):
-        t0 = time.perf_counter()
-        plan = th.th_plan_create(model, src, dst, w["chunk_bytes"])
-        plan_ms += (time.perf_counter() - t0) * 1e3
-        ck_plan = th.th_plan_create(model, src, dst, w["chunk_bytes"], th.TH_FLAG_CHECKSUM)
-        regs = layouts.registered_tensors(model, src)
-        src_dev = [synth.weight_values(t["rows"] * t["cols"], t["dtype"], w["seed"] * 16 + h, i, "cuda",
-                                       is_norm=lts[t["parts"][0][0]]["role"] == "norm")
-                   for i, t in enumerate(regs)]
-        if dst_dev is None:
-            dst_dev = dev.alloc_tensors(plan, 1, fill_bits=0)
-        wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=0)
-        jobs.append(dict(plan=plan, ck_plan=ck_plan, src=src_dev, src_ptrs=dev.ptrs(src_dev), wire=wire_dev,
-                         wptrs=wptrs, layout=src, regs=regs))
-    return jobs, dst_dev, dev.ptrs(dst_dev), plan_ms
+    for part in w["parts"]:
+        dst = part["reader"]
+        dst_dev = None
+        for src in part["holders"]:
+            t0 = time.perf_counter()
+            plan = th.th_plan_create(model, src, dst, w["chunk_bytes"])
+            plan_ms += (time.perf_counter() - t0) * 1e3
+            ck_plan = th.th_plan_create(model, src, dst, w["chunk_bytes"], th.TH_FLAG_CHECKSUM)
+            regs = layouts.registered_tensors(model, src)
+            key = tuple(sorted(src.items()))
+            if key not in resident:
+                h = len(resident)
+                resident[key] = [synth.weight_values(t["rows"] * t["cols"], t["dtype"], w["seed"] * 16 + h, i, "cuda",
+                                                     is_norm=lts[t["parts"][0][0]]["role"] == "norm")
+                                 for i, t in enumerate(regs)]
+            src_dev = resident[key]
+            if dst_dev is None:
+                dst_dev = dev.alloc_tensors(plan, 1, fill_bits=0)
+            wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=0)
+            jobs.append(dict(plan=plan, ck_plan=ck_plan, src=src_dev, src_ptrs=dev.ptrs(src_dev), wire=wire_dev,
+                             wptrs=wptrs, layout=src, regs=regs, dst=dst_dev, dst_ptrs=dev.ptrs(dst_dev)))
+    return jobs, plan_ms
 
 
 def cpu_baseline(synth, w, jobs, budget_s=15.0):
@@ -125,8 +132,9 @@ def build_scatter_inputs(th, dev, synth, w, torch):
                                               th.TH_FLAG_CHECKSUM)
     wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=0)
     src_ptrs = pool.data_ptr() + d["pool_off"].astype(np.uint64) * np.uint64(4)
-    job = dict(plan=plan, ck_plan=ck_plan, src=pool, src_ptrs=src_ptrs, wire=wire_dev, wptrs=wptrs, desc=d, keep=arena_store)
-    return [job], [arena], np.array([arena.data_ptr()], dtype=np.uint64), plan_ms
+    job = dict(plan=plan, ck_plan=ck_plan, src=pool, src_ptrs=src_ptrs, wire=wire_dev, wptrs=wptrs, desc=d,
+               keep=arena_store, dst=[arena], dst_ptrs=np.array([arena.data_ptr()], dtype=np.uint64))
+    return [job], plan_ms
 
 
 def cpu_baseline_scatter(synth, w, jobs, budget_s=15.0):
@@ -197,9 +205,9 @@ def main():
     th.th_plan_create(w0["model"], w0["holders"][0], w0["reader"], w0["chunk_bytes"]).destroy()
     w = synth.workload(args.workload)
     if w["kind"] == "scatter":
-        jobs, dst_dev, dst_ptrs, plan_ms = build_scatter_inputs(th, dev, synth, w, torch)
+        jobs, plan_ms = build_scatter_inputs(th, dev, synth, w, torch)
     else:
-        jobs, dst_dev, dst_ptrs, plan_ms = build_inputs(th, dev, synth, w, torch)
+        jobs, plan_ms = build_inputs(th, dev, synth, w, torch)
     stream = dev.current_stream()
 
     pack_bytes = sum(j["plan"].src_read_bytes + j["plan"].payload_bytes for j in jobs)     # read src + write wire
@@ -216,7 +224,7 @@ def main():
                 if side == 0:
                     th.th_pack(j["plan"], j["src_ptrs"], j["wptrs"], 0, n, stream)
                 else:
-                    th.th_unpack(j["plan"], j["wptrs"], 0, n, dst_ptrs, stream)
+                    th.th_unpack(j["plan"], j["wptrs"], 0, n, j["dst_ptrs"], stream)
                 if events is not None:
                     e1.record()
                     events[side].append((e0, e1))
@@ -273,11 +281,11 @@ def main():
     direct_bytes = sum(j["plan"].src_read_bytes + j["plan"].payload_bytes for j in jobs)
     for _ in range(3):
         for j in jobs:
-            th.th_reshard(j["plan"], j["src_ptrs"], dst_ptrs, stream)
+            th.th_reshard(j["plan"], j["src_ptrs"], j["dst_ptrs"], stream)
     c0.record()
     for _ in range(10):
         for j in jobs:
-            th.th_reshard(j["plan"], j["src_ptrs"], dst_ptrs, stream)
+            th.th_reshard(j["plan"], j["src_ptrs"], j["dst_ptrs"], stream)
     c1.record()
     torch.cuda.synchronize()
     direct_ms = c0.elapsed_time(c1) / 10
@@ -293,7 +301,8 @@ def main():
             n = j["ck_plan"].num_chunks
             th.th_pack_checksum(j["ck_plan"], j["src_ptrs"], j["wptrs"], 0, n, ps.data_ptr(), stream)
         for j, (ps, us) in zip(jobs, sums):
-            th.th_unpack_checksum(j["ck_plan"], j["wptrs"], 0, j["ck_plan"].num_chunks, dst_ptrs, us.data_ptr(), stream)
+            th.th_unpack_checksum(j["ck_plan"], j["wptrs"], 0, j["ck_plan"].num_chunks, j["dst_ptrs"], us.data_ptr(),
+                                  stream)
 
     for _ in range(3):
         checksum_step()
@@ -312,7 +321,7 @@ def main():
                 th.th_pack(j["plan"], j["src_ptrs"], j["wptrs"][c:c + 1], c, 1, stream)
         for j in jobs:
             for c in range(j["plan"].num_chunks):
-                th.th_unpack(j["plan"], j["wptrs"][c:c + 1], c, 1, dst_ptrs, stream)
+                th.th_unpack(j["plan"], j["wptrs"][c:c + 1], c, 1, j["dst_ptrs"], stream)
 
     per_chunk_sweep()
     torch.cuda.synchronize()
@@ -334,7 +343,7 @@ def main():
             for j in jobs:
                 for c in range(j["plan"].num_chunks):
                     th.th_pack(j["plan"], j["src_ptrs"], rp[c & 1], c, 1, stream)
-                    th.th_unpack(j["plan"], rp[c & 1], c, 1, dst_ptrs, stream)
+                    th.th_unpack(j["plan"], rp[c & 1], c, 1, j["dst_ptrs"], stream)
 
         ring_sweep()
         torch.cuda.synchronize()
@@ -356,7 +365,7 @@ def main():
         hptrs = dev.chunk_ptrs(plan, host)[:nck]
         res = {}
         for name, call in (("th_pack", lambda: th.th_pack(plan, j["src_ptrs"], hptrs, 0, nck, stream)),
-                           ("th_unpack", lambda: th.th_unpack(plan, hptrs, 0, nck, dst_ptrs, stream))):
+                           ("th_unpack", lambda: th.th_unpack(plan, hptrs, 0, nck, j["dst_ptrs"], stream))):
             call()
             torch.cuda.synchronize()
             c0.record()
@@ -375,7 +384,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32->bf16 (integer RNE)" if w["kind"] == "scatter" else "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "model": w["model_name"], "chunk_bytes": w["chunk_bytes"],
-                   "holders": len(jobs), "payload_bytes": sum(j["plan"].payload_bytes for j in jobs),
+                   "plans": len(jobs), "payload_bytes": sum(j["plan"].payload_bytes for j in jobs),
                    "sweep_bytes": sweep_bytes, "chunks": sum(j["plan"].num_chunks for j in jobs),
                    "tile_bytes": th.th_config_get(th.TH_CFG_TILE_BYTES),
                    "tile_bytes_any": th.th_config_get(th.TH_CFG_TILE_BYTES_ANY),

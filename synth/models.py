@@ -80,6 +80,19 @@ WORKLOADS = {
     # random wire order, narrowed to bf16 through 16 MiB chunks into a dense arena
     "cfg5_scatter_fp32_to_bf16": dict(kind="scatter", n_tensors=100_000, seed=5, chunk_bytes=16 * MiB),
     "small_scatter": dict(kind="scatter", n_tensors=2_000, seed=15, chunk_bytes=1 * MiB),
+    # whole-model sweeps of the same three models: every reader rank the resident holders can feed
+    # (parts = independent (holders -> reader) groups; holders named twice are resident once)
+    "cfg2_8b_tp1_to_tp4_all_readers": dict(
+        model="dense8b", seed=2, chunk_bytes=64 * MiB,
+        parts=[dict(holders=[layout(1, 0)], reader=layout(4, r, f32_store="bf16")) for r in range(4)]),
+    "cfg3_70b_tp8_to_tp4_two_readers": dict(
+        model="dense70b", seed=3, chunk_bytes=256 * MiB,
+        parts=[dict(holders=[layout(8, 2 * r), layout(8, 2 * r + 1)], reader=layout(4, r, f32_store="bf16"))
+               for r in range(2)]),
+    "cfg4_moe_ep8_to_tp2_all_holders": dict(
+        model="moe", seed=4, chunk_bytes=4 * MiB,
+        holders=[layout(1, 0, ep_size=8, ep_rank=p) for p in range(8)],
+        reader=layout(2, 0, experts_stacked=1, f32_store="bf16")),
     # reduced variants
     "small_dense_tp1_to_tp4": dict(
         model="dense_small", seed=12, chunk_bytes=1 * MiB,
@@ -128,6 +141,10 @@ def workload(name):
     if w["kind"] == "model":
         w["model_name"] = w["model"]
         w["model"] = dict(MODELS[w["model"]])
+        if "parts" not in w:
+            w["parts"] = [dict(holders=w["holders"], reader=w["reader"])]
+        else:  # the first part doubles as the workload's plain (holders, reader) pair
+            w["holders"], w["reader"] = w["parts"][0]["holders"], w["parts"][0]["reader"]
     else:
         w["model_name"] = "scattered fp32 tensors"
     return w

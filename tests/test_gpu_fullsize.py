@@ -32,9 +32,10 @@ def int16_sum(t):
     return total
 
 
-def run_model_fullsize(name, sample_fn):
+def run_model_fullsize(name, sample_fn, part=0, holders=None, sends_everything=True):
     w = synth.workload(name)
-    model, dst = w["model"], w["reader"]
+    model, dst = w["model"], w["parts"][part]["reader"]
+    w["holders"] = [h for i, h in enumerate(w["parts"][part]["holders"]) if holders is None or i in holders]
     lts = layouts.logical_tensors(model)
     stream = dev.current_stream()
     dst_dev = None
@@ -76,7 +77,9 @@ def run_model_fullsize(name, sample_fn):
                 reg["name"], dst_regs[it["dst_id"]]["name"])
             checked += 1
         log("oracle agreed on %d sampled plan items" % checked)
-        assert checked >= len(sample) - 2 * len([t for t in regs if "norm" in t["name"]]) and checked > 0
+        assert checked > 0
+        if sends_everything:
+            assert checked >= len(sample) - 2 * len([t for t in regs if "norm" in t["name"]])
         plan.destroy()
         del src_dev, wire_dev
     return w, dst_dev, dst_regs, wire_sum
@@ -170,6 +173,32 @@ def test_scattered_sweep_full_size():
     g = synth.to_bits(arena_dev)
     assert g[0] == 0x7FA5 and np.all(g[d["arena_elems"] + 1:] == 0x7FA5)
     plan.destroy()
+
+
+def test_8b_last_reader_rank_full_size():
+    w, dst_dev, dst_regs, wire_sum = run_model_fullsize(
+        "cfg2_8b_tp1_to_tp4_all_readers", lambda regs: layer_sample(regs, {1, 30}), part=3)
+    assert sum(int16_sum(t) for t in dst_dev) == wire_sum
+
+
+def test_70b_second_reader_full_size():
+    w, dst_dev, dst_regs, wire_sum = run_model_fullsize(
+        "cfg3_70b_tp8_to_tp4_two_readers", lambda regs: layer_sample(regs, {2, 78}), part=1)
+    assert sum(int16_sum(t) for t in dst_dev) == wire_sum
+
+
+def test_moe_other_holder_full_size():
+    """A holder that is not the reader's primary source sends its eight experts and nothing else."""
+    w, dst_dev, dst_regs, wire_sum = run_model_fullsize(
+        "cfg4_moe_ep8_to_tp2_all_holders", lambda regs: layer_sample(regs, {0, 12, 23}), holders={5}, sends_everything=False)
+    for t, reg in zip(dst_dev, dst_regs):
+        v = t.view(torch.int16)
+        if ".experts.w" in reg["name"]:
+            slabs = v.view(64, -1)
+            assert bool((slabs[:40] == 0x7FA5).all()) and bool((slabs[48:] == 0x7FA5).all()), reg["name"]
+            assert not bool((slabs[40:48] == 0x7FA5).all(dim=1).any())
+        else:
+            assert bool((v == 0x7FA5).all()), reg["name"]
 
 
 def sums_host(t):
