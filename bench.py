@@ -24,12 +24,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # the counter reads for th_reference_copy of known size; summaries under profiles/).  Valid only for
 # the kernel sources they were taken with: bench.py reports null once those files have changed.
 TRAFFIC_SOURCES = ("th_kernels.hip", "th_planner.cpp", "th_internal.hpp")
-TRAFFIC_SHA256 = "448cca52320fc47e0c201457f2016878e24d352de7fca996e80d6a3d605341d3"
+TRAFFIC_SHA256 = "4cce467451ea49a91d5cc6e95918a809557a46d3b2bc925ecb404b0c50559fb9"
 TRAFFIC_BYTES = {
-    "cfg2_8b_tp1_to_tp4": {"th_pack": 8047563341, "th_unpack": 8046999728},
-    "cfg3_70b_tp8_to_tp4": {"th_pack": 35349366699, "th_unpack": 35348044028},
-    "cfg4_moe_ep8_to_tp2": {"th_pack": 5821401099, "th_unpack": 5821162381},
-    "cfg5_scatter_fp32_to_bf16": {"th_pack": 37140380236, "th_unpack": 22673869394},
+    "cfg2_8b_tp1_to_tp4": {"th_pack": 8047564877, "th_unpack": 8047015920},
+    "cfg3_70b_tp8_to_tp4": {"th_pack": 35349370081, "th_unpack": 35348058227},
+    "cfg4_moe_ep8_to_tp2": {"th_pack": 5821402423, "th_unpack": 5821177433},
+    "cfg5_scatter_fp32_to_bf16": {"th_pack": 36774105630, "th_unpack": 22474486549},
 }
 
 
@@ -116,8 +116,10 @@ def build_scatter_inputs(th, dev, synth, w, torch):
     import numpy as np
     d = synth.scatter_description(w["n_tensors"], w["seed"])
     pool = synth.scatter_values(d["pool_elems"] + 3, w["seed"], "cuda")[1:]
-    arena_store = torch.zeros(d["arena_elems"] + 9, dtype=torch.bfloat16, device="cuda")
-    arena = arena_store[1:]
+    # the arena itself starts where the allocator puts it (line-aligned); the slices inside it are only
+    # 2-byte aligned
+    arena_store = torch.zeros(d["arena_elems"] + 8, dtype=torch.bfloat16, device="cuda")
+    arena = arena_store
     n = w["n_tensors"]
     segs = np.zeros(n, dtype=th.binding.SEGMENT_NP)
     segs["src_tensor"], segs["dst_tensor"] = d["seg_src_tensor"], 0

@@ -65,30 +65,52 @@ __device__ __forceinline__ void st8(gdst_t p, uint32_t lo, uint32_t hi) {
     v.x = lo, v.y = hi;
     __builtin_nontemporal_store(v, reinterpret_cast<TH_GLOBAL u32x2*>(p));
 }
-// Stores of the vector-path kernels with one or two vectors per thread: non-temporal at agent scope
-// (written through instead of held in this XCD's L2).  Measured inside this kernel against plain
-// non-temporal stores: +1.5 to 3 % on the 8B-shaped reshard, +1 % on the 70B-shaped one.  Not for
-// the any-alignment paths, whose wavefronts also write parts of cache lines (there it cost 8 %);
-// agent scope alone or system scope cost 9 %.
+// Full-line stores: non-temporal at agent scope (written through instead of held in this XCD's L2).
+// When every store instruction of a wavefront covers whole 128-byte lines this is the fastest store
+// on this memory system (a plain copy gains 2 %, a narrowing copy 2-5 % over plain non-temporal
+// stores); when a wavefront's stores start mid-line, so that two instructions each write part of a
+// line, it is the slowest by far (-18 to -30 %, against -3 % for plain non-temporal stores).  The
+// kernels therefore pick the policy per tile from the destination address (line_aligned below).
 //
-// The compiler has no builtin for a 128-bit store with these bits, so it is one asm instruction,
-// and the compiler does not know that it is a store: the memory system reads a store's data
-// registers some time after the instruction has issued, and the compiler protects only the stores
-// it knows from a later instruction that reuses those registers.  (A checksum computed after such
-// a store, in place over the stored registers, corrupted what arrived in memory.)  Hence the rule
-// for this function: it is called only from the tail of the kernel, after every other instruction
-// that writes a vector register, and the stored values are kept live up to the end of the kernel
-// (hold_live), so that no register of theirs can be handed out again.  tests/test_kernel_tail.py
-// checks this on the compiled code of every kernel instance.
+// The compiler has no builtin for a store with these bits, so it is one asm instruction, and the
+// compiler does not know that it is a store.  What it would do for a store of its own: the data
+// registers of a store of more than 8 bytes must not be written by a vector instruction in the two
+// cycles after the store issues (the hardware still reads them), so the compiler puts `s_nop 1`
+// between such a pair.  (A checksum computed right after an asm store, in place over the stored
+// registers, corrupted what arrived in memory.)  The asm statement carries that wait itself;
+// 8-byte stores have no such window.  tests/test_kernel_tail.py checks the compiled code.
 __device__ __forceinline__ void st16_through(gdst_t p, u32x4 v) {
-    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
 }
-__device__ __forceinline__ void st8_through(gdst_t p, uint32_t lo, uint32_t hi) {  // same rule
+__device__ __forceinline__ void st8_through(gdst_t p, uint32_t lo, uint32_t hi) {
     u32x2 v;
     v.x = lo, v.y = hi;
     asm volatile("global_store_dwordx2 %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ void hold_live(u32x4 v) { asm volatile("" ::"v"(v)); }
+// Store with the policy of the tile: `through` is uniform over the workgroup.
+__device__ __forceinline__ void st16_as(bool through, gdst_t p, u32x4 v) {
+    if (through)
+        st16_through(p, v);
+    else
+        st16(p, v);
+}
+__device__ __forceinline__ void st8_as(bool through, gdst_t p, uint32_t lo, uint32_t hi) {
+    if (through)
+        st8_through(p, lo, hi);
+    else
+        st8(p, lo, hi);
+}
+constexpr uint64_t kLine = 128;  // bytes of a cache line
+// True when consecutive units of a tile land on consecutive bytes that start on a line boundary and
+// stay on line boundaries over row ends: `first` is the address of the tile's first unit, rows hold
+// per_row units of `unit` bytes and lie `stride` bytes apart (per_row = 0xFFFFFFFF: a single row).
+// Then every wavefront's store instruction covers whole lines (64 lanes x 8 or 16 bytes).
+__device__ __forceinline__ bool line_aligned(gdst_t first, uint64_t stride, uint32_t per_row, uint32_t unit) {
+    const uint64_t a = reinterpret_cast<uintptr_t>(first);
+    if (per_row == 0xFFFFFFFFu) return (a & (kLine - 1)) == 0;
+    return ((a | stride | ((uint64_t)per_row * unit)) & (kLine - 1)) == 0;
+}
 
 // What a one- or two-vector tile still has to store when its copy routine returns.
 struct LateStores {
@@ -96,6 +118,7 @@ struct LateStores {
     u32x4 v[2];  // narrow: the 8 bytes to store are v.x, v.y
     bool on[2] = {false, false};
     bool narrow = false;
+    bool through = false;  // store policy of the tile (uniform)
 };
 
 // fp32 bits -> bf16 bits, round to nearest even in integer arithmetic.  No flush of
@@ -227,7 +250,7 @@ __device__ __forceinline__ void wave_sum_store(const Sum& s, uint64_t* out) {
 template <int BT, int SUM, int U>
 __device__ __forceinline__ void copy_vec_pass(gsrc_t src, gdst_t dst, uint64_t ss, uint64_t ds, uint32_t base,
                                               uint32_t count, uint32_t vpr, uint32_t col0, uint32_t magic,
-                                              bool narrow, Sum& acc) {
+                                              bool narrow, bool through, Sum& acc) {
     const uint32_t tid = threadIdx.x;
     const uint32_t du = narrow ? 8u : 16u;  // destination bytes per unit
     u32x4 v[U];
@@ -248,9 +271,9 @@ __device__ __forceinline__ void copy_vec_pass(gsrc_t src, gdst_t dst, uint64_t s
             gdst_t d = dst + (size_t)row[u] * ds + (size_t)col[u] * du;
             if (narrow) {
                 v[u] = convert_slot<4, 2>(v[u]);
-                st8(d, v[u].x, v[u].y);
+                st8_as(through, d, v[u].x, v[u].y);
             } else {
-                st16(d, v[u]);
+                st16_as(through, d, v[u]);
             }
             if (SUM == 1)
                 sum_halves(acc, v[u], 0, narrow ? 4 : 8, (int64_t)(((uint64_t)row[u] * ds + (uint64_t)col[u] * du) / 2));
@@ -267,12 +290,14 @@ template <int BT, int SUM, int VPT>
 __device__ __forceinline__ void copy_vec(gsrc_t src, gdst_t dst, uint64_t ss, uint64_t ds, uint32_t count,
                                          uint32_t vpr, uint32_t col0, uint32_t magic, bool narrow, Sum& acc,
                                          LateStores& late) {
+    const bool through = line_aligned(dst + (size_t)col0 * (narrow ? 8u : 16u), ds, vpr, narrow ? 8u : 16u);
     if (VPT == 1 || VPT == 2) {
         constexpr int N = VPT ? VPT : 1;  // (VPT == 0 never gets here)
         const uint32_t tid = threadIdx.x;
         const uint32_t du = narrow ? 8u : 16u;  // destination bytes per unit
         uint32_t row[N], col[N];
         late.narrow = narrow;
+        late.through = through;
 #pragma unroll
         for (int u = 0; u < N; ++u) {
             const uint32_t i = u * BT + tid;
@@ -293,12 +318,12 @@ __device__ __forceinline__ void copy_vec(gsrc_t src, gdst_t dst, uint64_t ss, ui
                            (int64_t)(((uint64_t)row[u] * ds + (uint64_t)col[u] * du) / 2));
         }
     } else if (count <= BT) {
-        copy_vec_pass<BT, SUM, 1>(src, dst, ss, ds, 0, count, vpr, col0, magic, narrow, acc);
+        copy_vec_pass<BT, SUM, 1>(src, dst, ss, ds, 0, count, vpr, col0, magic, narrow, through, acc);
     } else if (count <= 2 * BT) {
-        copy_vec_pass<BT, SUM, 2>(src, dst, ss, ds, 0, count, vpr, col0, magic, narrow, acc);
+        copy_vec_pass<BT, SUM, 2>(src, dst, ss, ds, 0, count, vpr, col0, magic, narrow, through, acc);
     } else {
         for (uint32_t base = 0; base < count; base += BT * kUnroll)
-            copy_vec_pass<BT, SUM, kUnroll>(src, dst, ss, ds, base, count, vpr, col0, magic, narrow, acc);
+            copy_vec_pass<BT, SUM, kUnroll>(src, dst, ss, ds, base, count, vpr, col0, magic, narrow, through, acc);
     }
 }
 
@@ -460,15 +485,16 @@ __device__ __forceinline__ u32x4 gather_slot(gsrc_t src, uint64_t ss, uint32_t n
 // were fetched: lanes that took different fetch paths must not write their parts of a cache line
 // at different times (that showed up as 1.2x the ideal HBM write traffic).
 // rel: byte offset of the slot's element 0 from the tile's wire base when the wire is the destination.
+// through: store policy of the tile's full slots (uniform over the workgroup).
 template <int DES, int SLOT, int SUM>
-__device__ __forceinline__ void commit_slot(const Slot<DES>& s, int64_t rel, Sum& acc) {
+__device__ __forceinline__ void commit_slot(const Slot<DES>& s, int64_t rel, Sum& acc, bool through = false) {
     constexpr int EPV = SLOT / DES;
     if (SUM == 1) sum_halves(acc, s.o, s.first * DES / 2, s.last * DES / 2, rel / 2);
     if (s.first == 0 && s.last == EPV) {
         if (SLOT == 16)
-            st16(s.d, s.o);
+            st16_as(through, s.d, s.o);
         else
-            st8(s.d, s.o.x, s.o.y);
+            st8_as(through, s.d, s.o.x, s.o.y);
     } else {
         const uint32_t w[4] = {s.o.x, s.o.y, s.o.z, s.o.w};
 #pragma unroll
@@ -513,6 +539,9 @@ __device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, 
     const uint32_t full_end = (lead + limit) / EPV;
     const uint32_t hi = full_end < nslots ? full_end : nslots;
     const uint32_t tid = threadIdx.x;
+    // A tile that starts on a line boundary (the planner cuts a run there when the base pointer is
+    // line-aligned) has slot t at dst + t * SLOT, and a wavefront's 64 slots are whole lines.
+    const bool through = (reinterpret_cast<uintptr_t>(dst) & (kLine - 1)) == 0;
     // element e0 = slot * EPV - lead of the tile -> its row and column in the source rectangle
     auto locate = [&](uint32_t slot, uint32_t skip, uint32_t& row, uint32_t& col) {
         const uint32_t x = col0 + slot * EPV - lead + skip;
@@ -556,7 +585,7 @@ __device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, 
                     s.o = convert_slot<SES, DES>(a);
                     s.d = dst + ((ptrdiff_t)ti * EPV - (ptrdiff_t)lead) * DES;
                     s.first = 0, s.last = EPV;
-                    commit_slot<DES, SLOT, SUM>(s, ((int64_t)ti * EPV - (int64_t)lead) * DES, acc);
+                    commit_slot<DES, SLOT, SUM>(s, ((int64_t)ti * EPV - (int64_t)lead) * DES, acc, through);
                 }
             }
         }
@@ -573,7 +602,7 @@ __device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, 
             }
             s.d = dst + ((ptrdiff_t)t * EPV - (ptrdiff_t)lead) * DES;
             s.first = 0, s.last = EPV;
-            commit_slot<DES, SLOT, SUM>(s, ((int64_t)t * EPV - (int64_t)lead) * DES, acc);
+            commit_slot<DES, SLOT, SUM>(s, ((int64_t)t * EPV - (int64_t)lead) * DES, acc, through);
         }
     }
 
@@ -722,22 +751,19 @@ __global__ __launch_bounds__(VEC ? kBlockThreads : kBlockThreadsAny, TH_MIN_WAVE
     if (CHECKSUM) wave_sum_store(acc, partials + 2 * ((size_t)(threadIdx.x >> 6) * partial_stride + b));
     if (prefetch) asm volatile("" ::"v"(ahead));  // keeps the prefetch load alive; its value is not used
     if (VPT) {
-        // the tile's data stores: the last instructions of the kernel (see st16_through).  The first
-        // hold_live makes every lane's loads land before the branches, so that the one after the
-        // stores needs no wait (which would also wait for the stores to complete).
+        // the tile's data stores come last: every load of the workgroup is issued before any store.
+        // The first hold_live makes every lane's loads land before the branches.
 #pragma unroll
         for (int u = 0; u < (VPT ? VPT : 1); ++u) hold_live(late.v[u]);
 #pragma unroll
         for (int u = 0; u < (VPT ? VPT : 1); ++u) {
             if (late.on[u]) {
                 if (late.narrow)
-                    st8_through(late.p[u], late.v[u].x, late.v[u].y);
+                    st8_as(late.through, late.p[u], late.v[u].x, late.v[u].y);
                 else
-                    st16_through(late.p[u], late.v[u]);
+                    st16_as(late.through, late.p[u], late.v[u]);
             }
         }
-#pragma unroll
-        for (int u = 0; u < (VPT ? VPT : 1); ++u) hold_live(late.v[u]);
     }
 }
 
@@ -794,8 +820,7 @@ __global__ __launch_bounds__(kBlockThreads) void th_reference_copy_kernel(const 
     const uint64_t i = (uint64_t)b * kBlockThreads + threadIdx.x;
     if (i < nvec) {
         const u32x4 v = ld16((gsrc_t)(src + i));
-        st16_through((gdst_t)(dst + i), v);  // last instruction, and the value stays live: see st16_through
-        hold_live(v);
+        st16_as((reinterpret_cast<uintptr_t>(dst) & (kLine - 1)) == 0, (gdst_t)(dst + i), v);
     }
 }
 

@@ -59,7 +59,13 @@ void tile_run(std::vector<Tile>* outs, Side S, Side D, uint64_t nrows, uint64_t 
         // full whatever the row length; a tile may start mid-row and wrap over row ends.
         const uint64_t cap = tile_bytes / 16;  // units per tile: one per thread at the default size
         const uint64_t total = nrows * units;
-        for (uint64_t v0 = 0; v0 < total; v0 += cap) {
+        // When row length and row stride are whole 128-byte lines of the destination, a run that
+        // starts mid-line gets a shorter first tile, so that every later tile starts on a line
+        // (the kernel then stores whole lines per wavefront).
+        const bool lines_repeat = nrows == 1 || ((units * vd) % 128 == 0 && D.stride % 128 == 0);
+        const uint64_t first_short = lines_repeat ? (D.off % 128) / vd : 0;
+        for (uint64_t v0 = 0, n; v0 < total; v0 += n) {
+            n = std::min(v0 ? cap : cap - first_short, total - v0);
             Tile t;
             std::memset(&t, 0, sizeof t);
             const uint64_t row0 = nrows == 1 ? 0 : v0 / units;
@@ -71,7 +77,7 @@ void tile_run(std::vector<Tile>* outs, Side S, Side D, uint64_t nrows, uint64_t 
             t.dst_stride = D.stride;
             t.src_buf = S.buf;
             t.dst_buf = D.buf;
-            t.count = (uint32_t)std::min(cap, total - v0);
+            t.count = (uint32_t)n;
             t.flags = flags;
             if (nrows == 1 || units >= cap || units == 1) {
                 // at most one wrap inside a tile: the kernel compares instead of dividing
@@ -98,10 +104,10 @@ void tile_run(std::vector<Tile>* outs, Side S, Side D, uint64_t nrows, uint64_t 
         const uint64_t cap = tb / D.es;                // elements a tile can hold
         uint64_t pos = D.off;
         while (pos < end) {
-            // The first tile of a run is one slot short so that, with a base pointer that is not
-            // 16-byte aligned, its partial leading slot still leaves it at most tb / 16 slots.
-            const uint64_t room = (pos == D.off && tb > 16) ? tb - 16 : tb;
-            uint64_t stop = std::min(end, pos / 16 * 16 + room);
+            // Tiles end on 128-byte lines of the destination buffer (the first tile of a run is up
+            // to a line short): with a line-aligned base pointer every later tile of the run starts
+            // on a line, its slots need no shifting and each wavefront stores whole lines.
+            uint64_t stop = std::min(end, pos / 128 * 128 + tb);
             // a tile that is not the last of its run writes the 16-byte slot straddling its end
             // whole, so at least 16 more bytes of the run must follow it
             if (end - stop < 16) stop = end;
