@@ -333,6 +333,31 @@ def main():
     torch.cuda.synchronize()
     per_chunk_ms = (time.perf_counter() - t0) / 3 * 1e3
 
+    # per-chunk pipeline recorded once into a HIP graph and replayed (what a reader that serves
+    # version after version out of the same registered tensors would do): pack(c) -> unpack(c)
+    # chains dealt to four parallel branches, so that one chunk's tail overlaps the next one's start
+    cap_stream = torch.cuda.Stream()
+    branches = [torch.cuda.Stream() for _ in range(4)]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=cap_stream):
+        for b in branches:
+            b.wait_stream(cap_stream)
+        for j in jobs:
+            for c in range(j["plan"].num_chunks):
+                b = branches[c % len(branches)].cuda_stream
+                th.th_pack(j["plan"], j["src_ptrs"], j["wptrs"][c:c + 1], c, 1, b)
+                th.th_unpack(j["plan"], j["wptrs"][c:c + 1], c, 1, j["dst_ptrs"], b)
+        for b in branches:
+            cap_stream.wait_stream(b)
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(3):
+        graph.replay()
+    torch.cuda.synchronize()
+    graph_ms = (time.perf_counter() - t0) / 3 * 1e3
+    del graph
+
     # chunk ring: two wire buffers reused round-robin, unpack(c) right after pack(c), so a chunk is
     # read back while it still sits in the memory-side cache (what a co-located pipeline would see)
     ring_ms = None
@@ -402,6 +427,9 @@ def main():
                            "pack_and_unpack_sums_agree": checksums_agree},
         "per_chunk_calls_sweep": {"ms": round(per_chunk_ms, 4), "calls": 2 * sum(j["plan"].num_chunks for j in jobs),
                                   "GB/s": round(sweep_bytes / (per_chunk_ms * 1e-3) / 1e9, 1)},
+        "per_chunk_graph_sweep": {"ms": round(graph_ms, 4), "kernel_nodes": 2 * sum(j["plan"].num_chunks for j in jobs),
+                                  "branches": 4,
+                                  "GB/s": round(sweep_bytes / (graph_ms * 1e-3) / 1e9, 1)},
         "chunk_ring_sweep": None if ring_ms is None else {
             "ms": round(ring_ms, 4), "ring_chunks": 2, "GB/s": round(sweep_bytes / (ring_ms * 1e-3) / 1e9, 1)},
         "th_reshard_direct": {"ms": round(direct_ms, 4), "GB/s": round(direct_bytes / (direct_ms * 1e-3) / 1e9, 1)},

@@ -183,8 +183,17 @@ int th_plan_create_from_segments(const th_segment* segs, size_t n,
  * 32nd such call synchronises the device to free replaced tables; a call with
  * tables seen before, or with at most 8 chunks and known tensor pointers, only
  * launches).
- * Errors (synchronous): TH_ERR_ARG, TH_ERR_RANGE, TH_ERR_HIP.  Device-side
- * faults surface at the caller's next synchronisation. */
+ * Graph capture: th_pack, th_unpack, their checksum variants, th_reshard and
+ * th_signal may be called on a stream that is being captured (a per-chunk
+ * pipeline replayed version after version, as tensors are registered once,
+ * Sec. 4.2).  Such a call only records kernel launches.  It needs its pointer
+ * tables on the device already: make the same call (same tensor pointers, and
+ * for more than 8 chunks the same wire pointers and range) once outside capture
+ * first, else it fails with TH_ERR_UNSUPPORTED and records nothing.  Tables used
+ * under capture stay on the device until th_plan_destroy, which must come after
+ * the last replay.
+ * Errors (synchronous): TH_ERR_ARG, TH_ERR_RANGE, TH_ERR_HIP, TH_ERR_UNSUPPORTED.
+ * Device-side faults surface at the caller's next synchronisation. */
 int th_pack(const th_plan* plan, const void* const* src_ptrs, uint32_t n_src,
             void* const* wire_ptrs, uint32_t chunk_first, uint32_t chunk_count, void* hip_stream);
 

@@ -42,6 +42,7 @@ struct PtrSlot {
     void** dev = nullptr;
     size_t cap = 0;  // entries allocated on the device
     uint64_t stamp = 0;
+    bool pinned = false;  // a captured graph refers to the device table: kept until the plan dies
 };
 
 // Small cache of uploaded pointer tables: callers usually pass the same registered
@@ -50,6 +51,11 @@ struct PtrSlot {
 // the kernel launch.  A device table is never overwritten: a kernel that was handed it may
 // still be running.  When a slot gets a new key, its old device table is retired and freed
 // later, after a device synchronisation (once per kRetireBatch retirements) or with the plan.
+//
+// Stream capture: a call on a capturing stream may not allocate or copy, so its tables must already
+// be in the cache (the caller makes the same call once outside capture); the slots it uses are
+// pinned, because the captured kernels keep the device tables' addresses for as long as the graph
+// is replayed.
 struct PtrCache {
     static constexpr size_t kSlots = 8;
     static constexpr size_t kRetireBatch = 32;
@@ -68,17 +74,30 @@ struct PtrCache {
     }
 
     // Returns the slot holding exactly key[0..n) (uploading it if new), or nullptr on error.
-    PtrSlot* get(const uintptr_t* key, size_t n, bool& fresh) {
+    // capturing: the call's stream is being captured into a graph.
+    PtrSlot* get(const uintptr_t* key, size_t n, bool capturing, bool& fresh, int& rc) {
         fresh = false;
-        if (PtrSlot* hit = find(key, n)) return hit;
-        PtrSlot* s;
-        if (slots.size() < kSlots) {
+        rc = TH_ERR_HIP;  // what a nullptr means unless said otherwise below
+        if (PtrSlot* hit = find(key, n)) {
+            hit->pinned |= capturing;
+            return hit;
+        }
+        if (capturing) {
+            set_error("the stream is being captured and this call's pointer tables are not on the device yet: "
+                      "make the same call once outside capture");
+            rc = TH_ERR_UNSUPPORTED;
+            return nullptr;
+        }
+        PtrSlot* s = nullptr;
+        size_t unpinned = 0;
+        for (PtrSlot& c : slots) {
+            if (c.pinned) continue;
+            ++unpinned;
+            if (!s || c.stamp < s->stamp) s = &c;
+        }
+        if (unpinned < kSlots) {  // pinned slots do not count against the cache size
             slots.emplace_back();
             s = &slots.back();
-        } else {
-            s = &slots[0];
-            for (PtrSlot& c : slots)
-                if (c.stamp < s->stamp) s = &c;
         }
         s->host.clear();
         if (s->dev) {
@@ -191,6 +210,15 @@ int finish_plan(th_plan* p, size_t chunk_bytes, unsigned flags, bool aligned16, 
     return TH_OK;
 }
 
+// Whether work enqueued on `stream` is being recorded into a graph instead of run.
+int stream_capturing(void* stream, bool& capturing) {
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    const hipError_t e = hipStreamIsCapturing(static_cast<hipStream_t>(stream), &st);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamIsCapturing");
+    capturing = st != hipStreamCaptureStatusNone;
+    return TH_OK;
+}
+
 // A plan's tables live on the device that was current when it was created.
 int check_device(const th_plan* p) {
     int dev = -1;
@@ -205,14 +233,15 @@ int check_device(const th_plan* p) {
 
 // Looks up / uploads the device table of the tensor base pointers of one side (0 = source tensors,
 // 1 = destination tensors) and validates a table that was not seen before.  Caller holds p->mu.
-int tensor_table(const th_plan* p, int side, const void* const* ptrs, uint32_t n, PtrSlot** out) {
+int tensor_table(const th_plan* p, int side, const void* const* ptrs, uint32_t n, bool capturing, PtrSlot** out) {
     const Manifest& m = p->m;
     static_assert(sizeof(uintptr_t) == sizeof(void*), "pointer tables are compared as integers");
     const uintptr_t* key = reinterpret_cast<const uintptr_t*>(ptrs);
     bool fresh = false;
-    PtrSlot* ts = p->tensor_cache[side].get(key, n, fresh);
+    int rc = TH_OK;
+    PtrSlot* ts = p->tensor_cache[side].get(key, n, capturing, fresh, rc);
     *out = ts;
-    if (!ts) return TH_ERR_HIP;
+    if (!ts) return rc;
     if (!fresh) return TH_OK;
     for (uint32_t i = 0; i < n; ++i) {
         const TensorInfo& t = m.tensors[side][i];
@@ -276,9 +305,11 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
             return TH_ERR_ARG;
         }
     }
+    bool capturing = false;
+    if (int rc = stream_capturing(stream, capturing)) return rc;
     std::lock_guard<std::mutex> lk(p->mu);
     PtrSlot* ts = nullptr;
-    if (int rc = tensor_table(p, side, tensor_ptrs, n_tensors, &ts)) return rc;
+    if (int rc = tensor_table(p, side, tensor_ptrs, n_tensors, capturing, &ts)) return rc;
     // Short chunk ranges carry their wire pointers in the kernel arguments; longer ones use a
     // cached device table whose entry 0 is skipped by the kernel's indexing.
     InlineWire inl;
@@ -293,8 +324,9 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
         wkey[0] = chunk_first;
         for (uint32_t i = 0; i < chunk_count; ++i) wkey[i + 1] = reinterpret_cast<uintptr_t>(wire_ptrs[i]);
         bool fresh = false;
-        ws = p->wire_cache[side].get(wkey.data(), wkey.size(), fresh);
-        if (!ws) return TH_ERR_HIP;
+        int wrc = TH_OK;
+        ws = p->wire_cache[side].get(wkey.data(), wkey.size(), capturing, fresh, wrc);
+        if (!ws) return wrc;
         wire_tab = reinterpret_cast<const void* const*>(ws->dev + 1);
     }
     const void* const* tens_tab = reinterpret_cast<const void* const*>(ts->dev);
@@ -427,10 +459,12 @@ int th_reshard(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, vo
         return TH_ERR_ARG;
     }
     if (int rc = check_device(p)) return rc;
+    bool capturing = false;
+    if (int rc = stream_capturing(hip_stream, capturing)) return rc;
     std::lock_guard<std::mutex> lk(p->mu);
     PtrSlot *ss = nullptr, *ds = nullptr;
-    if (int rc = tensor_table(p, 0, src_ptrs, n_src, &ss)) return rc;
-    if (int rc = tensor_table(p, 1, const_cast<const void* const*>(dst_ptrs), n_dst, &ds)) return rc;
+    if (int rc = tensor_table(p, 0, src_ptrs, n_src, capturing, &ss)) return rc;
+    if (int rc = tensor_table(p, 1, const_cast<const void* const*>(dst_ptrs), n_dst, capturing, &ds)) return rc;
     const void* const* stab = reinterpret_cast<const void* const*>(ss->dev);
     void* const* dtab = reinterpret_cast<void* const*>(ds->dev);
     InlineWire no_inline;

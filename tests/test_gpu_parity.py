@@ -555,3 +555,63 @@ def test_progress_counter_in_pinned_host_memory():
     with pytest.raises(th.ThError):
         th.th_signal(counter.data_ptr() + 4, 1, stream)
     plan.destroy()
+
+
+def test_per_chunk_calls_captured_in_a_graph_and_replayed():
+    """A per-chunk pack / unpack pipeline recorded once into a HIP graph and replayed for new weight
+    versions in the same registered tensors.  Every replay is checked against the oracle, with eager
+    work and synchronisation in between; the graph's pointer tables survive more new tables than the
+    plan's cache holds; a call whose tables are not on the device yet is refused under capture."""
+    w = synth.workload("small_dense_tp1_to_tp4")
+    model, src, dst = w["model"], w["holders"][0], w["reader"]
+    plan = th.th_plan_create(model, src, dst, 64 * 1024)
+    n = plan.num_chunks
+    assert n > 16
+    tensors = holder_tensors_cpu(model, src, 300)
+    src_dev = [to_dev(t) for t in tensors]
+    dst_dev = dev.alloc_tensors(plan, 1, fill_bits=SENT16)
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=SENT8)
+    sp, dp = dev.ptrs(src_dev), dev.ptrs(dst_dev)
+    s = torch.cuda.Stream()
+
+    def pipeline():
+        for c in range(0, n, 3):  # one to three chunks per call: wire pointers travel in the kernel arguments
+            k = min(3, n - c)
+            th.th_pack(plan, sp, wptrs[c:c + k], c, k, s.cuda_stream)
+            th.th_unpack(plan, wptrs[c:c + k], c, k, dp, s.cuda_stream)
+
+    other = [to_dev(t) for t in tensors]
+    pipeline()  # eager once: uploads the tensor pointer tables
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        with pytest.raises(th.ThError) as e:  # tables never seen: refused, nothing recorded
+            th.th_pack(plan, dev.ptrs(other), wptrs[:1], 0, 1, s.cuda_stream)
+        pipeline()
+    assert e.value.code == -3 and "outside capture" in str(e.value)
+    for rep in range(4):
+        tensors = holder_tensors_cpu(model, src, 400 + rep)
+        for d_, t in zip(src_dev, tensors):
+            d_.copy_(to_dev(t))
+        for t in dst_dev:
+            t.view(torch.int16).fill_(0x25C3)
+        wire_dev.fill_(SENT8)
+        # eager calls with ten other tensor tables: more than the cache keeps
+        for k in range(10):
+            shifted = [to_dev(t) for t in tensors[:2]] + other[2:]
+            th.th_pack(plan, dev.ptrs(shifted), wptrs[:1], 0, 1, dev.current_stream())
+            torch.cuda.synchronize()
+        wire_dev.fill_(SENT8)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        wire = reshard.pack(model, src, dst, tensors)
+        want = reshard.empty_tensors(model, dst, fill=0x25C3)
+        for t, wnt in zip(layouts.registered_tensors(model, dst), want):
+            if t["dtype"] == "f32":
+                wnt[...] = 0x25C3 * 0x10001
+        reshard.unpack(model, src, dst, wire, want)
+        assert np.array_equal(wire_dev.cpu().numpy()[:plan.wire_bytes], wire), "replay %d" % rep
+        assert_same([synth.to_bits(t) for t in dst_dev], [x.reshape(-1) for x in want])
+    del g
+    plan.destroy()

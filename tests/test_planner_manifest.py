@@ -403,3 +403,37 @@ def test_full_size_plans_cover_every_destination_element_once():
         if name.startswith("cfg2"):
             assert covered == sum(t["rows"] * t["cols"] * reshard.ESIZE[t["dtype"]] for t in dst_regs)
         plan.destroy()
+
+
+@pytest.mark.parametrize("flags", [0, th.TH_FLAG_PTRS_ALIGNED16])
+def test_tiles_of_a_contiguous_destination_start_on_cache_lines(flags):
+    """Within a run whose destination is contiguous, every tile after the first starts on a 128-byte
+    line of the destination buffer (dense path always; vector path when rows are whole lines)."""
+    rng = np.random.default_rng(77)
+    n = 40
+    q = 8 if flags else 1                           # elements per 16 bytes in the aligned regime
+    segs = np.zeros(n, dtype=th.binding.SEGMENT_NP)
+    src_len, fill = [], 0
+    for k in range(n):
+        ln = int(rng.integers(3000, 40000)) // q * q
+        segs[k]["src_tensor"], segs[k]["dst_tensor"] = k, 0
+        segs[k]["src_elem_off"], segs[k]["src_row_stride"] = int(rng.integers(0, 9)) * q, ln
+        segs[k]["dst_elem_off"], segs[k]["dst_row_stride"] = fill, ln
+        segs[k]["nrows"], segs[k]["row_len"] = 1, ln
+        segs[k]["src_dtype"] = segs[k]["dst_dtype"] = th.TH_BF16
+        src_len.append(ln + 64)
+        fill += ln + int(rng.integers(0, 7)) * q    # runs start at any element (or any 16 bytes)
+    plan = th.th_plan_create_from_segments(segs, src_len, [fill + 8], 1 << 20, flags | HOST)
+    for side in (0, 1):
+        later = 0
+        prev = None
+        for i in range(plan.num_tiles(side)):
+            t = plan.tile(side, i)
+            assert t.kind == (0 if flags else 2)
+            key = (t.src_tensor, t.src_buf, t.dst_buf)
+            if key == prev:                          # a later tile of the same run (and chunk)
+                assert t.dst_byte_off % 128 == 0, (side, i, t.dst_byte_off)
+                later += 1
+            prev = key
+        assert later > 50
+    plan.destroy()
