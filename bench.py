@@ -24,12 +24,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # the counter reads for th_reference_copy of known size; summaries under profiles/).  Valid only for
 # the kernel sources they were taken with: bench.py reports null once those files have changed.
 TRAFFIC_SOURCES = ("th_kernels.hip", "th_planner.cpp", "th_internal.hpp")
-TRAFFIC_SHA256 = "4cce467451ea49a91d5cc6e95918a809557a46d3b2bc925ecb404b0c50559fb9"
+TRAFFIC_SHA256 = "25bd1dc8df8dd9b6f60d55b9d9ce3d1618f893777f456fe1c55e65e7ee6c3e9b"
 TRAFFIC_BYTES = {
-    "cfg2_8b_tp1_to_tp4": {"th_pack": 8047564877, "th_unpack": 8047015920},
-    "cfg3_70b_tp8_to_tp4": {"th_pack": 35349370081, "th_unpack": 35348058227},
-    "cfg4_moe_ep8_to_tp2": {"th_pack": 5821402423, "th_unpack": 5821177433},
-    "cfg5_scatter_fp32_to_bf16": {"th_pack": 36774105630, "th_unpack": 22474486549},
+    "cfg2_8b_tp1_to_tp4": {"th_pack": 8047565421, "th_unpack": 8047016336},
+    "cfg3_70b_tp8_to_tp4": {"th_pack": 35349369921, "th_unpack": 35348059507},
+    "cfg4_moe_ep8_to_tp2": {"th_pack": 5821401067, "th_unpack": 5821178477},
+    "cfg5_scatter_fp32_to_bf16": {"th_pack": 36870270435, "th_unpack": 22474610776},
 }
 
 
