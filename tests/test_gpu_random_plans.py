@@ -72,7 +72,7 @@ def device_tensor(bits, shift_elems):
     return store, store.data_ptr() + shift_elems * bits.dtype.itemsize
 
 
-@pytest.mark.parametrize("seed", range(160))
+@pytest.mark.parametrize("seed", range(400))
 def test_random_segment_plan(seed):
     rng = np.random.default_rng(9000 + seed)
     p = draw_plan(rng)
