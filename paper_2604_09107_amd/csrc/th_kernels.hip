@@ -77,7 +77,7 @@ __device__ __forceinline__ void st8(gdst_t p, uint32_t lo, uint32_t hi) {
 // cycles after the store issues (the hardware still reads them), so the compiler puts `s_nop 1`
 // between such a pair.  (A checksum computed right after an asm store, in place over the stored
 // registers, corrupted what arrived in memory.)  The asm statement carries that wait itself;
-// 8-byte stores have no such window.  tests/test_kernel_tail.py checks the compiled code.
+// 8-byte stores have no such window.  tests/test_asm_stores.py checks the compiled code.
 __device__ __forceinline__ void st16_through(gdst_t p, u32x4 v) {
     asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
 }
