@@ -179,6 +179,8 @@ def main():
     ap.add_argument("--no-specialize", action="store_true", help="always launch the all-paths kernel")
     ap.add_argument("--tile-bytes-any", type=int, default=0, help="override the any-alignment tile size")
     ap.add_argument("--tile-bytes-narrow", type=int, default=0, help="override the tile size of narrowing copies")
+    ap.add_argument("--tile-bytes-checksum", type=int, default=0,
+                    help="override the vector-path tile size of checksum plans")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the reshard path has no cross-GPU step (every holder/reader pair is an "
@@ -201,6 +203,8 @@ def main():
         th.th_config_set(th.TH_CFG_TILE_BYTES_ANY, args.tile_bytes_any)
     if args.tile_bytes_narrow:
         th.th_config_set(th.TH_CFG_TILE_BYTES_NARROW, args.tile_bytes_narrow)
+    if args.tile_bytes_checksum:
+        th.th_config_set(th.TH_CFG_TILE_BYTES_CHECKSUM, args.tile_bytes_checksum)
     # one throw-away plan first: the process's first HIP call loads the library's code object
     # (~0.1 s, once per process), which is not part of creating a plan
     w0 = synth.workload("cfg1_tiny_tp2_to_tp1")
