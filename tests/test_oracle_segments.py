@@ -89,3 +89,98 @@ def test_mixed_dtypes_and_same_tensor_runs_share_alignment():
     segments.unpack(segs, wire, dsts, dts_d)
     assert list(dsts[0]) == [101, 102, 103, 106, 107, 108, 111, 112, 113, 120, 121, 122]
     assert list(dsts[1][2:5] - 0x3F800000) == [0, 1, 2] and list(dsts[1][6:9] - 0x3F800000) == [3, 4, 5]
+
+
+# ---- narrowing at unpack: the wire carries the holder's dtype ------------------------------------
+
+def mixed_case():
+    """Five segments over three source tensors, two dtypes, strided on both sides."""
+    segs = dict(src_tensor=np.array([0, 0, 1, 2, 2]), dst_tensor=np.array([0, 0, 1, 0, 0]),
+                src_off=np.array([2, 31, 1, 0, 40]), src_stride=np.array([7, 5, 6, 9, 11]),
+                dst_off=np.array([0, 12, 3, 30, 60]), dst_stride=np.array([4, 5, 4, 7, 3]),
+                nrows=np.array([3, 2, 2, 4, 1]), row_len=np.array([3, 5, 3, 5, 3]))
+    rng = np.random.default_rng(11)
+    f32 = lambda n: rng.integers(0, 1 << 32, n, dtype=np.uint64).astype(np.uint32)
+    srcs = [f32(60), np.arange(20, dtype=np.uint16) + 0x4000, f32(64)]
+    # the rounding cases that matter, planted where segments read them
+    srcs[0][2:5] = [0x3F808000, 0x3F818000, 0x7F800001]       # tie to even (down / up), signalling NaN
+    srcs[2][0:3] = [0x7F7F8000, 0x00008001, 0xFFC12345]       # overflow to Inf, subnormal, negative NaN
+    dts_s = ["f32", "f32", "bf16", "f32", "f32"]
+    dts_d = ["bf16", "bf16", "bf16", "bf16", "bf16"]
+    return segs, srcs, dts_s, dts_d
+
+
+def test_wire_offsets_follow_the_wire_dtype():
+    """Segment sizes on the wire are counted in the dtype the wire carries: with narrowing at unpack
+    that is the source's, so fp32 segments take 4 bytes per element; a new source tensor re-aligns."""
+    segs, srcs, dts_s, dts_d = mixed_case()
+    offs_p, total_p = segments.wire_offsets(segs, dts_d)
+    offs_u, total_u = segments.wire_offsets(segs, dts_s)
+    # by hand: element counts 9, 10 | 6 | 20, 3
+    assert list(offs_p) == [0, 18, 48, 64, 104] and total_p == 110
+    assert list(offs_u) == [0, 36, 80, 96, 176] and total_u == 188
+    # the stream is 2 bytes longer per narrowed element, up to the alignment gaps
+    narrowed = 9 + 10 + 20 + 3
+    gaps_p = (48 - 38) + (64 - 60)
+    gaps_u = (80 - 76) + (96 - 92)
+    assert (total_u - gaps_u) - (total_p - gaps_p) == 2 * narrowed
+
+
+def test_pack_narrowing_at_unpack_matches_python_loops():
+    segs, srcs, dts_s, dts_d = mixed_case()
+    wire = segments.pack(segs, srcs, dts_s, dts_d, narrow_at="unpack")
+    expect = bytearray()
+    prev = None
+    for k in range(len(segs["nrows"])):
+        t = int(segs["src_tensor"][k])
+        if t != prev:
+            expect += b"\0" * (-len(expect) % 16)
+            prev = t
+        es = 4 if dts_s[k] == "f32" else 2
+        for r in range(int(segs["nrows"][k])):
+            for c in range(int(segs["row_len"][k])):
+                u = int(srcs[t][int(segs["src_off"][k]) + r * int(segs["src_stride"][k]) + c])
+                expect += u.to_bytes(es, "little")      # source bits, unconverted
+    assert wire.tobytes() == bytes(expect)
+    assert len(wire) == segments.wire_offsets(segs, dts_s)[1]
+
+
+def test_unpack_of_a_source_dtype_wire_gives_the_same_reader_bits():
+    """Narrowing at unpack lands the same bits in the same places as narrowing at pack, element by
+    element: destination[d_off + r * d_stride + c] = narrow(source[s_off + r * s_stride + c])."""
+    segs, srcs, dts_s, dts_d = mixed_case()
+    sentinel = 0xABCD
+    by_pack = [np.full(80, sentinel, dtype=np.uint16), np.full(16, sentinel, dtype=np.uint16)]
+    by_unpack = [a.copy() for a in by_pack]
+    counts = [np.zeros(80, dtype=np.int32), np.zeros(16, dtype=np.int32)]
+    segments.unpack(segs, segments.pack(segs, srcs, dts_s, dts_d), by_pack, dts_d)
+    segments.unpack(segs, segments.pack(segs, srcs, dts_s, dts_d, narrow_at="unpack"), by_unpack, dts_d,
+                    counts=counts, wire_dtype=dts_s)
+    loops = [np.full(80, sentinel, dtype=np.uint16), np.full(16, sentinel, dtype=np.uint16)]
+    for k in range(len(segs["nrows"])):
+        for r in range(int(segs["nrows"][k])):
+            for c in range(int(segs["row_len"][k])):
+                u = srcs[int(segs["src_tensor"][k])][int(segs["src_off"][k]) + r * int(segs["src_stride"][k]) + c]
+                v = rne.narrow(np.array([u], dtype=np.uint32))[0] if dts_s[k] == "f32" else u
+                loops[int(segs["dst_tensor"][k])][int(segs["dst_off"][k]) + r * int(segs["dst_stride"][k]) + c] = v
+    for a, b, c in zip(by_pack, by_unpack, loops):
+        assert np.array_equal(a, c) and np.array_equal(b, c)
+    assert all(cnt.max() == 1 for cnt in counts)            # every covered element written once
+    assert (loops[0] == sentinel).sum() == 80 - (9 + 10 + 20 + 3)
+    # the planted rounding cases arrived as the narrowing rule says
+    assert list(loops[0][0:3]) == [0x3F80, 0x3F82, 0x7FC0]
+    assert list(loops[0][30:33]) == [0x7F80, 0x0001, 0xFFC1]
+
+
+def test_scattered_case_narrowing_at_unpack_round_trip():
+    d, segs, srcs = small_case()
+    wire = segments.pack(segs, srcs, "f32", "bf16", narrow_at="unpack")
+    offs, total = segments.wire_offsets(segs, "f32")
+    assert total == len(wire) and np.all(offs % 16 == 0)    # one segment per tensor: every one re-aligns
+    n_el = int((d["seg_nrows"] * d["seg_row_len"]).sum())
+    assert total - 4 * n_el == sum(-4 * int(a) * int(b) % 16 for a, b in zip(d["seg_nrows"][:-1], d["seg_row_len"][:-1]))
+    arena = np.full(d["arena_elems"] + 8, 0xABCD, dtype=np.uint16)
+    segments.unpack(segs, wire, [arena], "bf16", wire_dtype="f32")
+    ref = np.full(d["arena_elems"] + 8, 0xABCD, dtype=np.uint16)
+    segments.unpack(segs, segments.pack(segs, srcs, "f32", "bf16"), [ref], "bf16")
+    assert np.array_equal(arena, ref)
