@@ -239,6 +239,22 @@ int th_unpack_checksum(const th_plan* plan, const void* const* wire_ptrs, uint32
 int th_signal(uint64_t* flag, uint64_t value, void* hip_stream);
 uint32_t th_plan_tensors_complete(const th_plan* plan, uint32_t n_chunks_done);
 
+/* th_pack for callers that cannot allocate device memory: code whose stream is
+ * being captured into a HIP graph, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same result and same errors as th_pack, but the call
+ * allocates nothing (no device memory, no pinned memory, no host heap) and keeps
+ * nothing between calls: the two device pointer tables of the launch live in a
+ * fixed array inside the library (64 KiB per GPU, held until the process ends)
+ * and are filled on hip_stream, through kernel arguments, before the copy kernel
+ * runs.  Limits: at most 4096 source tensors in the plan and 4096 chunks per
+ * call, else TH_ERR_RANGE.  Every pointer is checked on every call.  All calls
+ * on one GPU share that array: calls on the same stream are ordered by it; calls
+ * that may overlap in time on one GPU (different streams, different threads)
+ * race and must be serialised by the caller.  On a capturing stream the call
+ * records its kernels without any earlier call outside capture. */
+int th_pack_noalloc(const th_plan* plan, const void* const* src_ptrs, uint32_t n_src,
+                    void* const* wire_ptrs, uint32_t chunk_first, uint32_t chunk_count, void* hip_stream);
+
 /* Co-located holder and reader (trainer and rollout time-sharing one GPU, Sec.
  * 2.1): move what the reader needs straight from the holder's registered tensors
  * into the reader's, with the same narrowing, without a wire in between - half

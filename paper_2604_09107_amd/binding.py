@@ -108,6 +108,7 @@ _plan_create = _sig("th_plan_create", C.c_int, C.POINTER(_ModelDesc), C.POINTER(
 _plan_create_seg = _sig("th_plan_create_from_segments", C.c_int, _P, C.c_size_t, _P, C.c_uint32, _P, C.c_uint32,
                         C.c_size_t, C.c_uint, C.POINTER(_P))
 _pack = _sig("th_pack", C.c_int, _P, _P, C.c_uint32, _P, C.c_uint32, C.c_uint32, _P)
+_pack_noalloc = _sig("th_pack_noalloc", C.c_int, _P, _P, C.c_uint32, _P, C.c_uint32, C.c_uint32, _P)
 _unpack = _sig("th_unpack", C.c_int, _P, _P, C.c_uint32, C.c_uint32, _P, C.c_uint32, _P)
 _pack_sum = _sig("th_pack_checksum", C.c_int, _P, _P, C.c_uint32, _P, C.c_uint32, C.c_uint32, _P, _P)
 _unpack_sum = _sig("th_unpack_checksum", C.c_int, _P, _P, C.c_uint32, C.c_uint32, _P, C.c_uint32, _P, _P)
@@ -250,6 +251,14 @@ def th_pack(plan, src_ptrs, wire_ptrs, chunk_first, chunk_count, stream=0):
     if len(w) != chunk_count:
         raise ValueError("need one wire pointer per chunk in the range")
     _check(_pack(plan.handle, s.ctypes.data, len(s), w.ctypes.data, chunk_first, chunk_count, stream))
+
+
+def th_pack_noalloc(plan, src_ptrs, wire_ptrs, chunk_first, chunk_count, stream=0):
+    """th_pack with its device pointer tables in a fixed array inside the library (allocates nothing)."""
+    s, w = _ptr_array(src_ptrs), _ptr_array(wire_ptrs)
+    if len(w) != chunk_count:
+        raise ValueError("need one wire pointer per chunk in the range")
+    _check(_pack_noalloc(plan.handle, s.ctypes.data, len(s), w.ctypes.data, chunk_first, chunk_count, stream))
 
 
 def th_unpack(plan, wire_ptrs, chunk_first, chunk_count, dst_ptrs, stream=0):

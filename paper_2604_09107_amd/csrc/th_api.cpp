@@ -436,6 +436,84 @@ int th_unpack(const th_plan* plan, const void* const* wire_ptrs, uint32_t chunk_
                     chunk_count, nullptr, false, hip_stream);
 }
 
+int th_pack_noalloc(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, void* const* wire_ptrs,
+                    uint32_t chunk_first, uint32_t chunk_count, void* hip_stream) {
+    if (!p) {
+        set_error("plan is NULL");
+        return TH_ERR_ARG;
+    }
+    if (p->host_only) {
+        set_error("plan was created with TH_FLAG_HOST_ONLY");
+        return TH_ERR_ARG;
+    }
+    const Manifest& m = p->m;
+    if (n_src != m.tensors[0].size()) {
+        set_error("%u tensor pointers given, plan has %zu source tensors", n_src, m.tensors[0].size());
+        return TH_ERR_ARG;
+    }
+    if ((uint64_t)chunk_first + chunk_count > m.n_chunks) {
+        set_error("chunk range [%u, %u+%u) outside the plan's %u chunks", chunk_first, chunk_first, chunk_count,
+                  m.n_chunks);
+        return TH_ERR_RANGE;
+    }
+    if (n_src > kStaticTensors || chunk_count > kStaticChunks) {
+        set_error("th_pack_noalloc takes at most %u source tensors and %u chunks per call (got %u and %u)",
+                  kStaticTensors, kStaticChunks, n_src, chunk_count);
+        return TH_ERR_RANGE;
+    }
+    if (chunk_count == 0) return TH_OK;
+    if (!wire_ptrs || (n_src && !src_ptrs)) {
+        set_error("null pointer array");
+        return TH_ERR_ARG;
+    }
+    uint64_t tile0[2], ntiles[2];
+    for (int k = 0; k < 2; ++k) {
+        tile0[k] = m.chunk_tile0[0][k][chunk_first];
+        ntiles[k] = m.chunk_tile0[0][k][chunk_first + chunk_count] - tile0[k];
+    }
+    if (ntiles[0] + ntiles[1] == 0) return TH_OK;
+    if (int rc = check_device(p)) return rc;
+    // nothing is cached here, so every call checks every pointer
+    for (uint32_t i = 0; i < chunk_count; ++i) {
+        const uintptr_t a = reinterpret_cast<uintptr_t>(wire_ptrs[i]);
+        if (a == 0 || a % 16) {
+            set_error("wire pointer %u is NULL or not 16-byte aligned", i);
+            return TH_ERR_ARG;
+        }
+    }
+    for (uint32_t i = 0; i < n_src; ++i) {
+        const TensorInfo& t = m.tensors[0][i];
+        if (!t.used) continue;
+        const uintptr_t a = reinterpret_cast<uintptr_t>(src_ptrs[i]);
+        const uintptr_t need = t.need16 ? 16 : esize(t.dtype);
+        if (a == 0 || a % need) {
+            set_error("source tensor %u (%s): pointer %p is %s", i, t.name.c_str(), (void*)a, a ? "misaligned" : "NULL");
+            return TH_ERR_ARG;
+        }
+    }
+    InlineWire inl;
+    std::memset(&inl, 0, sizeof inl);
+    uint32_t n_wire_table = chunk_count;
+    if (chunk_count <= kInlineChunks) {  // short ranges carry their wire pointers in the kernel arguments
+        inl.n = chunk_count;
+        for (uint32_t i = 0; i < chunk_count; ++i) inl.p[i] = wire_ptrs[i];
+        n_wire_table = 0;
+    }
+    const void* const* tens_tab = nullptr;
+    const void* const* wire_tab = nullptr;
+    if (int rc = stage_static_tables(src_ptrs, n_src, const_cast<const void* const*>(wire_ptrs), n_wire_table,
+                                     hip_stream, &tens_tab, &wire_tab))
+        return rc;
+    int rc = TH_OK;
+    for (int k = 0; k < 2 && rc == TH_OK; ++k) {
+        if (!ntiles[k]) continue;
+        const int instance = (k == 0 && p->specialize) ? p->vec_instance : (int)VEC_ALL_PATHS;
+        rc = launch_tiles(MODE_PACK, instance, p->d_tiles[0], tile0[k], ntiles[k], tens_tab,
+                          const_cast<void* const*>(wire_tab), chunk_first, inl, nullptr, m.tiles[0].size(), hip_stream);
+    }
+    return rc;
+}
+
 int th_reshard(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, void* const* dst_ptrs,
                uint32_t n_dst, void* hip_stream) {
     if (!p) {

@@ -163,6 +163,14 @@ int launch_checksum_finalize(const Tile* tiles, const uint64_t* partials, const 
                              uint64_t tile0, uint64_t ntiles, uint64_t list_tiles, bool vec_only, uint64_t* sums,
                              void* stream);
 
+// Allocation-free variant of the pointer tables: copies the pointers, through kernel arguments, into
+// a fixed per-device array inside the library (kStaticTensors + kStaticChunks entries) on `stream`
+// and returns the device addresses of the two tables.  Every call on a device shares that array.
+constexpr uint32_t kStaticTensors = 4096, kStaticChunks = 4096;
+int stage_static_tables(const void* const* tensor_ptrs, uint32_t n_tensors, const void* const* wire_ptrs,
+                        uint32_t n_wire, void* stream, const void* const** tensor_table,
+                        const void* const** wire_table);
+
 int launch_reference_copy(void* dst, const void* src, uint64_t nbytes, void* stream);
 int launch_signal(uint64_t* flag, uint64_t value, void* stream);
 

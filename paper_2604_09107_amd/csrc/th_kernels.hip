@@ -827,6 +827,26 @@ __global__ __launch_bounds__(kBlockThreads) void th_reference_copy_kernel(const 
     }
 }
 
+// ---- pointer tables without allocation ----------------------------------------------------------
+//
+// For callers that cannot allocate: the two device pointer tables of a pack launch (tensor base
+// pointers, wire chunk pointers) live in this fixed array instead of allocated device memory.  Every
+// GPU holds its own copy of the array at its own address; in host code the array's name is only a
+// stand-in for the symbol, so the address is looked up once per device (static_scratch below) and
+// host code uses that pointer, never the name.
+constexpr size_t kStaticScratchBytes = ((size_t)kStaticTensors + kStaticChunks) * sizeof(void*);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Pointers travel to the array in the kernel arguments, kPtrBatch at a time: no copy from host
+// memory, nothing for the runtime to stage.
+constexpr uint32_t kPtrBatch = 256;
+struct PtrBatch {
+    const void* p[kPtrBatch];
+};
+__global__ __launch_bounds__(kPtrBatch) void th_fill_table_kernel(const void** table, uint32_t n, PtrBatch batch) {
+    if (threadIdx.x < n) table[threadIdx.x] = batch.p[threadIdx.x];
+}
+
 // Progress counter store: ordered after everything earlier in the stream, visible system-wide.
 __global__ void th_signal_kernel(uint64_t* flag, uint64_t value) {
     __atomic_store_n(flag, value, __ATOMIC_RELEASE);  // system scope: host and peers may poll it
@@ -841,6 +861,74 @@ int launch_signal(uint64_t* flag, uint64_t value, void* stream) {
         set_error("kernel launch failed: %s", hipGetErrorString(e));
         return TH_ERR_HIP;
     }
+    return TH_OK;
+}
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices];  // per device: address of that device's copy of `scratch`
+
+// Device address of the current device's copy of the static array (looked up on the first call per
+// device, with that device current).
+int static_scratch(unsigned char** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        set_error("hipGetDevice: %s", hipGetErrorString(e));
+        return TH_ERR_HIP;
+    }
+    if (dev < 0 || dev >= kMaxDevices) {
+        set_error("device %d: only devices 0..%d can use the allocation-free entry point", dev, kMaxDevices - 1);
+        return TH_ERR_UNSUPPORTED;
+    }
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            set_error("hipGetSymbolAddress(static pointer tables): %s", hipGetErrorString(e));
+            return TH_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = static_cast<unsigned char*>(g_scratch_ptr[dev]);
+    return TH_OK;
+}
+
+int fill_table(const void** table, const void* const* ptrs, uint32_t n, hipStream_t st) {
+    for (uint32_t done = 0; done < n; done += kPtrBatch) {
+        PtrBatch b;
+        const uint32_t m = n - done < kPtrBatch ? n - done : kPtrBatch;
+        for (uint32_t i = 0; i < kPtrBatch; ++i) b.p[i] = i < m ? ptrs[done + i] : nullptr;
+        hipLaunchKernelGGL(th_fill_table_kernel, dim3(1), dim3(kPtrBatch), 0, st, table + done, m, b);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) {
+            set_error("kernel launch failed: %s", hipGetErrorString(e));
+            return TH_ERR_HIP;
+        }
+    }
+    return TH_OK;
+}
+}  // namespace
+
+int stage_static_tables(const void* const* tensor_ptrs, uint32_t n_tensors, const void* const* wire_ptrs,
+                        uint32_t n_wire, void* stream, const void* const** tensor_table,
+                        const void* const** wire_table) {
+    if (n_tensors > kStaticTensors || n_wire > kStaticChunks) {
+        set_error("%u tensor pointers / %u wire pointers exceed the fixed tables of the allocation-free entry "
+                  "point (%u / %u)", n_tensors, n_wire, kStaticTensors, kStaticChunks);
+        return TH_ERR_RANGE;
+    }
+    unsigned char* base = nullptr;
+    if (int rc = static_scratch(&base)) return rc;
+    const void** tt = reinterpret_cast<const void**>(base);
+    const void** wt = tt + kStaticTensors;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (int rc = fill_table(tt, tensor_ptrs, n_tensors, st)) return rc;
+    if (int rc = fill_table(wt, wire_ptrs, n_wire, st)) return rc;
+    *tensor_table = tt;
+    *wire_table = wt;
     return TH_OK;
 }
 
