@@ -7,6 +7,11 @@ narrowed fp32 element 4 + 2 at pack and 2 + 2 at unpack (10 per sweep).  The
 plan (host planner + one table upload) is created once per (holder, reader,
 model) and reused for every weight version, so it is timed separately and
 reported as plan_ms.
+
+Without --workload the line is the 70B-shaped reshard (the largest single-GPU
+configuration, two plans, about 106 GB resident) and carries the 8B-shaped
+reshard as a second, complete block under "secondary": the two workloads the
+bandwidth target is stated for.
 """
 import argparse
 import json
@@ -19,6 +24,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
+PRIMARY, SECONDARY = "cfg3_70b_tp8_to_tp4", "cfg2_8b_tp1_to_tp4"
 
 # HBM bytes per launch (FETCH_SIZE + WRITE_SIZE from two rocprofv3 --pmc runs, each scaled by what
 # the counter reads for th_reference_copy of known size; summaries under profiles/).  Valid only for
@@ -44,10 +50,10 @@ def measured_traffic(workload, kernel):
 
 
 def build_inputs(th, dev, synth, w, torch):
-    """Plans, resident source tensors, wire buffers and destination tensors of a model workload."""
-    from oracle import layouts  # only for tensor roles of the synthetic values (norm vs weight)
+    """Plans, resident source tensors, wire buffers and destination tensors of a model workload.
+    Tensor shapes and dtypes come from the plan; a tensor whose name says it is a normalisation
+    weight holds ones, every other one seeded N(0, 0.02) values."""
     model = w["model"]
-    lts = layouts.logical_tensors(model)
     jobs = []
     resident = {}          # holder layout -> its tensors in HBM (a holder feeding several readers is resident once)
     plan_ms = 0.0
@@ -59,56 +65,96 @@ def build_inputs(th, dev, synth, w, torch):
             plan = th.th_plan_create(model, src, dst, w["chunk_bytes"])
             plan_ms += (time.perf_counter() - t0) * 1e3
             ck_plan = th.th_plan_create(model, src, dst, w["chunk_bytes"], th.TH_FLAG_CHECKSUM)
-            regs = layouts.registered_tensors(model, src)
+            regs = plan.tensors(0)
             key = tuple(sorted(src.items()))
             if key not in resident:
                 h = len(resident)
                 resident[key] = [synth.weight_values(t["rows"] * t["cols"], t["dtype"], w["seed"] * 16 + h, i, "cuda",
-                                                     is_norm=lts[t["parts"][0][0]]["role"] == "norm")
+                                                     is_norm="norm" in t["name"])
                                  for i, t in enumerate(regs)]
             src_dev = resident[key]
             if dst_dev is None:
                 dst_dev = dev.alloc_tensors(plan, 1, fill_bits=0)
             wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=0)
             jobs.append(dict(plan=plan, ck_plan=ck_plan, src=src_dev, src_ptrs=dev.ptrs(src_dev), wire=wire_dev,
-                             wptrs=wptrs, layout=src, regs=regs, dst=dst_dev, dst_ptrs=dev.ptrs(dst_dev)))
+                             wptrs=wptrs, layout=src, reader=dst, regs=regs, dst=dst_dev, dst_ptrs=dev.ptrs(dst_dev)))
     return jobs, plan_ms
 
 
-def cpu_baseline(synth, w, jobs, budget_s=15.0):
-    """The oracle as it stands, on the host cores, over a bounded prefix of the same workload:
-    plan items (holder tensors in wire order) until about budget_s seconds of oracle work."""
+def host_threads():
+    """Threads the all-cores leg uses: the cores this process may run on."""
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:
+        n = os.cpu_count() or 1
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env and env.isdigit() and int(env) > 0:
+        n = min(n, int(env))
+    return max(1, n)
+
+
+def run_timed(work, n_threads):
+    """Seconds to run the callables in `work`, one after the other or on a pool of threads (numpy's
+    indexing and the C narrowing routine release the interpreter lock)."""
+    if n_threads == 1:
+        t0 = time.perf_counter()
+        for f in work:
+            f()
+        return time.perf_counter() - t0
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(n_threads) as pool:
+        t0 = time.perf_counter()
+        list(pool.map(lambda f: f(), work))
+        return time.perf_counter() - t0
+
+
+def baseline_record(sweep_bytes, t1, tn, threads, what):
+    return dict(value=round(sweep_bytes / t1 / 1e9, 3), unit="GB/s", cores=1, kind="oracle",
+                all_cores=dict(value=round(sweep_bytes / tn / 1e9, 3), unit="GB/s", cores=threads,
+                               host_cores=os.cpu_count()),
+                sample="%s (%.2f GB moved; %.1f s on one thread, %.1f s on %d threads)"
+                       % (what, sweep_bytes / 1e9, t1, tn, threads))
+
+
+def cpu_baseline(synth, w, jobs, budget_bytes=20e9):
+    """The oracle as it stands, on the host cores, over a bounded prefix of the same workload: plan
+    items (holder tensors in wire order) until about budget_bytes of sweep bytes (about 10 s on one
+    thread), first on one thread, then the same items on all cores (one item per task)."""
     import numpy as np
-    from oracle import reshard
-    model, dst = w["model"], w["reader"]
+    from oracle import layouts, reshard
+    model = w["model"]
     job = jobs[0]
-    dst_cpu = {}
-    sweep_bytes = 0
-    spent = 0.0
-    n_items = 0
-    dst_regs = None
+    dst = job["reader"]
+    dst_regs = layouts.registered_tensors(model, dst)
+    items, srcs, sweep_bytes = [], {}, 0
     for it in reshard.plan_items(model, job["layout"], dst):
         reg = job["regs"][it["src_id"]]
-        src_bits = synth.to_bits(job["src"][it["src_id"]]).reshape(reg["rows"], reg["cols"])  # D2H, not timed
-        if it["dst_id"] not in dst_cpu:
-            if dst_regs is None:
-                from oracle import layouts
-                dst_regs = layouts.registered_tensors(model, dst)
-            t = dst_regs[it["dst_id"]]
-            dst_cpu = {it["dst_id"]: np.zeros((t["rows"], t["cols"]), dtype=reshard.NPBITS[t["dtype"]])}
-        t0 = time.perf_counter()
-        wire = reshard.item_wire(it, src_bits)                                  # pack: gather + convert
-        nr, nc = len(it["src_r"]), len(it["src_c"])
-        dst_cpu[it["dst_id"]][np.ix_(it["dst_r"], it["dst_c"])] = wire.reshape(nr, nc)  # unpack: scatter
-        spent += time.perf_counter() - t0
-        n = nr * nc
+        if it["src_id"] not in srcs:                                           # D2H, not timed
+            srcs[it["src_id"]] = synth.to_bits(job["src"][it["src_id"]]).reshape(reg["rows"], reg["cols"])
+        n = len(it["src_r"]) * len(it["src_c"])
         sweep_bytes += n * (reshard.ESIZE[it["src_dtype"]] + 3 * reshard.ESIZE[it["dst_dtype"]])
-        n_items += 1
-        if spent >= budget_s:
+        items.append(it)
+        if sweep_bytes >= budget_bytes:
             break
-    return dict(value=round(sweep_bytes / spent / 1e9, 3), unit="GB/s", cores=1, kind="oracle",
-                sample="first %d plan items of the workload in wire order (%.2f GB moved, %.1f s of oracle time)"
-                       % (n_items, sweep_bytes / 1e9, spent))
+    dst_cpu = {}
+    for it in items:
+        if it["dst_id"] not in dst_cpu:
+            t = dst_regs[it["dst_id"]]
+            dst_cpu[it["dst_id"]] = np.zeros((t["rows"], t["cols"]), dtype=reshard.NPBITS[t["dtype"]])
+
+    def one(it):
+        def f():
+            wire = reshard.item_wire(it, srcs[it["src_id"]])                                  # pack: gather + convert
+            nr, nc = len(it["src_r"]), len(it["src_c"])
+            dst_cpu[it["dst_id"]][np.ix_(it["dst_r"], it["dst_c"])] = wire.reshape(nr, nc)   # unpack: scatter
+        return f
+
+    work = [one(it) for it in items]
+    threads = host_threads()
+    t1 = run_timed(work, 1)
+    tn = run_timed(work, threads)
+    return baseline_record(sweep_bytes, t1, tn, threads,
+                           "first %d plan items of the workload in wire order" % len(items))
 
 
 def build_scatter_inputs(th, dev, synth, w, torch):
@@ -139,8 +185,8 @@ def build_scatter_inputs(th, dev, synth, w, torch):
     return [job], plan_ms
 
 
-def cpu_baseline_scatter(synth, w, jobs, budget_s=15.0):
-    """The segment oracle on the host over a bounded prefix of the wire order."""
+def cpu_baseline_scatter(synth, w, jobs, budget_bytes=6e9):
+    """The segment oracle on the host over a bounded prefix of the wire order, one thread and all cores."""
     import numpy as np
     from oracle import segments
     d, pool = jobs[0]["desc"], jobs[0]["src"]
@@ -148,68 +194,54 @@ def cpu_baseline_scatter(synth, w, jobs, budget_s=15.0):
     osegs = dict(src_tensor=d["seg_src_tensor"], dst_tensor=np.zeros(n, dtype=np.int64),
                  src_off=d["seg_src_off"], src_stride=d["seg_src_stride"], dst_off=d["seg_dst_off"],
                  dst_stride=d["seg_dst_stride"], nrows=d["seg_nrows"], row_len=d["seg_row_len"])
-    spent, sweep_bytes, k = 0.0, 0, 0
-    while k < n and spent < budget_s:
+    srcs, outs, sweep_bytes, k = {}, [], 0, 0
+    while k < n and sweep_bytes < budget_bytes:
         t = int(d["seg_src_tensor"][k])
         o, m = int(d["pool_off"][t]), int(d["n_elems"][t])
-        src = {t: synth.to_bits(pool[o:o + m])}                      # D2H, not timed
+        srcs[t] = synth.to_bits(pool[o:o + m])                           # D2H, not timed
         nel = int(d["seg_nrows"][k]) * int(d["seg_row_len"][k])
-        out = np.zeros(nel, dtype=np.uint16)
-        t0 = time.perf_counter()
-        wire = segments.segment_wire(osegs, k, src, "f32", "bf16")  # pack: gather + narrow
-        out[:] = wire                                                # unpack: dense destination slice
-        spent += time.perf_counter() - t0
+        outs.append(np.zeros(nel, dtype=np.uint16))
         sweep_bytes += nel * 10
         k += 1
-    return dict(value=round(sweep_bytes / spent / 1e9, 3), unit="GB/s", cores=1, kind="oracle",
-                sample="first %d segments of the wire order (%.2f GB moved, %.1f s of oracle time)"
-                       % (k, sweep_bytes / 1e9, spent))
+
+    def one(i):
+        def f():
+            wire = segments.segment_wire(osegs, i, srcs, "f32", "bf16")  # pack: gather + narrow
+            outs[i][:] = wire                                            # unpack: dense destination slice
+        return f
+
+    work = [one(i) for i in range(k)]
+    threads = host_threads()
+    t1 = run_timed(work, 1)
+    tn = run_timed(work, threads)
+    return baseline_record(sweep_bytes, t1, tn, threads, "first %d segments of the wire order" % k)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2_8b_tp1_to_tp4")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--offload", action="store_true",
-                    help="also time th_pack into / th_unpack out of pinned host memory (up to 2 GiB of chunks)")
-    ap.add_argument("--tile-bytes", type=int, default=0, help="override the vector-path tile size")
-    ap.add_argument("--no-specialize", action="store_true", help="always launch the all-paths kernel")
-    ap.add_argument("--tile-bytes-any", type=int, default=0, help="override the any-alignment tile size")
-    ap.add_argument("--tile-bytes-narrow", type=int, default=0, help="override the tile size of narrowing copies")
-    ap.add_argument("--tile-bytes-checksum", type=int, default=0,
-                    help="override the vector-path tile size of checksum plans")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: the reshard path has no cross-GPU step (every holder/reader pair is an "
-              "independent plan); run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
+def resident_bytes(jobs):
+    """Bytes of HBM the workload's inputs, wire buffers and outputs occupy (shared buffers once)."""
+    seen, total = set(), 0
+    for j in jobs:
+        for t in (j["src"] if isinstance(j["src"], list) else [j["src"]]) + [j["wire"]] + list(j["dst"]):
+            if t.data_ptr() not in seen:
+                seen.add(t.data_ptr())
+                total += t.numel() * t.element_size()
+    return total
 
-    import numpy as np
-    import torch
-    import synth
-    import paper_2604_09107_amd as th
-    from paper_2604_09107_amd import device as dev
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    if args.tile_bytes:
-        th.th_config_set(th.TH_CFG_TILE_BYTES, args.tile_bytes)
-    if args.no_specialize:
-        th.th_config_set(th.TH_CFG_SPECIALIZE, 0)
-    if args.tile_bytes_any:
-        th.th_config_set(th.TH_CFG_TILE_BYTES_ANY, args.tile_bytes_any)
-    if args.tile_bytes_narrow:
-        th.th_config_set(th.TH_CFG_TILE_BYTES_NARROW, args.tile_bytes_narrow)
-    if args.tile_bytes_checksum:
-        th.th_config_set(th.TH_CFG_TILE_BYTES_CHECKSUM, args.tile_bytes_checksum)
-    # one throw-away plan first: the process's first HIP call loads the library's code object
-    # (~0.1 s, once per process), which is not part of creating a plan
-    w0 = synth.workload("cfg1_tiny_tp2_to_tp1")
-    th.th_plan_create(w0["model"], w0["holders"][0], w0["reader"], w0["chunk_bytes"]).destroy()
-    w = synth.workload(args.workload)
+def time_with_events(torch, fn, reps):
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(reps):
+        fn()
+    c1.record()
+    torch.cuda.synchronize()
+    return c0.elapsed_time(c1) / reps
+
+
+def measure(args, name, extras, want_cpu_baseline, mods):
+    """Times one workload; returns (headline fields, everything else) as two dicts."""
+    np, torch, synth, th, dev = mods
+    w = synth.workload(name)
     if w["kind"] == "scatter":
         jobs, plan_ms = build_scatter_inputs(th, dev, synth, w, torch)
     else:
@@ -257,6 +289,45 @@ def main():
     k_unpack = unpack_bytes / len(jobs) / (unpack_ms * 1e-3) / 1e9
     dom = ("th_pack", k_pack, pack_ms) if pack_ms >= unpack_ms else ("th_unpack", k_unpack, unpack_ms)
 
+    value = sweep_bytes / (ms_per_step * 1e-3) / 1e9
+    head = {
+        "value": round(value, 1), "unit": "GB/s", "ms_per_step": round(ms_per_step, 4),
+        "dtype": "f32->bf16 (integer RNE)" if w["kind"] == "scatter" else "bf16",
+        "config": {"workload": name, "shapes": w["model_name"], "chunk_bytes": w["chunk_bytes"],
+                   "plans": len(jobs), "payload_bytes": sum(j["plan"].payload_bytes for j in jobs),
+                   "sweep_bytes": sweep_bytes, "chunks": sum(j["plan"].num_chunks for j in jobs),
+                   "resident_bytes": resident_bytes(jobs),
+                   "tile_bytes": th.th_config_get(th.TH_CFG_TILE_BYTES),
+                   "tile_bytes_any": th.th_config_get(th.TH_CFG_TILE_BYTES_ANY),
+                   "tile_bytes_narrow": th.th_config_get(th.TH_CFG_TILE_BYTES_NARROW)},
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
+        "plan_ms": round(plan_ms, 3),
+        "kernels": {"th_pack": {"ms": round(pack_ms, 4), "GB/s": round(k_pack, 1),
+                                "median_ms": round(pack_all[n_launch // 2], 4), "min_ms": round(pack_all[0], 4)},
+                    "th_unpack": {"ms": round(unpack_ms, 4), "GB/s": round(k_unpack, 1),
+                                  "median_ms": round(unpack_all[n_launch // 2], 4),
+                                  "min_ms": round(unpack_all[0], 4)}},
+        "roofline": {"bound": "hbm", "kernel": dom[0], "achieved": round(dom[1], 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(dom[1] / HBM_PEAK_GBPS, 4),
+                     "traffic": measured_traffic(name, dom[0])},
+    }
+    out = {}
+    if extras:
+        out.update(extra_sweeps(args, jobs, sweep_bytes, stream, mods))
+    if want_cpu_baseline:
+        out["cpu_baseline"] = (cpu_baseline_scatter if w["kind"] == "scatter" else cpu_baseline)(synth, w, jobs)
+    for j in jobs:
+        j["plan"].destroy()
+        j["ck_plan"].destroy()
+    return head, out
+
+
+def extra_sweeps(args, jobs, sweep_bytes, stream, mods):
+    """Secondary figures of a workload: yardstick copies, the wire-free reshard, the sweep with
+    checksums, the sweep in one call per chunk (eager, as a graph, through a ring of two buffers),
+    and the offload replica in pinned host memory."""
+    np, torch, synth, th, dev = mods
+    out = {}
     # practical ceiling: a plain device-to-device copy of the same number of bytes
     nbytes = jobs[0]["plan"].payload_bytes
     a = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
@@ -264,37 +335,28 @@ def main():
     for _ in range(3):
         b.copy_(a)
     torch.cuda.synchronize()
-    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    c0.record()
-    for _ in range(10):
-        b.copy_(a)
-    c1.record()
-    torch.cuda.synchronize()
-    copy_gbps = 2 * nbytes * 10 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    ms = time_with_events(torch, lambda: b.copy_(a), 10)
+    copy_gbps = 2 * nbytes / (ms * 1e-3) / 1e9
     # ... and the library's own plain copy kernel (same launch shape as the aligned path)
     n16 = nbytes // 16 * 16
     for _ in range(3):
         th.th_reference_copy(b.data_ptr(), a.data_ptr(), n16, stream)
-    c0.record()
-    for _ in range(10):
-        th.th_reference_copy(b.data_ptr(), a.data_ptr(), n16, stream)
-    c1.record()
-    torch.cuda.synchronize()
-    ref_gbps = 2 * n16 * 10 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    ms = time_with_events(torch, lambda: th.th_reference_copy(b.data_ptr(), a.data_ptr(), n16, stream), 10)
+    ref_gbps = 2 * n16 / (ms * 1e-3) / 1e9
     del a, b
+    out["d2d_copy_GB/s"] = {"torch_copy_": round(copy_gbps, 1), "th_reference_copy": round(ref_gbps, 1)}
 
     # co-located variant: th_reshard straight from holder tensors to reader tensors (no wire)
     direct_bytes = sum(j["plan"].src_read_bytes + j["plan"].payload_bytes for j in jobs)
+
+    def direct():
+        for j in jobs:
+            th.th_reshard(j["plan"], j["src_ptrs"], j["dst_ptrs"], stream)
+
     for _ in range(3):
-        for j in jobs:
-            th.th_reshard(j["plan"], j["src_ptrs"], j["dst_ptrs"], stream)
-    c0.record()
-    for _ in range(10):
-        for j in jobs:
-            th.th_reshard(j["plan"], j["src_ptrs"], j["dst_ptrs"], stream)
-    c1.record()
-    torch.cuda.synchronize()
-    direct_ms = c0.elapsed_time(c1) / 10
+        direct()
+    direct_ms = time_with_events(torch, direct, 10)
+    out["th_reshard_direct"] = {"ms": round(direct_ms, 4), "GB/s": round(direct_bytes / (direct_ms * 1e-3) / 1e9, 1)}
 
     # sweep with the per-tensor wire checksums fused into both directions
     sums = [(torch.zeros(2 * j["plan"].num_tensors(0), dtype=torch.int64, device="cuda"),
@@ -312,13 +374,10 @@ def main():
 
     for _ in range(3):
         checksum_step()
-    c0.record()
-    for _ in range(10):
-        checksum_step()
-    c1.record()
-    torch.cuda.synchronize()
-    checksum_ms = c0.elapsed_time(c1) / 10
+    checksum_ms = time_with_events(torch, checksum_step, 10)
     checksums_agree = all(bool((ps == us).all()) for ps, us in sums)
+    out["checksum_sweep"] = {"ms": round(checksum_ms, 4), "GB/s": round(sweep_bytes / (checksum_ms * 1e-3) / 1e9, 1),
+                             "pack_and_unpack_sums_agree": checksums_agree}
 
     # streaming use: one call per chunk (a reader consuming the prefix that has arrived)
     def per_chunk_sweep():
@@ -329,13 +388,19 @@ def main():
             for c in range(j["plan"].num_chunks):
                 th.th_unpack(j["plan"], j["wptrs"][c:c + 1], c, 1, j["dst_ptrs"], stream)
 
-    per_chunk_sweep()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(3):
-        per_chunk_sweep()
-    torch.cuda.synchronize()
-    per_chunk_ms = (time.perf_counter() - t0) / 3 * 1e3
+    def wall_ms(fn, reps=3):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps * 1e3
+
+    n_calls = 2 * sum(j["plan"].num_chunks for j in jobs)
+    per_chunk_ms = wall_ms(per_chunk_sweep)
+    out["per_chunk_calls_sweep"] = {"ms": round(per_chunk_ms, 4), "calls": n_calls,
+                                    "GB/s": round(sweep_bytes / (per_chunk_ms * 1e-3) / 1e9, 1)}
 
     # per-chunk pipeline recorded once into a HIP graph and replayed (what a reader that serves
     # version after version out of the same registered tensors would do): pack(c) -> unpack(c)
@@ -344,27 +409,23 @@ def main():
     branches = [torch.cuda.Stream() for _ in range(4)]
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=cap_stream):
-        for b in branches:
-            b.wait_stream(cap_stream)
+        for br in branches:
+            br.wait_stream(cap_stream)
         for j in jobs:
             for c in range(j["plan"].num_chunks):
-                b = branches[c % len(branches)].cuda_stream
-                th.th_pack(j["plan"], j["src_ptrs"], j["wptrs"][c:c + 1], c, 1, b)
-                th.th_unpack(j["plan"], j["wptrs"][c:c + 1], c, 1, j["dst_ptrs"], b)
-        for b in branches:
-            cap_stream.wait_stream(b)
-    graph.replay()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(3):
-        graph.replay()
-    torch.cuda.synchronize()
-    graph_ms = (time.perf_counter() - t0) / 3 * 1e3
+                br = branches[c % len(branches)].cuda_stream
+                th.th_pack(j["plan"], j["src_ptrs"], j["wptrs"][c:c + 1], c, 1, br)
+                th.th_unpack(j["plan"], j["wptrs"][c:c + 1], c, 1, j["dst_ptrs"], br)
+        for br in branches:
+            cap_stream.wait_stream(br)
+    graph_ms = wall_ms(graph.replay)
     del graph
+    out["per_chunk_graph_sweep"] = {"ms": round(graph_ms, 4), "kernel_nodes": n_calls, "branches": 4,
+                                    "GB/s": round(sweep_bytes / (graph_ms * 1e-3) / 1e9, 1)}
 
     # chunk ring: two wire buffers reused round-robin, unpack(c) right after pack(c), so a chunk is
     # read back while it still sits in the memory-side cache (what a co-located pipeline would see)
-    ring_ms = None
+    out["chunk_ring_sweep"] = None
     cb_max = max(j["plan"].chunk_bytes(0) for j in jobs if j["plan"].num_chunks)
     if 2 * cb_max <= (192 << 20):
         ring = torch.empty(2 * cb_max, dtype=torch.uint8, device="cuda")
@@ -376,76 +437,90 @@ def main():
                     th.th_pack(j["plan"], j["src_ptrs"], rp[c & 1], c, 1, stream)
                     th.th_unpack(j["plan"], rp[c & 1], c, 1, j["dst_ptrs"], stream)
 
-        ring_sweep()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(3):
-            ring_sweep()
-        torch.cuda.synchronize()
-        ring_ms = (time.perf_counter() - t0) / 3 * 1e3
+        ring_ms = wall_ms(ring_sweep)
         del ring
+        out["chunk_ring_sweep"] = {"ms": round(ring_ms, 4), "ring_chunks": 2,
+                                   "GB/s": round(sweep_bytes / (ring_ms * 1e-3) / 1e9, 1)}
 
     # offload replica: wire chunks in pinned host memory, written / read over the host link
-    offload = None
-    if args.offload:
+    if args.offload_bytes > 0:
         j = jobs[0]
         plan = j["plan"]
-        nck = max(1, min(plan.num_chunks, (2 << 30) // plan.chunk_bytes(0)))
+        nck = max(1, min(plan.num_chunks, args.offload_bytes // plan.chunk_bytes(0)))
         nbytes = sum(plan.chunk_bytes(c) for c in range(nck))
         host = torch.empty(nbytes + 16, dtype=torch.uint8, pin_memory=True)
         hptrs = dev.chunk_ptrs(plan, host)[:nck]
         res = {}
-        for name, call in (("th_pack", lambda: th.th_pack(plan, j["src_ptrs"], hptrs, 0, nck, stream)),
+        for what, call in (("th_pack", lambda: th.th_pack(plan, j["src_ptrs"], hptrs, 0, nck, stream)),
                            ("th_unpack", lambda: th.th_unpack(plan, hptrs, 0, nck, j["dst_ptrs"], stream))):
             call()
             torch.cuda.synchronize()
-            c0.record()
-            for _ in range(3):
-                call()
-            c1.record()
-            torch.cuda.synchronize()
-            ms = c0.elapsed_time(c1) / 3
-            res[name] = {"ms": round(ms, 3), "host_link_GB/s": round(nbytes / (ms * 1e-3) / 1e9, 2)}
-        offload = {"chunks": nck, "bytes": nbytes, **res}
+            ms = time_with_events(torch, call, 3)
+            res[what] = {"ms": round(ms, 3), "host_link_GB/s": round(nbytes / (ms * 1e-3) / 1e9, 2)}
+        out["offload_pinned_host"] = {"chunks": nck, "bytes": nbytes, **res}
+        del host
+    return out
 
-    value = sweep_bytes / (ms_per_step * 1e-3) / 1e9
-    out = {
-        "metric": "reshard pack+unpack effective HBM GB/s",
-        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32->bf16 (integer RNE)" if w["kind"] == "scatter" else "bf16", "data": "synthetic",
-        "config": {"workload": args.workload, "model": w["model_name"], "chunk_bytes": w["chunk_bytes"],
-                   "plans": len(jobs), "payload_bytes": sum(j["plan"].payload_bytes for j in jobs),
-                   "sweep_bytes": sweep_bytes, "chunks": sum(j["plan"].num_chunks for j in jobs),
-                   "tile_bytes": th.th_config_get(th.TH_CFG_TILE_BYTES),
-                   "tile_bytes_any": th.th_config_get(th.TH_CFG_TILE_BYTES_ANY),
-                   "tile_bytes_narrow": th.th_config_get(th.TH_CFG_TILE_BYTES_NARROW)},
-        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
-        "plan_ms": round(plan_ms, 3),
-        "kernels": {"th_pack": {"ms": round(pack_ms, 4), "GB/s": round(k_pack, 1),
-                                "median_ms": round(pack_all[n_launch // 2], 4), "min_ms": round(pack_all[0], 4)},
-                    "th_unpack": {"ms": round(unpack_ms, 4), "GB/s": round(k_unpack, 1),
-                                  "median_ms": round(unpack_all[n_launch // 2], 4),
-                                  "min_ms": round(unpack_all[0], 4)}},
-        "checksum_sweep": {"ms": round(checksum_ms, 4), "GB/s": round(sweep_bytes / (checksum_ms * 1e-3) / 1e9, 1),
-                           "pack_and_unpack_sums_agree": checksums_agree},
-        "per_chunk_calls_sweep": {"ms": round(per_chunk_ms, 4), "calls": 2 * sum(j["plan"].num_chunks for j in jobs),
-                                  "GB/s": round(sweep_bytes / (per_chunk_ms * 1e-3) / 1e9, 1)},
-        "per_chunk_graph_sweep": {"ms": round(graph_ms, 4), "kernel_nodes": 2 * sum(j["plan"].num_chunks for j in jobs),
-                                  "branches": 4,
-                                  "GB/s": round(sweep_bytes / (graph_ms * 1e-3) / 1e9, 1)},
-        "chunk_ring_sweep": None if ring_ms is None else {
-            "ms": round(ring_ms, 4), "ring_chunks": 2, "GB/s": round(sweep_bytes / (ring_ms * 1e-3) / 1e9, 1)},
-        "th_reshard_direct": {"ms": round(direct_ms, 4), "GB/s": round(direct_bytes / (direct_ms * 1e-3) / 1e9, 1)},
-        "d2d_copy_GB/s": {"torch_copy_": round(copy_gbps, 1), "th_reference_copy": round(ref_gbps, 1)},
-        "roofline": {"bound": "hbm", "kernel": dom[0], "achieved": round(dom[1], 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(dom[1] / HBM_PEAK_GBPS, 4),
-                     "traffic": measured_traffic(args.workload, dom[0])},
-    }
-    if offload:
-        out["offload_pinned_host"] = offload
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = (cpu_baseline_scatter if w["kind"] == "scatter" else cpu_baseline)(synth, w, jobs)
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=None,
+                    help="time this workload alone (default: %s, with %s as the secondary block)" % (PRIMARY, SECONDARY))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="time only the pack + unpack sweep")
+    ap.add_argument("--offload-bytes", type=int, default=1 << 30,
+                    help="bytes of wire chunks the offload leg places in pinned host memory (0: skip the leg)")
+    ap.add_argument("--tile-bytes", type=int, default=0, help="override the vector-path tile size")
+    ap.add_argument("--no-specialize", action="store_true", help="always launch the all-paths kernel")
+    ap.add_argument("--tile-bytes-any", type=int, default=0, help="override the any-alignment tile size")
+    ap.add_argument("--tile-bytes-narrow", type=int, default=0, help="override the tile size of narrowing copies")
+    ap.add_argument("--tile-bytes-checksum", type=int, default=0,
+                    help="override the vector-path tile size of checksum plans")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the reshard path has no cross-GPU step (every holder/reader pair is an "
+              "independent plan); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth
+    import paper_2604_09107_amd as th
+    from paper_2604_09107_amd import device as dev
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    if args.tile_bytes:
+        th.th_config_set(th.TH_CFG_TILE_BYTES, args.tile_bytes)
+    if args.no_specialize:
+        th.th_config_set(th.TH_CFG_SPECIALIZE, 0)
+    if args.tile_bytes_any:
+        th.th_config_set(th.TH_CFG_TILE_BYTES_ANY, args.tile_bytes_any)
+    if args.tile_bytes_narrow:
+        th.th_config_set(th.TH_CFG_TILE_BYTES_NARROW, args.tile_bytes_narrow)
+    if args.tile_bytes_checksum:
+        th.th_config_set(th.TH_CFG_TILE_BYTES_CHECKSUM, args.tile_bytes_checksum)
+    # one throw-away plan first: the process's first HIP call loads the library's code object
+    # (~0.1 s, once per process), which is not part of creating a plan
+    w0 = synth.workload("cfg1_tiny_tp2_to_tp1")
+    th.th_plan_create(w0["model"], w0["holders"][0], w0["reader"], w0["chunk_bytes"]).destroy()
+    mods = (np, torch, synth, th, dev)
+
+    name = args.workload or PRIMARY
+    head, rest = measure(args, name, not args.no_extras, not args.no_cpu_baseline, mods)
+    out = {"metric": "reshard pack+unpack effective HBM GB/s", "value": head.pop("value"), "unit": head.pop("unit"),
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head.pop("ms_per_step"),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": head.pop("dtype"),
+           "data": "synthetic"}
+    out.update(head)
+    out.update(rest)
+    if args.workload is None:
+        torch.cuda.empty_cache()
+        head2, _ = measure(args, SECONDARY, False, False, mods)
+        out["secondary"] = head2
     print(json.dumps(out))
 
 
