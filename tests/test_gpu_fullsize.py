@@ -1,9 +1,14 @@
 """GPU parity at the full benchmark sizes, in the launch configuration bench.py
 times (default tile size, all chunks in one call).  The oracle cannot hold these
-workloads whole, so it is run tensor by tensor on a sample of holder tensors
-(wire bytes and landing place compared bit for bit), and properties that hold
-at any size cover the rest."""
+workloads whole, so it is streamed: holder tensor by holder tensor (segment by
+segment for the scattered sweep) the source bits come back from the device, the
+oracle computes what that tensor puts on the wire, and the GPU's wire bytes and
+the place where they landed in the reader's tensors are compared bit for bit.
+Every holder tensor and every segment goes through it; properties that hold at
+any size (sentinels in what the plan does not own, zero gaps, sums of 16-bit
+halves) are checked on top."""
 import time
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 import pytest
@@ -16,6 +21,8 @@ from oracle import checksum, layouts, reshard, segments
 from test_planner_manifest import scatter_segments
 
 pytestmark = pytest.mark.gpu
+
+ORACLE_THREADS = 16   # numpy indexing and the C narrowing routine release the interpreter lock
 
 
 def log(msg):
@@ -32,7 +39,40 @@ def int16_sum(t):
     return total
 
 
-def run_model_fullsize(name, sample_fn, part=0, holders=None, sends_everything=True):
+class Backlog:
+    """Oracle comparisons queued on a thread pool, bounded by the bytes they hold."""
+
+    def __init__(self, limit_bytes=8 << 30):
+        self.pool = ThreadPoolExecutor(ORACLE_THREADS)
+        self.limit = limit_bytes
+        self.pending = []   # (future, bytes)
+        self.held = 0
+
+    def submit(self, nbytes, fn, *args):
+        while self.pending and self.held + nbytes > self.limit:
+            f, b = self.pending.pop(0)
+            f.result()
+            self.held -= b
+        self.pending.append((self.pool.submit(fn, *args), nbytes))
+        self.held += nbytes
+
+    def drain(self):
+        for f, _ in self.pending:
+            f.result()
+        self.pending, self.held = [], 0
+        self.pool.shutdown()
+
+
+def compare_item(it, src_bits, got_wire, dst_bits, src_name, dst_name):
+    want = reshard.item_wire(it, src_bits)
+    assert np.array_equal(got_wire.view(want.dtype), want), "wire of %s differs" % src_name
+    landed = dst_bits[np.ix_(it["dst_r"], it["dst_c"])]
+    assert np.array_equal(landed.reshape(-1), want), "%s landed wrong in %s" % (src_name, dst_name)
+
+
+def run_model_fullsize(name, part=0, holders=None):
+    """Packs and unpacks every chosen holder of the workload's part, then streams every plan item
+    through the oracle.  Returns what the any-size checks need."""
     w = synth.workload(name)
     model, dst = w["model"], w["parts"][part]["reader"]
     w["holders"] = [h for i, h in enumerate(w["parts"][part]["holders"]) if holders is None or i in holders]
@@ -41,6 +81,7 @@ def run_model_fullsize(name, sample_fn, part=0, holders=None, sends_everything=T
     dst_dev = None
     dst_regs = layouts.registered_tensors(model, dst)
     wire_sum = 0
+    covered = 0
     for h, src in enumerate(w["holders"]):
         plan = th.th_plan_create(model, src, dst, w["chunk_bytes"])
         regs = layouts.registered_tensors(model, src)
@@ -58,64 +99,97 @@ def run_model_fullsize(name, sample_fn, part=0, holders=None, sends_everything=T
         log("packed + unpacked")
         assert plan.wire_bytes == reshard.wire_bytes(model, src, dst)
         wire_sum += int16_sum(wire_dev[:plan.wire_bytes])
-        sample = set(sample_fn(regs))
-        checked = 0
-        dst_cache = {}
+        backlog = Backlog()
+        src_cache, dst_cache = (None, None), (None, None)
+        checked, prev_end, senders = 0, 0, set()
         for it in reshard.plan_items(model, src, dst):
-            if it["src_id"] not in sample:
-                continue
-            reg = regs[it["src_id"]]
-            src_bits = synth.to_bits(src_dev[it["src_id"]]).reshape(reg["rows"], reg["cols"])
-            want = reshard.item_wire(it, src_bits)
-            got = wire_dev[it["wire_off"]:it["wire_off"] + want.nbytes].cpu().numpy().view(want.dtype)
-            assert np.array_equal(got, want), "wire of %s differs" % reg["name"]
-            if it["dst_id"] not in dst_cache:
-                dst_cache = {it["dst_id"]: synth.to_bits(dst_dev[it["dst_id"]]).reshape(
-                    dst_regs[it["dst_id"]]["rows"], dst_regs[it["dst_id"]]["cols"])}
-            landed = dst_cache[it["dst_id"]][np.ix_(it["dst_r"], it["dst_c"])]
-            assert np.array_equal(landed.reshape(-1), want), "%s landed wrong in %s" % (
-                reg["name"], dst_regs[it["dst_id"]]["name"])
+            sid, did = it["src_id"], it["dst_id"]
+            if src_cache[0] != sid:
+                src_cache = (sid, synth.to_bits(src_dev[sid]).reshape(regs[sid]["rows"], regs[sid]["cols"]))
+            if dst_cache[0] != did:
+                dst_cache = (did, synth.to_bits(dst_dev[did]).reshape(dst_regs[did]["rows"], dst_regs[did]["cols"]))
+            n = len(it["src_r"]) * len(it["src_c"])
+            nb = n * reshard.ESIZE[it["wire_dtype"]]
+            off = it["wire_off"]
+            # the alignment gap in front of the item is zero
+            assert off - prev_end <= 14 and (off == prev_end or not wire_dev[prev_end:off].any().item())
+            prev_end = off + nb
+            got = wire_dev[off:off + nb].cpu().numpy()
+            backlog.submit(src_cache[1].nbytes + dst_cache[1].nbytes + nb, compare_item, it, src_cache[1], got,
+                           dst_cache[1], regs[sid]["name"], dst_regs[did]["name"])
             checked += 1
-        log("oracle agreed on %d sampled plan items" % checked)
+            covered += n
+            senders.add(sid)
+        backlog.drain()
+        assert prev_end == plan.wire_bytes
+        log("oracle agreed on all %d plan items (%d of %d holder tensors send)" % (checked, len(senders), len(regs)))
         assert checked > 0
-        if sends_everything:
-            assert checked >= len(sample) - 2 * len([t for t in regs if "norm" in t["name"]])
         plan.destroy()
         del src_dev, wire_dev
-    return w, dst_dev, dst_regs, wire_sum
+    return w, dst_dev, dst_regs, wire_sum, covered
 
 
-def layer_sample(regs, layers):
-    keep = []
-    for i, t in enumerate(regs):
-        n = t["name"]
-        if not n.startswith("layers.") or int(n.split(".")[1]) in layers:
-            keep.append(i)
-    return keep
+def reader_elements(dst_regs):
+    return sum(t["rows"] * t["cols"] for t in dst_regs)
 
 
 def test_8b_tp1_to_tp4_full_size():
-    w, dst_dev, dst_regs, wire_sum = run_model_fullsize(
-        "cfg2_8b_tp1_to_tp4", lambda regs: layer_sample(regs, {0, 17, 31}))
-    # the reader's shard is covered completely: same multiset of 16-bit halves as the wire
+    w, dst_dev, dst_regs, wire_sum, covered = run_model_fullsize("cfg2_8b_tp1_to_tp4")
+    # every element of the reader's shard was covered by a plan item (each verified in place above)
+    assert covered == reader_elements(dst_regs)
     assert sum(int16_sum(t) for t in dst_dev) == wire_sum
 
 
 def test_70b_tp8_to_tp4_full_size():
-    w, dst_dev, dst_regs, wire_sum = run_model_fullsize(
-        "cfg3_70b_tp8_to_tp4", lambda regs: layer_sample(regs, {0, 41, 79}))
+    w, dst_dev, dst_regs, wire_sum, covered = run_model_fullsize("cfg3_70b_tp8_to_tp4")
+    assert covered == reader_elements(dst_regs)
     assert sum(int16_sum(t) for t in dst_dev) == wire_sum
 
 
 def test_moe_ep8_to_tp2_full_size():
-    w, dst_dev, dst_regs, wire_sum = run_model_fullsize(
-        "cfg4_moe_ep8_to_tp2", lambda regs: layer_sample(regs, {0, 11, 23}))
+    w, dst_dev, dst_regs, wire_sum, covered = run_model_fullsize("cfg4_moe_ep8_to_tp2")
     # experts 8..63 of the stacked tensors belong to other holders: their slabs keep the sentinel
     for t, reg in zip(dst_dev, dst_regs):
         if ".experts.w" in reg["name"]:
             slabs = t.view(torch.int16).view(64, -1)
             assert bool((slabs[8:] == 0x7FA5).all()), reg["name"]
             assert not bool((slabs[:8] == 0x7FA5).all())
+
+
+def scatter_oracle_segments(d, n):
+    return dict(src_tensor=d["seg_src_tensor"], dst_tensor=np.zeros(n, dtype=np.int64),
+                src_off=d["seg_src_off"], src_stride=d["seg_src_stride"], dst_off=d["seg_dst_off"],
+                dst_stride=d["seg_dst_stride"], nrows=d["seg_nrows"], row_len=d["seg_row_len"])
+
+
+def for_every_scatter_segment(d, pool_dev, fn, batch_elems=1 << 29):
+    """Calls fn(k, sources) for every segment k of the scattered sweep on the oracle's thread pool.
+    The fp32 pool comes back from the device in batches of consecutive tensors (2 GiB each);
+    `sources` maps a tensor id of the batch to its bits."""
+    n = len(d["n_elems"])
+    where = np.empty(n, dtype=np.int64)          # tensor id -> position of its segment in the wire order
+    where[d["seg_src_tensor"]] = np.arange(n)
+    backlog = Backlog(limit_bytes=12 << 30)
+    t = 0
+    while t < n:
+        t_end = t
+        while t_end < n and (t_end == t or d["pool_off"][t_end] + d["n_elems"][t_end] - d["pool_off"][t] <= batch_elems):
+            t_end += 1
+        base = int(d["pool_off"][t])
+        stop = int(d["pool_off"][t_end - 1] + d["n_elems"][t_end - 1])
+        block = synth.to_bits(pool_dev[base:stop])
+        srcs = {i: block[int(d["pool_off"][i]) - base:int(d["pool_off"][i]) - base + int(d["n_elems"][i])]
+                for i in range(t, t_end)}
+
+        def batch(ids, srcs=srcs):
+            for i in ids:
+                fn(int(where[i]), srcs)
+
+        ids = np.arange(t, t_end)
+        for part in np.array_split(ids, min(len(ids), 4 * ORACLE_THREADS)):
+            backlog.submit(block.nbytes // (4 * ORACLE_THREADS), batch, part)
+        t = t_end
+    backlog.drain()
 
 
 @pytest.mark.parametrize("arena_shift", [0, 1])
@@ -140,36 +214,27 @@ def test_scattered_sweep_full_size(arena_shift):
     torch.cuda.synchronize()
     log("packed + unpacked: wire %.2f GB in %d chunks, %d / %d tiles" % (
         plan.wire_bytes / 1e9, plan.num_chunks, plan.num_tiles(0), plan.num_tiles(1)))
-    osegs = dict(src_tensor=d["seg_src_tensor"], dst_tensor=np.zeros(n, dtype=np.int64),
-                 src_off=d["seg_src_off"], src_stride=d["seg_src_stride"], dst_off=d["seg_dst_off"],
-                 dst_stride=d["seg_dst_stride"], nrows=d["seg_nrows"], row_len=d["seg_row_len"])
+    osegs = scatter_oracle_segments(d, n)
     offs, total = segments.wire_offsets(osegs, "bf16")
     assert total == plan.wire_bytes
     assert plan.payload_bytes == 2 * d["arena_elems"] and plan.src_read_bytes == 4 * d["arena_elems"]
-    # sample: random segments, the smallest and the largest ones, and the first / last on the wire
-    rng = np.random.default_rng(seed)
-    size = d["seg_nrows"] * d["seg_row_len"]
-    order = np.argsort(size)
-    ks = set(rng.choice(n, 1500, replace=False).tolist()) | set(order[:200].tolist()) | set(order[-12:].tolist())
-    ks |= {0, 1, n - 2, n - 1}
+    wire_host = wire_dev.cpu().numpy()
+    arena_host = synth.to_bits(arena[:d["arena_elems"]])
+    log("wire and arena on the host")
 
-    class Lazy:  # source tensors fetched from the device on demand
-        def __getitem__(self, t):
-            o, m = int(d["pool_off"][t]), int(d["n_elems"][t])
-            return synth.to_bits(pool_dev[o:o + m])
-
-    for k in sorted(ks):
-        want = segments.segment_wire(osegs, k, Lazy(), "f32", "bf16")
-        got = wire_dev[int(offs[k]):int(offs[k]) + want.nbytes].cpu().numpy().view(np.uint16)
-        assert np.array_equal(got, want), "wire of segment %d differs" % k
+    def compare(k, srcs):
+        want = segments.segment_wire(osegs, k, srcs, "f32", "bf16")
+        lo = int(offs[k])
+        assert np.array_equal(wire_host[lo:lo + want.nbytes].view(np.uint16), want), "wire of segment %d differs" % k
         a = int(d["seg_dst_off"][k])
-        landed = synth.to_bits(arena[a:a + len(want)])
-        assert np.array_equal(landed, want), "segment %d landed wrong" % k
+        assert np.array_equal(arena_host[a:a + len(want)], want), "segment %d landed wrong" % k
         # the gap up to the next segment's start is zero
-        end = int(offs[k]) + want.nbytes
+        end = lo + want.nbytes
         nxt = int(offs[k + 1]) if k + 1 < n else end
-        assert nxt - end <= 14 and not wire_dev[end:nxt].any().item()
-    log("oracle agreed on %d sampled segments" % len(ks))
+        assert nxt - end <= 14 and not wire_host[end:nxt].any()
+
+    for_every_scatter_segment(d, pool_dev, compare)
+    log("oracle agreed on all %d segments" % n)
     # any-size properties: arena = every wire element exactly once (sums of 16-bit halves agree, gaps are
     # zero and add nothing), guard elements around the arena untouched
     assert int16_sum(arena[:d["arena_elems"]]) == int16_sum(wire_dev[:plan.wire_bytes])
@@ -179,21 +244,20 @@ def test_scattered_sweep_full_size(arena_shift):
 
 
 def test_8b_last_reader_rank_full_size():
-    w, dst_dev, dst_regs, wire_sum = run_model_fullsize(
-        "cfg2_8b_tp1_to_tp4_all_readers", lambda regs: layer_sample(regs, {1, 30}), part=3)
+    w, dst_dev, dst_regs, wire_sum, covered = run_model_fullsize("cfg2_8b_tp1_to_tp4_all_readers", part=3)
+    assert covered == reader_elements(dst_regs)
     assert sum(int16_sum(t) for t in dst_dev) == wire_sum
 
 
 def test_70b_second_reader_full_size():
-    w, dst_dev, dst_regs, wire_sum = run_model_fullsize(
-        "cfg3_70b_tp8_to_tp4_two_readers", lambda regs: layer_sample(regs, {2, 78}), part=1)
+    w, dst_dev, dst_regs, wire_sum, covered = run_model_fullsize("cfg3_70b_tp8_to_tp4_two_readers", part=1)
+    assert covered == reader_elements(dst_regs)
     assert sum(int16_sum(t) for t in dst_dev) == wire_sum
 
 
 def test_moe_other_holder_full_size():
     """A holder that is not the reader's primary source sends its eight experts and nothing else."""
-    w, dst_dev, dst_regs, wire_sum = run_model_fullsize(
-        "cfg4_moe_ep8_to_tp2_all_holders", lambda regs: layer_sample(regs, {0, 12, 23}), holders={5}, sends_everything=False)
+    w, dst_dev, dst_regs, wire_sum, covered = run_model_fullsize("cfg4_moe_ep8_to_tp2_all_holders", holders={5})
     for t, reg in zip(dst_dev, dst_regs):
         v = t.view(torch.int16)
         if ".experts.w" in reg["name"]:
@@ -208,11 +272,11 @@ def sums_host(t):
     return t.cpu().numpy().view(np.uint64).reshape(-1, 2)
 
 
-@pytest.mark.parametrize("name,layers", [("cfg2_8b_tp1_to_tp4", {0, 17, 31}), ("cfg4_moe_ep8_to_tp2", {0, 23})])
-def test_model_checksums_full_size(name, layers):
+@pytest.mark.parametrize("name", ["cfg2_8b_tp1_to_tp4", "cfg4_moe_ep8_to_tp2"])
+def test_model_checksums_full_size(name):
     """Fused checksums in the configuration the benchmark's checksum sweep times: both sides agree
-    for every holder tensor, the oracle (from the source bits alone) on a sample of them, and the
-    reader tensors equal those of the plain calls."""
+    for every holder tensor, the oracle (from the source bits alone) agrees on every one of them, and
+    the reader tensors equal those of the plain calls."""
     w = synth.workload(name)
     model, src, dst = w["model"], w["holders"][0], w["reader"]
     lts = layouts.logical_tensors(model)
@@ -235,25 +299,40 @@ def test_model_checksums_full_size(name, layers):
     log("packed + unpacked with checksums")
     got_p, got_u = sums_host(ps), sums_host(us)
     assert np.array_equal(got_p, got_u)
-    sample = set(layer_sample(regs, layers))
-    runs = {}
-    for it in reshard.plan_items(model, src, dst):
-        if it["src_id"] in sample:
-            reg = regs[it["src_id"]]
-            bits = synth.to_bits(src_dev[it["src_id"]]).reshape(reg["rows"], reg["cols"])
-            runs.setdefault(it["src_id"], []).append((it["wire_off"], reshard.item_wire(it, bits).view(np.uint8)))
-    for t, parts in runs.items():
+    backlog = Backlog()
+    cache = (None, None)
+    open_run = {}
+
+    def check_run(t, parts):
         lo = min(o for o, _ in parts)
         run = np.zeros(max(o + len(b) for o, b in parts) - lo, dtype=np.uint8)
         for o, b in parts:
             run[o - lo:o - lo + len(b)] = b
         assert tuple(int(v) for v in got_p[t]) == checksum.run_checksum(run), regs[t]["name"]
+
+    def run_of(t, items, bits):
+        check_run(t, [(it["wire_off"], reshard.item_wire(it, bits).view(np.uint8)) for it in items])
+
+    n_runs = 0
+    for it in list(reshard.plan_items(model, src, dst)) + [None]:
+        if open_run and (it is None or it["src_id"] != open_run["t"]):   # a tensor's items are consecutive
+            backlog.submit(open_run["bits"].nbytes, run_of, open_run["t"], open_run["items"], open_run["bits"])
+            n_runs += 1
+            open_run = {}
+        if it is None:
+            break
+        if not open_run:
+            reg = regs[it["src_id"]]
+            open_run = dict(t=it["src_id"], items=[],
+                            bits=synth.to_bits(src_dev[it["src_id"]]).reshape(reg["rows"], reg["cols"]))
+        open_run["items"].append(it)
+    backlog.drain()
     sends = {it["src_id"] for it in reshard.plan_items(model, src, dst)}
     for t in range(len(regs)):
         if t not in sends:
             assert not got_p[t].any(), regs[t]["name"]
-    log("oracle agreed on the checksums of %d sampled tensors" % len(runs))
-    assert len(runs) >= 10
+    log("oracle agreed on the checksums of all %d sending tensors" % n_runs)
+    assert n_runs == len(sends)
     # the checksum variant moves the same data as the plain calls
     th.th_pack(plain, dev.ptrs(src_dev), wptrs, 0, plain.num_chunks, stream)
     th.th_unpack(plain, wptrs, 0, plain.num_chunks, dev.ptrs(ref_dev), stream)
@@ -286,23 +365,13 @@ def test_scattered_checksums_full_size():
     got_p, got_u = sums_host(ps), sums_host(us)
     assert np.array_equal(got_p, got_u)
     assert np.array_equal(np.sort(d["seg_src_tensor"]), np.arange(n))   # one segment per tensor, wire order shuffled
-    osegs = dict(src_tensor=d["seg_src_tensor"], dst_tensor=np.zeros(n, dtype=np.int64),
-                 src_off=d["seg_src_off"], src_stride=d["seg_src_stride"], dst_off=d["seg_dst_off"],
-                 dst_stride=d["seg_dst_stride"], nrows=d["seg_nrows"], row_len=d["seg_row_len"])
-    rng = np.random.default_rng(seed + 1)
-    size = d["seg_nrows"] * d["seg_row_len"]
-    order = np.argsort(size)
-    ks = set(rng.choice(n, 800, replace=False).tolist()) | set(order[:100].tolist()) | set(order[-8:].tolist())
-    ks |= {0, n - 1}
+    osegs = scatter_oracle_segments(d, n)
 
-    class Lazy:
-        def __getitem__(self, t):
-            o, m = int(d["pool_off"][t]), int(d["n_elems"][t])
-            return synth.to_bits(pool_dev[o:o + m])
-
-    for k in sorted(ks):
-        want = segments.segment_wire(osegs, k, Lazy(), "f32", "bf16")
+    def compare(k, srcs):
+        want = segments.segment_wire(osegs, k, srcs, "f32", "bf16")
         t = int(d["seg_src_tensor"][k])
         assert tuple(int(v) for v in got_p[t]) == checksum.run_checksum(want.view(np.uint8)), "tensor %d" % t
-    log("oracle agreed on the checksums of %d sampled tensors" % len(ks))
+
+    for_every_scatter_segment(d, pool_dev, compare)
+    log("oracle agreed on the checksums of all %d tensors" % n)
     plan.destroy()
