@@ -1,11 +1,11 @@
 /* th.h - C ABI of the GPU-resident reshard path of Reference-Oriented Storage
  * weight transfer (TensorHub).
  *
- * Where this sits in the paper.  A reader materialises weight version v "into
- * the handle's registered tensors" from a replica held by other workers
+ * Where this sits in the paper.  A reader brings weight version v into the
+ * tensors it registered with its handle, from a replica held by other workers
  * (Sec. 3.1 replicate, Sec. 4.2 Registration / Replicate); before transfer the
- * weights are "resharded and converted to inference-ready format" (Sec. 2.1,
- * step 4); the transfer engine copies tensor data slice by slice into staging
+ * weights are resharded and put into the format the inference engine keeps them
+ * in (Sec. 2.1, step 4); the transfer engine copies tensor data slice by slice into staging
  * buffers (Sec. 4.3.2, RDMA Copy) and compacts small tensors into contiguous
  * buffers that the receiver unpacks into their slices (Sec. 4.3.2, Tiny-Tensor
  * Optimization); a reader may consume the prefix of tensors that has arrived
@@ -266,10 +266,14 @@ int th_reshard(const th_plan* plan, const void* const* src_ptrs, uint32_t n_src,
                uint32_t n_dst, void* hip_stream);
 
 /* Free the plan and its device tables.  NULL is accepted.  The caller must
- * have synchronised every stream that still runs work of this plan. */
+ * have synchronised every stream that still runs work of this plan.  (A plan
+ * lives as long as the registration it was made for: tensors are registered
+ * once per handle and reused for every version, Sec. 4.2.) */
 int th_plan_destroy(th_plan* plan);
 
-/* ---- read-only queries (host) ------------------------------------------------------------- */
+/* ---- read-only queries (host) -------------------------------------------------------------
+ * What a caller needs to size its staging buffers (Sec. 4.3.2: the buffers that are registered and
+ * transferred) and to know which registered tensors (Sec. 4.2) the plan expects, in which order. */
 
 uint32_t th_plan_num_chunks(const th_plan* plan);
 size_t th_plan_chunk_bytes(const th_plan* plan, uint32_t chunk); /* 0 if out of range */
@@ -334,15 +338,16 @@ int th_plan_get_tile(const th_plan* plan, int side, size_t i, th_tile_info* out)
  * chunk == num_chunks gives the end of that sub-list */
 size_t th_plan_chunk_first_tile(const th_plan* plan, int side, int path_class, uint32_t chunk);
 
-/* Yardstick, not part of the transfer path: a plain device-to-device copy of
+/* Yardstick, not part of the transfer path and not from the paper: a plain device-to-device copy of
  * nbytes (multiple of 16; dst / src device pointers, 16-byte aligned, not
  * overlapping) enqueued on hip_stream with the same launch shape as the aligned
  * pack / unpack path.  Benchmarks use it as the practical bandwidth ceiling and as
  * the known-size kernel against which HBM byte counters are scaled. */
 int th_reference_copy(void* dst, const void* src, size_t nbytes, void* hip_stream);
 
-/* Process-wide tuning knobs, read when a plan is created.  Returns TH_ERR_ARG
- * for an unknown key or an out-of-range value. */
+/* Process-wide tuning knobs of this implementation (nothing in the paper corresponds to them), read
+ * when a plan is created: a plan keeps the values it was created with.  Returns TH_ERR_ARG for an
+ * unknown key or an out-of-range value. */
 enum {
     TH_CFG_TILE_BYTES = 1,    /* destination bytes per tile (one workgroup's share) on the 16-byte
                                  vector path; multiple of 4096 in [4096, 524288]; default 16384 */
@@ -351,8 +356,11 @@ enum {
                                      bf16; default 8192 */
     TH_CFG_TILE_BYTES_CHECKSUM = 4, /* vector-path tile size in plans created with TH_FLAG_CHECKSUM;
                                        default 32768 (amortises the per-wavefront reduction) */
-    TH_CFG_SPECIALIZE = 3      /* nonzero (default): vector-path tiles are launched with a kernel that
+    TH_CFG_SPECIALIZE = 3,     /* nonzero (default): vector-path tiles are launched with a kernel that
                                   contains only that path */
+    TH_CFG_PLANNER_THREADS = 6 /* 1..3 (default 3): host threads that build the tile lists of a large plan;
+                                  1 = the calling thread alone (also what happens when a thread cannot
+                                  be started) */
 };
 int th_config_set(int key, uint64_t value);
 uint64_t th_config_get(int key);

@@ -5,8 +5,9 @@ destination tensor maps through the reader's shard index to a global element
 (I, J) of a logical weight; the one holder whose shard index contains (I, J)
 supplies it:   dst[i, j] = convert(src[i', j']).
 
-Wire (a reading motivated by "compacts ... into contiguous buffers" and by the
-tensor-ordered prefix a reader may fetch, Sec. 4.3.2 / 4.3.3).  For one
+Wire (a reading motivated by the compaction of small tensors into contiguous
+staging buffers and by the tensor-ordered prefix a reader may fetch, Sec. 4.3.2
+/ 4.3.3).  For one
 (holder, reader) pair the stream is, for each of the holder's registered
 tensors in registration order, the elements of that tensor the reader needs,
 in the tensor's row-major order, already converted to the reader's dtype

@@ -191,7 +191,7 @@ int upload_tables(th_plan* p) {
     return TH_OK;
 }
 
-int finish_plan(th_plan* p, size_t chunk_bytes, unsigned flags, bool aligned16, th_plan** out) {
+int finish_plan(th_plan* p, size_t chunk_bytes, unsigned flags, bool aligned16) {
     Tuning tune = current_tuning();
     p->specialize = tune.specialize;
     if (flags & TH_FLAG_CHECKSUM) tune.tile_bytes = tune.tile_bytes_checksum;
@@ -202,12 +202,7 @@ int finish_plan(th_plan* p, size_t chunk_bytes, unsigned flags, bool aligned16, 
         p->checksum = (flags & TH_FLAG_CHECKSUM) != 0;
         if (!p->host_only) rc = upload_tables(p);
     }
-    if (rc != TH_OK) {
-        th_plan_destroy(p);
-        return rc;
-    }
-    *out = p;
-    return TH_OK;
+    return rc;
 }
 
 // Whether work enqueued on `stream` is being recorded into a graph instead of run.
@@ -355,6 +350,26 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
 
 using namespace th;
 
+namespace {
+// Nothing may leave an extern "C" entry point as an exception (the host containers of the pointer
+// table cache can throw on allocation failure).
+template <class F>
+int no_throw(F&& body) {
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        set_error("out of memory");
+        return TH_ERR_NOMEM;
+    } catch (const std::exception& e) {
+        set_error("internal error: %s", e.what());
+        return TH_ERR_NOMEM;
+    } catch (...) {
+        set_error("internal error");
+        return TH_ERR_NOMEM;
+    }
+}
+}  // namespace
+
 extern "C" {
 
 int th_plan_create(const th_model_desc* model, const th_layout* src, const th_layout* dst, size_t chunk_bytes,
@@ -364,23 +379,18 @@ int th_plan_create(const th_model_desc* model, const th_layout* src, const th_la
         return TH_ERR_ARG;
     }
     *out = nullptr;
-    th_plan* p = new (std::nothrow) th_plan;
-    if (!p) {
-        set_error("out of memory");
-        return TH_ERR_NOMEM;
+    th_plan* p = nullptr;
+    const int rc = no_throw([&] {
+        p = new th_plan;
+        if (int e = build_model_segments(*model, *src, *dst, (flags & TH_FLAG_NARROW_AT_UNPACK) != 0, p->m)) return e;
+        return finish_plan(p, chunk_bytes, flags, /*aligned16=*/true);
+    });
+    if (rc != TH_OK) {
+        th_plan_destroy(p);  // frees whatever device tables were uploaded already
+        return rc;
     }
-    try {
-        int rc = build_model_segments(*model, *src, *dst, (flags & TH_FLAG_NARROW_AT_UNPACK) != 0, p->m);
-        if (rc != TH_OK) {
-            delete p;
-            return rc;
-        }
-        return finish_plan(p, chunk_bytes, flags, /*aligned16=*/true, out);
-    } catch (const std::bad_alloc&) {
-        delete p;
-        set_error("out of memory");
-        return TH_ERR_NOMEM;
-    }
+    *out = p;
+    return TH_OK;
 }
 
 int th_plan_create_from_segments(const th_segment* segs, size_t n, const uint64_t* src_tensor_elems,
@@ -391,49 +401,53 @@ int th_plan_create_from_segments(const th_segment* segs, size_t n, const uint64_
         return TH_ERR_ARG;
     }
     *out = nullptr;
-    th_plan* p = new (std::nothrow) th_plan;
-    if (!p) {
-        set_error("out of memory");
-        return TH_ERR_NOMEM;
+    th_plan* p = nullptr;
+    const int rc = no_throw([&] {
+        p = new th_plan;
+        if (int e = segments_from_user(segs, n, src_tensor_elems, n_src, dst_tensor_elems, n_dst,
+                                       (flags & TH_FLAG_NARROW_AT_UNPACK) != 0, p->m))
+            return e;
+        return finish_plan(p, chunk_bytes, flags, (flags & TH_FLAG_PTRS_ALIGNED16) != 0);
+    });
+    if (rc != TH_OK) {
+        th_plan_destroy(p);
+        return rc;
     }
-    try {
-        int rc = segments_from_user(segs, n, src_tensor_elems, n_src, dst_tensor_elems, n_dst,
-                                    (flags & TH_FLAG_NARROW_AT_UNPACK) != 0, p->m);
-        if (rc != TH_OK) {
-            delete p;
-            return rc;
-        }
-        return finish_plan(p, chunk_bytes, flags, (flags & TH_FLAG_PTRS_ALIGNED16) != 0, out);
-    } catch (const std::bad_alloc&) {
-        delete p;
-        set_error("out of memory");
-        return TH_ERR_NOMEM;
-    }
+    *out = p;
+    return TH_OK;
 }
 
 int th_pack(const th_plan* plan, const void* const* src_ptrs, uint32_t n_src, void* const* wire_ptrs,
             uint32_t chunk_first, uint32_t chunk_count, void* hip_stream) {
-    return run_side(plan, 0, src_ptrs, n_src, const_cast<const void* const*>(wire_ptrs), chunk_first,
-                    chunk_count, nullptr, false, hip_stream);
+    return no_throw([&] {
+        return run_side(plan, 0, src_ptrs, n_src, const_cast<const void* const*>(wire_ptrs), chunk_first, chunk_count,
+                        nullptr, false, hip_stream);
+    });
 }
 
 int th_pack_checksum(const th_plan* plan, const void* const* src_ptrs, uint32_t n_src, void* const* wire_ptrs,
                      uint32_t chunk_first, uint32_t chunk_count, uint64_t* sums, void* hip_stream) {
-    return run_side(plan, 0, src_ptrs, n_src, const_cast<const void* const*>(wire_ptrs), chunk_first,
-                    chunk_count, sums, true, hip_stream);
+    return no_throw([&] {
+        return run_side(plan, 0, src_ptrs, n_src, const_cast<const void* const*>(wire_ptrs), chunk_first, chunk_count,
+                        sums, true, hip_stream);
+    });
 }
 
 int th_unpack_checksum(const th_plan* plan, const void* const* wire_ptrs, uint32_t chunk_first,
                        uint32_t chunk_count, void* const* dst_ptrs, uint32_t n_dst, uint64_t* sums,
                        void* hip_stream) {
-    return run_side(plan, 1, const_cast<const void* const*>(dst_ptrs), n_dst, wire_ptrs, chunk_first,
-                    chunk_count, sums, true, hip_stream);
+    return no_throw([&] {
+        return run_side(plan, 1, const_cast<const void* const*>(dst_ptrs), n_dst, wire_ptrs, chunk_first, chunk_count,
+                        sums, true, hip_stream);
+    });
 }
 
 int th_unpack(const th_plan* plan, const void* const* wire_ptrs, uint32_t chunk_first, uint32_t chunk_count,
               void* const* dst_ptrs, uint32_t n_dst, void* hip_stream) {
-    return run_side(plan, 1, const_cast<const void* const*>(dst_ptrs), n_dst, wire_ptrs, chunk_first,
-                    chunk_count, nullptr, false, hip_stream);
+    return no_throw([&] {
+        return run_side(plan, 1, const_cast<const void* const*>(dst_ptrs), n_dst, wire_ptrs, chunk_first, chunk_count,
+                        nullptr, false, hip_stream);
+    });
 }
 
 int th_pack_noalloc(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, void* const* wire_ptrs,
@@ -541,8 +555,11 @@ int th_reshard(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, vo
     if (int rc = stream_capturing(hip_stream, capturing)) return rc;
     std::lock_guard<std::mutex> lk(p->mu);
     PtrSlot *ss = nullptr, *ds = nullptr;
-    if (int rc = tensor_table(p, 0, src_ptrs, n_src, capturing, &ss)) return rc;
-    if (int rc = tensor_table(p, 1, const_cast<const void* const*>(dst_ptrs), n_dst, capturing, &ds)) return rc;
+    if (int rc = no_throw([&] { return tensor_table(p, 0, src_ptrs, n_src, capturing, &ss); })) return rc;
+    if (int rc = no_throw([&] {
+            return tensor_table(p, 1, const_cast<const void* const*>(dst_ptrs), n_dst, capturing, &ds);
+        }))
+        return rc;
     const void* const* stab = reinterpret_cast<const void* const*>(ss->dev);
     void* const* dtab = reinterpret_cast<void* const*>(ds->dev);
     InlineWire no_inline;
@@ -717,6 +734,13 @@ int th_config_set(int key, uint64_t value) {
         case TH_CFG_SPECIALIZE:
             g_tuning.specialize = value != 0;
             return TH_OK;
+        case TH_CFG_PLANNER_THREADS:
+            if (value < 1 || value > 3) {
+                set_error("planner threads must be 1, 2 or 3");
+                return TH_ERR_ARG;
+            }
+            g_tuning.planner_threads = (unsigned)value;
+            return TH_OK;
         case TH_CFG_TILE_BYTES_CHECKSUM:
             if (value < 4096 || value > 524288 || value % 4096) {
                 set_error("tile bytes must be a multiple of 4096 in [4096, 524288]");
@@ -748,7 +772,8 @@ uint64_t th_config_get(int key) {
     return key == TH_CFG_TILE_BYTES ? g_tuning.tile_bytes : key == TH_CFG_TILE_BYTES_ANY ? g_tuning.tile_bytes_any
            : key == TH_CFG_SPECIALIZE ? (uint64_t)g_tuning.specialize
            : key == TH_CFG_TILE_BYTES_CHECKSUM ? g_tuning.tile_bytes_checksum
-           : key == TH_CFG_TILE_BYTES_NARROW ? g_tuning.tile_bytes_narrow : 0;
+           : key == TH_CFG_TILE_BYTES_NARROW ? g_tuning.tile_bytes_narrow
+           : key == TH_CFG_PLANNER_THREADS ? g_tuning.planner_threads : 0;
 }
 
 const char* th_last_error(void) { return g_err; }

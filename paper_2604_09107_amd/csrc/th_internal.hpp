@@ -114,6 +114,7 @@ struct Tuning {
     uint64_t tile_bytes_checksum = 32768;  // vector path in plans with checksums: two vectors per thread amortise
                                            // the per-wavefront reduction
     bool specialize = true;           // launch vector-path tiles with the kernel that holds only that path
+    unsigned planner_threads = 3;     // threads that build a large plan's three tile lists (1: the calling thread alone)
 };
 Tuning current_tuning();
 

@@ -9,7 +9,9 @@
 #include <algorithm>
 #include <array>
 #include <cstdarg>
+#include <exception>
 #include <map>
+#include <new>
 
 #include "th_internal.hpp"
 
@@ -258,8 +260,8 @@ struct Piece {  // a needed rectangle in holder-tensor coordinates and where it 
 
 }  // namespace
 
-int build_model_segments(const th_model_desc& m, const th_layout& src, const th_layout& dst,
-                         bool narrow_at_unpack, Manifest& man) {
+static int build_model_segments_impl(const th_model_desc& m, const th_layout& src, const th_layout& dst,
+                                     bool narrow_at_unpack, Manifest& man) {
     if ((m.kind != TH_MODEL_DENSE && m.kind != TH_MODEL_MOE) || m.n_layers < 0 || m.hidden < 1 ||
         m.n_q_heads < 1 || m.n_kv_heads < 1 || m.head_dim < 1 || m.vocab < 1 ||
         (m.weight_dtype != TH_BF16 && m.weight_dtype != TH_F32) ||
@@ -414,6 +416,23 @@ int build_model_segments(const th_model_desc& m, const th_layout& src, const th_
     for (Segment& g : man.segments)
         if (g.wire_off + (g.nrows - 1) * g.wire_stride + g.row_len * esize(g.wire_dtype) == last_end) g.pad_after = 0;
     return TH_OK;
+}
+
+// Nothing may leave this file as an exception: the callers are extern "C".
+int build_model_segments(const th_model_desc& m, const th_layout& src, const th_layout& dst,
+                         bool narrow_at_unpack, Manifest& man) {
+    try {
+        return build_model_segments_impl(m, src, dst, narrow_at_unpack, man);
+    } catch (const std::bad_alloc&) {
+        set_error("out of memory");
+        return TH_ERR_NOMEM;
+    } catch (const std::exception& e) {
+        set_error("layout planner failed: %s", e.what());
+        return TH_ERR_NOMEM;
+    } catch (...) {
+        set_error("layout planner failed");
+        return TH_ERR_NOMEM;
+    }
 }
 
 }  // namespace th

@@ -2,6 +2,8 @@
 // device work list (tiles).  Integer arithmetic only.
 #include <algorithm>
 #include <cstring>
+#include <exception>
+#include <new>
 #include <thread>
 
 #include "th_internal.hpp"
@@ -180,8 +182,8 @@ void tile_run(std::vector<Tile>* outs, Side S, Side D, uint64_t nrows, uint64_t 
 
 }  // namespace
 
-int segments_from_user(const th_segment* segs, size_t n, const uint64_t* src_elems, uint32_t n_src,
-                       const uint64_t* dst_elems, uint32_t n_dst, bool narrow_at_unpack, Manifest& m) {
+static int segments_from_user_impl(const th_segment* segs, size_t n, const uint64_t* src_elems, uint32_t n_src,
+                                   const uint64_t* dst_elems, uint32_t n_dst, bool narrow_at_unpack, Manifest& m) {
     if ((n && !segs) || (n_src && !src_elems) || (n_dst && !dst_elems)) {
         set_error("null segment or tensor-size array");
         return TH_ERR_ARG;
@@ -264,7 +266,7 @@ int segments_from_user(const th_segment* segs, size_t n, const uint64_t* src_ele
     return TH_OK;
 }
 
-int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning& tune) {
+static int finish_manifest_impl(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning& tune) {
     if (CB == 0 || CB % 16) {
         set_error("chunk_bytes must be a positive multiple of 16");
         return TH_ERR_ARG;
@@ -428,16 +430,41 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
         }
     };
 
-    if (guess < 4096) {  // small plans: not worth two threads
-        build_side(0);
-        build_side(1);
-        build_direct();
-    } else {
-        std::thread t0(build_side, 0), t1(build_side, 1);
-        build_direct();
-        t0.join();
-        t1.join();
+    // The three lists are independent.  Large plans build the two per-direction lists on threads of
+    // their own; an exception inside a list builder is caught where it is thrown and handed back
+    // after the join, and a thread that cannot be started leaves its list to this thread.
+    int status[3] = {TH_OK, TH_OK, TH_OK};
+    auto guarded = [&](int which) {
+        try {
+            if (which < 2)
+                build_side(which);
+            else
+                build_direct();
+        } catch (...) {
+            status[which] = TH_ERR_NOMEM;
+        }
+    };
+    std::thread workers[2];
+    bool started[2] = {false, false};
+    if (guess >= 4096 && tune.planner_threads > 1) {  // small plans: not worth two threads
+        for (int k = 0; k < 2; ++k) {
+            try {
+                workers[k] = std::thread(guarded, k);
+                started[k] = true;
+            } catch (...) {
+            }
+        }
     }
+    guarded(2);
+    for (int k = 0; k < 2; ++k)
+        if (!started[k]) guarded(k);
+    for (int k = 0; k < 2; ++k)
+        if (started[k]) workers[k].join();
+    for (int k = 0; k < 3; ++k)
+        if (status[k] != TH_OK) {
+            set_error("out of memory while building the tile lists");
+            return status[k];
+        }
     for (int l = 0; l < 3; ++l)
         for (int s = 0; s < 2; ++s)
             for (size_t i = 0; i < m.tensors[s].size(); ++i) {
@@ -445,6 +472,34 @@ int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning&
                 if (seen[l][s].need16[i]) m.tensors[s][i].need16 = true;
             }
     return TH_OK;
+}
+
+// Nothing may leave the planner as an exception: the callers are extern "C".
+template <class F>
+static int no_throw(F&& body) {
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        set_error("out of memory");
+        return TH_ERR_NOMEM;
+    } catch (const std::exception& e) {
+        set_error("planner failed: %s", e.what());
+        return TH_ERR_NOMEM;
+    } catch (...) {
+        set_error("planner failed");
+        return TH_ERR_NOMEM;
+    }
+}
+
+int segments_from_user(const th_segment* segs, size_t n, const uint64_t* src_elems, uint32_t n_src,
+                       const uint64_t* dst_elems, uint32_t n_dst, bool narrow_at_unpack, Manifest& m) {
+    return no_throw([&] {
+        return segments_from_user_impl(segs, n, src_elems, n_src, dst_elems, n_dst, narrow_at_unpack, m);
+    });
+}
+
+int finish_manifest(Manifest& m, uint64_t CB, bool ptrs_aligned16, const Tuning& tune) {
+    return no_throw([&] { return finish_manifest_impl(m, CB, ptrs_aligned16, tune); });
 }
 
 }  // namespace th
