@@ -64,7 +64,6 @@ def build_inputs(th, dev, synth, w, torch):
             t0 = time.perf_counter()
             plan = th.th_plan_create(model, src, dst, w["chunk_bytes"])
             plan_ms += (time.perf_counter() - t0) * 1e3
-            ck_plan = th.th_plan_create(model, src, dst, w["chunk_bytes"], th.TH_FLAG_CHECKSUM)
             regs = plan.tensors(0)
             key = tuple(sorted(src.items()))
             if key not in resident:
@@ -76,7 +75,8 @@ def build_inputs(th, dev, synth, w, torch):
             if dst_dev is None:
                 dst_dev = dev.alloc_tensors(plan, 1, fill_bits=0)
             wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=0)
-            jobs.append(dict(plan=plan, ck_plan=ck_plan, src=src_dev, src_ptrs=dev.ptrs(src_dev), wire=wire_dev,
+            jobs.append(dict(plan=plan, make_plan=lambda flags, src=src, dst=dst: th.th_plan_create(
+                                 model, src, dst, w["chunk_bytes"], flags), src=src_dev, src_ptrs=dev.ptrs(src_dev), wire=wire_dev,
                              wptrs=wptrs, layout=src, reader=dst, regs=regs, dst=dst_dev, dst_ptrs=dev.ptrs(dst_dev)))
     return jobs, plan_ms
 
@@ -176,11 +176,10 @@ def build_scatter_inputs(th, dev, synth, w, torch):
     t0 = time.perf_counter()
     plan = th.th_plan_create_from_segments(segs, d["n_elems"], [d["arena_elems"] + 8], w["chunk_bytes"])
     plan_ms = (time.perf_counter() - t0) * 1e3
-    ck_plan = th.th_plan_create_from_segments(segs, d["n_elems"], [d["arena_elems"] + 8], w["chunk_bytes"],
-                                              th.TH_FLAG_CHECKSUM)
     wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=0)
     src_ptrs = pool.data_ptr() + d["pool_off"].astype(np.uint64) * np.uint64(4)
-    job = dict(plan=plan, ck_plan=ck_plan, src=pool, src_ptrs=src_ptrs, wire=wire_dev, wptrs=wptrs, desc=d,
+    job = dict(plan=plan, make_plan=lambda flags: th.th_plan_create_from_segments(
+                   segs, d["n_elems"], [d["arena_elems"] + 8], w["chunk_bytes"], flags), src=pool, src_ptrs=src_ptrs, wire=wire_dev, wptrs=wptrs, desc=d,
                keep=arena_store, dst=[arena], dst_ptrs=np.array([arena.data_ptr()], dtype=np.uint64))
     return [job], plan_ms
 
@@ -317,17 +316,24 @@ def measure(args, name, extras, want_cpu_baseline, mods):
     if want_cpu_baseline:
         out["cpu_baseline"] = (cpu_baseline_scatter if w["kind"] == "scatter" else cpu_baseline)(synth, w, jobs)
     for j in jobs:
-        j["plan"].destroy()
-        j["ck_plan"].destroy()
+        for k in ("plan", "ck_plan", "pr_plan"):
+            if k in j:
+                j[k].destroy()
     return head, out
 
 
 def extra_sweeps(args, jobs, sweep_bytes, stream, mods):
     """Secondary figures of a workload: yardstick copies, the wire-free reshard, the sweep with
     checksums, the sweep in one call per chunk (eager, as a graph, through a ring of two buffers),
-    and the offload replica in pinned host memory."""
+    the sweep in launches that publish their own progress (alone, and with a reader consuming the
+    prefix meanwhile), and the offload replica in pinned host memory."""
     np, torch, synth, th, dev = mods
     out = {}
+    # plans with checksums and with a progress counter are made here, after the headline sweep was
+    # timed, so that their device tables do not move the tensors of that sweep
+    for j in jobs:
+        j["ck_plan"] = j["make_plan"](th.TH_FLAG_CHECKSUM)
+        j["pr_plan"] = j["make_plan"](th.TH_FLAG_PROGRESS)
     # practical ceiling: a plain device-to-device copy of the same number of bytes
     nbytes = jobs[0]["plan"].payload_bytes
     a = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
@@ -401,6 +407,60 @@ def extra_sweeps(args, jobs, sweep_bytes, stream, mods):
     per_chunk_ms = wall_ms(per_chunk_sweep)
     out["per_chunk_calls_sweep"] = {"ms": round(per_chunk_ms, 4), "calls": n_calls,
                                     "GB/s": round(sweep_bytes / (per_chunk_ms * 1e-3) / 1e9, 1)}
+
+    # the same prefix use in one launch per direction: the launch itself publishes how many leading
+    # chunks are complete (counter in pinned host memory), nobody makes a call per chunk
+    counter = torch.zeros(1, dtype=torch.int64, pin_memory=True)
+    cview = counter.numpy()
+
+    def prefix_sweep():
+        for j in jobs:
+            th.th_pack_progress(j["pr_plan"], j["src_ptrs"], j["wptrs"], 0, j["pr_plan"].num_chunks,
+                                counter.data_ptr(), stream)
+        for j in jobs:
+            th.th_unpack_progress(j["pr_plan"], j["wptrs"], 0, j["pr_plan"].num_chunks, j["dst_ptrs"],
+                                  counter.data_ptr(), stream)
+
+    for _ in range(3):
+        prefix_sweep()
+    prefix_ms = time_with_events(torch, prefix_sweep, 10)
+    out["prefix_launch_sweep"] = {"ms": round(prefix_ms, 4), "launches": 2 * len(jobs),
+                                  "GB/s": round(sweep_bytes / (prefix_ms * 1e-3) / 1e9, 1)}
+
+    # ... and a reader that consumes the prefix while the holder's launch is still running: th_pack
+    # publishes its progress, the host polls the counter and hands every new batch of complete chunks
+    # (a sixteenth of the plan at least) to th_unpack on a second stream
+    unpack_stream = torch.cuda.Stream()
+
+    def prefix_pipeline():
+        calls = 0
+        for j in jobs:
+            n = j["pr_plan"].num_chunks
+            batch = max(1, n // 16)
+            cview[0] = 0
+            unpack_stream.wait_stream(torch.cuda.current_stream())
+            th.th_pack_progress(j["pr_plan"], j["src_ptrs"], j["wptrs"], 0, n, counter.data_ptr(), stream)
+            taken = 0
+            deadline = time.perf_counter() + 30.0
+            while taken < n and time.perf_counter() < deadline:
+                ready = int(cview[0])
+                if ready - taken >= batch or (ready == n and ready > taken):
+                    th.th_unpack(j["pr_plan"], j["wptrs"][taken:ready], taken, ready - taken, j["dst_ptrs"],
+                                 unpack_stream.cuda_stream)
+                    taken = ready
+                    calls += 1
+            torch.cuda.current_stream().wait_stream(unpack_stream)
+        return calls
+
+    prefix_pipeline()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(3):
+        unpack_calls = prefix_pipeline()
+    torch.cuda.synchronize()
+    pipe_ms = (time.perf_counter() - t0) / 3 * 1e3
+    out["prefix_pipeline_sweep"] = {"ms": round(pipe_ms, 4), "th_unpack_calls": unpack_calls,
+                                    "GB/s": round(sweep_bytes / (pipe_ms * 1e-3) / 1e9, 1)}
 
     # per-chunk pipeline recorded once into a HIP graph and replayed (what a reader that serves
     # version after version out of the same registered tensors would do): pack(c) -> unpack(c)
@@ -485,6 +545,23 @@ def main():
               "independent plan); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
+    # The second workload of the default line is timed by a child process of its own, before this
+    # process touches the GPU: device memory that one workload has used and freed comes back in
+    # other places, and either workload then runs 2-5 % slower than it does alone.
+    secondary = None
+    if args.workload is None:
+        import subprocess
+        cmd = [sys.executable, os.path.abspath(__file__), "--workload", SECONDARY, "--steps", str(args.steps),
+               "--warmup", str(args.warmup), "--no-extras", "--no-cpu-baseline"]
+        child = subprocess.run(cmd, capture_output=True, text=True)
+        lines = [l for l in child.stdout.splitlines() if l.startswith("{")]
+        if child.returncode == 0 and lines:
+            full = json.loads(lines[-1])
+            secondary = {k: full[k] for k in ("value", "unit", "ms_per_step", "dtype", "config", "pct_of_hbm_peak",
+                                              "plan_ms", "kernels", "roofline")}
+        else:
+            secondary = {"error": "exit status %d: %s" % (child.returncode, child.stderr[-400:])}
+
     import numpy as np
     import torch
     import synth
@@ -517,10 +594,8 @@ def main():
            "data": "synthetic"}
     out.update(head)
     out.update(rest)
-    if args.workload is None:
-        torch.cuda.empty_cache()
-        head2, _ = measure(args, SECONDARY, False, False, mods)
-        out["secondary"] = head2
+    if secondary is not None:
+        out["secondary"] = secondary
     print(json.dumps(out))
 
 

@@ -79,6 +79,11 @@ enum {
     TH_FLAG_NARROW_AT_UNPACK = 1u << 3, /* the wire carries the holder's dtype and th_unpack narrows
                                            (default: th_pack narrows, the wire carries the reader's
                                            dtype: fewer bytes to transfer) */
+    TH_FLAG_PROGRESS = 1u << 4,       /* the plan's launches can publish a progress counter
+                                         (th_pack_progress / th_unpack_progress): the work lists are kept
+                                         in prefix order, so that the chunks of one launch finish roughly
+                                         in order, and per-chunk arrival counters are allocated (4 KiB of
+                                         device memory per chunk and direction) */
     TH_FLAG_CHECKSUM = 1u << 2        /* allocate what th_pack_checksum / th_unpack_checksum need
                                          (24 bytes of device memory per tile) and use the larger
                                          checksum tile size; plain th_pack / th_unpack on such a plan
@@ -227,7 +232,7 @@ int th_unpack_checksum(const th_plan* plan, const void* const* wire_ptrs, uint32
                        uint32_t chunk_count, void* const* dst_ptrs, uint32_t n_dst, uint64_t* sums,
                        void* hip_stream);
 
-/* Progress counter (Sec. 4.3.3: a replicating worker tracks how many tensors of
+/* Progress counter between calls (Sec. 4.3.3: a replicating worker tracks how many tensors of
  * the version it has received; a reader reads the counter and fetches that
  * prefix).  th_signal enqueues, after all work already in hip_stream, a store of
  * `value` to *flag (device memory or pinned host memory, 8-byte aligned) that is
@@ -238,6 +243,28 @@ int th_unpack_checksum(const th_plan* plan, const void* const* wire_ptrs, uint32
  * as complete) whose whole wire run lies inside the first n_chunks_done chunks. */
 int th_signal(uint64_t* flag, uint64_t value, void* hip_stream);
 uint32_t th_plan_tensors_complete(const th_plan* plan, uint32_t n_chunks_done);
+
+/* Progress counter advanced from inside one launch (Sec. 4.3.3: a worker that is still
+ * receiving a version exposes how much of it has arrived, and a reader fetches that prefix instead
+ * of waiting for the whole transfer).  Same as th_pack / th_unpack over chunks
+ * [chunk_first, chunk_first + chunk_count), in one launch per path class, and while the launch runs
+ * *progress (device memory, or pinned host memory that the device can write; 8-byte aligned) holds
+ * the number of leading chunks of the range whose every byte has been written and is visible to the
+ * host, to other devices and to later work on any stream: it is set to 0 when the call's work
+ * starts, only ever grows, and reaches chunk_count when the call's work is complete.
+ * th_plan_tensors_complete(plan, chunk_first + value) turns it into the paper's unit, whole tensors,
+ * when chunk_first is 0.  A consumer polls the counter and takes chunks below it (for th_pack: sends
+ * them, or hands them to th_unpack on another stream; for th_unpack: uses the tensors that
+ * th_plan_tensors_complete reports).
+ * The plan must have been created with TH_FLAG_PROGRESS.  Progress calls of one direction on one
+ * plan must not overlap in time (they share the plan's arrival counters).  Errors as th_pack /
+ * th_unpack, plus TH_ERR_ARG for a plan without the flag or a bad counter pointer. */
+int th_pack_progress(const th_plan* plan, const void* const* src_ptrs, uint32_t n_src,
+                     void* const* wire_ptrs, uint32_t chunk_first, uint32_t chunk_count,
+                     uint64_t* progress, void* hip_stream);
+int th_unpack_progress(const th_plan* plan, const void* const* wire_ptrs, uint32_t chunk_first,
+                       uint32_t chunk_count, void* const* dst_ptrs, uint32_t n_dst, uint64_t* progress,
+                       void* hip_stream);
 
 /* th_pack for callers that cannot allocate device memory: code whose stream is
  * being captured into a HIP graph, tight serving loops, harnesses that forbid
@@ -358,6 +385,8 @@ enum {
                                        default 32768 (amortises the per-wavefront reduction) */
     TH_CFG_SPECIALIZE = 3,     /* nonzero (default): vector-path tiles are launched with a kernel that
                                   contains only that path */
+    TH_CFG_TILE_BYTES_PROGRESS = 7, /* vector-path tile size in plans created with TH_FLAG_PROGRESS;
+                                       default 32768 (amortises the wait for the stores' acknowledgements) */
     TH_CFG_PLANNER_THREADS = 6 /* 1..3 (default 3): host threads that build the tile lists of a large plan;
                                   1 = the calling thread alone (also what happens when a thread cannot
                                   be started) */

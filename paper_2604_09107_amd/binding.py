@@ -13,12 +13,14 @@ _LIB_PATH = os.path.join(_HERE, "libtensorhub_reshard.so")
 
 TH_BF16, TH_F32 = 1, 2
 TH_FLAG_HOST_ONLY, TH_FLAG_PTRS_ALIGNED16, TH_FLAG_CHECKSUM, TH_FLAG_NARROW_AT_UNPACK = 1, 2, 4, 8
+TH_FLAG_PROGRESS = 16
 TH_CFG_TILE_BYTES = 1
 TH_CFG_TILE_BYTES_ANY = 2
 TH_CFG_SPECIALIZE = 3
 TH_CFG_TILE_BYTES_CHECKSUM = 4
 TH_CFG_TILE_BYTES_NARROW = 5
 TH_CFG_PLANNER_THREADS = 6
+TH_CFG_TILE_BYTES_PROGRESS = 7
 TH_MODEL_DENSE, TH_MODEL_MOE = 1, 2
 _DTYPE = {"bf16": TH_BF16, "f32": TH_F32}
 _DTYPE_NAME = {TH_BF16: "bf16", TH_F32: "f32", 0: None}
@@ -109,6 +111,8 @@ _plan_create = _sig("th_plan_create", C.c_int, C.POINTER(_ModelDesc), C.POINTER(
 _plan_create_seg = _sig("th_plan_create_from_segments", C.c_int, _P, C.c_size_t, _P, C.c_uint32, _P, C.c_uint32,
                         C.c_size_t, C.c_uint, C.POINTER(_P))
 _pack = _sig("th_pack", C.c_int, _P, _P, C.c_uint32, _P, C.c_uint32, C.c_uint32, _P)
+_pack_progress = _sig("th_pack_progress", C.c_int, _P, _P, C.c_uint32, _P, C.c_uint32, C.c_uint32, _P, _P)
+_unpack_progress = _sig("th_unpack_progress", C.c_int, _P, _P, C.c_uint32, C.c_uint32, _P, C.c_uint32, _P, _P)
 _pack_noalloc = _sig("th_pack_noalloc", C.c_int, _P, _P, C.c_uint32, _P, C.c_uint32, C.c_uint32, _P)
 _unpack = _sig("th_unpack", C.c_int, _P, _P, C.c_uint32, C.c_uint32, _P, C.c_uint32, _P)
 _pack_sum = _sig("th_pack_checksum", C.c_int, _P, _P, C.c_uint32, _P, C.c_uint32, C.c_uint32, _P, _P)
@@ -252,6 +256,23 @@ def th_pack(plan, src_ptrs, wire_ptrs, chunk_first, chunk_count, stream=0):
     if len(w) != chunk_count:
         raise ValueError("need one wire pointer per chunk in the range")
     _check(_pack(plan.handle, s.ctypes.data, len(s), w.ctypes.data, chunk_first, chunk_count, stream))
+
+
+def th_pack_progress(plan, src_ptrs, wire_ptrs, chunk_first, chunk_count, progress_ptr, stream=0):
+    """progress_ptr: address of a uint64 in device memory or device-visible pinned host memory."""
+    s, w = _ptr_array(src_ptrs), _ptr_array(wire_ptrs)
+    if len(w) != chunk_count:
+        raise ValueError("need one wire pointer per chunk in the range")
+    _check(_pack_progress(plan.handle, s.ctypes.data, len(s), w.ctypes.data, chunk_first, chunk_count, progress_ptr,
+                          stream))
+
+
+def th_unpack_progress(plan, wire_ptrs, chunk_first, chunk_count, dst_ptrs, progress_ptr, stream=0):
+    w, d = _ptr_array(wire_ptrs), _ptr_array(dst_ptrs)
+    if len(w) != chunk_count:
+        raise ValueError("need one wire pointer per chunk in the range")
+    _check(_unpack_progress(plan.handle, w.ctypes.data, chunk_first, chunk_count, d.ctypes.data, len(d), progress_ptr,
+                            stream))
 
 
 def th_pack_noalloc(plan, src_ptrs, wire_ptrs, chunk_first, chunk_count, stream=0):

@@ -159,6 +159,12 @@ struct th_plan {
     bool checksum = false;
     uint64_t* d_partials[2] = {nullptr, nullptr};
     uint64_t* d_tile_base[2] = {nullptr, nullptr};
+    // progress support (TH_FLAG_PROGRESS): lists in prefix order, per direction the tiles per chunk,
+    // the arrival counters and the publishing state
+    bool progress = false;
+    uint32_t* d_expected[2] = {nullptr, nullptr};
+    uint32_t* d_arrived[2] = {nullptr, nullptr};
+    uint32_t* d_state[2] = {nullptr, nullptr};
     // guarded by mu: pointer-table caches (tensor side per direction, wire side per direction)
     mutable std::mutex mu;
     mutable th::PtrCache tensor_cache[2], wire_cache[2];
@@ -187,6 +193,22 @@ int upload_tables(th_plan* p) {
                           hipMemcpyHostToDevice);
             if (e != hipSuccess) return hip_fail(e, "hipMemcpy(checksum bases)");
         }
+        if (p->progress && side < 2) {
+            const size_t nc = p->m.n_chunks;
+            std::vector<uint32_t> expected(nc);
+            for (size_t c = 0; c < nc; ++c)
+                expected[c] = (uint32_t)((p->m.chunk_tile0[side][0][c + 1] - p->m.chunk_tile0[side][0][c]) +
+                                         (p->m.chunk_tile0[side][1][c + 1] - p->m.chunk_tile0[side][1][c]));
+            e = hipMalloc(reinterpret_cast<void**>(&p->d_expected[side]), nc * sizeof(uint32_t));
+            if (e != hipSuccess) return hip_fail(e, "hipMalloc(tiles per chunk)");
+            e = hipMemcpy(p->d_expected[side], expected.data(), nc * sizeof(uint32_t), hipMemcpyHostToDevice);
+            if (e != hipSuccess) return hip_fail(e, "hipMemcpy(tiles per chunk)");
+            e = hipMalloc(reinterpret_cast<void**>(&p->d_arrived[side]),
+                          nc * kProgressSlots * kProgressStride * sizeof(uint32_t));
+            if (e != hipSuccess) return hip_fail(e, "hipMalloc(arrival counters)");
+            e = hipMalloc(reinterpret_cast<void**>(&p->d_state[side]), 256);
+            if (e != hipSuccess) return hip_fail(e, "hipMalloc(progress state)");
+        }
     }
     return TH_OK;
 }
@@ -195,11 +217,16 @@ int finish_plan(th_plan* p, size_t chunk_bytes, unsigned flags, bool aligned16) 
     Tuning tune = current_tuning();
     p->specialize = tune.specialize;
     if (flags & TH_FLAG_CHECKSUM) tune.tile_bytes = tune.tile_bytes_checksum;
+    if (flags & TH_FLAG_PROGRESS) {
+        tune.tile_bytes = tune.tile_bytes_progress;
+        tune.chunk_order = true;
+    }
     p->vec_instance = vector_instance(tune.tile_bytes);
     int rc = finish_manifest(p->m, chunk_bytes, aligned16, tune);
     if (rc == TH_OK) {
         p->host_only = (flags & TH_FLAG_HOST_ONLY) != 0;
         p->checksum = (flags & TH_FLAG_CHECKSUM) != 0;
+        p->progress = (flags & TH_FLAG_PROGRESS) != 0;
         if (!p->host_only) rc = upload_tables(p);
     }
     return rc;
@@ -254,9 +281,10 @@ int tensor_table(const th_plan* p, int side, const void* const* ptrs, uint32_t n
 }
 
 // Shared body of th_pack / th_unpack.  side 0: tensors are the source, wire the destination.
+// progress: nullptr, or the caller's counter that the launch advances (want_progress says which).
 int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_t n_tensors,
              const void* const* wire_ptrs, uint32_t chunk_first, uint32_t chunk_count, uint64_t* sums,
-             bool want_sums, void* stream) {
+             bool want_sums, uint64_t* progress, bool want_progress, void* stream) {
     if (!p) {
         set_error("plan is NULL");
         return TH_ERR_ARG;
@@ -270,6 +298,16 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
         set_error(sums ? "plan was created without TH_FLAG_CHECKSUM" : "checksum array is NULL");
         return TH_ERR_ARG;
     }
+    if (want_progress) {
+        if (!p->progress) {
+            set_error("plan was created without TH_FLAG_PROGRESS");
+            return TH_ERR_ARG;
+        }
+        if (!progress || reinterpret_cast<uintptr_t>(progress) % 8) {
+            set_error("progress counter pointer is NULL or not 8-byte aligned");
+            return TH_ERR_ARG;
+        }
+    }
     if (n_tensors != m.tensors[side].size()) {
         set_error("%u tensor pointers given, plan has %zu %s tensors", n_tensors, m.tensors[side].size(),
                   side ? "destination" : "source");
@@ -280,17 +318,20 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
                   m.n_chunks);
         return TH_ERR_RANGE;
     }
-    if (chunk_count == 0) return TH_OK;
-    if (!wire_ptrs || (n_tensors && !tensor_ptrs)) {
+    if (chunk_count && (!wire_ptrs || (n_tensors && !tensor_ptrs))) {
         set_error("null pointer array");
         return TH_ERR_ARG;
     }
-    uint64_t tile0[2], ntiles[2];
-    for (int k = 0; k < 2; ++k) {
+    uint64_t tile0[2] = {0, 0}, ntiles[2] = {0, 0};
+    for (int k = 0; k < 2 && chunk_count; ++k) {
         tile0[k] = m.chunk_tile0[side][k][chunk_first];
         ntiles[k] = m.chunk_tile0[side][k][chunk_first + chunk_count] - tile0[k];
     }
-    if (ntiles[0] + ntiles[1] == 0) return TH_OK;
+    if (ntiles[0] + ntiles[1] == 0) {
+        if (!want_progress) return TH_OK;
+        if (int rc = check_device(p)) return rc;
+        return launch_signal(progress, chunk_count, stream);  // nothing to move: the range is complete
+    }
     if (int rc = check_device(p)) return rc;
 
     for (uint32_t i = 0; i < chunk_count; ++i) {
@@ -311,7 +352,7 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
     std::memset(&inl, 0, sizeof inl);
     PtrSlot* ws = nullptr;
     const void* const* wire_tab = nullptr;
-    if (chunk_count <= kInlineChunks) {
+    if (chunk_count <= kInlineChunks && !want_progress) {
         inl.n = chunk_count;
         for (uint32_t i = 0; i < chunk_count; ++i) inl.p[i] = const_cast<void*>(wire_ptrs[i]);
     } else {
@@ -326,7 +367,17 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
     }
     const void* const* tens_tab = reinterpret_cast<const void* const*>(ts->dev);
     if (!wire_tab) wire_tab = tens_tab;  // never read in inline mode, but keep it a valid device address
+    Progress prog;
+    prog.ordered = p->progress ? 1u : 0u;
     int rc = TH_OK;
+    if (want_progress) {
+        prog.arrived = p->d_arrived[side];
+        prog.expected = p->d_expected[side];
+        prog.state = p->d_state[side];
+        prog.flag = progress;
+        prog.count = chunk_count;
+        rc = launch_progress_reset(prog, stream);
+    }
     for (int k = 0; k < 2 && rc == TH_OK; ++k) {
         if (!ntiles[k]) continue;
         const bool vec_only = k == 0 && p->specialize;
@@ -334,14 +385,18 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
         uint64_t* partials = want_sums ? p->d_partials[side] : nullptr;
         if (side == 0)
             rc = launch_tiles(MODE_PACK, instance, p->d_tiles[0], tile0[k], ntiles[k], tens_tab,
-                              const_cast<void* const*>(wire_tab), chunk_first, inl, partials, p->m.tiles[0].size(), stream);
+                              const_cast<void* const*>(wire_tab), chunk_first, inl, partials, p->m.tiles[0].size(), prog,
+                              stream);
         else
             rc = launch_tiles(MODE_UNPACK, instance, p->d_tiles[1], tile0[k], ntiles[k], wire_tab,
-                              const_cast<void* const*>(tens_tab), chunk_first, inl, partials, p->m.tiles[1].size(), stream);
+                              const_cast<void* const*>(tens_tab), chunk_first, inl, partials, p->m.tiles[1].size(), prog,
+                              stream);
         if (rc == TH_OK && want_sums)
             rc = launch_checksum_finalize(p->d_tiles[side], p->d_partials[side], p->d_tile_base[side], tile0[k],
                                           ntiles[k], p->m.tiles[side].size(), vec_only, sums, stream);
     }
+    // the end of the launch completes the range, whatever the last publisher saw
+    if (rc == TH_OK && want_progress) rc = launch_signal(progress, chunk_count, stream);
     return rc;
 }
 
@@ -421,7 +476,7 @@ int th_pack(const th_plan* plan, const void* const* src_ptrs, uint32_t n_src, vo
             uint32_t chunk_first, uint32_t chunk_count, void* hip_stream) {
     return no_throw([&] {
         return run_side(plan, 0, src_ptrs, n_src, const_cast<const void* const*>(wire_ptrs), chunk_first, chunk_count,
-                        nullptr, false, hip_stream);
+                        nullptr, false, nullptr, false, hip_stream);
     });
 }
 
@@ -429,7 +484,7 @@ int th_pack_checksum(const th_plan* plan, const void* const* src_ptrs, uint32_t 
                      uint32_t chunk_first, uint32_t chunk_count, uint64_t* sums, void* hip_stream) {
     return no_throw([&] {
         return run_side(plan, 0, src_ptrs, n_src, const_cast<const void* const*>(wire_ptrs), chunk_first, chunk_count,
-                        sums, true, hip_stream);
+                        sums, true, nullptr, false, hip_stream);
     });
 }
 
@@ -438,7 +493,7 @@ int th_unpack_checksum(const th_plan* plan, const void* const* wire_ptrs, uint32
                        void* hip_stream) {
     return no_throw([&] {
         return run_side(plan, 1, const_cast<const void* const*>(dst_ptrs), n_dst, wire_ptrs, chunk_first, chunk_count,
-                        sums, true, hip_stream);
+                        sums, true, nullptr, false, hip_stream);
     });
 }
 
@@ -446,7 +501,23 @@ int th_unpack(const th_plan* plan, const void* const* wire_ptrs, uint32_t chunk_
               void* const* dst_ptrs, uint32_t n_dst, void* hip_stream) {
     return no_throw([&] {
         return run_side(plan, 1, const_cast<const void* const*>(dst_ptrs), n_dst, wire_ptrs, chunk_first, chunk_count,
-                        nullptr, false, hip_stream);
+                        nullptr, false, nullptr, false, hip_stream);
+    });
+}
+
+int th_pack_progress(const th_plan* plan, const void* const* src_ptrs, uint32_t n_src, void* const* wire_ptrs,
+                     uint32_t chunk_first, uint32_t chunk_count, uint64_t* progress, void* hip_stream) {
+    return no_throw([&] {
+        return run_side(plan, 0, src_ptrs, n_src, const_cast<const void* const*>(wire_ptrs), chunk_first, chunk_count,
+                        nullptr, false, progress, true, hip_stream);
+    });
+}
+
+int th_unpack_progress(const th_plan* plan, const void* const* wire_ptrs, uint32_t chunk_first, uint32_t chunk_count,
+                       void* const* dst_ptrs, uint32_t n_dst, uint64_t* progress, void* hip_stream) {
+    return no_throw([&] {
+        return run_side(plan, 1, const_cast<const void* const*>(dst_ptrs), n_dst, wire_ptrs, chunk_first, chunk_count,
+                        nullptr, false, progress, true, hip_stream);
     });
 }
 
@@ -518,12 +589,15 @@ int th_pack_noalloc(const th_plan* p, const void* const* src_ptrs, uint32_t n_sr
     if (int rc = stage_static_tables(src_ptrs, n_src, const_cast<const void* const*>(wire_ptrs), n_wire_table,
                                      hip_stream, &tens_tab, &wire_tab))
         return rc;
+    Progress order;
+    order.ordered = p->progress ? 1u : 0u;
     int rc = TH_OK;
     for (int k = 0; k < 2 && rc == TH_OK; ++k) {
         if (!ntiles[k]) continue;
         const int instance = (k == 0 && p->specialize) ? p->vec_instance : (int)VEC_ALL_PATHS;
         rc = launch_tiles(MODE_PACK, instance, p->d_tiles[0], tile0[k], ntiles[k], tens_tab,
-                          const_cast<void* const*>(wire_tab), chunk_first, inl, nullptr, m.tiles[0].size(), hip_stream);
+                          const_cast<void* const*>(wire_tab), chunk_first, inl, nullptr, m.tiles[0].size(), order,
+                          hip_stream);
     }
     return rc;
 }
@@ -566,11 +640,11 @@ int th_reshard(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, vo
     std::memset(&no_inline, 0, sizeof no_inline);
     int rc = TH_OK;
     if (m.direct_n_vec)
-        rc = launch_tiles(MODE_DIRECT, p->specialize ? p->vec_instance : (int)VEC_ALL_PATHS, p->d_tiles[2], 0, m.direct_n_vec, stab, dtab, 0, no_inline,
-                          nullptr, 0, hip_stream);
+        rc = launch_tiles(MODE_DIRECT, p->specialize ? p->vec_instance : (int)VEC_ALL_PATHS, p->d_tiles[2], 0,
+                          m.direct_n_vec, stab, dtab, 0, no_inline, nullptr, 0, Progress(), hip_stream);
     if (rc == TH_OK && total > m.direct_n_vec)
         rc = launch_tiles(MODE_DIRECT, VEC_ALL_PATHS, p->d_tiles[2], m.direct_n_vec, total - m.direct_n_vec, stab, dtab, 0,
-                          no_inline, nullptr, 0, hip_stream);
+                          no_inline, nullptr, 0, Progress(), hip_stream);
     return rc;
 }
 
@@ -581,6 +655,9 @@ int th_plan_destroy(th_plan* p) {
     for (int side = 0; side < 2; ++side) {
         if (p->d_partials[side]) (void)hipFree(p->d_partials[side]);
         if (p->d_tile_base[side]) (void)hipFree(p->d_tile_base[side]);
+        if (p->d_expected[side]) (void)hipFree(p->d_expected[side]);
+        if (p->d_arrived[side]) (void)hipFree(p->d_arrived[side]);
+        if (p->d_state[side]) (void)hipFree(p->d_state[side]);
     }
     for (int side = 0; side < 2; ++side) {
         p->tensor_cache[side].release();
@@ -748,6 +825,13 @@ int th_config_set(int key, uint64_t value) {
             }
             g_tuning.tile_bytes_checksum = value;
             return TH_OK;
+        case TH_CFG_TILE_BYTES_PROGRESS:
+            if (value < 4096 || value > 524288 || value % 4096) {
+                set_error("tile bytes must be a multiple of 4096 in [4096, 524288]");
+                return TH_ERR_ARG;
+            }
+            g_tuning.tile_bytes_progress = value;
+            return TH_OK;
         case TH_CFG_TILE_BYTES_ANY:
             if (value < 4096 || value > 524288 || value % 4096) {
                 set_error("tile bytes must be a multiple of 4096 in [4096, 524288]");
@@ -773,7 +857,8 @@ uint64_t th_config_get(int key) {
            : key == TH_CFG_SPECIALIZE ? (uint64_t)g_tuning.specialize
            : key == TH_CFG_TILE_BYTES_CHECKSUM ? g_tuning.tile_bytes_checksum
            : key == TH_CFG_TILE_BYTES_NARROW ? g_tuning.tile_bytes_narrow
-           : key == TH_CFG_PLANNER_THREADS ? g_tuning.planner_threads : 0;
+           : key == TH_CFG_PLANNER_THREADS ? g_tuning.planner_threads
+           : key == TH_CFG_TILE_BYTES_PROGRESS ? g_tuning.tile_bytes_progress : 0;
 }
 
 const char* th_last_error(void) { return g_err; }

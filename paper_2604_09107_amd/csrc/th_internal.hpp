@@ -113,8 +113,10 @@ struct Tuning {
     uint64_t tile_bytes_narrow = 8192;  // any-alignment paths when the copy narrows fp32 to bf16 (8-byte slots)
     uint64_t tile_bytes_checksum = 32768;  // vector path in plans with checksums: two vectors per thread amortise
                                            // the per-wavefront reduction
+    uint64_t tile_bytes_progress = 32768;  // vector path in plans that publish a progress counter
     bool specialize = true;           // launch vector-path tiles with the kernel that holds only that path
     unsigned planner_threads = 3;     // threads that build a large plan's three tile lists (1: the calling thread alone)
+    bool chunk_order = false;         // pack / unpack lists in prefix order (plans that publish a progress counter)
 };
 Tuning current_tuning();
 
@@ -151,12 +153,30 @@ struct InlineWire {
     void* p[kInlineChunks];
     uint32_t n;  // 0: use the device table
 };
+// What a launch needs to know about tile order and progress publishing (by value in the kernel
+// arguments).  ordered: the list is in prefix order, workgroup b runs record b.  arrived != nullptr:
+// the launch counts finished tiles per chunk and publishes the number of leading complete chunks of
+// its range to *flag (device, or pinned host memory).
+constexpr uint32_t kProgressSlots = 16;   // arrival counters per chunk
+constexpr uint32_t kProgressStride = 64;  // uint32 words between two counters (256 bytes)
+constexpr uint32_t kCheckEvery = 128;     // every so many list positions a workgroup tries to publish
+struct Progress {
+    uint32_t* arrived = nullptr;         // device: [chunks of the range][kProgressSlots] counters, kProgressStride apart
+    const uint32_t* expected = nullptr;  // device: per chunk of the plan, the tiles of both path classes
+    uint32_t* state = nullptr;           // device: [0] lock, [1] leading chunks of the range known complete
+    uint64_t* flag = nullptr;            // the caller's counter
+    uint32_t count = 0;                  // chunks in the range
+    uint32_t pos0 = 0;                   // list position of the launch's first tile
+    uint32_t ordered = 0;
+};
 // partials: nullptr, or device array of kPartialsPerTile x list_tiles pairs of uint64, list_tiles
 // being the length of the whole list `tiles`: wavefront w of the workgroup that runs tile i writes
 // the checksum terms (A, B with tile-local positions) of what it moved into pair [w][i].
 int launch_tiles(int mode, int instance, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first,
-                 const InlineWire& inl, uint64_t* partials, uint64_t list_tiles, void* stream);
+                 const InlineWire& inl, uint64_t* partials, uint64_t list_tiles, const Progress& prog, void* stream);
+// Zeroes the counters, the publishing state and the caller's counter of a progress launch.
+int launch_progress_reset(const Progress& prog, void* stream);
 // Adds the per-tile terms of tiles [tile0, tile0 + ntiles) into sums[2 * src_tensor + {0, 1}].
 // vec_only: whether the launch_tiles call that filled the pairs ran a vector-only instance (it fixes
 // the wavefronts per tile).

@@ -100,6 +100,23 @@ __device__ __forceinline__ void st8_as(bool through, gdst_t p, uint32_t lo, uint
     else
         st8(p, lo, hi);
 }
+// Single elements (run edges, alignment gaps).  WT: written through to memory like the full-line
+// stores (an agent-scope store), for launches whose progress counter vouches for every byte of a
+// chunk without a cache write-back.
+template <bool WT>
+__device__ __forceinline__ void st_elem16(gdst_t p, uint16_t v) {
+    if (WT)
+        __hip_atomic_store(reinterpret_cast<TH_GLOBAL uint16_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else
+        *reinterpret_cast<TH_GLOBAL uint16_t*>(p) = v;
+}
+template <bool WT>
+__device__ __forceinline__ void st_elem32(gdst_t p, uint32_t v) {
+    if (WT)
+        __hip_atomic_store(reinterpret_cast<TH_GLOBAL uint32_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else
+        *reinterpret_cast<TH_GLOBAL uint32_t*>(p) = v;
+}
 constexpr uint64_t kLine = 128;  // bytes of a cache line
 // True when consecutive units of a tile land on consecutive bytes that start on a line boundary and
 // stay on line boundaries over row ends: `first` is the address of the tile's first unit, rows hold
@@ -285,11 +302,12 @@ __device__ __forceinline__ void copy_vec_pass(gsrc_t src, gdst_t dst, uint64_t s
 // With VPT = 1 or 2 the stores are left to the caller (late), which issues them as its last
 // instructions; all loads are issued before anything else, in straight-line code (threads past the
 // end load the tile's last vector again and store nothing).
-template <int BT, int SUM, int VPT>
+// WT: every store is written through, whatever the alignment.
+template <int BT, int SUM, int VPT, bool WT>
 __device__ __forceinline__ void copy_vec(gsrc_t src, gdst_t dst, uint64_t ss, uint64_t ds, uint32_t count,
                                          uint32_t vpr, uint32_t col0, uint32_t magic, bool narrow, Sum& acc,
                                          LateStores& late) {
-    const bool through = line_aligned(dst + (size_t)col0 * (narrow ? 8u : 16u), ds, vpr, narrow ? 8u : 16u);
+    const bool through = WT || line_aligned(dst + (size_t)col0 * (narrow ? 8u : 16u), ds, vpr, narrow ? 8u : 16u);
     if (VPT == 1 || VPT == 2) {
         constexpr int N = VPT ? VPT : 1;  // (VPT == 0 never gets here)
         const uint32_t tid = threadIdx.x;
@@ -489,8 +507,8 @@ __device__ __forceinline__ u32x4 gather_slot(gsrc_t src, uint64_t ss, uint32_t n
 // at different times (that showed up as 1.2x the ideal HBM write traffic).
 // rel: byte offset of the slot's element 0 from the tile's wire base when the wire is the destination.
 // through: store policy of the tile's full slots (uniform over the workgroup).
-template <int DES, int SLOT, int SUM>
-__device__ __forceinline__ void commit_slot(const Slot<DES>& s, int64_t rel, Sum& acc, bool through = false) {
+template <int DES, int SLOT, int SUM, bool WT>
+__device__ __forceinline__ void commit_slot(const Slot<DES>& s, int64_t rel, Sum& acc, bool through = WT) {
     constexpr int EPV = SLOT / DES;
     if (SUM == 1) sum_halves(acc, s.o, s.first * DES / 2, s.last * DES / 2, rel / 2);
     if (s.first == 0 && s.last == EPV) {
@@ -504,9 +522,9 @@ __device__ __forceinline__ void commit_slot(const Slot<DES>& s, int64_t rel, Sum
         for (int j = 0; j < EPV; ++j) {
             if (j >= s.first && j < s.last) {
                 if (DES == 4)
-                    *reinterpret_cast<TH_GLOBAL uint32_t*>(s.d + j * DES) = w[j % 4];
+                    st_elem32<WT>(s.d + j * DES, w[j % 4]);
                 else
-                    *reinterpret_cast<TH_GLOBAL uint16_t*>(s.d + j * DES) = (uint16_t)(w[(j / 2) % 4] >> (16 * (j & 1)));
+                    st_elem16<WT>(s.d + j * DES, (uint16_t)(w[(j / 2) % 4] >> (16 * (j & 1))));
             }
         }
     }
@@ -527,7 +545,7 @@ __device__ __forceinline__ void commit_slot(const Slot<DES>& s, int64_t rel, Sum
 // first use, so a pass costs one memory latency.  Rows shorter than a slot, and wrapping slots
 // whose source bytes enter a checksum, take the general loop; the run's partial first and last
 // slot are gathered element by element by one thread each.
-template <int BT, int SES, int DES, int SUM>
+template <int BT, int SES, int DES, int SUM, bool WT>
 __device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, uint32_t count, uint32_t nc,
                                            uint32_t col0, uint32_t magic, bool head_skip, bool tail_ok, Sum& acc) {
     constexpr int SLOT = SlotBytes<SES, DES>::value;
@@ -544,7 +562,7 @@ __device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, 
     const uint32_t tid = threadIdx.x;
     // A tile that starts on a line boundary (the planner cuts a run there when the base pointer is
     // line-aligned) has slot t at dst + t * SLOT, and a wavefront's 64 slots are whole lines.
-    const bool through = (reinterpret_cast<uintptr_t>(dst) & (kLine - 1)) == 0;
+    const bool through = WT || (reinterpret_cast<uintptr_t>(dst) & (kLine - 1)) == 0;
     // element e0 = slot * EPV - lead of the tile -> its row and column in the source rectangle
     auto locate = [&](uint32_t slot, uint32_t skip, uint32_t& row, uint32_t& col) {
         const uint32_t x = col0 + slot * EPV - lead + skip;
@@ -588,7 +606,7 @@ __device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, 
                     s.o = convert_slot<SES, DES>(a);
                     s.d = dst + ((ptrdiff_t)ti * EPV - (ptrdiff_t)lead) * DES;
                     s.first = 0, s.last = EPV;
-                    commit_slot<DES, SLOT, SUM>(s, ((int64_t)ti * EPV - (int64_t)lead) * DES, acc, through);
+                    commit_slot<DES, SLOT, SUM, WT>(s, ((int64_t)ti * EPV - (int64_t)lead) * DES, acc, through);
                 }
             }
         }
@@ -605,7 +623,7 @@ __device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, 
             }
             s.d = dst + ((ptrdiff_t)t * EPV - (ptrdiff_t)lead) * DES;
             s.first = 0, s.last = EPV;
-            commit_slot<DES, SLOT, SUM>(s, ((int64_t)t * EPV - (int64_t)lead) * DES, acc, through);
+            commit_slot<DES, SLOT, SUM, WT>(s, ((int64_t)t * EPV - (int64_t)lead) * DES, acc, through);
         }
     }
 
@@ -621,12 +639,12 @@ __device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, 
         uint32_t row, col;
         locate(t, (uint32_t)s.first, row, col);
         s.o = gather_slot<SES, DES, SUM, false>(src, ss, nc, row, col, s.first, s.last, 0, acc);
-        commit_slot<DES, SLOT, SUM>(s, (int64_t)e0 * DES, acc);
+        commit_slot<DES, SLOT, SUM, WT>(s, (int64_t)e0 * DES, acc);
     }
 }
 
 // Strided destination: each destination row is cut into aligned 16-byte slots of its own.
-template <int BT, int SES, int DES, int SUM>
+template <int BT, int SES, int DES, int SUM, bool WT>
 __device__ __forceinline__ void copy_any(gsrc_t src, gdst_t dst, uint64_t ss, uint64_t ds, uint32_t nrows,
                                          uint32_t ncols, uint32_t lg, Sum& acc) {
     constexpr int SLOT = SlotBytes<SES, DES>::value;
@@ -655,27 +673,76 @@ __device__ __forceinline__ void copy_any(gsrc_t src, gdst_t dst, uint64_t ss, ui
                 q.o = gather_slot<SES, DES, SUM, false>(s, 0, 0xFFFFFFFFu, 0, (uint32_t)(e0 + q.first), q.first,
                                                         q.last, row_rel, acc);
             // wire = destination: the slot's element 0 sits e0 elements into the destination row
-            commit_slot<DES, SLOT, SUM>(q, (int64_t)r * (int64_t)ds + (int64_t)e0 * DES, acc);
+            commit_slot<DES, SLOT, SUM, WT>(q, (int64_t)r * (int64_t)ds + (int64_t)e0 * DES, acc);
         }
     }
 }
 
+// ---- progress counter ----------------------------------------------------------------------------
+//
+// A launch over a chunk range can publish how many leading chunks of the range are complete while
+// it is still running (the paper's progress counter, Sec. 4.3.3: a reader consumes the prefix that
+// has arrived).  The tile list of such a plan is in prefix order (workgroup b runs record b; see the
+// planner), so chunks finish roughly in order.
+//
+//   arrival   When every wavefront of a workgroup has seen its stores acknowledged (in such a launch
+//             every store is written through to memory, also the part-line ones that otherwise
+//             stay in this XCD's L2), one lane adds 1 to a counter of the tile's chunk.  The add returns nothing, so nobody
+//             waits for it.  A chunk has kProgressSlots counters, 256 bytes apart, picked by list
+//             position, so that no single address takes every arrival.
+//   publish   Every kCheckEvery-th workgroup, while its own loads are in flight, tries a lock
+//             (one attempt, never a spin); the holder walks the prefix forward over every chunk
+//             whose counters add up to the chunk's tile count, stores the new value to the caller's
+//             counter and opens the lock.  Stores to the caller's counter happen only under the
+//             lock, in increasing order; the host enqueues a final store of the range's length
+//             behind the launch, which covers the chunks whose last tiles no later workgroup saw.
+// All control words are read and written with agent-scope atomics (they bypass the per-XCD L2).
+__device__ __forceinline__ uint32_t agent_load(const uint32_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void advance_prefix(const Progress& pr, uint32_t first_chunk) {
+    uint32_t open = 0;
+    if (!__hip_atomic_compare_exchange_strong(&pr.state[0], &open, 1u, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT))
+        return;  // somebody else is publishing
+    const uint32_t p0 = agent_load(&pr.state[1]);
+    uint32_t p = p0;
+    while (p < pr.count) {
+        uint32_t sum = 0;
+#pragma unroll
+        for (uint32_t sl = 0; sl < kProgressSlots; ++sl)
+            sum += agent_load(&pr.arrived[((size_t)p * kProgressSlots + sl) * kProgressStride]);
+        if (sum != pr.expected[first_chunk + p]) break;
+        ++p;
+    }
+    if (p != p0) {
+        __hip_atomic_store(&pr.state[1], p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(pr.flag, (uint64_t)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    // release: the store to the caller's counter has been performed before the lock opens, so the
+    // next holder's store cannot overtake it
+    __hip_atomic_store(&pr.state[0], 0u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // INLINE: the wire pointers come from the kernel arguments (short chunk ranges) instead of the table.
-template <int MODE, int VEC, bool CHECKSUM, bool INLINE>
+// PROGRESS: the launch counts finished tiles per chunk and publishes the complete prefix (above).
+template <int MODE, int VEC, bool CHECKSUM, bool INLINE, bool PROGRESS>
 __global__ __launch_bounds__(VEC ? kBlockThreads : kBlockThreadsAny, TH_MIN_WAVES_PER_EU) void th_tiles_kernel(const Tile* __restrict__ tiles,
                                                                   const void* const* __restrict__ src_table,
                                                                   void* const* __restrict__ dst_table,
                                                                   uint32_t wire_first, uint32_t partial_stride,
-                                                                  InlineWire inl, uint64_t* __restrict__ partials) {
+                                                                  InlineWire inl, uint64_t* __restrict__ partials,
+                                                                  Progress prog) {
     // Workgroups are dealt to the 8 XCDs round-robin (workgroup b runs on XCD b mod 8).  Give
     // each XCD one contiguous eighth of the tile list so that it streams through its own
     // address range instead of every 8th tile.
     constexpr bool VEC_ONLY = VEC != VEC_ALL_PATHS;
     constexpr int BT = VEC_ONLY ? kBlockThreads : kBlockThreadsAny;
     constexpr int VPT = VEC == VEC_ONE ? 1 : VEC == VEC_TWO ? 2 : 0;
+    // (A list in prefix order has that arrangement built in, chunk by chunk: record b is workgroup b's.)
     uint32_t b = blockIdx.x;
     const uint32_t per_xcd = gridDim.x >> 3;
-    if (b < per_xcd * 8) b = (b & 7) * per_xcd + (b >> 3);
+    if (!prog.ordered && b < per_xcd * 8) b = (b & 7) * per_xcd + (b >> 3);
 
     const Tile& t = tiles[b];  // uniform: fetched by the scalar unit
     const uint32_t flags = t.flags;
@@ -710,42 +777,47 @@ __global__ __launch_bounds__(VEC ? kBlockThreads : kBlockThreadsAny, TH_MIN_WAVE
         ahead = *(const TH_GLOBAL uint32_t*)next;
     }
 
+    // publishing runs where it hides best: behind the tile's loads when they are all issued up front
+    // (one or two vectors per thread), else before the copy
+    const bool publisher = PROGRESS && threadIdx.x == 0 && ((prog.pos0 + b) & (kCheckEvery - 1)) == 0;
+    if (publisher && !(VPT && kind == TILE_KIND_VEC)) advance_prefix(prog, wire_first);
     if (kind == TILE_KIND_VEC) {
         const bool narrow = (flags & TILE_SRC_F32) && !(flags & TILE_DST_F32);
-        copy_vec<BT, SUM, VPT>(src, dst, ss, ds, count, ncols, col0, magic, narrow, acc, late);
+        copy_vec<BT, SUM, VPT, PROGRESS>(src, dst, ss, ds, count, ncols, col0, magic, narrow, acc, late);
+        if (publisher && VPT) advance_prefix(prog, wire_first);
     } else if (kind == TILE_KIND_DENSE) {
         const bool head_skip = (flags & TILE_HEAD_SKIP) != 0, tail_ok = (flags & TILE_TAIL_OK) != 0;
         unsigned des = 2;
         if (flags & TILE_DST_F32) {
-            copy_dense<BT, 4, 4, SUM>(src, dst, ss, count, ncols, col0, magic, head_skip, tail_ok, acc);
+            copy_dense<BT, 4, 4, SUM, PROGRESS>(src, dst, ss, count, ncols, col0, magic, head_skip, tail_ok, acc);
             des = 4;
         } else if (flags & TILE_SRC_F32) {
-            copy_dense<BT, 4, 2, SUM>(src, dst, ss, count, ncols, col0, magic, head_skip, tail_ok, acc);
+            copy_dense<BT, 4, 2, SUM, PROGRESS>(src, dst, ss, count, ncols, col0, magic, head_skip, tail_ok, acc);
         } else {
-            copy_dense<BT, 2, 2, SUM>(src, dst, ss, count, ncols, col0, magic, head_skip, tail_ok, acc);
+            copy_dense<BT, 2, 2, SUM, PROGRESS>(src, dst, ss, count, ncols, col0, magic, head_skip, tail_ok, acc);
         }
         if (PACK) {
             // zero the alignment gap that follows a tensor's last element on the wire
             const uint32_t pad = (flags & TILE_PAD_MASK) >> TILE_PAD_SHIFT;
             if (threadIdx.x * 2 < pad)
-                *reinterpret_cast<TH_GLOBAL uint16_t*>(dst + (size_t)count * des + threadIdx.x * 2) = 0;
+                st_elem16<PROGRESS>(dst + (size_t)count * des + threadIdx.x * 2, 0);
         }
     } else {
         const uint32_t lg = (flags & TILE_LG_LANES_MASK) >> TILE_LG_LANES_SHIFT;
         unsigned des = 2;
         if (flags & TILE_DST_F32) {
-            copy_any<BT, 4, 4, SUM>(src, dst, ss, ds, count, ncols, lg, acc);
+            copy_any<BT, 4, 4, SUM, PROGRESS>(src, dst, ss, ds, count, ncols, lg, acc);
             des = 4;
         } else if (flags & TILE_SRC_F32) {
-            copy_any<BT, 4, 2, SUM>(src, dst, ss, ds, count, ncols, lg, acc);
+            copy_any<BT, 4, 2, SUM, PROGRESS>(src, dst, ss, ds, count, ncols, lg, acc);
         } else {
-            copy_any<BT, 2, 2, SUM>(src, dst, ss, ds, count, ncols, lg, acc);
+            copy_any<BT, 2, 2, SUM, PROGRESS>(src, dst, ss, ds, count, ncols, lg, acc);
         }
         if (PACK) {
             const uint32_t pad = (flags & TILE_PAD_MASK) >> TILE_PAD_SHIFT;
             if (threadIdx.x * 2 < pad) {
                 gdst_t end = dst + (size_t)(count - 1) * ds + (size_t)ncols * des;
-                *reinterpret_cast<TH_GLOBAL uint16_t*>(end + threadIdx.x * 2) = 0;
+                st_elem16<PROGRESS>(end + threadIdx.x * 2, 0);
             }
         }
     }
@@ -767,6 +839,31 @@ __global__ __launch_bounds__(VEC ? kBlockThreads : kBlockThreadsAny, TH_MIN_WAVE
                     st16_as(late.through, late.p[u], late.v[u]);
             }
         }
+    }
+    if (PROGRESS) {
+        // arrival: after every wavefront of the workgroup has had its stores acknowledged.  Every store
+        // of such a launch is written through to memory, so an acknowledged store is visible to
+        // everyone and no cache has to be written back.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const uint32_t chunk = (MODE == MODE_PACK ? t.dst_buf : t.src_buf) - wire_first;
+            const uint32_t slot = (prog.pos0 + b) & (kProgressSlots - 1);
+            __hip_atomic_fetch_add(&prog.arrived[((size_t)chunk * kProgressSlots + slot) * kProgressStride], 1u,
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// Clears the arrival counters and the publishing state of a progress launch and sets the caller's
+// counter to zero (a kernel, not a memset: the call may be recorded into a graph).
+__global__ __launch_bounds__(256) void th_progress_reset_kernel(Progress prog) {
+    const uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i < prog.count * kProgressSlots) prog.arrived[(size_t)i * kProgressStride] = 0;
+    if (i == 0) {
+        prog.state[0] = 0;
+        prog.state[1] = 0;
+        __hip_atomic_store(prog.flag, (uint64_t)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
 
@@ -932,16 +1029,29 @@ int stage_static_tables(const void* const* tensor_ptrs, uint32_t n_tensors, cons
     return TH_OK;
 }
 
+int launch_progress_reset(const Progress& prog, void* stream) {
+    const uint32_t n = prog.count * kProgressSlots;
+    hipLaunchKernelGGL(th_progress_reset_kernel, dim3((n + 255) / 256 ? (n + 255) / 256 : 1), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), prog);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("kernel launch failed: %s", hipGetErrorString(e));
+        return TH_ERR_HIP;
+    }
+    return TH_OK;
+}
+
 int launch_tiles(int mode, int instance, const Tile* tiles, uint64_t tile0, uint64_t ntiles,
                  const void* const* src_table, void* const* dst_table, uint32_t wire_first, const InlineWire& inl,
-                 uint64_t* partials, uint64_t list_tiles, void* stream) {
+                 uint64_t* partials, uint64_t list_tiles, const Progress& prog, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     constexpr uint64_t kMaxGrid = 1u << 30;
-    typedef void (*kernel_t)(const Tile*, const void* const*, void* const*, uint32_t, uint32_t, InlineWire, uint64_t*);
+    typedef void (*kernel_t)(const Tile*, const void* const*, void* const*, uint32_t, uint32_t, InlineWire, uint64_t*,
+                             Progress);
     // [mode][instance][checksum][inline wire pointers]
-#define TH_K(M, V) {{th_tiles_kernel<M, V, false, false>, th_tiles_kernel<M, V, false, true>}, \
-                    {th_tiles_kernel<M, V, true, false>, th_tiles_kernel<M, V, true, true>}}
-#define TH_KD(V) {{th_tiles_kernel<MODE_DIRECT, V, false, false>, nullptr}, {nullptr, nullptr}}
+#define TH_K(M, V) {{th_tiles_kernel<M, V, false, false, false>, th_tiles_kernel<M, V, false, true, false>}, \
+                    {th_tiles_kernel<M, V, true, false, false>, th_tiles_kernel<M, V, true, true, false>}}
+#define TH_KD(V) {{th_tiles_kernel<MODE_DIRECT, V, false, false, false>, nullptr}, {nullptr, nullptr}}
     static const kernel_t kernels[3][4][2][2] = {
         {TH_K(MODE_PACK, VEC_ALL_PATHS), TH_K(MODE_PACK, VEC_ONE), TH_K(MODE_PACK, VEC_TWO), TH_K(MODE_PACK, VEC_ANY)},
         {TH_K(MODE_UNPACK, VEC_ALL_PATHS), TH_K(MODE_UNPACK, VEC_ONE), TH_K(MODE_UNPACK, VEC_TWO),
@@ -949,21 +1059,33 @@ int launch_tiles(int mode, int instance, const Tile* tiles, uint64_t tile0, uint
         {TH_KD(VEC_ALL_PATHS), TH_KD(VEC_ONE), TH_KD(VEC_TWO), TH_KD(VEC_ANY)}};
 #undef TH_K
 #undef TH_KD
+    // launches that publish progress: [mode][instance], no checksum, wire pointers from the table
+#define TH_KP(M) {th_tiles_kernel<M, VEC_ALL_PATHS, false, false, true>, th_tiles_kernel<M, VEC_ONE, false, false, true>, \
+                  th_tiles_kernel<M, VEC_TWO, false, false, true>, th_tiles_kernel<M, VEC_ANY, false, false, true>}
+    static const kernel_t progress_kernels[2][4] = {TH_KP(MODE_PACK), TH_KP(MODE_UNPACK)};
+#undef TH_KP
     if (instance < 0 || instance > VEC_ANY) {
         set_error("no such instance of the tile kernel");
         return TH_ERR_ARG;
     }
     const bool vec_only = instance != VEC_ALL_PATHS;
-    const kernel_t kernel = kernels[mode][instance][partials ? 1 : 0][inl.n ? 1 : 0];
+    const bool counting = prog.arrived != nullptr;
+    kernel_t kernel = nullptr;
+    if (!counting)
+        kernel = kernels[mode][instance][partials ? 1 : 0][inl.n ? 1 : 0];
+    else if (mode != MODE_DIRECT && !partials && !inl.n)
+        kernel = progress_kernels[mode][instance];
     if (!kernel) {
         set_error("no such variant of the tile kernel");
         return TH_ERR_ARG;
     }
+    Progress pr = prog;
     while (ntiles) {
         const uint64_t n = ntiles < kMaxGrid ? ntiles : kMaxGrid;
+        pr.pos0 = (uint32_t)tile0;  // low bits of the list position pick counter slots and publishers
         hipLaunchKernelGGL(kernel, dim3((uint32_t)n), dim3(vec_only ? kBlockThreads : kBlockThreadsAny), 0, st,
                            tiles + tile0, src_table, dst_table, wire_first, (uint32_t)list_tiles, inl,
-                           partials ? partials + 2 * tile0 : nullptr);
+                           partials ? partials + 2 * tile0 : nullptr, pr);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) {
             set_error("kernel launch failed: %s", hipGetErrorString(e));

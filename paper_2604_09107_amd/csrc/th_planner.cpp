@@ -403,6 +403,29 @@ static int finish_manifest_impl(Manifest& m, uint64_t CB, bool ptrs_aligned16, c
             m.tiles[side].insert(m.tiles[side].end(), tiles[1].begin(), tiles[1].end());
             m.tile_base[side].insert(m.tile_base[side].end(), base[1].begin(), base[1].end());
         }
+        if (tune.chunk_order) {
+            // Prefix order: workgroup b of a launch runs the record at list position b, and workgroups
+            // are dealt to the 8 XCDs round-robin.  Inside every chunk, the positions that fall to one
+            // XCD (equal position mod 8) get consecutive tiles of the chunk, so each XCD still streams
+            // through a contiguous piece, and the chunks of a launch finish roughly in order.
+            std::vector<Tile>& list = m.tiles[side];
+            std::vector<uint64_t>& bases = m.tile_base[side];
+            std::vector<Tile> tmp;
+            std::vector<uint64_t> tmp_base;
+            for (unsigned k = 0; k < 2; ++k)
+                for (size_t c = 0; c < m.n_chunks; ++c) {
+                    const uint64_t t0 = m.chunk_tile0[side][k][c], t1 = m.chunk_tile0[side][k][c + 1];
+                    if (t1 - t0 < 2) continue;
+                    tmp.assign(list.begin() + t0, list.begin() + t1);
+                    tmp_base.assign(bases.begin() + t0, bases.begin() + t1);
+                    uint64_t from = 0;
+                    for (uint64_t x = 0; x < 8; ++x)
+                        for (uint64_t pos = t0 + ((x + 8 - (t0 & 7)) & 7); pos < t1; pos += 8, ++from) {
+                            list[pos] = tmp[from];
+                            bases[pos] = tmp_base[from];
+                        }
+                }
+        }
     };
 
     // direct list: holder tensors -> reader tensors without the wire, one pass over the segments

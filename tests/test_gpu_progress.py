@@ -1,0 +1,209 @@
+"""The progress counter that one launch advances while it runs (th_pack_progress /
+th_unpack_progress): results bit for bit against the oracle, and the counter's contract observed
+from the host - it starts at 0, only grows, ends at the number of chunks, and a chunk below the
+counter is complete at the moment the host sees the counter pass it."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import synth
+import paper_2604_09107_amd as th
+from paper_2604_09107_amd import device as dev
+from oracle import layouts, reshard
+from helpers import holder_tensors_cpu
+
+pytestmark = pytest.mark.gpu
+
+SENT8, SENT16 = 0xEE, 0xA5C3
+
+
+def to_dev(bits2d):
+    return synth.from_bits(np.ascontiguousarray(bits2d).reshape(-1), "cuda")
+
+
+def host_counter():
+    t = torch.full((1,), -1, dtype=torch.int64, pin_memory=True)
+    return t, t.numpy()
+
+
+@pytest.mark.parametrize("name,chunk_bytes", [("cfg1_tiny_tp2_to_tp1", 64 * 1024), ("small_dense_tp1_to_tp4", 32 * 1024),
+                                              ("small_dense_tp4_to_tp2", 16 * 1024), ("small_moe_ep4_to_tp2", 16 * 1024),
+                                              ("small_dense_trainer_to_rollout", 48 * 1024)])
+@pytest.mark.parametrize("where", ["pinned_host", "device"])
+def test_progress_calls_move_what_the_oracle_says(name, chunk_bytes, where):
+    """Every holder of the workload through th_pack_progress / th_unpack_progress (all chunks, then
+    two sub-ranges), wire and reader tensors against the oracle; the counter ends at the range's
+    length.  Plain th_pack / th_unpack on the same plan (prefix-ordered lists) give the same bytes."""
+    w = synth.workload(name)
+    model, dst = w["model"], w["reader"]
+    stream = dev.current_stream()
+    want = reshard.empty_tensors(model, dst, fill=SENT16)
+    for t, x in zip(layouts.registered_tensors(model, dst), want):
+        if t["dtype"] == "f32":
+            x[...] = SENT16 * 0x10001
+    dst_dev = dst_plain = None
+    keep, view = host_counter()
+    dev_flag = torch.full((2,), -1, dtype=torch.int64, device="cuda")
+    flag_ptr = keep.data_ptr() if where == "pinned_host" else dev_flag.data_ptr()
+
+    def flag_value():
+        return int(view[0]) if where == "pinned_host" else int(dev_flag[0].item())
+
+    for src in w["holders"]:
+        plan = th.th_plan_create(model, src, dst, chunk_bytes, th.TH_FLAG_PROGRESS)
+        tensors = holder_tensors_cpu(model, src, w["seed"], pattern=True)
+        src_dev = [to_dev(t) for t in tensors]
+        if dst_dev is None:
+            dst_dev = dev.alloc_tensors(plan, 1, fill_bits=SENT16)
+            dst_plain = dev.alloc_tensors(plan, 1, fill_bits=SENT16)
+        n = plan.num_chunks
+        assert n >= 12
+        wire = reshard.pack(model, src, dst, tensors)
+        reshard.unpack(model, src, dst, wire, want)
+        # all chunks in one call
+        wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=SENT8)
+        th.th_pack_progress(plan, dev.ptrs(src_dev), wptrs, 0, n, flag_ptr, stream)
+        torch.cuda.synchronize()
+        assert flag_value() == n
+        assert np.array_equal(wire_dev.cpu().numpy()[:plan.wire_bytes], wire)
+        # two sub-ranges, the second first
+        wire2, wptrs2 = dev.alloc_wire(plan, fill_byte=SENT8)
+        cut = n // 3
+        th.th_pack_progress(plan, dev.ptrs(src_dev), wptrs2[cut:], cut, n - cut, flag_ptr, stream)
+        torch.cuda.synchronize()
+        assert flag_value() == n - cut
+        assert bool((wire2[:cut * chunk_bytes] == SENT8).all())
+        th.th_pack_progress(plan, dev.ptrs(src_dev), wptrs2[:cut], 0, cut, flag_ptr, stream)
+        torch.cuda.synchronize()
+        assert flag_value() == cut
+        assert torch.equal(wire2, wire_dev)
+        # unpack with progress: a range, then the rest
+        th.th_unpack_progress(plan, wptrs[cut:], cut, n - cut, dev.ptrs(dst_dev), flag_ptr, stream)
+        torch.cuda.synchronize()
+        assert flag_value() == n - cut
+        th.th_unpack_progress(plan, wptrs[:cut], 0, cut, dev.ptrs(dst_dev), flag_ptr, stream)
+        torch.cuda.synchronize()
+        assert flag_value() == cut
+        # the plain calls on the prefix-ordered plan
+        wire3, wptrs3 = dev.alloc_wire(plan, fill_byte=SENT8)
+        th.th_pack(plan, dev.ptrs(src_dev), wptrs3, 0, n, stream)
+        th.th_unpack(plan, wptrs3, 0, n, dev.ptrs(dst_plain), stream)
+        torch.cuda.synchronize()
+        assert torch.equal(wire3, wire_dev)
+        # an empty range completes at once
+        th.th_pack_progress(plan, dev.ptrs(src_dev), wptrs[:0], n, 0, flag_ptr, stream)
+        torch.cuda.synchronize()
+        assert flag_value() == 0
+        plan.destroy()
+    for g, p, x in zip(dst_dev, dst_plain, want):
+        assert np.array_equal(synth.to_bits(g), x.reshape(-1))
+        assert np.array_equal(synth.to_bits(p), x.reshape(-1))
+
+
+def test_counter_seen_from_the_host_during_one_launch():
+    """The MoE-shaped reshard (693 chunks of 4 MiB, about 350,000 tiles) packed by one call while the
+    host polls the counter in pinned memory.  Whenever the counter has moved, the newest chunk below
+    it is copied to the host at once, on another stream, while the launch is still running: the copy
+    must already hold the chunk's final bytes."""
+    w = synth.workload("cfg4_moe_ep8_to_tp2")
+    model, src, dst = w["model"], w["holders"][0], w["reader"]
+    stream = dev.current_stream()
+    plan = th.th_plan_create(model, src, dst, w["chunk_bytes"], th.TH_FLAG_PROGRESS)
+    plain = th.th_plan_create(model, src, dst, w["chunk_bytes"])
+    n, cb = plan.num_chunks, plan.chunk_bytes(0)
+    src_dev = [synth.weight_values(t["rows"] * t["cols"], t["dtype"], w["seed"] * 16, i, "cuda",
+                                   is_norm="norm" in t["name"]) for i, t in enumerate(plan.tensors(0))]
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=SENT8)
+    ref_dev, rptrs = dev.alloc_wire(plain, fill_byte=SENT8)
+    th.th_pack(plain, dev.ptrs(src_dev), rptrs, 0, n, stream)       # the reference wire (itself checked against the
+    torch.cuda.synchronize()                                        # oracle by the full-size parity tests)
+    keep, view = host_counter()
+    side = torch.cuda.Stream()
+    grabbed = torch.empty((64, cb), dtype=torch.uint8, pin_memory=True)
+    seen, taken = [], []
+    for attempt in range(3):                                        # the first call also uploads the pointer tables
+        wire_dev.fill_(SENT8)
+        torch.cuda.synchronize()
+        seen, taken = [], []
+        view[0] = -1
+        th.th_pack_progress(plan, dev.ptrs(src_dev), wptrs, 0, n, keep.data_ptr(), stream)
+        deadline = time.perf_counter() + 20.0
+        last = -1
+        while last < n and time.perf_counter() < deadline:
+            v = int(view[0])
+            if v != last:
+                seen.append(v)
+                if v > 0 and len(taken) < grabbed.shape[0]:
+                    c = v - 1                                       # complete, says the counter
+                    with torch.cuda.stream(side):
+                        grabbed[len(taken), :plan.chunk_bytes(c)].copy_(
+                            wire_dev[c * cb:c * cb + plan.chunk_bytes(c)], non_blocking=True)
+                    taken.append(c)
+                last = v
+        torch.cuda.synchronize()
+        assert last == n, "the counter stopped at %d of %d" % (last, n)
+        if len(seen) > 8:
+            break
+    print("[progress] counter values seen by the host: %d distinct, first %s, chunks copied early: %d" % (
+        len(seen), seen[:6], len(taken)), flush=True)
+    assert seen[0] in (-1, 0) and seen[-1] == n
+    assert all(b > a for a, b in zip(seen, seen[1:])), "the counter went backwards"
+    assert len(seen) > 8, "the host never saw the launch in flight: %s" % seen
+    assert torch.equal(wire_dev, ref_dev)
+    ref = ref_dev.cpu().numpy()
+    for k, c in enumerate(taken):
+        nb = plan.chunk_bytes(c)
+        assert np.array_equal(grabbed[k, :nb].numpy(), ref[c * cb:c * cb + nb]), \
+            "chunk %d was reported complete before its bytes were there" % c
+    # whole tensors, the paper's unit
+    assert plan.tensors_complete(n) == plan.num_tensors(0)
+    assert 0 < plan.tensors_complete(n // 2) < plan.num_tensors(0)
+    # the unpack side: counter contract and reader tensors equal to the plain calls'
+    dst_dev = dev.alloc_tensors(plan, 1, fill_bits=SENT16)
+    dst_ref = dev.alloc_tensors(plain, 1, fill_bits=SENT16)
+    th.th_unpack(plain, rptrs, 0, n, dev.ptrs(dst_ref), stream)
+    torch.cuda.synchronize()
+    view[0] = -1
+    th.th_unpack_progress(plan, wptrs, 0, n, dev.ptrs(dst_dev), keep.data_ptr(), stream)
+    seen_u, last = [], -1
+    deadline = time.perf_counter() + 20.0
+    while last < n and time.perf_counter() < deadline:
+        v = int(view[0])
+        if v != last:
+            seen_u.append(v)
+            last = v
+    torch.cuda.synchronize()
+    assert last == n and all(b > a for a, b in zip(seen_u, seen_u[1:]))
+    for a, b in zip(dst_dev, dst_ref):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    plan.destroy()
+    plain.destroy()
+
+
+def test_argument_errors():
+    w = synth.workload("cfg1_tiny_tp2_to_tp1")
+    model, src, dst = w["model"], w["holders"][0], w["reader"]
+    stream = dev.current_stream()
+    plain = th.th_plan_create(model, src, dst, 1 << 16)
+    plan = th.th_plan_create(model, src, dst, 1 << 16, th.TH_FLAG_PROGRESS)
+    src_dev = [to_dev(t) for t in holder_tensors_cpu(model, src, w["seed"], pattern=True)]
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=SENT8)
+    flag = torch.zeros(2, dtype=torch.int64, device="cuda")
+    with pytest.raises(th.ThError) as e:
+        th.th_pack_progress(plain, dev.ptrs(src_dev), wptrs, 0, plan.num_chunks, flag.data_ptr(), stream)
+    assert e.value.code == -1 and "TH_FLAG_PROGRESS" in str(e.value)
+    with pytest.raises(th.ThError) as e:
+        th.th_pack_progress(plan, dev.ptrs(src_dev), wptrs, 0, plan.num_chunks, flag.data_ptr() + 4, stream)
+    assert e.value.code == -1
+    with pytest.raises(th.ThError) as e:
+        th.th_unpack_progress(plan, wptrs, 0, plan.num_chunks, dev.ptrs(src_dev)[:1], 0, stream)
+    assert e.value.code == -1
+    with pytest.raises(th.ThError) as e:
+        th.th_pack_progress(plan, dev.ptrs(src_dev), wptrs[:1], plan.num_chunks, 1, flag.data_ptr(), stream)
+    assert e.value.code == -4
+    torch.cuda.synchronize()
+    assert bool((wire_dev == SENT8).all())
+    plan.destroy()
+    plain.destroy()

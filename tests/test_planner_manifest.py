@@ -437,3 +437,49 @@ def test_tiles_of_a_contiguous_destination_start_on_cache_lines(flags):
             prev = key
         assert later > 50
     plan.destroy()
+
+
+@pytest.mark.parametrize("name,chunk_bytes,tile_bytes", [("small_dense_tp1_to_tp4", 128 * 1024, 4096),
+                                                        ("small_moe_ep4_to_tp2", 64 * 1024, 4096),
+                                                        ("small_dense_tp4_to_tp2", 256 * 1024, 16384)])
+def test_prefix_ordered_lists_hold_the_same_tiles_chunk_by_chunk(name, chunk_bytes, tile_bytes):
+    """A plan that can publish progress keeps every chunk's tiles in that chunk's list positions
+    (so chunks finish in order) and, inside a chunk, gives the positions that fall to one XCD
+    (equal position mod 8) consecutive tiles.  The lists still reproduce the oracle's wire and the
+    tile checksum bases move with their tiles."""
+    w = synth.workload(name)
+    model, src, dst = w["model"], w["holders"][0], w["reader"]
+    with tile_sizes(tile_bytes):
+        th.th_config_set(th.TH_CFG_TILE_BYTES_PROGRESS, tile_bytes)
+        try:
+            plain = th.th_plan_create(model, src, dst, chunk_bytes, HOST)
+            ordered = th.th_plan_create(model, src, dst, chunk_bytes, HOST | th.TH_FLAG_PROGRESS)
+        finally:
+            th.th_config_set(th.TH_CFG_TILE_BYTES_PROGRESS, 16384)
+    tensors = holder_tensors_cpu(model, src, w["seed"], pattern=True)
+    want_chunks = reshard.chunks(reshard.pack(model, src, dst, tensors), chunk_bytes)
+    moved = 0
+    for side in (0, 1):
+        assert ordered.num_tiles(side) == plain.num_tiles(side)
+        for k in (0, 1):
+            for c in range(plain.num_chunks):
+                t0, t1 = plain.chunk_first_tile(side, k, c), plain.chunk_first_tile(side, k, c + 1)
+                assert (t0, t1) == (ordered.chunk_first_tile(side, k, c), ordered.chunk_first_tile(side, k, c + 1))
+                a = [bytes(plain.tile(side, i)) for i in range(t0, t1)]
+                b = [bytes(ordered.tile(side, i)) for i in range(t0, t1)]
+                # positions of XCD 0 (in order), then those of XCD 1, ... give back the chunk's tiles in order
+                dealt = [b[p - t0] for x in range(8) for p in range(t0, t1) if p % 8 == x]
+                assert dealt == a
+                moved += a != b
+    assert moved > 0
+    tchunks = [np.full(len(c), 0xEE, dtype=np.uint8) for c in want_chunks]
+    exec_tiles(ordered, 0, flat_u8(tensors), tchunks)
+    for c, (g, x) in enumerate(zip(tchunks, want_chunks)):
+        assert np.array_equal(g, x), "chunk %d" % c
+    got = tile_checksums(ordered, 0, want_chunks, ordered.num_tensors(0))
+    assert np.array_equal(got, tile_checksums(plain, 0, want_chunks, plain.num_tensors(0)))
+    # the wire-free list is not divided by chunk and keeps its order
+    assert [bytes(ordered.tile(2, i)) for i in range(ordered.num_tiles(2))] == \
+           [bytes(plain.tile(2, i)) for i in range(plain.num_tiles(2))]
+    plain.destroy()
+    ordered.destroy()
