@@ -298,7 +298,8 @@ def measure(args, name, extras, want_cpu_baseline, mods):
                    "resident_bytes": resident_bytes(jobs),
                    "tile_bytes": th.th_config_get(th.TH_CFG_TILE_BYTES),
                    "tile_bytes_any": th.th_config_get(th.TH_CFG_TILE_BYTES_ANY),
-                   "tile_bytes_narrow": th.th_config_get(th.TH_CFG_TILE_BYTES_NARROW)},
+                   "tile_bytes_narrow": th.th_config_get(th.TH_CFG_TILE_BYTES_NARROW),
+                   "short_tile_slots": th.th_config_get(th.TH_CFG_SHORT_TILE_SLOTS)},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "plan_ms": round(plan_ms, 3),
         "kernels": {"th_pack": {"ms": round(pack_ms, 4), "GB/s": round(k_pack, 1),
@@ -537,6 +538,8 @@ def main():
     ap.add_argument("--no-specialize", action="store_true", help="always launch the all-paths kernel")
     ap.add_argument("--tile-bytes-any", type=int, default=0, help="override the any-alignment tile size")
     ap.add_argument("--tile-bytes-narrow", type=int, default=0, help="override the tile size of narrowing copies")
+    ap.add_argument("--short-slots", type=int, default=-1,
+                    help="override the largest tile (in destination slots) that runs on one wavefront")
     ap.add_argument("--tile-bytes-checksum", type=int, default=0,
                     help="override the vector-path tile size of checksum plans")
     args = ap.parse_args()
@@ -580,6 +583,8 @@ def main():
         th.th_config_set(th.TH_CFG_TILE_BYTES_NARROW, args.tile_bytes_narrow)
     if args.tile_bytes_checksum:
         th.th_config_set(th.TH_CFG_TILE_BYTES_CHECKSUM, args.tile_bytes_checksum)
+    if args.short_slots >= 0:
+        th.th_config_set(th.TH_CFG_SHORT_TILE_SLOTS, args.short_slots)
     # one throw-away plan first: the process's first HIP call loads the library's code object
     # (~0.1 s, once per process), which is not part of creating a plan
     w0 = synth.workload("cfg1_tiny_tp2_to_tp1")

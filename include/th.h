@@ -334,9 +334,13 @@ int th_plan_get_run(const th_plan* plan, size_t i, th_run* out);
 
 /* The device work list, for inspection.  side 0 = th_pack's tiles, 1 =
  * th_unpack's, 2 = th_reshard's (src_buf = source tensor id, dst_buf = destination
- * tensor id; not divided by chunk).  A side's list holds first every tile of the 16-byte vector path
- * (path class 0), then every other tile (class 1), each sub-list ordered by
- * chunk, so a chunk range is at most two launches.  A tile is one workgroup's share of a
+ * tensor id; not divided by chunk).  A side's list holds first the tiles of runs on the 16-byte
+ * vector path (path class 0), then those of the other runs (class 1), then those of short runs of
+ * either kind (class 2: runs of at most TH_CFG_SHORT_TILE_SLOTS 16-byte vectors or destination
+ * slots of 16 bytes, 8 when narrowing; each of their tiles runs on one wavefront, so that thousands of
+ * small tensors batched into one launch keep every wavefront slot busy, which is what the paper's
+ * Tiny-Tensor Optimization is after, Sec. 4.3.2), each sub-list ordered by chunk, so a chunk range
+ * is at most three launches.  A tile is one workgroup's share of a
  * run, described as a copy from (src_buf, src_byte_off) to (dst_buf,
  * dst_byte_off).  For side 0 src_buf is a source tensor id and dst_buf a chunk
  * index; for side 1 src_buf is a chunk index and dst_buf a destination tensor
@@ -361,7 +365,7 @@ typedef struct th_tile_info {
 } th_tile_info;
 size_t th_plan_num_tiles(const th_plan* plan, int side);
 int th_plan_get_tile(const th_plan* plan, int side, size_t i, th_tile_info* out);
-/* index (into the side's list) of the first tile of `chunk` within sub-list `path_class`;
+/* index (into the side's list) of the first tile of `chunk` within sub-list `path_class` (0..2);
  * chunk == num_chunks gives the end of that sub-list */
 size_t th_plan_chunk_first_tile(const th_plan* plan, int side, int path_class, uint32_t chunk);
 
@@ -387,6 +391,9 @@ enum {
                                   contains only that path */
     TH_CFG_TILE_BYTES_PROGRESS = 7, /* vector-path tile size in plans created with TH_FLAG_PROGRESS;
                                        default 32768 (amortises the wait for the stores' acknowledgements) */
+    TH_CFG_SHORT_TILE_SLOTS = 8, /* largest run, in 16-byte vectors / destination slots, whose tiles run on
+                                    one wavefront instead of a workgroup of 512 or 1024 threads;
+                                    default 512, 0 = none */
     TH_CFG_PLANNER_THREADS = 6 /* 1..3 (default 3): host threads that build the tile lists of a large plan;
                                   1 = the calling thread alone (also what happens when a thread cannot
                                   be started) */

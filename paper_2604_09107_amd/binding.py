@@ -21,6 +21,7 @@ TH_CFG_TILE_BYTES_CHECKSUM = 4
 TH_CFG_TILE_BYTES_NARROW = 5
 TH_CFG_PLANNER_THREADS = 6
 TH_CFG_TILE_BYTES_PROGRESS = 7
+TH_CFG_SHORT_TILE_SLOTS = 8
 TH_MODEL_DENSE, TH_MODEL_MOE = 1, 2
 _DTYPE = {"bf16": TH_BF16, "f32": TH_F32}
 _DTYPE_NAME = {TH_BF16: "bf16", TH_F32: "f32", 0: None}

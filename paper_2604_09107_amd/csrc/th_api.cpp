@@ -197,8 +197,8 @@ int upload_tables(th_plan* p) {
             const size_t nc = p->m.n_chunks;
             std::vector<uint32_t> expected(nc);
             for (size_t c = 0; c < nc; ++c)
-                expected[c] = (uint32_t)((p->m.chunk_tile0[side][0][c + 1] - p->m.chunk_tile0[side][0][c]) +
-                                         (p->m.chunk_tile0[side][1][c + 1] - p->m.chunk_tile0[side][1][c]));
+                for (int k = 0; k < kPathClasses; ++k)
+                    expected[c] += (uint32_t)(p->m.chunk_tile0[side][k][c + 1] - p->m.chunk_tile0[side][k][c]);
             e = hipMalloc(reinterpret_cast<void**>(&p->d_expected[side]), nc * sizeof(uint32_t));
             if (e != hipSuccess) return hip_fail(e, "hipMalloc(tiles per chunk)");
             e = hipMemcpy(p->d_expected[side], expected.data(), nc * sizeof(uint32_t), hipMemcpyHostToDevice);
@@ -220,6 +220,7 @@ int finish_plan(th_plan* p, size_t chunk_bytes, unsigned flags, bool aligned16) 
     if (flags & TH_FLAG_PROGRESS) {
         tune.tile_bytes = tune.tile_bytes_progress;
         tune.chunk_order = true;
+        tune.short_slots = 0;  // one list in chunk order: no class that would run after the others
     }
     p->vec_instance = vector_instance(tune.tile_bytes);
     int rc = finish_manifest(p->m, chunk_bytes, aligned16, tune);
@@ -230,6 +231,12 @@ int finish_plan(th_plan* p, size_t chunk_bytes, unsigned flags, bool aligned16) 
         if (!p->host_only) rc = upload_tables(p);
     }
     return rc;
+}
+
+// The kernel instance that runs the tiles of path class k (0 vector path, 1 other, 2 short).
+int class_instance(const th_plan* p, int k) {
+    if (k == 2) return ALL_PATHS_SHORT;
+    return (k == 0 && p->specialize) ? p->vec_instance : (int)VEC_ALL_PATHS;
 }
 
 // Whether work enqueued on `stream` is being recorded into a graph instead of run.
@@ -322,12 +329,12 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
         set_error("null pointer array");
         return TH_ERR_ARG;
     }
-    uint64_t tile0[2] = {0, 0}, ntiles[2] = {0, 0};
-    for (int k = 0; k < 2 && chunk_count; ++k) {
+    uint64_t tile0[kPathClasses] = {0, 0, 0}, ntiles[kPathClasses] = {0, 0, 0};
+    for (int k = 0; k < kPathClasses && chunk_count; ++k) {
         tile0[k] = m.chunk_tile0[side][k][chunk_first];
         ntiles[k] = m.chunk_tile0[side][k][chunk_first + chunk_count] - tile0[k];
     }
-    if (ntiles[0] + ntiles[1] == 0) {
+    if (ntiles[0] + ntiles[1] + ntiles[2] == 0) {
         if (!want_progress) return TH_OK;
         if (int rc = check_device(p)) return rc;
         return launch_signal(progress, chunk_count, stream);  // nothing to move: the range is complete
@@ -378,10 +385,9 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
         prog.count = chunk_count;
         rc = launch_progress_reset(prog, stream);
     }
-    for (int k = 0; k < 2 && rc == TH_OK; ++k) {
+    for (int k = 0; k < kPathClasses && rc == TH_OK; ++k) {
         if (!ntiles[k]) continue;
-        const bool vec_only = k == 0 && p->specialize;
-        const int instance = vec_only ? p->vec_instance : (int)VEC_ALL_PATHS;
+        const int instance = class_instance(p, k);
         uint64_t* partials = want_sums ? p->d_partials[side] : nullptr;
         if (side == 0)
             rc = launch_tiles(MODE_PACK, instance, p->d_tiles[0], tile0[k], ntiles[k], tens_tab,
@@ -393,7 +399,7 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
                               stream);
         if (rc == TH_OK && want_sums)
             rc = launch_checksum_finalize(p->d_tiles[side], p->d_partials[side], p->d_tile_base[side], tile0[k],
-                                          ntiles[k], p->m.tiles[side].size(), vec_only, sums, stream);
+                                          ntiles[k], p->m.tiles[side].size(), instance, sums, stream);
     }
     // the end of the launch completes the range, whatever the last publisher saw
     if (rc == TH_OK && want_progress) rc = launch_signal(progress, chunk_count, stream);
@@ -551,12 +557,12 @@ int th_pack_noalloc(const th_plan* p, const void* const* src_ptrs, uint32_t n_sr
         set_error("null pointer array");
         return TH_ERR_ARG;
     }
-    uint64_t tile0[2], ntiles[2];
-    for (int k = 0; k < 2; ++k) {
+    uint64_t tile0[kPathClasses], ntiles[kPathClasses];
+    for (int k = 0; k < kPathClasses; ++k) {
         tile0[k] = m.chunk_tile0[0][k][chunk_first];
         ntiles[k] = m.chunk_tile0[0][k][chunk_first + chunk_count] - tile0[k];
     }
-    if (ntiles[0] + ntiles[1] == 0) return TH_OK;
+    if (ntiles[0] + ntiles[1] + ntiles[2] == 0) return TH_OK;
     if (int rc = check_device(p)) return rc;
     // nothing is cached here, so every call checks every pointer
     for (uint32_t i = 0; i < chunk_count; ++i) {
@@ -592,9 +598,9 @@ int th_pack_noalloc(const th_plan* p, const void* const* src_ptrs, uint32_t n_sr
     Progress order;
     order.ordered = p->progress ? 1u : 0u;
     int rc = TH_OK;
-    for (int k = 0; k < 2 && rc == TH_OK; ++k) {
+    for (int k = 0; k < kPathClasses && rc == TH_OK; ++k) {
         if (!ntiles[k]) continue;
-        const int instance = (k == 0 && p->specialize) ? p->vec_instance : (int)VEC_ALL_PATHS;
+        const int instance = class_instance(p, k);
         rc = launch_tiles(MODE_PACK, instance, p->d_tiles[0], tile0[k], ntiles[k], tens_tab,
                           const_cast<void* const*>(wire_tab), chunk_first, inl, nullptr, m.tiles[0].size(), order,
                           hip_stream);
@@ -639,12 +645,13 @@ int th_reshard(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, vo
     InlineWire no_inline;
     std::memset(&no_inline, 0, sizeof no_inline);
     int rc = TH_OK;
-    if (m.direct_n_vec)
-        rc = launch_tiles(MODE_DIRECT, p->specialize ? p->vec_instance : (int)VEC_ALL_PATHS, p->d_tiles[2], 0,
-                          m.direct_n_vec, stab, dtab, 0, no_inline, nullptr, 0, Progress(), hip_stream);
-    if (rc == TH_OK && total > m.direct_n_vec)
-        rc = launch_tiles(MODE_DIRECT, VEC_ALL_PATHS, p->d_tiles[2], m.direct_n_vec, total - m.direct_n_vec, stab, dtab, 0,
-                          no_inline, nullptr, 0, Progress(), hip_stream);
+    uint64_t first = 0;
+    for (int k = 0; k < kPathClasses && rc == TH_OK; ++k) {
+        if (m.direct_n[k])
+            rc = launch_tiles(MODE_DIRECT, class_instance(p, k), p->d_tiles[2], first, m.direct_n[k], stab, dtab, 0,
+                              no_inline, nullptr, 0, Progress(), hip_stream);
+        first += m.direct_n[k];
+    }
     return rc;
 }
 
@@ -768,7 +775,7 @@ int th_plan_get_tile(const th_plan* p, int side, size_t i, th_tile_info* out) {
 }
 
 size_t th_plan_chunk_first_tile(const th_plan* p, int side, int path_class, uint32_t chunk) {
-    if (!p || (side != 0 && side != 1) || (path_class != 0 && path_class != 1) || chunk > p->m.n_chunks) return 0;
+    if (!p || (side != 0 && side != 1) || path_class < 0 || path_class >= kPathClasses || chunk > p->m.n_chunks) return 0;
     return (size_t)p->m.chunk_tile0[side][path_class][chunk];
 }
 
@@ -810,6 +817,13 @@ int th_config_set(int key, uint64_t value) {
             return TH_OK;
         case TH_CFG_SPECIALIZE:
             g_tuning.specialize = value != 0;
+            return TH_OK;
+        case TH_CFG_SHORT_TILE_SLOTS:
+            if (value > 4096) {
+                set_error("short tiles hold at most 4096 slots");
+                return TH_ERR_ARG;
+            }
+            g_tuning.short_slots = value;
             return TH_OK;
         case TH_CFG_PLANNER_THREADS:
             if (value < 1 || value > 3) {
@@ -858,7 +872,8 @@ uint64_t th_config_get(int key) {
            : key == TH_CFG_TILE_BYTES_CHECKSUM ? g_tuning.tile_bytes_checksum
            : key == TH_CFG_TILE_BYTES_NARROW ? g_tuning.tile_bytes_narrow
            : key == TH_CFG_PLANNER_THREADS ? g_tuning.planner_threads
-           : key == TH_CFG_TILE_BYTES_PROGRESS ? g_tuning.tile_bytes_progress : 0;
+           : key == TH_CFG_TILE_BYTES_PROGRESS ? g_tuning.tile_bytes_progress
+           : key == TH_CFG_SHORT_TILE_SLOTS ? g_tuning.short_slots : 0;
 }
 
 const char* th_last_error(void) { return g_err; }

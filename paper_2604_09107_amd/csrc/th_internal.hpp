@@ -86,19 +86,25 @@ constexpr int kBlockThreads = TH_BLOCK_THREADS;  // threads per workgroup (one t
 #endif
 constexpr int kBlockThreadsAny = TH_BLOCK_THREADS_ANY;
 static_assert(kBlockThreadsAny <= kBlockThreads && kBlockThreads % 64 == 0 && kBlockThreadsAny % 64 == 0, "workgroup sizes");
+// Short tiles (the whole of a short run, or the last piece of a longer one) get one wavefront each:
+// a workgroup of 512 threads would leave most of its wavefront slots idle on them, and a compute
+// unit holds 32 one-wavefront workgroups as easily as four large ones.
+constexpr int kBlockThreadsShort = 64;
+constexpr int kPathClasses = 3;  // sub-lists of a work list: vector path, other tiles, short tiles
 constexpr int kPartialsPerTile = kBlockThreads / 64;  // checksum pairs reserved per tile: one per wavefront
 
 struct Manifest {
     std::vector<TensorInfo> tensors[2];  // 0 = source side, 1 = destination side
     std::vector<Segment> segments;       // wire order
     std::vector<th_run> runs;            // segments cut at chunk boundaries, wire order
-    // Work list per direction (0 = pack, 1 = unpack): first every KIND_VEC tile, then every other
-    // tile, each sub-list ordered by chunk, so that a chunk range is two contiguous tile ranges and
-    // the vector-path range can be launched with the kernel that holds only that path.
+    // Work list per direction (0 = pack, 1 = unpack): first the KIND_VEC tiles of runs that are not
+    // short, then the other tiles of such runs, then the tiles of short runs, each sub-list ordered by
+    // chunk, so that a chunk range is three contiguous tile ranges: the vector-path range is launched
+    // with the kernel that holds only that path, the short runs with one-wavefront workgroups.
     std::vector<Tile> tiles[3];               // [2]: direct holder tensor -> reader tensor list (no wire)
-    std::vector<uint64_t> chunk_tile0[2][2];  // [side][class]: first tile of each chunk (+ end of the sub-list)
+    std::vector<uint64_t> chunk_tile0[2][kPathClasses];  // [side][class]: first tile of each chunk (+ end of the sub-list)
     std::vector<uint64_t> tensor_wire_end;    // per source tensor: end of its last run on the wire (0: sends nothing)
-    uint64_t direct_n_vec = 0;                // KIND_VEC tiles at the front of tiles[2]
+    uint64_t direct_n[kPathClasses] = {0, 0, 0};  // tiles[2]: tiles of each class, in class order
     std::vector<uint64_t> run_starts;         // per run: Segment::run_start of the segment it was cut from
     // per pack / unpack tile: 16-bit units between the start of its tensor's wire run and the tile's
     // wire-side base offset (what a tile-local checksum position has to be shifted by)
@@ -115,6 +121,8 @@ struct Tuning {
                                            // the per-wavefront reduction
     uint64_t tile_bytes_progress = 32768;  // vector path in plans that publish a progress counter
     bool specialize = true;           // launch vector-path tiles with the kernel that holds only that path
+    uint64_t short_slots = 512;       // a run of at most this many 16-byte vectors / destination slots (16 bytes; 8
+                                      // when narrowing) is short: its tiles run on one wavefront (0: no run is short)
     unsigned planner_threads = 3;     // threads that build a large plan's three tile lists (1: the calling thread alone)
     bool chunk_order = false;         // pack / unpack lists in prefix order (plans that publish a progress counter)
 };
@@ -136,11 +144,17 @@ inline unsigned esize(int dtype) { return dtype == TH_F32 ? 4u : 2u; }
 // Launches one kernel over tiles [tile0, tile0 + ntiles) of `tiles` (device pointer).
 // mode: which of the two pointer tables is indexed by chunk (pack: destination, unpack: source,
 // direct: neither).  wire_first: chunk index that entry 0 of the wire pointer table stands for.
-// instance: which build of the kernel runs the range.  VEC_ALL_PATHS holds every path; the others
-// hold the vector path only (every tile of the range must be KIND_VEC) for tiles of at most one,
-// at most two, or any number of vectors per thread of a kBlockThreads workgroup.
+// instance: which build of the kernel runs the range.  VEC_ALL_PATHS holds every path, on
+// kBlockThreadsAny threads, ALL_PATHS_SHORT the same on one wavefront; the others hold the vector
+// path only (every tile of the range must be KIND_VEC) for tiles of at most one, at most two, or any
+// number of vectors per thread of a kBlockThreads workgroup.
 enum TileMode { MODE_PACK = 0, MODE_UNPACK = 1, MODE_DIRECT = 2 };
-enum TileInstance { VEC_ALL_PATHS = 0, VEC_ONE = 1, VEC_TWO = 2, VEC_ANY = 3 };
+enum TileInstance { VEC_ALL_PATHS = 0, VEC_ONE = 1, VEC_TWO = 2, VEC_ANY = 3, ALL_PATHS_SHORT = 4 };
+constexpr int kTileInstances = 5;
+// Threads per workgroup of a kernel instance.
+inline int instance_threads(int instance) {
+    return instance == VEC_ALL_PATHS ? kBlockThreadsAny : instance == ALL_PATHS_SHORT ? kBlockThreadsShort : kBlockThreads;
+}
 // The vector-only instance for tiles of up to tile_bytes.
 inline int vector_instance(uint64_t tile_bytes) {
     const uint64_t vectors = tile_bytes / 16;
@@ -178,10 +192,10 @@ int launch_tiles(int mode, int instance, const Tile* tiles, uint64_t tile0, uint
 // Zeroes the counters, the publishing state and the caller's counter of a progress launch.
 int launch_progress_reset(const Progress& prog, void* stream);
 // Adds the per-tile terms of tiles [tile0, tile0 + ntiles) into sums[2 * src_tensor + {0, 1}].
-// vec_only: whether the launch_tiles call that filled the pairs ran a vector-only instance (it fixes
-// the wavefronts per tile).
+// instance: the kernel instance of the launch_tiles call that filled the pairs (it fixes the
+// wavefronts per tile).
 int launch_checksum_finalize(const Tile* tiles, const uint64_t* partials, const uint64_t* tile_base,
-                             uint64_t tile0, uint64_t ntiles, uint64_t list_tiles, bool vec_only, uint64_t* sums,
+                             uint64_t tile0, uint64_t ntiles, uint64_t list_tiles, int instance, uint64_t* sums,
                              void* stream);
 
 // Allocation-free variant of the pointer tables: copies the pointers, through kernel arguments, into

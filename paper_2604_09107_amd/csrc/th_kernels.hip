@@ -1,8 +1,9 @@
-// gfx950 kernels of the reshard path: one launch moves every tile of a chunk range.
+// gfx950 kernels of the reshard path: one launch moves every tile of one class of a chunk range.
 //
 // Pure data movement, bound by HBM bandwidth: no matrix cores.  One workgroup
 // (kBlockThreads threads in the instance that holds only the vector path,
-// kBlockThreadsAny in the one that holds every path; wavefronts of 64) takes one
+// kBlockThreadsAny in the one that holds every path, a single wavefront of 64 in the
+// instance that runs short tiles: one wavefront per short run) takes one
 // 64-byte tile record, which the scalar unit fetches once for the whole workgroup,
 // resolves its two base pointers through the pointer tables, and copies a sub-rectangle:
 //
@@ -627,9 +628,11 @@ __device__ __forceinline__ void copy_dense(gsrc_t src, gdst_t dst, uint64_t ss, 
         }
     }
 
-    // partial slots: thread 0 takes the first, a thread of another wavefront the last
+    // partial slots: thread 0 takes the first, a thread of another wavefront (of the other half of a
+    // one-wavefront workgroup) the last
+    constexpr uint32_t kTailThread = BT > 64 ? 64 : BT / 2;
     const bool head = lead && !head_skip, tail = hi < nslots && (nslots > 1 || !lead);
-    if ((head && tid == 0) || (tail && tid == 64)) {
+    if ((head && tid == 0) || (tail && tid == kTailThread)) {
         const uint32_t t = tid == 0 ? 0u : nslots - 1;
         Slot<DES> s;
         const int32_t e0 = (int32_t)(t * EPV) - (int32_t)lead;
@@ -727,7 +730,8 @@ __device__ __forceinline__ void advance_prefix(const Progress& pr, uint32_t firs
 // INLINE: the wire pointers come from the kernel arguments (short chunk ranges) instead of the table.
 // PROGRESS: the launch counts finished tiles per chunk and publishes the complete prefix (above).
 template <int MODE, int VEC, bool CHECKSUM, bool INLINE, bool PROGRESS>
-__global__ __launch_bounds__(VEC ? kBlockThreads : kBlockThreadsAny, TH_MIN_WAVES_PER_EU) void th_tiles_kernel(const Tile* __restrict__ tiles,
+__global__ __launch_bounds__(VEC == VEC_ALL_PATHS ? kBlockThreadsAny : VEC == ALL_PATHS_SHORT ? kBlockThreadsShort : kBlockThreads,
+                             TH_MIN_WAVES_PER_EU) void th_tiles_kernel(const Tile* __restrict__ tiles,
                                                                   const void* const* __restrict__ src_table,
                                                                   void* const* __restrict__ dst_table,
                                                                   uint32_t wire_first, uint32_t partial_stride,
@@ -736,8 +740,8 @@ __global__ __launch_bounds__(VEC ? kBlockThreads : kBlockThreadsAny, TH_MIN_WAVE
     // Workgroups are dealt to the 8 XCDs round-robin (workgroup b runs on XCD b mod 8).  Give
     // each XCD one contiguous eighth of the tile list so that it streams through its own
     // address range instead of every 8th tile.
-    constexpr bool VEC_ONLY = VEC != VEC_ALL_PATHS;
-    constexpr int BT = VEC_ONLY ? kBlockThreads : kBlockThreadsAny;
+    constexpr bool VEC_ONLY = VEC != VEC_ALL_PATHS && VEC != ALL_PATHS_SHORT;
+    constexpr int BT = VEC == VEC_ALL_PATHS ? kBlockThreadsAny : VEC == ALL_PATHS_SHORT ? kBlockThreadsShort : kBlockThreads;
     constexpr int VPT = VEC == VEC_ONE ? 1 : VEC == VEC_TWO ? 2 : 0;
     // (A list in prefix order has that arrangement built in, chunk by chunk: record b is workgroup b's.)
     uint32_t b = blockIdx.x;
@@ -1052,23 +1056,22 @@ int launch_tiles(int mode, int instance, const Tile* tiles, uint64_t tile0, uint
 #define TH_K(M, V) {{th_tiles_kernel<M, V, false, false, false>, th_tiles_kernel<M, V, false, true, false>}, \
                     {th_tiles_kernel<M, V, true, false, false>, th_tiles_kernel<M, V, true, true, false>}}
 #define TH_KD(V) {{th_tiles_kernel<MODE_DIRECT, V, false, false, false>, nullptr}, {nullptr, nullptr}}
-    static const kernel_t kernels[3][4][2][2] = {
-        {TH_K(MODE_PACK, VEC_ALL_PATHS), TH_K(MODE_PACK, VEC_ONE), TH_K(MODE_PACK, VEC_TWO), TH_K(MODE_PACK, VEC_ANY)},
-        {TH_K(MODE_UNPACK, VEC_ALL_PATHS), TH_K(MODE_UNPACK, VEC_ONE), TH_K(MODE_UNPACK, VEC_TWO),
-         TH_K(MODE_UNPACK, VEC_ANY)},
-        {TH_KD(VEC_ALL_PATHS), TH_KD(VEC_ONE), TH_KD(VEC_TWO), TH_KD(VEC_ANY)}};
+#define TH_ALL(K, M) {K(M, VEC_ALL_PATHS), K(M, VEC_ONE), K(M, VEC_TWO), K(M, VEC_ANY), K(M, ALL_PATHS_SHORT)}
+#define TH_KDM(M, V) TH_KD(V)
+    static const kernel_t kernels[3][kTileInstances][2][2] = {TH_ALL(TH_K, MODE_PACK), TH_ALL(TH_K, MODE_UNPACK),
+                                                              TH_ALL(TH_KDM, MODE_DIRECT)};
+    // launches that publish progress: [mode][instance], no checksum, wire pointers from the table
+#define TH_KP(M, V) th_tiles_kernel<M, V, false, false, true>
+    static const kernel_t progress_kernels[2][kTileInstances] = {TH_ALL(TH_KP, MODE_PACK), TH_ALL(TH_KP, MODE_UNPACK)};
 #undef TH_K
 #undef TH_KD
-    // launches that publish progress: [mode][instance], no checksum, wire pointers from the table
-#define TH_KP(M) {th_tiles_kernel<M, VEC_ALL_PATHS, false, false, true>, th_tiles_kernel<M, VEC_ONE, false, false, true>, \
-                  th_tiles_kernel<M, VEC_TWO, false, false, true>, th_tiles_kernel<M, VEC_ANY, false, false, true>}
-    static const kernel_t progress_kernels[2][4] = {TH_KP(MODE_PACK), TH_KP(MODE_UNPACK)};
+#undef TH_KDM
 #undef TH_KP
-    if (instance < 0 || instance > VEC_ANY) {
+#undef TH_ALL
+    if (instance < 0 || instance >= kTileInstances) {
         set_error("no such instance of the tile kernel");
         return TH_ERR_ARG;
     }
-    const bool vec_only = instance != VEC_ALL_PATHS;
     const bool counting = prog.arrived != nullptr;
     kernel_t kernel = nullptr;
     if (!counting)
@@ -1083,7 +1086,7 @@ int launch_tiles(int mode, int instance, const Tile* tiles, uint64_t tile0, uint
     while (ntiles) {
         const uint64_t n = ntiles < kMaxGrid ? ntiles : kMaxGrid;
         pr.pos0 = (uint32_t)tile0;  // low bits of the list position pick counter slots and publishers
-        hipLaunchKernelGGL(kernel, dim3((uint32_t)n), dim3(vec_only ? kBlockThreads : kBlockThreadsAny), 0, st,
+        hipLaunchKernelGGL(kernel, dim3((uint32_t)n), dim3(instance_threads(instance)), 0, st,
                            tiles + tile0, src_table, dst_table, wire_first, (uint32_t)list_tiles, inl,
                            partials ? partials + 2 * tile0 : nullptr, pr);
         const hipError_t e = hipGetLastError();
@@ -1098,10 +1101,10 @@ int launch_tiles(int mode, int instance, const Tile* tiles, uint64_t tile0, uint
 }
 
 int launch_checksum_finalize(const Tile* tiles, const uint64_t* partials, const uint64_t* tile_base, uint64_t tile0,
-                             uint64_t ntiles, uint64_t list_tiles, bool vec_only, uint64_t* sums, void* stream) {
+                             uint64_t ntiles, uint64_t list_tiles, int instance, uint64_t* sums, void* stream) {
     if (!ntiles) return TH_OK;
     const uint64_t grid = (ntiles + 255) / 256;
-    const uint32_t waves = (vec_only ? kBlockThreads : kBlockThreadsAny) / 64;  // of the kernel that ran these tiles
+    const uint32_t waves = instance_threads(instance) / 64;  // of the kernel that ran these tiles
     hipLaunchKernelGGL(th_checksum_finalize_kernel, dim3((uint32_t)grid), dim3(256), 0,
                        static_cast<hipStream_t>(stream), tiles + tile0, partials + 2 * tile0, tile_base + tile0,
                        ntiles, waves, (uint32_t)list_tiles, sums);

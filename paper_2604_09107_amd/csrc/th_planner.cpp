@@ -30,7 +30,8 @@ struct Side {  // one end of a copy, in bytes
 };
 
 // Append the tiles of one run, seen as a copy S -> D of nrows x ncols elements.
-// outs[0] receives vector-path tiles, outs[1] all others; a run's tiles are all of one class.
+// outs[0] receives the tiles of vector-path runs, outs[1] those of other runs, outs[2] those of
+// short runs of either kind (one wavefront each); a run's tiles are all of one class.
 void tile_run(std::vector<Tile>* outs, Side S, Side D, uint64_t nrows, uint64_t ncols, unsigned pad,
               bool bases_aligned16, const Tuning& tune, bool& used_vec) {
     // rows that follow each other without a gap on both ends are one long row
@@ -47,7 +48,13 @@ void tile_run(std::vector<Tile>* outs, Side S, Side D, uint64_t nrows, uint64_t 
                      D.off % vd == 0 && ncols % unit_elems == 0 &&
                      (nrows == 1 || (S.stride % vs == 0 && D.stride % vd == 0));
     used_vec = vec;
-    std::vector<Tile>& out = outs[vec ? 0 : 1];
+    // A run that is short as a whole (at most short_slots of the kernel's units of work per thread:
+    // 16-byte vectors, or destination slots of 16 bytes, 8 when narrowing, one more per row for the
+    // slot a row end can straddle) goes to the short class, whose tiles get one wavefront each.  The
+    // last piece of a long run stays with the run's own class.
+    const uint64_t slot_bytes = narrows ? 8 : 16;
+    const uint64_t run_slots = vec ? nrows * (ncols / unit_elems) : nrows * ((ncols * D.es + slot_bytes - 1) / slot_bytes + 1);
+    std::vector<Tile>& out = outs[run_slots <= tune.short_slots ? 2 : vec ? 0 : 1];
     const uint64_t tile_bytes = vec ? tune.tile_bytes : narrows ? tune.tile_bytes_narrow : tune.tile_bytes_any;
     uint32_t flags = vec ? TILE_KIND_VEC : TILE_KIND_ANY;
     if (S.es == 4) flags |= TILE_SRC_F32;
@@ -352,12 +359,35 @@ static int finish_manifest_impl(Manifest& m, uint64_t CB, bool ptrs_aligned16, c
     // One list per direction: vector-path tiles first, each sub-list grouped by chunk.  Runs come in
     // wire order, so within a class the tiles are generated in chunk order already: the two classes
     // are collected separately and joined, nothing is sorted or copied twice.
+    // The short class is one more launch per call, with a tail of its own: it pays when short runs
+    // are a good part of the list (thousands of tiny tensors: 3 to 7 times faster), not when a few
+    // percent of the tiles are short (the scattered sweep loses 0.8 % to it).  A list gets the class
+    // when at least one piece of work in eight is a short run; `bytes` are a list's destination bytes.
+    auto tuning_for = [&](uint64_t short_runs, uint64_t bytes) {
+        Tuning t = tune;
+        const uint64_t est_tiles = bytes / std::max<uint64_t>(4096, std::min({t.tile_bytes, t.tile_bytes_any, t.tile_bytes_narrow})) + short_runs;
+        if (short_runs * 8 < est_tiles) t.short_slots = 0;
+        return t;
+    };
+    auto run_is_short = [&](uint64_t nrows, uint64_t ncols, unsigned es_src, unsigned es_dst) {
+        const uint64_t slot = (es_src == 4 && es_dst == 2) ? 8 : 16;
+        return nrows * ((ncols * es_dst + slot - 1) / slot + 1) <= tune.short_slots;
+    };
+
     auto build_side = [&](int side) {
-        std::vector<Tile> tiles[2];
-        std::vector<uint64_t> base[2];
-        bool reserved[2] = {false, false};
+        uint64_t short_runs = 0, list_bytes = 0;
+        for (const th_run& r : m.runs) {
+            const unsigned es_from = esize(side == 0 ? r.src_dtype : r.wire_dtype);
+            const unsigned es_to = esize(side == 0 ? r.wire_dtype : r.dst_dtype);
+            short_runs += run_is_short(r.nrows, r.row_len, es_from, es_to);
+            list_bytes += r.nrows * r.row_len * es_to;
+        }
+        const Tuning tune = tuning_for(short_runs, list_bytes);  // shadows the plan's: this list's
+        std::vector<Tile> tiles[kPathClasses];
+        std::vector<uint64_t> base[kPathClasses];
+        bool reserved[kPathClasses] = {false, false, false};
         Seen& mine = seen[side][side];  // pack learns about source tensors, unpack about destination tensors
-        for (unsigned k = 0; k < 2; ++k) m.chunk_tile0[side][k].assign((size_t)m.n_chunks + 1, 0);
+        for (unsigned k = 0; k < kPathClasses; ++k) m.chunk_tile0[side][k].assign((size_t)m.n_chunks + 1, 0);
         for (size_t ri = 0; ri < m.runs.size(); ++ri) {
             const th_run& r = m.runs[ri];
             const unsigned es_s = esize(r.src_dtype), es_w = esize(r.wire_dtype), es_d = esize(r.dst_dtype);
@@ -370,38 +400,69 @@ static int finish_manifest_impl(Manifest& m, uint64_t CB, bool ptrs_aligned16, c
                 D = Side{r.dst_tensor, r.dst_byte_off, r.dst_byte_stride, es_d};
             }
             bool vec = false;
-            const size_t before[2] = {tiles[0].size(), tiles[1].size()};
+            size_t before[kPathClasses];
+            for (unsigned k = 0; k < kPathClasses; ++k) before[k] = tiles[k].size();
             tile_run(tiles, S, D, r.nrows, r.row_len, side == 0 ? r.pad_bytes : 0, ptrs_aligned16, tune, vec);
-            const unsigned k = vec ? 0 : 1;
-            if (!reserved[k]) {  // first run of this class (most plans use one class only)
-                reserved[k] = true;
-                tiles[k].reserve(guess + 2 * m.runs.size());
-                base[k].reserve(guess + 2 * m.runs.size());
+            for (unsigned k = 0; k < kPathClasses; ++k) {
+                if (tiles[k].size() == before[k]) continue;
+                if (!reserved[k]) {  // first run of this class (most plans use one class only)
+                    reserved[k] = true;
+                    tiles[k].reserve(guess + 2 * m.runs.size());
+                    base[k].reserve(guess + 2 * m.runs.size());
+                }
+                for (size_t i = before[k]; i < tiles[k].size(); ++i) {
+                    Tile& t = tiles[k][i];
+                    t.src_tensor = r.src_tensor;
+                    const uint64_t wire_off = (uint64_t)r.chunk * CB + (side == 0 ? t.dst_off : t.src_off);
+                    base[k].push_back((wire_off - m.run_starts[ri]) / 2);
+                }
+                m.chunk_tile0[side][k][r.chunk + 1] += tiles[k].size() - before[k];
             }
-            for (size_t i = before[k]; i < tiles[k].size(); ++i) {
-                Tile& t = tiles[k][i];
-                t.src_tensor = r.src_tensor;
-                const uint64_t wire_off = (uint64_t)r.chunk * CB + (side == 0 ? t.dst_off : t.src_off);
-                base[k].push_back((wire_off - m.run_starts[ri]) / 2);
-            }
-            m.chunk_tile0[side][k][r.chunk + 1] += tiles[k].size() - before[k];
             const uint32_t tensor = side == 0 ? r.src_tensor : r.dst_tensor;
             mine.used[tensor] = 1;
             if (vec) mine.need16[tensor] = 1;
         }
-        for (unsigned k = 0; k < 2; ++k) {
-            std::vector<uint64_t>& first = m.chunk_tile0[side][k];
-            first[0] = k == 0 ? 0 : tiles[0].size();
-            for (size_t c = 0; c < m.n_chunks; ++c) first[c + 1] += first[c];
+        const int classes_in_use = !tiles[0].empty() + !tiles[1].empty() + !tiles[2].empty();
+        if (tune.chunk_order && classes_in_use > 1) {
+            // A plan that publishes progress finishes chunk after chunk, which launches class after
+            // class cannot: when its tiles are of more than one class they all go into one list in
+            // chunk order, run by the kernel that holds every path.  (A plan with vector-path tiles
+            // only, the usual case for model weights, keeps the vector-only kernel.)
+            std::vector<Tile> all;
+            std::vector<uint64_t> all_base;
+            all.reserve(tiles[0].size() + tiles[1].size() + tiles[2].size());
+            all_base.reserve(all.capacity());
+            size_t pos[kPathClasses] = {0, 0, 0};
+            for (size_t c = 0; c < m.n_chunks; ++c) {
+                uint64_t total = 0;
+                for (unsigned k = 0; k < kPathClasses; ++k) {
+                    const uint64_t cnt = m.chunk_tile0[side][k][c + 1];
+                    all.insert(all.end(), tiles[k].begin() + pos[k], tiles[k].begin() + pos[k] + cnt);
+                    all_base.insert(all_base.end(), base[k].begin() + pos[k], base[k].begin() + pos[k] + cnt);
+                    pos[k] += cnt;
+                    total += cnt;
+                    m.chunk_tile0[side][k][c + 1] = 0;
+                }
+                m.chunk_tile0[side][1][c + 1] = total;
+            }
+            tiles[0].clear(), tiles[2].clear(), base[0].clear(), base[2].clear();
+            tiles[1] = std::move(all);
+            base[1] = std::move(all_base);
         }
-        if (tiles[0].empty()) {
-            m.tiles[side] = std::move(tiles[1]);
-            m.tile_base[side] = std::move(base[1]);
-        } else {
-            m.tiles[side] = std::move(tiles[0]);
-            m.tile_base[side] = std::move(base[0]);
-            m.tiles[side].insert(m.tiles[side].end(), tiles[1].begin(), tiles[1].end());
-            m.tile_base[side].insert(m.tile_base[side].end(), base[1].begin(), base[1].end());
+        uint64_t class_start = 0;
+        for (unsigned k = 0; k < kPathClasses; ++k) {
+            std::vector<uint64_t>& first = m.chunk_tile0[side][k];
+            first[0] = class_start;
+            for (size_t c = 0; c < m.n_chunks; ++c) first[c + 1] += first[c];
+            class_start += tiles[k].size();
+        }
+        unsigned lead = 0;  // the first class that has tiles keeps its storage, the others are appended
+        while (lead + 1 < kPathClasses && tiles[lead].empty()) ++lead;
+        m.tiles[side] = std::move(tiles[lead]);
+        m.tile_base[side] = std::move(base[lead]);
+        for (unsigned k = lead + 1; k < kPathClasses; ++k) {
+            m.tiles[side].insert(m.tiles[side].end(), tiles[k].begin(), tiles[k].end());
+            m.tile_base[side].insert(m.tile_base[side].end(), base[k].begin(), base[k].end());
         }
         if (tune.chunk_order) {
             // Prefix order: workgroup b of a launch runs the record at list position b, and workgroups
@@ -412,7 +473,7 @@ static int finish_manifest_impl(Manifest& m, uint64_t CB, bool ptrs_aligned16, c
             std::vector<uint64_t>& bases = m.tile_base[side];
             std::vector<Tile> tmp;
             std::vector<uint64_t> tmp_base;
-            for (unsigned k = 0; k < 2; ++k)
+            for (unsigned k = 0; k < kPathClasses; ++k)
                 for (size_t c = 0; c < m.n_chunks; ++c) {
                     const uint64_t t0 = m.chunk_tile0[side][k][c], t1 = m.chunk_tile0[side][k][c + 1];
                     if (t1 - t0 < 2) continue;
@@ -430,27 +491,32 @@ static int finish_manifest_impl(Manifest& m, uint64_t CB, bool ptrs_aligned16, c
 
     // direct list: holder tensors -> reader tensors without the wire, one pass over the segments
     auto build_direct = [&]() {
-        std::vector<Tile> tiles[2];
-        bool reserved[2] = {false, false};
+        uint64_t short_runs = 0, list_bytes = 0;
+        for (const Segment& g : m.segments) {
+            short_runs += run_is_short(g.nrows, g.row_len, esize(g.src_dtype), esize(g.dst_dtype));
+            list_bytes += g.nrows * g.row_len * esize(g.dst_dtype);
+        }
+        const Tuning tune = tuning_for(short_runs, list_bytes);
+        std::vector<Tile> tiles[kPathClasses];
+        bool reserved = false;
         for (const Segment& g : m.segments) {
             const unsigned es_s = esize(g.src_dtype), es_d = esize(g.dst_dtype);
             const Side S{g.src_tensor, g.src_off * es_s, g.src_stride * es_s, es_s};
             const Side D{g.dst_tensor, g.dst_off * es_d, g.dst_stride * es_d, es_d};
             bool vec = false;
             tile_run(tiles, S, D, g.nrows, g.row_len, 0, ptrs_aligned16, tune, vec);
-            if (!reserved[vec ? 0 : 1]) {
-                reserved[vec ? 0 : 1] = true;
+            if (!reserved) {
+                reserved = true;
                 tiles[vec ? 0 : 1].reserve(guess + 2 * m.segments.size());
             }
             if (vec) seen[2][0].need16[g.src_tensor] = seen[2][1].need16[g.dst_tensor] = 1;
         }
-        m.direct_n_vec = tiles[0].size();
-        if (tiles[0].empty()) {
-            m.tiles[2] = std::move(tiles[1]);
-        } else {
-            m.tiles[2] = std::move(tiles[0]);
-            m.tiles[2].insert(m.tiles[2].end(), tiles[1].begin(), tiles[1].end());
-        }
+        unsigned lead = 0;
+        while (lead + 1 < kPathClasses && tiles[lead].empty()) ++lead;
+        for (unsigned k = 0; k < kPathClasses; ++k) m.direct_n[k] = tiles[k].size();
+        m.tiles[2] = std::move(tiles[lead]);
+        for (unsigned k = lead + 1; k < kPathClasses; ++k)
+            m.tiles[2].insert(m.tiles[2].end(), tiles[k].begin(), tiles[k].end());
     };
 
     // The three lists are independent.  Large plans build the two per-direction lists on threads of

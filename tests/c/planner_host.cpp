@@ -93,7 +93,7 @@ static bool same_lists(const Manifest& a, const Manifest& b) {
             return false;
     }
     for (int s = 0; s < 2; ++s)
-        for (int k = 0; k < 2; ++k)
+        for (int k = 0; k < kPathClasses; ++k)
             if (a.chunk_tile0[s][k] != b.chunk_tile0[s][k]) return false;
     return a.tile_base[0] == b.tile_base[0] && a.tile_base[1] == b.tile_base[1];
 }

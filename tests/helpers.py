@@ -70,8 +70,8 @@ def exec_tiles(plan, side, src_bufs, dst_bufs, chunk_range=None):
     """Run the device work list of one direction on the CPU."""
     if chunk_range is None:
         todo = range(plan.num_tiles(side))
-    else:  # a chunk range is one tile range per path class
-        todo = [i for k in (0, 1) for i in range(plan.chunk_first_tile(side, k, chunk_range[0]),
+    else:  # a chunk range is one tile range per path class (vector path, other tiles, short tiles)
+        todo = [i for k in (0, 1, 2) for i in range(plan.chunk_first_tile(side, k, chunk_range[0]),
                                                  plan.chunk_first_tile(side, k, chunk_range[1]))]
     for i in todo:
         t = plan.tile(side, i)
@@ -121,7 +121,8 @@ def tile_checksums(plan, side, wire_chunks, n_src_tensors):
 def tile_sizes(tile_bytes):
     """Plans created inside the block use `tile_bytes` for every tile kind (None: library defaults)."""
     import paper_2604_09107_amd as th
-    keys = (th.TH_CFG_TILE_BYTES, th.TH_CFG_TILE_BYTES_ANY, th.TH_CFG_TILE_BYTES_CHECKSUM, th.TH_CFG_TILE_BYTES_NARROW)
+    keys = (th.TH_CFG_TILE_BYTES, th.TH_CFG_TILE_BYTES_ANY, th.TH_CFG_TILE_BYTES_CHECKSUM, th.TH_CFG_TILE_BYTES_NARROW,
+            th.TH_CFG_TILE_BYTES_PROGRESS)
     old = [th.th_config_get(k) for k in keys]
     try:
         if tile_bytes:

@@ -615,3 +615,63 @@ def test_per_chunk_calls_captured_in_a_graph_and_replayed():
         assert_same([synth.to_bits(t) for t in dst_dev], [x.reshape(-1) for x in want])
     del g
     plan.destroy()
+
+
+@pytest.mark.parametrize("src_dt,dst_dt,aligned,lo,hi", [("bf16", "bf16", False, 1, 300), ("f32", "bf16", False, 1, 700),
+                                                        ("bf16", "bf16", True, 8, 512), ("f32", "bf16", True, 8, 1024),
+                                                        ("f32", "f32", False, 1, 200)])
+def test_thousands_of_tiny_runs_one_wavefront_each(src_dt, dst_dt, aligned, lo, hi):
+    """Short runs get a path class of their own whose tiles run on one wavefront each (the batching
+    of many small tensors into one launch): 6000 runs of a few bytes to a few KiB, two per source
+    tensor, aligned or not, against the segment oracle; the bytes between the runs stay untouched."""
+    n, per = 6000, 2
+    rng = np.random.default_rng(lo * 1000 + hi)
+    lens = rng.integers(lo, hi + 1, n)
+    gaps = rng.integers(0, 9, n)
+    if aligned:
+        lens, gaps = np.maximum(8, lens // 8 * 8), gaps // 8 * 8 + 8
+    es = {"bf16": 2, "f32": 4}
+    tid = np.arange(n) // per
+    src_off = np.concatenate(([0], np.cumsum(lens + gaps)[:-1]))
+    base = src_off[tid * per]
+    dst_off = np.concatenate(([0], np.cumsum(lens + (0 if not aligned else 8))[:-1])) + (0 if aligned else 3)
+    nt = n // per
+    t_elems = np.array([src_off[(t + 1) * per - 1] + lens[(t + 1) * per - 1] - base[t * per] for t in range(nt)]) + 8
+    total_dst = int(dst_off[-1] + lens[-1] + 16)
+    segs = np.zeros(n, dtype=th.binding.SEGMENT_NP)
+    segs["src_tensor"], segs["src_elem_off"], segs["dst_elem_off"] = tid, src_off - base, dst_off
+    segs["nrows"], segs["row_len"] = 1, lens
+    segs["src_row_stride"] = segs["dst_row_stride"] = lens
+    segs["src_dtype"], segs["dst_dtype"] = th.binding._DTYPE[src_dt], th.binding._DTYPE[dst_dt]
+    plan = th.th_plan_create_from_segments(segs, t_elems, [total_dst], 64 * 1024,
+                                           th.TH_FLAG_PTRS_ALIGNED16 if aligned else 0)
+    for side in (0, 1):
+        assert plan.chunk_first_tile(side, 2, plan.num_chunks) - plan.chunk_first_tile(side, 2, 0) >= n, "no short class"
+    bits = {"bf16": np.uint16, "f32": np.uint32}
+    srcs = [rng.integers(0, 1 << (8 * es[src_dt]), int(m), dtype=np.uint64).astype(bits[src_dt]) for m in t_elems]
+    if src_dt == "f32":
+        for a in srcs:
+            a[(a & 0x7F800000) == 0x7F800000] &= 0xFF7FFFFF     # no NaN / Inf patterns here: fp32 pass-through aside
+    osegs = dict(src_tensor=tid, dst_tensor=np.zeros(n, dtype=np.int64), src_off=src_off - base,
+                 src_stride=lens, dst_off=dst_off, dst_stride=lens, nrows=np.ones(n, dtype=np.int64), row_len=lens)
+    wire = segments.pack(osegs, srcs, src_dt, dst_dt)
+    want = np.full(total_dst, 0x7777 if dst_dt == "bf16" else 0x77777777, dtype=bits[dst_dt])
+    segments.unpack(osegs, wire, [want], dst_dt)
+    pad = 8 if aligned else 1                                    # tensors start 16-byte aligned, or only element-aligned
+    src_dev = [synth.from_bits(np.concatenate([np.zeros(pad, dtype=a.dtype), a]), "cuda")[pad:] for a in srcs]
+    if aligned:
+        assert all(t.data_ptr() % 16 == 0 for t in src_dev)
+    dst_dev = synth.from_bits(np.full(total_dst + 8, 0x7777 if dst_dt == "bf16" else 0x77777777, dtype=bits[dst_dt]),
+                              "cuda")
+    dst_view = dst_dev[8:] if aligned else dst_dev[1:1 + total_dst]
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=SENT8)
+    stream = dev.current_stream()
+    th.th_pack(plan, dev.ptrs(src_dev), wptrs, 0, plan.num_chunks, stream)
+    th.th_unpack(plan, wptrs, 0, plan.num_chunks, [dst_view.data_ptr()], stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(wire_dev.cpu().numpy()[:plan.wire_bytes], wire)
+    assert np.array_equal(synth.to_bits(dst_view)[:total_dst], want)
+    th.th_reshard(plan, dev.ptrs(src_dev), [dst_view.data_ptr()], stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(synth.to_bits(dst_view)[:total_dst], want)
+    plan.destroy()

@@ -182,6 +182,72 @@ def test_counter_seen_from_the_host_during_one_launch():
     plain.destroy()
 
 
+def test_scattered_narrowing_sweep_with_progress():
+    """Explicit segments (fp32 sources at 4-byte alignment narrowed into a 2-byte aligned arena: the
+    any-alignment paths, every store written through) and a plan that mixes aligned and unaligned
+    runs (one list in chunk order, all-paths kernel): wire and arena against the segment oracle."""
+    from oracle import segments
+    from test_planner_manifest import scatter_segments
+    stream = dev.current_stream()
+    keep, view = host_counter()
+    n, seed = 400, 23
+    d = synth.scatter_description(n, seed, min_bytes=256, max_bytes=1 << 17)
+    pool_dev = torch.empty(d["pool_elems"] + 4, dtype=torch.float32, device="cuda")[1:]
+    pool_dev[:d["pool_elems"]] = synth.scatter_values(d["pool_elems"], seed, "cuda", 0.05)
+    pool = synth.to_bits(pool_dev[:d["pool_elems"]])
+    srcs = [pool[o:o + m] for o, m in zip(d["pool_off"], d["n_elems"])]
+    osegs = dict(src_tensor=d["seg_src_tensor"], dst_tensor=np.zeros(n, dtype=np.int64),
+                 src_off=d["seg_src_off"], src_stride=d["seg_src_stride"], dst_off=d["seg_dst_off"],
+                 dst_stride=d["seg_dst_stride"], nrows=d["seg_nrows"], row_len=d["seg_row_len"])
+    wire = segments.pack(osegs, srcs, "f32", "bf16")
+    arena = np.full(d["arena_elems"] + 8, 0x7777, dtype=np.uint16)
+    segments.unpack(osegs, wire, [arena], "bf16")
+    plan = th.th_plan_create_from_segments(scatter_segments(d), d["n_elems"], [len(arena)], 16 * 1024,
+                                           th.TH_FLAG_PROGRESS)
+    nck = plan.num_chunks
+    assert nck > 20
+    src_ptrs = pool_dev.data_ptr() + d["pool_off"].astype(np.uint64) * np.uint64(4)
+    arena_dev = torch.empty(len(arena) + 1, dtype=torch.bfloat16, device="cuda")
+    arena_dev.view(torch.int16).fill_(0x7777)
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=SENT8)
+    th.th_pack_progress(plan, src_ptrs, wptrs, 0, nck, keep.data_ptr(), stream)
+    torch.cuda.synchronize()
+    assert int(view[0]) == nck
+    assert np.array_equal(wire_dev.cpu().numpy()[:plan.wire_bytes], wire)
+    th.th_unpack_progress(plan, wptrs, 0, nck, [arena_dev[1:].data_ptr()], keep.data_ptr(), stream)
+    torch.cuda.synchronize()
+    assert int(view[0]) == nck
+    assert np.array_equal(synth.to_bits(arena_dev[1:]), arena)
+    plan.destroy()
+    # aligned and unaligned bf16 runs in one plan
+    m = 90
+    segs = np.zeros(m, dtype=th.binding.SEGMENT_NP)
+    segs["src_tensor"] = np.arange(m) // 3
+    segs["nrows"], segs["row_len"] = 8, 2048
+    segs["src_row_stride"], segs["dst_row_stride"] = 2560, 2048
+    segs["src_elem_off"] = (np.arange(m) % 3) * 30000 + (np.arange(m) % 2)
+    segs["dst_elem_off"] = np.arange(m) * 8 * 2048
+    segs["src_dtype"] = segs["dst_dtype"] = th.TH_BF16
+    plan = th.th_plan_create_from_segments(segs, np.full(m // 3, 90000), [m * 8 * 2048], 96 * 1024,
+                                           th.TH_FLAG_PTRS_ALIGNED16 | th.TH_FLAG_PROGRESS)
+    assert {plan.tile(0, i).kind for i in range(plan.num_tiles(0))} == {0, 2}
+    assert plan.chunk_first_tile(0, 1, 0) == 0 and plan.chunk_first_tile(0, 2, 0) == plan.num_tiles(0)
+    rng = np.random.default_rng(5)
+    src_bits = [rng.integers(0, 1 << 16, 90000, dtype=np.uint16) for _ in range(m // 3)]
+    osegs = dict(src_tensor=segs["src_tensor"].astype(np.int64), dst_tensor=np.zeros(m, dtype=np.int64),
+                 src_off=segs["src_elem_off"].astype(np.int64), src_stride=segs["src_row_stride"].astype(np.int64),
+                 dst_off=segs["dst_elem_off"].astype(np.int64), dst_stride=segs["dst_row_stride"].astype(np.int64),
+                 nrows=segs["nrows"].astype(np.int64), row_len=segs["row_len"].astype(np.int64))
+    wire = segments.pack(osegs, src_bits, "bf16", "bf16")
+    src_dev = [synth.from_bits(b, "cuda") for b in src_bits]
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=SENT8)
+    th.th_pack_progress(plan, dev.ptrs(src_dev), wptrs, 0, plan.num_chunks, keep.data_ptr(), stream)
+    torch.cuda.synchronize()
+    assert int(view[0]) == plan.num_chunks
+    assert np.array_equal(wire_dev.cpu().numpy()[:plan.wire_bytes], wire)
+    plan.destroy()
+
+
 def test_argument_errors():
     w = synth.workload("cfg1_tiny_tp2_to_tp1")
     model, src, dst = w["model"], w["holders"][0], w["reader"]

@@ -81,19 +81,29 @@ def test_manifest_reproduces_oracle(name, tile_bytes):
             for c, (g, x) in enumerate(zip(tchunks, want_chunks)):
                 assert np.array_equal(g, x), "tiles: chunk %d" % c
             exec_tiles(plan, 1, tchunks, flat_u8(got_tiles))
-            # tiles: vector-path tiles first, then the others, each sub-list grouped by chunk
+            # tiles: vector-path tiles first, then the others, then the short ones, each sub-list grouped by chunk
+            short_slots = th.th_config_get(th.TH_CFG_SHORT_TILE_SLOTS)
             for side in (0, 1):
                 n = plan.num_chunks
-                f0 = [plan.chunk_first_tile(side, 0, c) for c in range(n + 1)]
-                f1 = [plan.chunk_first_tile(side, 1, c) for c in range(n + 1)]
-                assert f0[0] == 0 and f0[-1] == f1[0] and f1[-1] == plan.num_tiles(side)
-                assert f0 == sorted(f0) and f1 == sorted(f1)
-                for k, firsts in ((0, f0), (1, f1)):
+                firsts = [[plan.chunk_first_tile(side, k, c) for c in range(n + 1)] for k in range(3)]
+                assert firsts[0][0] == 0 and firsts[0][-1] == firsts[1][0] and firsts[1][-1] == firsts[2][0]
+                assert firsts[2][-1] == plan.num_tiles(side)
+                for k in range(3):
+                    assert firsts[k] == sorted(firsts[k])
                     for c in range(n):
-                        for i in range(firsts[c], firsts[c + 1]):
+                        for i in range(firsts[k][c], firsts[k][c + 1]):
                             t = plan.tile(side, i)
                             assert (t.dst_buf if side == 0 else t.src_buf) == c
-                            assert (t.kind == 0) == (k == 0)
+                            if k < 2:
+                                assert (t.kind == 0) == (k == 0)
+                            else:  # a tile of a short run fits the slots that make a run short
+                                slot = 8 if (t.elem_bytes_src, t.elem_bytes_dst) == (4, 2) else 16
+                                if t.kind == 1:
+                                    rows = t.count // t.row_len
+                                    slots = rows * ((t.row_len * t.elem_bytes_dst + slot - 1) // slot + 1)
+                                else:
+                                    slots = (t.count * t.elem_bytes_dst + slot - 1) // slot
+                                assert slots <= short_slots + 1
             plan.destroy()
         for a, b, x in zip(got_runs, got_tiles, want_dst):
             assert np.array_equal(a, x) and np.array_equal(b, x)
@@ -439,10 +449,25 @@ def test_tiles_of_a_contiguous_destination_start_on_cache_lines(flags):
     plan.destroy()
 
 
+@pytest.fixture
+def no_short_runs():
+    """Plans that publish progress have no short class; compare them with plain plans built the same way."""
+    old = th.th_config_get(th.TH_CFG_SHORT_TILE_SLOTS)
+    th.th_config_set(th.TH_CFG_SHORT_TILE_SLOTS, 0)
+    yield
+    th.th_config_set(th.TH_CFG_SHORT_TILE_SLOTS, old)
+
+
+def dealt_back(plan, side, t0, t1):
+    """Tiles at list positions [t0, t1) read the way the XCDs walk them: positions of XCD 0 in order, then XCD 1 ..."""
+    b = [bytes(plan.tile(side, i)) for i in range(t0, t1)]
+    return [b[p - t0] for x in range(8) for p in range(t0, t1) if p % 8 == x]
+
+
 @pytest.mark.parametrize("name,chunk_bytes,tile_bytes", [("small_dense_tp1_to_tp4", 128 * 1024, 4096),
                                                         ("small_moe_ep4_to_tp2", 64 * 1024, 4096),
                                                         ("small_dense_tp4_to_tp2", 256 * 1024, 16384)])
-def test_prefix_ordered_lists_hold_the_same_tiles_chunk_by_chunk(name, chunk_bytes, tile_bytes):
+def test_prefix_ordered_lists_hold_the_same_tiles_chunk_by_chunk(name, chunk_bytes, tile_bytes, no_short_runs):
     """A plan that can publish progress keeps every chunk's tiles in that chunk's list positions
     (so chunks finish in order) and, inside a chunk, gives the positions that fall to one XCD
     (equal position mod 8) consecutive tiles.  The lists still reproduce the oracle's wire and the
@@ -450,27 +475,20 @@ def test_prefix_ordered_lists_hold_the_same_tiles_chunk_by_chunk(name, chunk_byt
     w = synth.workload(name)
     model, src, dst = w["model"], w["holders"][0], w["reader"]
     with tile_sizes(tile_bytes):
-        th.th_config_set(th.TH_CFG_TILE_BYTES_PROGRESS, tile_bytes)
-        try:
-            plain = th.th_plan_create(model, src, dst, chunk_bytes, HOST)
-            ordered = th.th_plan_create(model, src, dst, chunk_bytes, HOST | th.TH_FLAG_PROGRESS)
-        finally:
-            th.th_config_set(th.TH_CFG_TILE_BYTES_PROGRESS, 16384)
+        plain = th.th_plan_create(model, src, dst, chunk_bytes, HOST)
+        ordered = th.th_plan_create(model, src, dst, chunk_bytes, HOST | th.TH_FLAG_PROGRESS)
     tensors = holder_tensors_cpu(model, src, w["seed"], pattern=True)
     want_chunks = reshard.chunks(reshard.pack(model, src, dst, tensors), chunk_bytes)
     moved = 0
     for side in (0, 1):
         assert ordered.num_tiles(side) == plain.num_tiles(side)
-        for k in (0, 1):
-            for c in range(plain.num_chunks):
-                t0, t1 = plain.chunk_first_tile(side, k, c), plain.chunk_first_tile(side, k, c + 1)
-                assert (t0, t1) == (ordered.chunk_first_tile(side, k, c), ordered.chunk_first_tile(side, k, c + 1))
-                a = [bytes(plain.tile(side, i)) for i in range(t0, t1)]
-                b = [bytes(ordered.tile(side, i)) for i in range(t0, t1)]
-                # positions of XCD 0 (in order), then those of XCD 1, ... give back the chunk's tiles in order
-                dealt = [b[p - t0] for x in range(8) for p in range(t0, t1) if p % 8 == x]
-                assert dealt == a
-                moved += a != b
+        assert plain.chunk_first_tile(side, 1, 0) == plain.num_tiles(side)      # vector-path tiles only
+        for c in range(plain.num_chunks):
+            t0, t1 = plain.chunk_first_tile(side, 0, c), plain.chunk_first_tile(side, 0, c + 1)
+            assert (t0, t1) == (ordered.chunk_first_tile(side, 0, c), ordered.chunk_first_tile(side, 0, c + 1))
+            a = [bytes(plain.tile(side, i)) for i in range(t0, t1)]
+            assert dealt_back(ordered, side, t0, t1) == a
+            moved += a != [bytes(ordered.tile(side, i)) for i in range(t0, t1)]
     assert moved > 0
     tchunks = [np.full(len(c), 0xEE, dtype=np.uint8) for c in want_chunks]
     exec_tiles(ordered, 0, flat_u8(tensors), tchunks)
@@ -481,5 +499,42 @@ def test_prefix_ordered_lists_hold_the_same_tiles_chunk_by_chunk(name, chunk_byt
     # the wire-free list is not divided by chunk and keeps its order
     assert [bytes(ordered.tile(2, i)) for i in range(ordered.num_tiles(2))] == \
            [bytes(plain.tile(2, i)) for i in range(plain.num_tiles(2))]
+    plain.destroy()
+    ordered.destroy()
+
+
+def test_prefix_ordered_plan_with_mixed_paths_keeps_one_list(no_short_runs):
+    """Launches run class after class, which cannot finish chunk after chunk: a plan that publishes
+    progress and has tiles of more than one path class keeps them all in one list in chunk order."""
+    n = 60
+    segs = np.zeros(n, dtype=th.binding.SEGMENT_NP)
+    segs["src_tensor"] = np.arange(n) // 3
+    segs["nrows"], segs["row_len"] = 8, 2048
+    segs["src_row_stride"], segs["dst_row_stride"] = 2560, 2048
+    segs["src_elem_off"] = (np.arange(n) % 3) * 30000 + (np.arange(n) % 2)    # every other run is off by one element
+    segs["dst_elem_off"] = np.arange(n) * 8 * 2048
+    segs["src_dtype"] = segs["dst_dtype"] = th.TH_BF16
+    args = (segs, np.full(n // 3, 90000), [n * 8 * 2048], 96 * 1024)
+    with tile_sizes(4096):
+        plain = th.th_plan_create_from_segments(*args, HOST | th.TH_FLAG_PTRS_ALIGNED16)
+        ordered = th.th_plan_create_from_segments(*args, HOST | th.TH_FLAG_PTRS_ALIGNED16 | th.TH_FLAG_PROGRESS)
+    mixed = 0
+    for side in (0, 1):
+        total = plain.num_tiles(side)
+        n_vec = plain.chunk_first_tile(side, 1, 0)
+        assert ordered.num_tiles(side) == total
+        if 0 < n_vec < total:     # pack: every other run starts off a 16-byte boundary of its tensor
+            mixed += 1
+            assert ordered.chunk_first_tile(side, 1, 0) == 0 and ordered.chunk_first_tile(side, 2, 0) == total
+            merged = 1
+        else:                     # unpack: wire and reader tensor are aligned, vector path throughout
+            assert n_vec == total and ordered.chunk_first_tile(side, 1, 0) == total
+            merged = 0
+        for c in range(plain.num_chunks):
+            a = [bytes(plain.tile(side, i)) for k in range(3)
+                 for i in range(plain.chunk_first_tile(side, k, c), plain.chunk_first_tile(side, k, c + 1))]
+            t0, t1 = ordered.chunk_first_tile(side, merged, c), ordered.chunk_first_tile(side, merged, c + 1)
+            assert t1 - t0 == len(a) and dealt_back(ordered, side, t0, t1) == a
+    assert mixed == 1
     plain.destroy()
     ordered.destroy()
