@@ -183,11 +183,16 @@ int th_plan_create_from_segments(const th_segment* segs, size_t n,
  *              th_plan_chunk_bytes(plan, chunk_first+i) bytes.  Every byte of the
  *              chunk is written (payload and zero gaps).
  * The host arrays are read before the call returns.  Pointer tables are kept on
- * the device and re-uploaded only when their contents change (the call that
- * brings a table not seen before allocates and copies synchronously, and every
- * 32nd such call synchronises the device to free replaced tables; a call with
+ * the device and re-uploaded only when their contents change: a call with
  * tables seen before, or with at most 8 chunks and known tensor pointers, only
- * launches).
+ * launches; a call that brings a table not seen before copies it with an
+ * asynchronous copy on hip_stream (from a pinned buffer the library keeps) and
+ * may allocate that buffer and the device table.  No call synchronises the
+ * device, a stream or the host: replaced tables are reused once events recorded
+ * on the streams that were handed them have completed, and freed with the plan.
+ * A stream that has been used with a plan must not be destroyed before the plan.
+ * Tensor pointers are checked (NULL, alignment) whenever a table is new; a table
+ * equal to one seen before was checked then.
  * Graph capture: th_pack, th_unpack, their checksum variants, th_reshard and
  * th_signal may be called on a stream that is being captured (a per-chunk
  * pipeline replayed version after version, as tensors are registered once,

@@ -36,21 +36,42 @@ int hip_fail(hipError_t e, const char* what) {
     return TH_ERR_HIP;
 }
 
-// A pointer table that lives on the device, with the host copy it was uploaded from.
+// Device storage of one pointer table: the table itself, a pinned host buffer of the same size that
+// it is uploaded from (the copy is asynchronous, so the bytes must stay put until it has run), and,
+// once the table has been replaced, the events that must have completed before the storage is used
+// again: one per stream that was handed the table.
+struct TableStore {
+    void** dev = nullptr;
+    void** staging = nullptr;
+    size_t cap = 0;  // entries
+    std::vector<hipEvent_t> busy;
+    bool lost = false;  // no way to tell when its last user is done: kept until the plan dies
+};
+
+// A pointer table on the device, with the host copy it was uploaded from.
 struct PtrSlot {
     std::vector<uintptr_t> host;
-    void** dev = nullptr;
-    size_t cap = 0;  // entries allocated on the device
+    TableStore store;
     uint64_t stamp = 0;
     bool pinned = false;  // a captured graph refers to the device table: kept until the plan dies
+    hipEvent_t ready = nullptr;  // the upload, recorded on the stream of the call that brought the table
+    bool ready_done = false;     // ... has been seen complete
+    hipStream_t ready_stream = nullptr;
+    std::vector<hipStream_t> users;  // streams that were handed the table
+    bool many_users = false;
 };
 
 // Small cache of uploaded pointer tables: callers usually pass the same registered
 // tensors and the same wire buffers version after version (tensors are registered once
 // and reused, Sec. 4.2), so steady-state calls upload nothing and make no HIP call besides
-// the kernel launch.  A device table is never overwritten: a kernel that was handed it may
-// still be running.  When a slot gets a new key, its old device table is retired and freed
-// later, after a device synchronisation (once per kRetireBatch retirements) or with the plan.
+// the kernel launch.
+//
+// Nothing here synchronises the device or the host.  A new table is copied from a pinned buffer
+// with an asynchronous copy on the call's own stream (calls on other streams that hit the table
+// before the copy has run make their stream wait for its event).  A device table is never
+// overwritten while a kernel that was handed it may still run: when a slot gets a new key, an
+// event is recorded on every stream that used the old table, and the old storage goes to a pool
+// from which it is taken again once those events have completed.  Storage is freed with the plan.
 //
 // Stream capture: a call on a capturing stream may not allocate or copy, so its tables must already
 // be in the cache (the caller makes the same call once outside capture); the slots it uses are
@@ -58,10 +79,22 @@ struct PtrSlot {
 // is replayed.
 struct PtrCache {
     static constexpr size_t kSlots = 8;
-    static constexpr size_t kRetireBatch = 32;
+    static constexpr size_t kMaxUsers = 8;
     std::vector<PtrSlot> slots;
-    std::vector<void**> retired;
+    std::vector<TableStore> pool;      // replaced tables waiting for their last users
+    std::vector<hipEvent_t> events;    // spare events
     uint64_t clock = 0;
+
+    hipEvent_t take_event() {
+        if (!events.empty()) {
+            hipEvent_t e = events.back();
+            events.pop_back();
+            return e;
+        }
+        hipEvent_t e = nullptr;
+        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return nullptr;
+        return e;
+    }
 
     // The slot whose host copy equals key[0..n), or nullptr.
     PtrSlot* find(const uintptr_t* key, size_t n) {
@@ -73,14 +106,95 @@ struct PtrCache {
         return nullptr;
     }
 
-    // Returns the slot holding exactly key[0..n) (uploading it if new), or nullptr on error.
+    // The call on `stream` is about to hand the slot's table to a kernel.
+    int use(PtrSlot* s, hipStream_t stream, bool capturing) {
+        if (!s->ready_done && s->ready) {
+            if (stream == s->ready_stream) {
+                // same stream as the upload: ordered behind it already
+            } else if (capturing) {
+                // a captured stream cannot wait for work outside the capture: wait here, once
+                const hipError_t e = hipEventSynchronize(s->ready);
+                if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize(pointer table)");
+                s->ready_done = true;
+            } else if (hipEventQuery(s->ready) == hipSuccess) {
+                s->ready_done = true;
+            } else {
+                const hipError_t e = hipStreamWaitEvent(stream, s->ready, 0);
+                if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(pointer table)");
+            }
+        }
+        if (!s->many_users && std::find(s->users.begin(), s->users.end(), stream) == s->users.end()) {
+            if (s->users.size() < kMaxUsers)
+                s->users.push_back(stream);
+            else
+                s->many_users = true;
+        }
+        return TH_OK;
+    }
+
+    // The slot's table has been replaced: its storage can be used again when every stream that was
+    // handed it has passed this point.
+    void retire(PtrSlot* s) {
+        TableStore old = std::move(s->store);
+        s->store = TableStore();
+        if (s->ready) events.push_back(s->ready);  // its stream's later event covers the upload too
+        s->ready = nullptr;
+        if (!old.dev) return;
+        old.lost = s->many_users;
+        for (hipStream_t st : s->users) {
+            if (old.lost) break;
+            hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+            hipEvent_t e = nullptr;
+            if (hipStreamIsCapturing(st, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone || !(e = take_event()) ||
+                hipEventRecord(e, st) != hipSuccess) {
+                (void)hipGetLastError();  // e.g. the caller has destroyed the stream: never reuse this storage
+                if (e) events.push_back(e);
+                old.lost = true;
+                break;
+            }
+            old.busy.push_back(e);
+        }
+        s->users.clear();
+        s->many_users = false;
+        pool.push_back(std::move(old));
+    }
+
+    // Storage for a table of n entries: from the pool when one is large enough and idle, else new.
+    int acquire(size_t n, TableStore* out) {
+        for (size_t i = 0; i < pool.size(); ++i) {
+            TableStore& t = pool[i];
+            if (t.lost || t.cap < n) continue;
+            while (!t.busy.empty() && hipEventQuery(t.busy.back()) == hipSuccess) {
+                events.push_back(t.busy.back());
+                t.busy.pop_back();
+            }
+            if (!t.busy.empty()) continue;
+            *out = std::move(t);
+            pool.erase(pool.begin() + i);
+            return TH_OK;
+        }
+        TableStore t;
+        t.cap = n ? n : 1;
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&t.dev), t.cap * sizeof(void*));
+        if (e != hipSuccess) return hip_fail(e, "hipMalloc(pointer table)");
+        e = hipHostMalloc(reinterpret_cast<void**>(&t.staging), t.cap * sizeof(void*), hipHostMallocDefault);
+        if (e != hipSuccess) {
+            (void)hipFree(t.dev);
+            return hip_fail(e, "hipHostMalloc(pointer table)");
+        }
+        *out = std::move(t);
+        return TH_OK;
+    }
+
+    // Returns the slot holding exactly key[0..n) (uploading it on `stream` if new), or nullptr on error.
     // capturing: the call's stream is being captured into a graph.
-    PtrSlot* get(const uintptr_t* key, size_t n, bool capturing, bool& fresh, int& rc) {
+    PtrSlot* get(const uintptr_t* key, size_t n, hipStream_t stream, bool capturing, bool& fresh, int& rc) {
         fresh = false;
         rc = TH_ERR_HIP;  // what a nullptr means unless said otherwise below
         if (PtrSlot* hit = find(key, n)) {
             hit->pinned |= capturing;
-            return hit;
+            rc = use(hit, stream, capturing);
+            return rc == TH_OK ? hit : nullptr;
         }
         if (capturing) {
             set_error("the stream is being captured and this call's pointer tables are not on the device yet: "
@@ -100,48 +214,47 @@ struct PtrCache {
             s = &slots.back();
         }
         s->host.clear();
-        if (s->dev) {
-            retired.push_back(s->dev);
-            s->dev = nullptr;
-            s->cap = 0;
-            if (retired.size() >= kRetireBatch) {
-                const hipError_t e = hipDeviceSynchronize();
-                if (e != hipSuccess) {
-                    hip_fail(e, "hipDeviceSynchronize");
-                    return nullptr;
-                }
-                for (void** d : retired) (void)hipFree(d);
-                retired.clear();
-            }
-        }
-        const size_t cap = n ? n : 1;
-        hipError_t e = hipMalloc(reinterpret_cast<void**>(&s->dev), cap * sizeof(void*));
-        if (e != hipSuccess) {
-            s->dev = nullptr;
-            hip_fail(e, "hipMalloc(pointer table)");
-            return nullptr;
-        }
-        s->cap = cap;
+        retire(s);
+        if ((rc = acquire(n, &s->store)) != TH_OK) return nullptr;
+        rc = TH_ERR_HIP;
         if (n) {
-            e = hipMemcpy(s->dev, key, n * sizeof(void*), hipMemcpyHostToDevice);
+            std::memcpy(s->store.staging, key, n * sizeof(void*));
+            const hipError_t e = hipMemcpyAsync(s->store.dev, s->store.staging, n * sizeof(void*), hipMemcpyHostToDevice, stream);
             if (e != hipSuccess) {
-                hip_fail(e, "hipMemcpy(pointer table)");
+                hip_fail(e, "hipMemcpyAsync(pointer table)");
                 return nullptr;
             }
+        }
+        s->ready = take_event();
+        s->ready_done = false;
+        s->ready_stream = stream;
+        if (!s->ready || hipEventRecord(s->ready, stream) != hipSuccess) {
+            set_error("could not record the pointer table's upload event");
+            return nullptr;
         }
         s->host.assign(key, key + n);
         s->stamp = ++clock;
         fresh = true;
-        return s;
+        rc = use(s, stream, false);
+        return rc == TH_OK ? s : nullptr;
     }
 
     // The plan is being destroyed: the caller has synchronised the streams that used it.
     void release() {
-        for (PtrSlot& s : slots)
-            if (s.dev) (void)hipFree(s.dev);
-        for (void** d : retired) (void)hipFree(d);
+        auto drop = [&](TableStore& t) {
+            if (t.dev) (void)hipFree(t.dev);
+            if (t.staging) (void)hipHostFree(t.staging);
+            for (hipEvent_t e : t.busy) (void)hipEventDestroy(e);
+        };
+        for (PtrSlot& s : slots) {
+            drop(s.store);
+            if (s.ready) (void)hipEventDestroy(s.ready);
+        }
+        for (TableStore& t : pool) drop(t);
+        for (hipEvent_t e : events) (void)hipEventDestroy(e);
         slots.clear();
-        retired.clear();
+        pool.clear();
+        events.clear();
     }
 };
 
@@ -262,29 +375,32 @@ int check_device(const th_plan* p) {
 
 // Looks up / uploads the device table of the tensor base pointers of one side (0 = source tensors,
 // 1 = destination tensors) and validates a table that was not seen before.  Caller holds p->mu.
-int tensor_table(const th_plan* p, int side, const void* const* ptrs, uint32_t n, bool capturing, PtrSlot** out) {
+int tensor_table(const th_plan* p, int side, const void* const* ptrs, uint32_t n, void* stream, bool capturing,
+                 PtrSlot** out) {
     const Manifest& m = p->m;
     static_assert(sizeof(uintptr_t) == sizeof(void*), "pointer tables are compared as integers");
     const uintptr_t* key = reinterpret_cast<const uintptr_t*>(ptrs);
-    bool fresh = false;
-    int rc = TH_OK;
-    PtrSlot* ts = p->tensor_cache[side].get(key, n, capturing, fresh, rc);
-    *out = ts;
-    if (!ts) return rc;
-    if (!fresh) return TH_OK;
-    for (uint32_t i = 0; i < n; ++i) {
-        const TensorInfo& t = m.tensors[side][i];
-        if (!t.used) continue;
-        const uintptr_t a = key[i];
-        const uintptr_t need = t.need16 ? 16 : esize(t.dtype);
-        if (a == 0 || a % need) {
-            ts->host.clear();  // do not keep a rejected table
-            set_error("%s tensor %u (%s): pointer %p is %s", side ? "destination" : "source", i, t.name.c_str(),
-                      (void*)a, a ? "misaligned" : "NULL");
-            return TH_ERR_ARG;
+    // A table equal to a cached one was checked when it was uploaded; a new one is checked before
+    // anything is enqueued for it.
+    if (!p->tensor_cache[side].find(key, n)) {
+        for (uint32_t i = 0; i < n; ++i) {
+            const TensorInfo& t = m.tensors[side][i];
+            if (!t.used) continue;
+            const uintptr_t a = key[i];
+            const uintptr_t need = t.need16 ? 16 : esize(t.dtype);
+            if (a == 0 || a % need) {
+                set_error("%s tensor %u (%s): pointer %p is %s", side ? "destination" : "source", i, t.name.c_str(),
+                          (void*)a, a ? "misaligned" : "NULL");
+                *out = nullptr;
+                return TH_ERR_ARG;
+            }
         }
     }
-    return TH_OK;
+    bool fresh = false;
+    int rc = TH_OK;
+    PtrSlot* ts = p->tensor_cache[side].get(key, n, static_cast<hipStream_t>(stream), capturing, fresh, rc);
+    *out = ts;
+    return ts ? TH_OK : rc;
 }
 
 // Shared body of th_pack / th_unpack.  side 0: tensors are the source, wire the destination.
@@ -352,7 +468,7 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
     if (int rc = stream_capturing(stream, capturing)) return rc;
     std::lock_guard<std::mutex> lk(p->mu);
     PtrSlot* ts = nullptr;
-    if (int rc = tensor_table(p, side, tensor_ptrs, n_tensors, capturing, &ts)) return rc;
+    if (int rc = tensor_table(p, side, tensor_ptrs, n_tensors, stream, capturing, &ts)) return rc;
     // Short chunk ranges carry their wire pointers in the kernel arguments; longer ones use a
     // cached device table whose entry 0 is skipped by the kernel's indexing.
     InlineWire inl;
@@ -368,11 +484,11 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
         for (uint32_t i = 0; i < chunk_count; ++i) wkey[i + 1] = reinterpret_cast<uintptr_t>(wire_ptrs[i]);
         bool fresh = false;
         int wrc = TH_OK;
-        ws = p->wire_cache[side].get(wkey.data(), wkey.size(), capturing, fresh, wrc);
+        ws = p->wire_cache[side].get(wkey.data(), wkey.size(), static_cast<hipStream_t>(stream), capturing, fresh, wrc);
         if (!ws) return wrc;
-        wire_tab = reinterpret_cast<const void* const*>(ws->dev + 1);
+        wire_tab = reinterpret_cast<const void* const*>(ws->store.dev + 1);
     }
-    const void* const* tens_tab = reinterpret_cast<const void* const*>(ts->dev);
+    const void* const* tens_tab = reinterpret_cast<const void* const*>(ts->store.dev);
     if (!wire_tab) wire_tab = tens_tab;  // never read in inline mode, but keep it a valid device address
     Progress prog;
     prog.ordered = p->progress ? 1u : 0u;
@@ -635,13 +751,13 @@ int th_reshard(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, vo
     if (int rc = stream_capturing(hip_stream, capturing)) return rc;
     std::lock_guard<std::mutex> lk(p->mu);
     PtrSlot *ss = nullptr, *ds = nullptr;
-    if (int rc = no_throw([&] { return tensor_table(p, 0, src_ptrs, n_src, capturing, &ss); })) return rc;
+    if (int rc = no_throw([&] { return tensor_table(p, 0, src_ptrs, n_src, hip_stream, capturing, &ss); })) return rc;
     if (int rc = no_throw([&] {
-            return tensor_table(p, 1, const_cast<const void* const*>(dst_ptrs), n_dst, capturing, &ds);
+            return tensor_table(p, 1, const_cast<const void* const*>(dst_ptrs), n_dst, hip_stream, capturing, &ds);
         }))
         return rc;
-    const void* const* stab = reinterpret_cast<const void* const*>(ss->dev);
-    void* const* dtab = reinterpret_cast<void* const*>(ds->dev);
+    const void* const* stab = reinterpret_cast<const void* const*>(ss->store.dev);
+    void* const* dtab = reinterpret_cast<void* const*>(ds->store.dev);
     InlineWire no_inline;
     std::memset(&no_inline, 0, sizeof no_inline);
     int rc = TH_OK;

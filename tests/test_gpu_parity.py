@@ -425,6 +425,46 @@ def test_pointer_tables_may_change_between_calls():
     plan.destroy()
 
 
+def test_new_pointer_tables_never_wait_for_other_streams():
+    """Re-registration in steady state: 120 calls, each with a tensor pointer table the library has not
+    seen, on two streams in turn, while a third stream is busy with a long queue of copies that nobody
+    waits for.  The calls and their streams finish while that queue is still running (no call
+    synchronises the device), every wire is the oracle's, and tables that come back are served again."""
+    w = synth.workload("small_dense_tp1_to_tp4")
+    model, src, dst = w["model"], w["holders"][0], w["reader"]
+    plan = th.th_plan_create(model, src, dst, 64 * 1024)          # many chunks: wire pointers in a device table too
+    assert plan.num_chunks > 8
+    tensors = holder_tensors_cpu(model, src, w["seed"], pattern=True)
+    want = reshard.pack(model, src, dst, tensors)
+    src_dev = [to_dev(t) for t in tensors]
+    twins = [to_dev(tensors[1]) for _ in range(120)]              # 120 homes for tensor 1: 120 distinct tables
+    wires = [dev.alloc_wire(plan, fill_byte=SENT8) for _ in range(4)]
+    busy, s1, s2 = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    big_a = torch.empty(4 << 30, dtype=torch.uint8, device="cuda")
+    big_b = torch.empty(4 << 30, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    done = torch.cuda.Event()
+    for _ in range(400):                                          # about half a second of copies
+        th.th_reference_copy(big_b.data_ptr(), big_a.data_ptr(), 4 << 30, busy.cuda_stream)
+    done.record(busy)
+    ptrs = dev.ptrs(src_dev)
+    for i, twin in enumerate(twins):
+        ptrs[1] = twin.data_ptr()
+        wire_dev, wptrs = wires[i % 4]
+        stream = (s1, s2)[i % 2]
+        th.th_pack(plan, ptrs, wptrs, 0, plan.num_chunks, stream.cuda_stream)
+        if i % 16 == 15:                                          # the same table again, on the other stream
+            th.th_pack(plan, ptrs, wires[(i + 1) % 4][1], 0, plan.num_chunks, (s2, s1)[i % 2].cuda_stream)
+    s1.synchronize()
+    s2.synchronize()
+    still_running = not done.query()
+    for wire_dev, _ in wires:
+        assert np.array_equal(wire_dev.cpu().numpy()[:plan.wire_bytes], want)
+    assert still_running, "the calls waited for another stream's work"
+    busy.synchronize()
+    plan.destroy()
+
+
 def test_wire_chunks_in_pinned_host_memory():
     """Offload replica: the wire chunks live in pinned host memory (device-accessible), the kernels
     write / read them over the host link; results are the oracle's, bit for bit."""
