@@ -187,15 +187,18 @@ struct PtrCache {
     }
 
     // Returns the slot holding exactly key[0..n) (uploading it on `stream` if new), or nullptr on error.
-    // capturing: the call's stream is being captured into a graph.
-    PtrSlot* get(const uintptr_t* key, size_t n, hipStream_t stream, bool capturing, bool& fresh, int& rc) {
-        fresh = false;
+    // capturing: the call's stream is being captured into a graph.  check: called for a table that is
+    // not in the cache, before anything is enqueued for it; a nonzero result refuses the table.
+    template <class Check>
+    PtrSlot* get(const uintptr_t* key, size_t n, hipStream_t stream, bool capturing, int& rc, Check&& check) {
         rc = TH_ERR_HIP;  // what a nullptr means unless said otherwise below
         if (PtrSlot* hit = find(key, n)) {
             hit->pinned |= capturing;
             rc = use(hit, stream, capturing);
             return rc == TH_OK ? hit : nullptr;
         }
+        if ((rc = check()) != TH_OK) return nullptr;
+        rc = TH_ERR_HIP;
         if (capturing) {
             set_error("the stream is being captured and this call's pointer tables are not on the device yet: "
                       "make the same call once outside capture");
@@ -234,7 +237,6 @@ struct PtrCache {
         }
         s->host.assign(key, key + n);
         s->stamp = ++clock;
-        fresh = true;
         rc = use(s, stream, false);
         return rc == TH_OK ? s : nullptr;
     }
@@ -332,7 +334,7 @@ int finish_plan(th_plan* p, size_t chunk_bytes, unsigned flags, bool aligned16) 
     if (flags & TH_FLAG_CHECKSUM) tune.tile_bytes = tune.tile_bytes_checksum;
     if (flags & TH_FLAG_PROGRESS) {
         tune.tile_bytes = tune.tile_bytes_progress;
-        tune.chunk_order = true;
+        tune.single_list = true;
         tune.short_slots = 0;  // one list in chunk order: no class that would run after the others
     }
     p->vec_instance = vector_instance(tune.tile_bytes);
@@ -382,7 +384,7 @@ int tensor_table(const th_plan* p, int side, const void* const* ptrs, uint32_t n
     const uintptr_t* key = reinterpret_cast<const uintptr_t*>(ptrs);
     // A table equal to a cached one was checked when it was uploaded; a new one is checked before
     // anything is enqueued for it.
-    if (!p->tensor_cache[side].find(key, n)) {
+    auto check = [&]() -> int {
         for (uint32_t i = 0; i < n; ++i) {
             const TensorInfo& t = m.tensors[side][i];
             if (!t.used) continue;
@@ -391,14 +393,13 @@ int tensor_table(const th_plan* p, int side, const void* const* ptrs, uint32_t n
             if (a == 0 || a % need) {
                 set_error("%s tensor %u (%s): pointer %p is %s", side ? "destination" : "source", i, t.name.c_str(),
                           (void*)a, a ? "misaligned" : "NULL");
-                *out = nullptr;
                 return TH_ERR_ARG;
             }
         }
-    }
-    bool fresh = false;
+        return TH_OK;
+    };
     int rc = TH_OK;
-    PtrSlot* ts = p->tensor_cache[side].get(key, n, static_cast<hipStream_t>(stream), capturing, fresh, rc);
+    PtrSlot* ts = p->tensor_cache[side].get(key, n, static_cast<hipStream_t>(stream), capturing, rc, check);
     *out = ts;
     return ts ? TH_OK : rc;
 }
@@ -482,16 +483,16 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
         std::vector<uintptr_t> wkey((size_t)chunk_count + 1);
         wkey[0] = chunk_first;
         for (uint32_t i = 0; i < chunk_count; ++i) wkey[i + 1] = reinterpret_cast<uintptr_t>(wire_ptrs[i]);
-        bool fresh = false;
         int wrc = TH_OK;
-        ws = p->wire_cache[side].get(wkey.data(), wkey.size(), static_cast<hipStream_t>(stream), capturing, fresh, wrc);
+        ws = p->wire_cache[side].get(wkey.data(), wkey.size(), static_cast<hipStream_t>(stream), capturing, wrc,
+                                     [] { return (int)TH_OK; });
         if (!ws) return wrc;
         wire_tab = reinterpret_cast<const void* const*>(ws->store.dev + 1);
     }
     const void* const* tens_tab = reinterpret_cast<const void* const*>(ts->store.dev);
     if (!wire_tab) wire_tab = tens_tab;  // never read in inline mode, but keep it a valid device address
     Progress prog;
-    prog.ordered = p->progress ? 1u : 0u;
+    prog.ordered = p->m.chunk_ordered ? 1u : 0u;
     int rc = TH_OK;
     if (want_progress) {
         prog.arrived = p->d_arrived[side];
@@ -712,7 +713,7 @@ int th_pack_noalloc(const th_plan* p, const void* const* src_ptrs, uint32_t n_sr
                                      hip_stream, &tens_tab, &wire_tab))
         return rc;
     Progress order;
-    order.ordered = p->progress ? 1u : 0u;
+    order.ordered = p->m.chunk_ordered ? 1u : 0u;
     int rc = TH_OK;
     for (int k = 0; k < kPathClasses && rc == TH_OK; ++k) {
         if (!ntiles[k]) continue;

@@ -111,6 +111,7 @@ struct Manifest {
     std::vector<uint64_t> tile_base[2];
     uint64_t chunk_bytes = 0, wire_bytes = 0, payload_bytes = 0, src_read_bytes = 0;
     uint32_t n_chunks = 0;
+    bool chunk_ordered = false;  // tiles[0], tiles[1] are in prefix order: workgroup b of a launch runs record b
 };
 
 struct Tuning {
@@ -124,7 +125,10 @@ struct Tuning {
     uint64_t short_slots = 512;       // a run of at most this many 16-byte vectors / destination slots (16 bytes; 8
                                       // when narrowing) is short: its tiles run on one wavefront (0: no run is short)
     unsigned planner_threads = 3;     // threads that build a large plan's three tile lists (1: the calling thread alone)
-    bool chunk_order = false;         // pack / unpack lists in prefix order (plans that publish a progress counter)
+    bool single_list = false;         // plans that publish a progress counter: one list in chunk order when the
+                                      // tiles are of more than one path class
+    uint64_t chunk_order_min_bytes = 1u << 20;  // lists of plans with chunks of at least this size are dealt to the
+                                                // XCDs chunk by chunk (prefix order) instead of as a whole
 };
 Tuning current_tuning();
 

@@ -873,8 +873,10 @@ __global__ __launch_bounds__(256) void th_progress_reset_kernel(Progress prog) {
 
 // One thread per tile: add up the pairs of the tile's wavefronts, shift the result to positions
 // counted from the start of its tensor's run (B += base * A) and add it to the tensor's sums.
-// Tiles of one tensor are neighbours in the list, so a wavefront usually holds one tensor and
-// issues one pair of atomics.
+// A wavefront's 64 tiles belong to a few tensors at most (one, in a list in whole-list order; up to
+// nine in prefix order, where neighbouring positions hold tiles of eight different pieces of a
+// chunk): the lanes of each tensor are added up within the wavefront, tensor after tensor, and one
+// lane issues that tensor's pair of atomics.
 __global__ __launch_bounds__(256) void th_checksum_finalize_kernel(const Tile* __restrict__ tiles,
                                                                    const uint64_t* __restrict__ partials,
                                                                    const uint64_t* __restrict__ tile_base,
@@ -882,10 +884,10 @@ __global__ __launch_bounds__(256) void th_checksum_finalize_kernel(const Tile* _
                                                                    uint32_t partial_stride,
                                                                    uint64_t* __restrict__ sums) {
     const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-    const bool active = i < n;
+    bool todo = i < n;
     uint32_t tensor = 0xFFFFFFFFu;
     uint64_t a = 0, bsum = 0;
-    if (active) {
+    if (todo) {
         tensor = tiles[i].src_tensor;
         for (uint32_t w = 0; w < waves; ++w) {
             const uint64_t* pair = partials + 2 * ((size_t)w * partial_stride + i);
@@ -894,22 +896,22 @@ __global__ __launch_bounds__(256) void th_checksum_finalize_kernel(const Tile* _
         }
         bsum += tile_base[i] * a;
     }
-    const uint32_t lead_tensor = __shfl(tensor, 0);
-    const bool same = __all(!active || tensor == lead_tensor);
-    if (same) {
+    // every pass takes the tensor of the first lane that is still to do; at most 64 passes, usually one
+    while (__any(todo)) {
+        const uint64_t left = __ballot(todo);
+        const uint32_t lead = __shfl(tensor, __builtin_ctzll(left));
+        const bool mine = todo && tensor == lead;
+        uint64_t ta = mine ? a : 0, tb = mine ? bsum : 0;
 #pragma unroll
         for (int off = 32; off; off >>= 1) {
-            a += __shfl_xor(a, off);
-            bsum += __shfl_xor(bsum, off);
+            ta += __shfl_xor(ta, off);
+            tb += __shfl_xor(tb, off);
         }
-        if ((threadIdx.x & 63) == 0 && lead_tensor != 0xFFFFFFFFu) {
-            atomicAdd(reinterpret_cast<unsigned long long*>(sums + 2 * (size_t)lead_tensor), (unsigned long long)a);
-            atomicAdd(reinterpret_cast<unsigned long long*>(sums + 2 * (size_t)lead_tensor + 1),
-                      (unsigned long long)bsum);
+        if ((threadIdx.x & 63) == 0) {
+            atomicAdd(reinterpret_cast<unsigned long long*>(sums + 2 * (size_t)lead), (unsigned long long)ta);
+            atomicAdd(reinterpret_cast<unsigned long long*>(sums + 2 * (size_t)lead + 1), (unsigned long long)tb);
         }
-    } else if (active) {
-        atomicAdd(reinterpret_cast<unsigned long long*>(sums + 2 * (size_t)tensor), (unsigned long long)a);
-        atomicAdd(reinterpret_cast<unsigned long long*>(sums + 2 * (size_t)tensor + 1), (unsigned long long)bsum);
+        todo = todo && !mine;
     }
 }
 
