@@ -395,7 +395,8 @@ enum {
     TH_CFG_SPECIALIZE = 3,     /* nonzero (default): vector-path tiles are launched with a kernel that
                                   contains only that path */
     TH_CFG_TILE_BYTES_PROGRESS = 7, /* vector-path tile size in plans created with TH_FLAG_PROGRESS;
-                                       default 32768 (amortises the wait for the stores' acknowledgements) */
+                                       default 16384 (launches that publish progress run them on
+                                       512-thread workgroups, two vectors per thread) */
     TH_CFG_SHORT_TILE_SLOTS = 8, /* largest run, in 16-byte vectors / destination slots, whose tiles run on
                                     one wavefront instead of a workgroup of 512 or 1024 threads;
                                     default 512, 0 = none */

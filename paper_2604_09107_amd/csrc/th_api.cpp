@@ -268,6 +268,7 @@ struct th_plan {
     bool host_only = false;
     bool specialize = true;
     int vec_instance = th::VEC_ANY;  // vector-only kernel instance that fits this plan's tile size
+    int vec_instance_progress = th::VEC_ANY;  // ... in launches that publish progress (smaller workgroups)
     int device = -1;
     th::Tile* d_tiles[3] = {nullptr, nullptr, nullptr};
     // checksum support (TH_FLAG_CHECKSUM): per-tile (A, B) pairs and per-tile position bases
@@ -338,6 +339,7 @@ int finish_plan(th_plan* p, size_t chunk_bytes, unsigned flags, bool aligned16) 
         tune.short_slots = 0;  // one list in chunk order: no class that would run after the others
     }
     p->vec_instance = vector_instance(tune.tile_bytes);
+    p->vec_instance_progress = vector_instance(tune.tile_bytes, kBlockThreadsProgress);
     int rc = finish_manifest(p->m, chunk_bytes, aligned16, tune);
     if (rc == TH_OK) {
         p->host_only = (flags & TH_FLAG_HOST_ONLY) != 0;
@@ -349,9 +351,10 @@ int finish_plan(th_plan* p, size_t chunk_bytes, unsigned flags, bool aligned16) 
 }
 
 // The kernel instance that runs the tiles of path class k (0 vector path, 1 other, 2 short).
-int class_instance(const th_plan* p, int k) {
+int class_instance(const th_plan* p, int k, bool progress = false) {
     if (k == 2) return ALL_PATHS_SHORT;
-    return (k == 0 && p->specialize) ? p->vec_instance : (int)VEC_ALL_PATHS;
+    if (k == 0 && p->specialize) return progress ? p->vec_instance_progress : p->vec_instance;
+    return VEC_ALL_PATHS;
 }
 
 // Whether work enqueued on `stream` is being recorded into a graph instead of run.
@@ -504,7 +507,7 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
     }
     for (int k = 0; k < kPathClasses && rc == TH_OK; ++k) {
         if (!ntiles[k]) continue;
-        const int instance = class_instance(p, k);
+        const int instance = class_instance(p, k, want_progress);
         uint64_t* partials = want_sums ? p->d_partials[side] : nullptr;
         if (side == 0)
             rc = launch_tiles(MODE_PACK, instance, p->d_tiles[0], tile0[k], ntiles[k], tens_tab,

@@ -90,6 +90,10 @@ static_assert(kBlockThreadsAny <= kBlockThreads && kBlockThreads % 64 == 0 && kB
 // a workgroup of 512 threads would leave most of its wavefront slots idle on them, and a compute
 // unit holds 32 one-wavefront workgroups as easily as four large ones.
 constexpr int kBlockThreadsShort = 64;
+// Launches that publish progress hold their wavefront slots until their stores are acknowledged;
+// workgroups of half the size, two vectors per thread, give the slots back in smaller lots (the
+// 8B- and MoE-shaped reshards gain 2-4 % over 1024 threads on tiles of twice the size).
+constexpr int kBlockThreadsProgress = 512;
 constexpr int kPathClasses = 3;  // sub-lists of a work list: vector path, other tiles, short tiles
 constexpr int kPartialsPerTile = kBlockThreads / 64;  // checksum pairs reserved per tile: one per wavefront
 
@@ -120,7 +124,7 @@ struct Tuning {
     uint64_t tile_bytes_narrow = 8192;  // any-alignment paths when the copy narrows fp32 to bf16 (8-byte slots)
     uint64_t tile_bytes_checksum = 32768;  // vector path in plans with checksums: two vectors per thread amortise
                                            // the per-wavefront reduction
-    uint64_t tile_bytes_progress = 32768;  // vector path in plans that publish a progress counter
+    uint64_t tile_bytes_progress = 16384;  // vector path in plans that publish a progress counter
     bool specialize = true;           // launch vector-path tiles with the kernel that holds only that path
     uint64_t short_slots = 512;       // a run of at most this many 16-byte vectors / destination slots (16 bytes; 8
                                       // when narrowing) is short: its tiles run on one wavefront (0: no run is short)
@@ -155,14 +159,17 @@ inline unsigned esize(int dtype) { return dtype == TH_F32 ? 4u : 2u; }
 enum TileMode { MODE_PACK = 0, MODE_UNPACK = 1, MODE_DIRECT = 2 };
 enum TileInstance { VEC_ALL_PATHS = 0, VEC_ONE = 1, VEC_TWO = 2, VEC_ANY = 3, ALL_PATHS_SHORT = 4 };
 constexpr int kTileInstances = 5;
-// Threads per workgroup of a kernel instance.
-inline int instance_threads(int instance) {
-    return instance == VEC_ALL_PATHS ? kBlockThreadsAny : instance == ALL_PATHS_SHORT ? kBlockThreadsShort : kBlockThreads;
+// Threads per workgroup of a kernel instance (progress: of its build that publishes progress).
+inline int instance_threads(int instance, bool progress = false) {
+    return instance == VEC_ALL_PATHS     ? kBlockThreadsAny
+           : instance == ALL_PATHS_SHORT ? kBlockThreadsShort
+           : progress                    ? kBlockThreadsProgress
+                                         : kBlockThreads;
 }
 // The vector-only instance for tiles of up to tile_bytes.
-inline int vector_instance(uint64_t tile_bytes) {
+inline int vector_instance(uint64_t tile_bytes, int threads = kBlockThreads) {
     const uint64_t vectors = tile_bytes / 16;
-    return vectors <= (uint64_t)kBlockThreads ? VEC_ONE : vectors <= 2 * (uint64_t)kBlockThreads ? VEC_TWO : VEC_ANY;
+    return vectors <= (uint64_t)threads ? VEC_ONE : vectors <= 2 * (uint64_t)threads ? VEC_TWO : VEC_ANY;
 }
 // Wire chunk pointers of a short chunk range travel in the kernel arguments instead of a device
 // table, so that chunk-by-chunk calls (a reader consuming a prefix) upload nothing.

@@ -730,7 +730,10 @@ __device__ __forceinline__ void advance_prefix(const Progress& pr, uint32_t firs
 // INLINE: the wire pointers come from the kernel arguments (short chunk ranges) instead of the table.
 // PROGRESS: the launch counts finished tiles per chunk and publishes the complete prefix (above).
 template <int MODE, int VEC, bool CHECKSUM, bool INLINE, bool PROGRESS>
-__global__ __launch_bounds__(VEC == VEC_ALL_PATHS ? kBlockThreadsAny : VEC == ALL_PATHS_SHORT ? kBlockThreadsShort : kBlockThreads,
+__global__ __launch_bounds__(VEC == VEC_ALL_PATHS     ? kBlockThreadsAny
+                             : VEC == ALL_PATHS_SHORT ? kBlockThreadsShort
+                             : PROGRESS               ? kBlockThreadsProgress
+                                                      : kBlockThreads,
                              TH_MIN_WAVES_PER_EU) void th_tiles_kernel(const Tile* __restrict__ tiles,
                                                                   const void* const* __restrict__ src_table,
                                                                   void* const* __restrict__ dst_table,
@@ -741,7 +744,10 @@ __global__ __launch_bounds__(VEC == VEC_ALL_PATHS ? kBlockThreadsAny : VEC == AL
     // each XCD one contiguous eighth of the tile list so that it streams through its own
     // address range instead of every 8th tile.
     constexpr bool VEC_ONLY = VEC != VEC_ALL_PATHS && VEC != ALL_PATHS_SHORT;
-    constexpr int BT = VEC == VEC_ALL_PATHS ? kBlockThreadsAny : VEC == ALL_PATHS_SHORT ? kBlockThreadsShort : kBlockThreads;
+    constexpr int BT = VEC == VEC_ALL_PATHS     ? kBlockThreadsAny
+                       : VEC == ALL_PATHS_SHORT ? kBlockThreadsShort
+                       : PROGRESS               ? kBlockThreadsProgress
+                                                : kBlockThreads;
     constexpr int VPT = VEC == VEC_ONE ? 1 : VEC == VEC_TWO ? 2 : 0;
     // (A list in prefix order has that arrangement built in, chunk by chunk: record b is workgroup b's.)
     uint32_t b = blockIdx.x;
@@ -1088,7 +1094,7 @@ int launch_tiles(int mode, int instance, const Tile* tiles, uint64_t tile0, uint
     while (ntiles) {
         const uint64_t n = ntiles < kMaxGrid ? ntiles : kMaxGrid;
         pr.pos0 = (uint32_t)tile0;  // low bits of the list position pick counter slots and publishers
-        hipLaunchKernelGGL(kernel, dim3((uint32_t)n), dim3(instance_threads(instance)), 0, st,
+        hipLaunchKernelGGL(kernel, dim3((uint32_t)n), dim3(instance_threads(instance, counting)), 0, st,
                            tiles + tile0, src_table, dst_table, wire_first, (uint32_t)list_tiles, inl,
                            partials ? partials + 2 * tile0 : nullptr, pr);
         const hipError_t e = hipGetLastError();
