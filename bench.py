@@ -311,7 +311,7 @@ def measure(args, name, extras, want_cpu_baseline, mods):
                      "unit": "GB/s", "frac": round(dom[1] / HBM_PEAK_GBPS, 4),
                      "traffic": measured_traffic(name, dom[0])},
     }
-    out = {}
+    out = {"d2d_copy_GB/s": yardsticks(jobs, stream, mods)}
     if extras:
         out.update(extra_sweeps(args, jobs, sweep_bytes, stream, mods))
     if want_cpu_baseline:
@@ -323,8 +323,29 @@ def measure(args, name, extras, want_cpu_baseline, mods):
     return head, out
 
 
+def yardsticks(jobs, stream, mods):
+    """What a plain device-to-device copy of the plan's payload reaches: torch's copy_ and the library's
+    own copy kernel (same launch shape as the aligned path; also the known-size kernel that the HBM
+    byte counters of a profile are scaled by)."""
+    np, torch, synth, th, dev = mods
+    nbytes = jobs[0]["plan"].payload_bytes
+    a = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    b = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    for _ in range(3):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    ms = time_with_events(torch, lambda: b.copy_(a), 10)
+    copy_gbps = 2 * nbytes / (ms * 1e-3) / 1e9
+    n16 = nbytes // 16 * 16
+    for _ in range(3):
+        th.th_reference_copy(b.data_ptr(), a.data_ptr(), n16, stream)
+    ms = time_with_events(torch, lambda: th.th_reference_copy(b.data_ptr(), a.data_ptr(), n16, stream), 10)
+    ref_gbps = 2 * n16 / (ms * 1e-3) / 1e9
+    return {"torch_copy_": round(copy_gbps, 1), "th_reference_copy": round(ref_gbps, 1), "bytes": n16}
+
+
 def extra_sweeps(args, jobs, sweep_bytes, stream, mods):
-    """Secondary figures of a workload: yardstick copies, the wire-free reshard, the sweep with
+    """Secondary figures of a workload: the wire-free reshard, the sweep with
     checksums, the sweep in one call per chunk (eager, as a graph, through a ring of two buffers),
     the sweep in launches that publish their own progress (alone, and with a reader consuming the
     prefix meanwhile), and the offload replica in pinned host memory."""
@@ -335,24 +356,6 @@ def extra_sweeps(args, jobs, sweep_bytes, stream, mods):
     for j in jobs:
         j["ck_plan"] = j["make_plan"](th.TH_FLAG_CHECKSUM)
         j["pr_plan"] = j["make_plan"](th.TH_FLAG_PROGRESS)
-    # practical ceiling: a plain device-to-device copy of the same number of bytes
-    nbytes = jobs[0]["plan"].payload_bytes
-    a = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-    b = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-    for _ in range(3):
-        b.copy_(a)
-    torch.cuda.synchronize()
-    ms = time_with_events(torch, lambda: b.copy_(a), 10)
-    copy_gbps = 2 * nbytes / (ms * 1e-3) / 1e9
-    # ... and the library's own plain copy kernel (same launch shape as the aligned path)
-    n16 = nbytes // 16 * 16
-    for _ in range(3):
-        th.th_reference_copy(b.data_ptr(), a.data_ptr(), n16, stream)
-    ms = time_with_events(torch, lambda: th.th_reference_copy(b.data_ptr(), a.data_ptr(), n16, stream), 10)
-    ref_gbps = 2 * n16 / (ms * 1e-3) / 1e9
-    del a, b
-    out["d2d_copy_GB/s"] = {"torch_copy_": round(copy_gbps, 1), "th_reference_copy": round(ref_gbps, 1)}
-
     # co-located variant: th_reshard straight from holder tensors to reader tensors (no wire)
     direct_bytes = sum(j["plan"].src_read_bytes + j["plan"].payload_bytes for j in jobs)
 

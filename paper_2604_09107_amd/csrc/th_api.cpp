@@ -495,7 +495,7 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
     const void* const* tens_tab = reinterpret_cast<const void* const*>(ts->store.dev);
     if (!wire_tab) wire_tab = tens_tab;  // never read in inline mode, but keep it a valid device address
     Progress prog;
-    prog.ordered = p->m.chunk_ordered ? 1u : 0u;
+    prog.ordered = 1;  // pack and unpack lists are walked in prefix order
     int rc = TH_OK;
     if (want_progress) {
         prog.arrived = p->d_arrived[side];
@@ -716,7 +716,7 @@ int th_pack_noalloc(const th_plan* p, const void* const* src_ptrs, uint32_t n_sr
                                      hip_stream, &tens_tab, &wire_tab))
         return rc;
     Progress order;
-    order.ordered = p->m.chunk_ordered ? 1u : 0u;
+    order.ordered = 1;
     int rc = TH_OK;
     for (int k = 0; k < kPathClasses && rc == TH_OK; ++k) {
         if (!ntiles[k]) continue;

@@ -115,7 +115,6 @@ struct Manifest {
     std::vector<uint64_t> tile_base[2];
     uint64_t chunk_bytes = 0, wire_bytes = 0, payload_bytes = 0, src_read_bytes = 0;
     uint32_t n_chunks = 0;
-    bool chunk_ordered = false;  // tiles[0], tiles[1] are in prefix order: workgroup b of a launch runs record b
 };
 
 struct Tuning {
@@ -131,8 +130,6 @@ struct Tuning {
     unsigned planner_threads = 3;     // threads that build a large plan's three tile lists (1: the calling thread alone)
     bool single_list = false;         // plans that publish a progress counter: one list in chunk order when the
                                       // tiles are of more than one path class
-    uint64_t chunk_order_min_bytes = 1u << 20;  // lists of plans with chunks of at least this size are dealt to the
-                                                // XCDs chunk by chunk (prefix order) instead of as a whole
 };
 Tuning current_tuning();
 
@@ -178,8 +175,34 @@ struct InlineWire {
     void* p[kInlineChunks];
     uint32_t n;  // 0: use the device table
 };
+// Which record of a launch's tile range workgroup q runs when the range is walked in prefix order
+// (th_pack / th_unpack and their variants).  Workgroups are dealt to the 8 XCDs round-robin
+// (workgroup q runs on XCD q mod 8).  The range is cut into blocks of 512 records; block after block
+// is handed out in launch order, and inside a block the 64 workgroups of one XCD take 64 consecutive
+// records (32 whole cache lines of records, 1 MiB of data at the default tile size), so each XCD
+// streams through contiguous memory, the eight XCDs stay within a few MiB of each other, and the
+// tiles of a launch, and with them its chunks, finish roughly in list order (what a progress counter
+// needs).  The records past the last whole block are taken as they come.  A bijection on [0, ntiles).
+// Measured against giving each XCD a contiguous eighth of the whole range: the same speed on the
+// model workloads, 2 % more on the scattered sweep; 64 records per XCD and block beat 8, 16 and 32
+// (by 1-4 %) and 512 (by 1-2 %), 128 is equal.
+#if defined(__HIPCC__)
+#define TH_HOST_DEVICE __host__ __device__
+#else
+#define TH_HOST_DEVICE
+#endif
+#ifndef TH_ORDER_GROUP_LOG2
+#define TH_ORDER_GROUP_LOG2 6
+#endif
+constexpr uint32_t kOrderGroup = 1u << TH_ORDER_GROUP_LOG2;  // consecutive records an XCD takes of a block
+constexpr uint32_t kOrderBlock = 8 * kOrderGroup;            // records per block
+TH_HOST_DEVICE inline uint32_t prefix_order_record(uint32_t q, uint32_t ntiles) {
+    if (q >= (ntiles & ~(kOrderBlock - 1))) return q;
+    return (q & ~(kOrderBlock - 1)) | ((q & 7u) << TH_ORDER_GROUP_LOG2) | ((q >> 3) & (kOrderGroup - 1));
+}
+
 // What a launch needs to know about tile order and progress publishing (by value in the kernel
-// arguments).  ordered: the list is in prefix order, workgroup b runs record b.  arrived != nullptr:
+// arguments).  ordered: the range is walked in prefix order (prefix_order_record).  arrived != nullptr:
 // the launch counts finished tiles per chunk and publishes the number of leading complete chunks of
 // its range to *flag (device, or pinned host memory).
 constexpr uint32_t kProgressSlots = 16;   // arrival counters per chunk

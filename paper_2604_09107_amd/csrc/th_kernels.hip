@@ -46,7 +46,7 @@ typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
 #ifndef TH_UNROLL
 #define TH_UNROLL 4
 #endif
-constexpr uint32_t kRecordsAhead = 256;  // tile records between a workgroup's own and the one it prefetches
+constexpr uint32_t kRecordsAhead = 256;  // tiles of its own XCD between a workgroup's record and the one it prefetches
 #ifndef TH_DENSE_IN_FLIGHT
 #define TH_DENSE_IN_FLIGHT 2
 #endif
@@ -749,10 +749,14 @@ __global__ __launch_bounds__(VEC == VEC_ALL_PATHS     ? kBlockThreadsAny
                        : PROGRESS               ? kBlockThreadsProgress
                                                 : kBlockThreads;
     constexpr int VPT = VEC == VEC_ONE ? 1 : VEC == VEC_TWO ? 2 : 0;
-    // (A list in prefix order has that arrangement built in, chunk by chunk: record b is workgroup b's.)
+    // That is how th_reshard's list is walked.  Pack and unpack lists are walked in prefix order:
+    // block after block of 512 records, each XCD taking 64 consecutive records of a block.
     uint32_t b = blockIdx.x;
     const uint32_t per_xcd = gridDim.x >> 3;
-    if (!prog.ordered && b < per_xcd * 8) b = (b & 7) * per_xcd + (b >> 3);
+    if (prog.ordered)
+        b = prefix_order_record(b, gridDim.x);
+    else if (b < per_xcd * 8)
+        b = (b & 7) * per_xcd + (b >> 3);
 
     const Tile& t = tiles[b];  // uniform: fetched by the scalar unit
     const uint32_t flags = t.flags;
@@ -779,11 +783,14 @@ __global__ __launch_bounds__(VEC == VEC_ALL_PATHS     ? kBlockThreadsAny
     // unit and be waited for, together with the next tile-record or pointer-table load.  This comes
     // after the tile's own uniform loads, which stay scalar only while no asm statement precedes them.
     uint32_t ahead = 0;
-    const bool prefetch = threadIdx.x == 0 && b + kRecordsAhead < gridDim.x;
+    // (In prefix order an XCD takes one record in eight over any stretch of whole blocks: its record
+    // 256 tiles from now sits 2048 records further on.)
+    const uint32_t ahead_by = prog.ordered ? 8 * kRecordsAhead : kRecordsAhead;
+    const bool prefetch = threadIdx.x == 0 && b + ahead_by < gridDim.x;
     if (prefetch) {
         uint32_t opaque_zero;
         asm("v_mov_b32 %0, 0" : "=v"(opaque_zero));
-        const TH_GLOBAL char* next = (const TH_GLOBAL char*)(tiles + b + kRecordsAhead) + opaque_zero;
+        const TH_GLOBAL char* next = (const TH_GLOBAL char*)(tiles + b + ahead_by) + opaque_zero;
         ahead = *(const TH_GLOBAL uint32_t*)next;
     }
 

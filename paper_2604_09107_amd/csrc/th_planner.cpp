@@ -279,12 +279,6 @@ static int finish_manifest_impl(Manifest& m, uint64_t CB, bool ptrs_aligned16, c
         return TH_ERR_ARG;
     }
     m.chunk_bytes = CB;
-    // Large chunks: each XCD walks a contiguous eighth of every chunk rather than of the whole list.
-    // The chunks of a launch then finish roughly in order (what a progress counter needs), and the
-    // eight XCDs stay within one chunk of each other in memory: the same speed on the model
-    // workloads, 2 % more on the scattered sweep.  Small chunks would leave each XCD a few tiles at a
-    // time, so their lists keep the whole-list order unless the plan publishes progress.
-    m.chunk_ordered = tune.single_list || CB >= tune.chunk_order_min_bytes;
     m.wire_bytes = m.payload_bytes = m.src_read_bytes = 0;
     m.tensor_wire_end.assign(m.tensors[0].size(), 0);
     for (const Segment& g : m.segments) {
@@ -469,29 +463,6 @@ static int finish_manifest_impl(Manifest& m, uint64_t CB, bool ptrs_aligned16, c
         for (unsigned k = lead + 1; k < kPathClasses; ++k) {
             m.tiles[side].insert(m.tiles[side].end(), tiles[k].begin(), tiles[k].end());
             m.tile_base[side].insert(m.tile_base[side].end(), base[k].begin(), base[k].end());
-        }
-        if (m.chunk_ordered) {
-            // Prefix order: workgroup b of a launch runs the record at list position b, and workgroups
-            // are dealt to the 8 XCDs round-robin.  Inside every chunk, the positions that fall to one
-            // XCD (equal position mod 8) get consecutive tiles of the chunk, so each XCD still streams
-            // through a contiguous piece, and the chunks of a launch finish roughly in order.
-            std::vector<Tile>& list = m.tiles[side];
-            std::vector<uint64_t>& bases = m.tile_base[side];
-            std::vector<Tile> tmp;
-            std::vector<uint64_t> tmp_base;
-            for (unsigned k = 0; k < kPathClasses; ++k)
-                for (size_t c = 0; c < m.n_chunks; ++c) {
-                    const uint64_t t0 = m.chunk_tile0[side][k][c], t1 = m.chunk_tile0[side][k][c + 1];
-                    if (t1 - t0 < 2) continue;
-                    tmp.assign(list.begin() + t0, list.begin() + t1);
-                    tmp_base.assign(bases.begin() + t0, bases.begin() + t1);
-                    uint64_t from = 0;
-                    for (uint64_t x = 0; x < 8; ++x)
-                        for (uint64_t pos = t0 + ((x + 8 - (t0 & 7)) & 7); pos < t1; pos += 8, ++from) {
-                            list[pos] = tmp[from];
-                            bases[pos] = tmp_base[from];
-                        }
-                }
         }
     };
 

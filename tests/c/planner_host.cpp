@@ -125,6 +125,24 @@ int main() {
         std::printf("segments %zu runs %zu tiles %zu/%zu/%zu wire %llu\n", a.segments.size(), a.runs.size(),
                     a.tiles[0].size(), a.tiles[1].size(), a.tiles[2].size(), (unsigned long long)a.wire_bytes);
     }
+    // 1b. the order in which a launch walks a tile range in prefix order: every record exactly once,
+    //     blocks in launch order, one run of consecutive records per XCD and block, the tail as it comes
+    const uint32_t B = kOrderBlock, G = kOrderGroup;
+    for (uint32_t n : {0u, 1u, 7u, B - 1, B, B + 1, 2 * B - 1, 2 * B, 3 * B + 17, 4096u, 100003u}) {
+        std::vector<uint8_t> hit(n, 0);
+        for (uint32_t q = 0; q < n; ++q) {
+            const uint32_t r = prefix_order_record(q, n);
+            CHECK(r < n && !hit[r]);
+            hit[r] = 1;
+            if (q >= n / B * B) {
+                CHECK(r == q);
+            } else {
+                CHECK(r / B == q / B);                                          // its own block
+                CHECK((r % B) / G == q % 8);                                    // XCD q mod 8 owns one piece of the block
+                if (q % B >= 8) CHECK(r == prefix_order_record(q - 8, n) + 1);  // ... and walks it in order
+            }
+        }
+    }
     // 2. odd explicit segments (rows of 1..97 elements, every alignment), small tiles and chunks
     const uint64_t src_n = 1000000;
     uint64_t dst_n = 0;

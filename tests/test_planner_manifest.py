@@ -458,52 +458,31 @@ def no_short_runs():
     th.th_config_set(th.TH_CFG_SHORT_TILE_SLOTS, old)
 
 
-def dealt_back(plan, side, t0, t1):
-    """Tiles at list positions [t0, t1) read the way the XCDs walk them: positions of XCD 0 in order, then XCD 1 ..."""
-    b = [bytes(plan.tile(side, i)) for i in range(t0, t1)]
-    return [b[p - t0] for x in range(8) for p in range(t0, t1) if p % 8 == x]
-
-
 @pytest.mark.parametrize("name,chunk_bytes,tile_bytes", [("small_dense_tp1_to_tp4", 128 * 1024, 4096),
                                                         ("small_moe_ep4_to_tp2", 64 * 1024, 4096),
                                                         ("small_dense_tp4_to_tp2", 256 * 1024, 16384)])
-def test_prefix_ordered_lists_hold_the_same_tiles_chunk_by_chunk(name, chunk_bytes, tile_bytes, no_short_runs):
-    """A plan that can publish progress keeps every chunk's tiles in that chunk's list positions
-    (so chunks finish in order) and, inside a chunk, gives the positions that fall to one XCD
-    (equal position mod 8) consecutive tiles.  The lists still reproduce the oracle's wire and the
-    tile checksum bases move with their tiles."""
+def test_plans_that_publish_progress_keep_the_plain_lists(name, chunk_bytes, tile_bytes, no_short_runs):
+    """Prefix order is a property of the launch (which record a workgroup takes), not of the lists:
+    a plan with the flag holds the same tiles in the same places as one without (and without a
+    short-run class), so everything the list tests establish carries over."""
     w = synth.workload(name)
     model, src, dst = w["model"], w["holders"][0], w["reader"]
     with tile_sizes(tile_bytes):
         plain = th.th_plan_create(model, src, dst, chunk_bytes, HOST)
         ordered = th.th_plan_create(model, src, dst, chunk_bytes, HOST | th.TH_FLAG_PROGRESS)
-    tensors = holder_tensors_cpu(model, src, w["seed"], pattern=True)
-    want_chunks = reshard.chunks(reshard.pack(model, src, dst, tensors), chunk_bytes)
-    moved = 0
+    for side in (0, 1, 2):
+        assert [bytes(ordered.tile(side, i)) for i in range(ordered.num_tiles(side))] == \
+               [bytes(plain.tile(side, i)) for i in range(plain.num_tiles(side))]
     for side in (0, 1):
-        assert ordered.num_tiles(side) == plain.num_tiles(side)
         assert plain.chunk_first_tile(side, 1, 0) == plain.num_tiles(side)      # vector-path tiles only
-        for c in range(plain.num_chunks):
-            t0, t1 = plain.chunk_first_tile(side, 0, c), plain.chunk_first_tile(side, 0, c + 1)
-            assert (t0, t1) == (ordered.chunk_first_tile(side, 0, c), ordered.chunk_first_tile(side, 0, c + 1))
-            a = [bytes(plain.tile(side, i)) for i in range(t0, t1)]
-            assert dealt_back(ordered, side, t0, t1) == a
-            moved += a != [bytes(ordered.tile(side, i)) for i in range(t0, t1)]
-    assert moved > 0
-    tchunks = [np.full(len(c), 0xEE, dtype=np.uint8) for c in want_chunks]
-    exec_tiles(ordered, 0, flat_u8(tensors), tchunks)
-    for c, (g, x) in enumerate(zip(tchunks, want_chunks)):
-        assert np.array_equal(g, x), "chunk %d" % c
-    got = tile_checksums(ordered, 0, want_chunks, ordered.num_tensors(0))
-    assert np.array_equal(got, tile_checksums(plain, 0, want_chunks, plain.num_tensors(0)))
-    # the wire-free list is not divided by chunk and keeps its order
-    assert [bytes(ordered.tile(2, i)) for i in range(ordered.num_tiles(2))] == \
-           [bytes(plain.tile(2, i)) for i in range(plain.num_tiles(2))]
+        for k in range(3):
+            assert [ordered.chunk_first_tile(side, k, c) for c in range(plain.num_chunks + 1)] == \
+                   [plain.chunk_first_tile(side, k, c) for c in range(plain.num_chunks + 1)]
     plain.destroy()
     ordered.destroy()
 
 
-def test_prefix_ordered_plan_with_mixed_paths_keeps_one_list(no_short_runs):
+def test_plan_that_publishes_progress_with_mixed_paths_keeps_one_list(no_short_runs):
     """Launches run class after class, which cannot finish chunk after chunk: a plan that publishes
     progress and has tiles of more than one path class keeps them all in one list in chunk order."""
     n = 60
@@ -534,7 +513,7 @@ def test_prefix_ordered_plan_with_mixed_paths_keeps_one_list(no_short_runs):
             a = [bytes(plain.tile(side, i)) for k in range(3)
                  for i in range(plain.chunk_first_tile(side, k, c), plain.chunk_first_tile(side, k, c + 1))]
             t0, t1 = ordered.chunk_first_tile(side, merged, c), ordered.chunk_first_tile(side, merged, c + 1)
-            assert t1 - t0 == len(a) and dealt_back(ordered, side, t0, t1) == a
+            assert [bytes(ordered.tile(side, i)) for i in range(t0, t1)] == a
     assert mixed == 1
     plain.destroy()
     ordered.destroy()
