@@ -273,3 +273,65 @@ def test_argument_errors():
     assert bool((wire_dev == SENT8).all())
     plan.destroy()
     plain.destroy()
+
+
+def test_progress_and_noalloc_calls_recorded_into_a_graph():
+    """th_pack_progress + th_unpack_progress (kernels only: the counters are cleared by a kernel, not
+    a memset) and th_pack_noalloc (which needs no earlier call outside capture) recorded into HIP
+    graphs and replayed for new weight versions in the same registered tensors; every replay, with
+    eager work and synchronisation between the replays, against the oracle."""
+    w = synth.workload("small_dense_tp1_to_tp4")
+    model, src, dst = w["model"], w["holders"][0], w["reader"]
+    plan = th.th_plan_create(model, src, dst, 64 * 1024, th.TH_FLAG_PROGRESS)
+    n = plan.num_chunks
+    tensors = holder_tensors_cpu(model, src, 500)
+    src_dev = [to_dev(t) for t in tensors]
+    dst_dev = dev.alloc_tensors(plan, 1, fill_bits=SENT16)
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=SENT8)
+    wire_na, wptrs_na = dev.alloc_wire(plan, fill_byte=SENT8)
+    sp, dp = dev.ptrs(src_dev), dev.ptrs(dst_dev)
+    keep, view = host_counter()
+    flag2 = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    s = torch.cuda.Stream()
+    # the progress calls need their pointer tables on the device before capture: one eager call each
+    th.th_pack_progress(plan, sp, wptrs, 0, n, keep.data_ptr(), s.cuda_stream)
+    th.th_unpack_progress(plan, wptrs, 0, n, dp, flag2.data_ptr(), s.cuda_stream)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        th.th_pack_progress(plan, sp, wptrs, 0, n, keep.data_ptr(), s.cuda_stream)
+        th.th_unpack_progress(plan, wptrs, 0, n, dp, flag2.data_ptr(), s.cuda_stream)
+    g_na = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g_na, stream=s):
+        th.th_pack_noalloc(plan, sp, wptrs_na, 0, n, s.cuda_stream)       # never called outside capture
+    for rep in range(4):
+        tensors = holder_tensors_cpu(model, src, 600 + rep)
+        for d_, t in zip(src_dev, tensors):
+            d_.copy_(to_dev(t))
+        for t in dst_dev:
+            t.view(torch.int16).fill_(0x25C3)
+        wire_dev.fill_(SENT8)
+        wire_na.fill_(SENT8)
+        view[0] = -1
+        flag2.fill_(-1)
+        # eager work of the program's own between the replays, on the shared arrays too
+        th.th_pack_noalloc(plan, sp, wptrs_na[n // 2:], n // 2, n - n // 2, dev.current_stream())
+        torch.cuda.synchronize()
+        wire_na.fill_(SENT8)
+        torch.cuda.synchronize()
+        g.replay()
+        g_na.replay()
+        torch.cuda.synchronize()
+        wire = reshard.pack(model, src, dst, tensors)
+        want = reshard.empty_tensors(model, dst, fill=0x25C3)
+        for t, x in zip(layouts.registered_tensors(model, dst), want):
+            if t["dtype"] == "f32":
+                x[...] = 0x25C3 * 0x10001
+        reshard.unpack(model, src, dst, wire, want)
+        assert int(view[0]) == n and int(flag2.item()) == n, "replay %d" % rep
+        assert np.array_equal(wire_dev.cpu().numpy()[:plan.wire_bytes], wire), "replay %d" % rep
+        assert np.array_equal(wire_na.cpu().numpy()[:plan.wire_bytes], wire), "replay %d (noalloc)" % rep
+        for g_, x in zip(dst_dev, want):
+            assert np.array_equal(synth.to_bits(g_), x.reshape(-1)), "replay %d" % rep
+    del g, g_na
+    plan.destroy()
