@@ -526,6 +526,52 @@ int run_side(const th_plan* p, int side, const void* const* tensor_ptrs, uint32_
     return rc;
 }
 
+// Body of th_reshard: each class of the direct list in one launch, source tensors to destination tensors.
+int run_reshard(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, void* const* dst_ptrs, uint32_t n_dst,
+                void* hip_stream) {
+    if (!p) {
+        set_error("plan is NULL");
+        return TH_ERR_ARG;
+    }
+    if (p->host_only) {
+        set_error("plan was created with TH_FLAG_HOST_ONLY");
+        return TH_ERR_ARG;
+    }
+    const Manifest& m = p->m;
+    if (n_src != m.tensors[0].size() || n_dst != m.tensors[1].size()) {
+        set_error("%u source / %u destination pointers given, plan has %zu / %zu tensors", n_src, n_dst,
+                  m.tensors[0].size(), m.tensors[1].size());
+        return TH_ERR_ARG;
+    }
+    const uint64_t total = m.tiles[2].size();
+    if (total == 0) return TH_OK;
+    if (!src_ptrs || !dst_ptrs) {
+        set_error("null pointer array");
+        return TH_ERR_ARG;
+    }
+    if (int rc = check_device(p)) return rc;
+    bool capturing = false;
+    if (int rc = stream_capturing(hip_stream, capturing)) return rc;
+    std::lock_guard<std::mutex> lk(p->mu);
+    PtrSlot *ss = nullptr, *ds = nullptr;
+    if (int rc = tensor_table(p, 0, src_ptrs, n_src, hip_stream, capturing, &ss)) return rc;
+    if (int rc = tensor_table(p, 1, const_cast<const void* const*>(dst_ptrs), n_dst, hip_stream, capturing, &ds))
+        return rc;
+    const void* const* stab = reinterpret_cast<const void* const*>(ss->store.dev);
+    void* const* dtab = reinterpret_cast<void* const*>(ds->store.dev);
+    InlineWire no_inline;
+    std::memset(&no_inline, 0, sizeof no_inline);
+    int rc = TH_OK;
+    uint64_t first = 0;
+    for (int k = 0; k < kPathClasses && rc == TH_OK; ++k) {
+        if (m.direct_n[k])
+            rc = launch_tiles(MODE_DIRECT, class_instance(p, k), p->d_tiles[2], first, m.direct_n[k], stab, dtab, 0,
+                              no_inline, nullptr, 0, Progress(), hip_stream);
+        first += m.direct_n[k];
+    }
+    return rc;
+}
+
 }  // namespace
 }  // namespace th
 
@@ -730,49 +776,7 @@ int th_pack_noalloc(const th_plan* p, const void* const* src_ptrs, uint32_t n_sr
 
 int th_reshard(const th_plan* p, const void* const* src_ptrs, uint32_t n_src, void* const* dst_ptrs,
                uint32_t n_dst, void* hip_stream) {
-    if (!p) {
-        set_error("plan is NULL");
-        return TH_ERR_ARG;
-    }
-    if (p->host_only) {
-        set_error("plan was created with TH_FLAG_HOST_ONLY");
-        return TH_ERR_ARG;
-    }
-    const Manifest& m = p->m;
-    if (n_src != m.tensors[0].size() || n_dst != m.tensors[1].size()) {
-        set_error("%u source / %u destination pointers given, plan has %zu / %zu tensors", n_src, n_dst,
-                  m.tensors[0].size(), m.tensors[1].size());
-        return TH_ERR_ARG;
-    }
-    const uint64_t total = m.tiles[2].size();
-    if (total == 0) return TH_OK;
-    if (!src_ptrs || !dst_ptrs) {
-        set_error("null pointer array");
-        return TH_ERR_ARG;
-    }
-    if (int rc = check_device(p)) return rc;
-    bool capturing = false;
-    if (int rc = stream_capturing(hip_stream, capturing)) return rc;
-    std::lock_guard<std::mutex> lk(p->mu);
-    PtrSlot *ss = nullptr, *ds = nullptr;
-    if (int rc = no_throw([&] { return tensor_table(p, 0, src_ptrs, n_src, hip_stream, capturing, &ss); })) return rc;
-    if (int rc = no_throw([&] {
-            return tensor_table(p, 1, const_cast<const void* const*>(dst_ptrs), n_dst, hip_stream, capturing, &ds);
-        }))
-        return rc;
-    const void* const* stab = reinterpret_cast<const void* const*>(ss->store.dev);
-    void* const* dtab = reinterpret_cast<void* const*>(ds->store.dev);
-    InlineWire no_inline;
-    std::memset(&no_inline, 0, sizeof no_inline);
-    int rc = TH_OK;
-    uint64_t first = 0;
-    for (int k = 0; k < kPathClasses && rc == TH_OK; ++k) {
-        if (m.direct_n[k])
-            rc = launch_tiles(MODE_DIRECT, class_instance(p, k), p->d_tiles[2], first, m.direct_n[k], stab, dtab, 0,
-                              no_inline, nullptr, 0, Progress(), hip_stream);
-        first += m.direct_n[k];
-    }
-    return rc;
+    return no_throw([&] { return run_reshard(p, src_ptrs, n_src, dst_ptrs, n_dst, hip_stream); });
 }
 
 int th_plan_destroy(th_plan* p) {
@@ -927,14 +931,13 @@ int th_reference_copy(void* dst, const void* src, size_t nbytes, void* hip_strea
 
 int th_config_set(int key, uint64_t value) {
     std::lock_guard<std::mutex> lk(g_cfg_mu);
+    uint64_t* tile_bytes = nullptr;
     switch (key) {
-        case TH_CFG_TILE_BYTES:
-            if (value < 4096 || value > 524288 || value % 4096) {
-                set_error("tile bytes must be a multiple of 4096 in [4096, 524288]");
-                return TH_ERR_ARG;
-            }
-            g_tuning.tile_bytes = value;
-            return TH_OK;
+        case TH_CFG_TILE_BYTES: tile_bytes = &g_tuning.tile_bytes; break;
+        case TH_CFG_TILE_BYTES_ANY: tile_bytes = &g_tuning.tile_bytes_any; break;
+        case TH_CFG_TILE_BYTES_NARROW: tile_bytes = &g_tuning.tile_bytes_narrow; break;
+        case TH_CFG_TILE_BYTES_CHECKSUM: tile_bytes = &g_tuning.tile_bytes_checksum; break;
+        case TH_CFG_TILE_BYTES_PROGRESS: tile_bytes = &g_tuning.tile_bytes_progress; break;
         case TH_CFG_SPECIALIZE:
             g_tuning.specialize = value != 0;
             return TH_OK;
@@ -952,37 +955,16 @@ int th_config_set(int key, uint64_t value) {
             }
             g_tuning.planner_threads = (unsigned)value;
             return TH_OK;
-        case TH_CFG_TILE_BYTES_CHECKSUM:
-            if (value < 4096 || value > 524288 || value % 4096) {
-                set_error("tile bytes must be a multiple of 4096 in [4096, 524288]");
-                return TH_ERR_ARG;
-            }
-            g_tuning.tile_bytes_checksum = value;
-            return TH_OK;
-        case TH_CFG_TILE_BYTES_PROGRESS:
-            if (value < 4096 || value > 524288 || value % 4096) {
-                set_error("tile bytes must be a multiple of 4096 in [4096, 524288]");
-                return TH_ERR_ARG;
-            }
-            g_tuning.tile_bytes_progress = value;
-            return TH_OK;
-        case TH_CFG_TILE_BYTES_ANY:
-            if (value < 4096 || value > 524288 || value % 4096) {
-                set_error("tile bytes must be a multiple of 4096 in [4096, 524288]");
-                return TH_ERR_ARG;
-            }
-            g_tuning.tile_bytes_any = value;
-            return TH_OK;
-        case TH_CFG_TILE_BYTES_NARROW:
-            if (value < 4096 || value > 524288 || value % 4096) {
-                set_error("tile bytes must be a multiple of 4096 in [4096, 524288]");
-                return TH_ERR_ARG;
-            }
-            g_tuning.tile_bytes_narrow = value;
-            return TH_OK;
+        default:
+            set_error("unknown configuration key %d", key);
+            return TH_ERR_ARG;
     }
-    set_error("unknown configuration key %d", key);
-    return TH_ERR_ARG;
+    if (value < 4096 || value > 524288 || value % 4096) {
+        set_error("tile bytes must be a multiple of 4096 in [4096, 524288]");
+        return TH_ERR_ARG;
+    }
+    *tile_bytes = value;
+    return TH_OK;
 }
 
 uint64_t th_config_get(int key) {
