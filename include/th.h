@@ -164,8 +164,9 @@ typedef struct th_segment {
  * boundary.  src_tensor_elems / dst_tensor_elems (host arrays of n_src / n_dst)
  * give each tensor's element count; every segment is bounds-checked against
  * them (TH_ERR_RANGE).  A tensor has one dtype: segments that disagree on a
- * tensor's dtype are rejected.  Overlapping destination segments are the
- * caller's responsibility. */
+ * tensor's dtype are rejected.  A segment of several rows must have rows of
+ * fewer than 2^31 elements (TH_ERR_UNSUPPORTED); a single row may be longer.
+ * Overlapping destination segments are the caller's responsibility. */
 int th_plan_create_from_segments(const th_segment* segs, size_t n,
                                  const uint64_t* src_tensor_elems, uint32_t n_src,
                                  const uint64_t* dst_tensor_elems, uint32_t n_dst,

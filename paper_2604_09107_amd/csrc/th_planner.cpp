@@ -245,6 +245,12 @@ static int segments_from_user_impl(const th_segment* segs, size_t n, const uint6
             set_error("segment %zu is too large", k);
             return TH_ERR_RANGE;
         }
+        // a tile record keeps a rectangle's row length, and the kernels a position in a row plus a tile's
+        // length, in 32 bits (a single row needs neither)
+        if (u.nrows > 1 && u.row_len >= (1ull << 31)) {
+            set_error("segment %zu: rows of 2^31 elements or more are supported only as single-row segments", k);
+            return TH_ERR_UNSUPPORTED;
+        }
         if ((int64_t)u.src_tensor != prev_tensor) {
             const uint64_t aligned = (wire + 15) / 16 * 16;
             if (!m.segments.empty()) m.segments.back().pad_after = (uint8_t)(aligned - wire);

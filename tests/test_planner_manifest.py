@@ -364,6 +364,22 @@ def test_error_paths():
     with pytest.raises(th.ThError) as e:
         th.th_plan_create_from_segments(bad, [32], [32], 4096, HOST)
     assert e.value.code == -4
+    # a tile record holds a rectangle's row length in 32 bits: rows of 2^31 elements are refused unless
+    # the segment is a single row, which is cut with 64-bit offsets
+    huge = seg.copy()
+    huge["nrows"], huge["row_len"], huge["src_row_stride"], huge["dst_row_stride"] = 2, 1 << 31, (1 << 31) + 8, 1 << 31
+    huge["src_dtype"] = th.TH_BF16
+    with pytest.raises(th.ThError) as e:
+        th.th_plan_create_from_segments(huge, [1 << 34], [1 << 34], 1 << 30, HOST)
+    assert e.value.code == -3 and "single-row" in str(e.value)
+    huge["nrows"], huge["row_len"], huge["src_elem_off"], huge["dst_elem_off"] = 1, 1 << 32, 3, 5
+    plan = th.th_plan_create_from_segments(huge, [1 << 34], [1 << 34], 1 << 30, HOST)
+    assert plan.wire_bytes == 2 << 32 and plan.num_chunks == 8
+    for side in (0, 1, 2):
+        last = plan.tile(side, plan.num_tiles(side) - 1)
+        tensor_side_end = (last.dst_byte_off if side else last.src_byte_off) + 2 * last.count
+        assert tensor_side_end == 2 * ((1 << 32) + (5 if side else 3))
+    plan.destroy()
 
 
 def test_empty_plan_and_empty_segments():
