@@ -30,12 +30,12 @@ PRIMARY, SECONDARY = "cfg3_70b_tp8_to_tp4", "cfg2_8b_tp1_to_tp4"
 # the counter reads for th_reference_copy of known size; summaries under profiles/).  Valid only for
 # the kernel sources they were taken with: bench.py reports null once those files have changed.
 TRAFFIC_SOURCES = ("th_kernels.hip", "th_planner.cpp", "th_internal.hpp")
-TRAFFIC_SHA256 = "0197de5de444e41958c79c7807c736dbbfa9e234dc9e84832e0358ceed5a3e6e"
+TRAFFIC_SHA256 = "070358030b56162ce929f6e75ccc9f7c200d40d1f79d6cb8095b91f4b1bed5b1"
 TRAFFIC_BYTES = {
-    "cfg2_8b_tp1_to_tp4": {"th_pack": 8047588877, "th_unpack": 8046977008},
-    "cfg3_70b_tp8_to_tp4": {"th_pack": 35349561777, "th_unpack": 35348360258},
-    "cfg4_moe_ep8_to_tp2": {"th_pack": 5821516899, "th_unpack": 5821209029},
-    "cfg5_scatter_fp32_to_bf16": {"th_pack": 36881514359, "th_unpack": 22477912336},
+    "cfg2_8b_tp1_to_tp4": {"th_pack": 8047590041, "th_unpack": 8046980732},
+    "cfg3_70b_tp8_to_tp4": {"th_pack": 35349565265, "th_unpack": 35348346210},
+    "cfg4_moe_ep8_to_tp2": {"th_pack": 5821519863, "th_unpack": 5821209113},
+    "cfg5_scatter_fp32_to_bf16": {"th_pack": 36887235165, "th_unpack": 22477880886},
 }
 
 
