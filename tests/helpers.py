@@ -136,3 +136,46 @@ def tile_sizes(tile_bytes):
 
 def flat_u8(arrs):
     return [np.ascontiguousarray(a).reshape(-1).view(np.uint8) for a in arrs]
+
+
+LARGE_DST_LEN = (1 << 31) + (1 << 28)  # bf16 elements: 4.8 GB
+
+
+def large_offset_segments(src_dt):
+    """Four bf16-destination segments whose last rows start beyond byte 2^32 of a 4.8 GB source tensor
+    and of a 4.8 GB destination tensor (oracle-style dict of int64 arrays, and the source length):
+    0 strided rows at element alignment, 1 strided rows with every offset a multiple of 16 bytes (48 rows
+    each, spread over the whole tensor),
+    2 one aligned row, 3 one row at odd element offsets."""
+    es_s = 4 if src_dt == "f32" else 2
+    src_len = (1 << 32) // es_s + (1 << 29) // es_s
+    pitch = ((1 << 32) // es_s // 47 // 8 + 1) * 8  # the last of 48 rows starts past byte 2^32
+    o = {k: np.zeros(4, dtype=np.int64) for k in
+         ("src_tensor", "dst_tensor", "src_off", "src_stride", "dst_off", "dst_stride", "nrows", "row_len")}
+    o["src_off"][0], o["src_stride"][0], o["dst_off"][0], o["dst_stride"][0] = 7, pitch + 3, 11, 46_000_001
+    o["nrows"][0], o["row_len"][0] = 48, 1000
+    o["src_off"][1], o["src_stride"][1], o["dst_off"][1], o["dst_stride"][1] = 4096, pitch, 500_000, 46_000_000
+    o["nrows"][1], o["row_len"][1] = 48, 1024
+    o["src_off"][2], o["dst_off"][2] = src_len - (1 << 22), 2_320_000_000
+    o["nrows"][2], o["row_len"][2] = 1, 1 << 20
+    o["src_off"][3], o["dst_off"][3] = src_len - (1 << 21) + 3, 2_330_000_005
+    o["nrows"][3], o["row_len"][3] = 1, 300_001
+    for k in (2, 3):
+        o["src_stride"][k] = o["dst_stride"][k] = o["row_len"][k]
+    last_src = o["src_off"] + (o["nrows"] - 1) * o["src_stride"] + o["row_len"]
+    last_dst = o["dst_off"] + (o["nrows"] - 1) * o["dst_stride"] + o["row_len"]
+    assert last_src.max() <= src_len and last_dst.max() <= LARGE_DST_LEN
+    assert np.all((last_src - o["row_len"]) * es_s > 1 << 32) and np.all((last_dst - o["row_len"]) * 2 > 1 << 32)
+    return o, src_len
+
+
+def library_segments(th, o, src_dt, dst_dt):
+    """The library's segment records for an oracle-style segment dict (one dtype pair for all)."""
+    segs = np.zeros(len(o["nrows"]), dtype=th.binding.SEGMENT_NP)
+    segs["src_tensor"], segs["dst_tensor"] = o["src_tensor"], o["dst_tensor"]
+    segs["src_elem_off"], segs["src_row_stride"] = o["src_off"], o["src_stride"]
+    segs["dst_elem_off"], segs["dst_row_stride"] = o["dst_off"], o["dst_stride"]
+    segs["nrows"], segs["row_len"] = o["nrows"], o["row_len"]
+    segs["src_dtype"] = th.TH_F32 if src_dt == "f32" else th.TH_BF16
+    segs["dst_dtype"] = th.TH_F32 if dst_dt == "f32" else th.TH_BF16
+    return segs

@@ -11,8 +11,8 @@ import pytest
 import synth
 import paper_2604_09107_amd as th
 from oracle import checksum, layouts, reshard, segments
-from helpers import (exec_runs_pack, exec_runs_unpack, exec_tiles, flat_u8, holder_tensors_cpu, tile_checksums,
-                     tile_sizes)
+from helpers import (LARGE_DST_LEN, exec_runs_pack, exec_runs_unpack, exec_tiles, flat_u8, holder_tensors_cpu,
+                     large_offset_segments, library_segments, tile_checksums, tile_sizes)
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HOST = th.TH_FLAG_HOST_ONLY
@@ -297,6 +297,49 @@ def test_explicit_segments_manifest_reproduces_oracle(chunk_bytes, tile_bytes):
         else:
             exec_runs_unpack(plan, chunks, [got.view(np.uint8)])
         assert np.array_equal(got, arena)
+    plan.destroy()
+
+
+@pytest.mark.parametrize("src_dt", ["bf16", "f32"])
+def test_offsets_beyond_four_gib_inside_one_tensor(src_dt):
+    """Rows that start past byte 2^32 of a 4.8 GB source and of a 4.8 GB destination tensor: the runs
+    and all three tile lists, run on the CPU, give the oracle's wire and destination.  (Both tensors
+    are untouched zero pages except where the segments read and write.)"""
+    o, src_len = large_offset_segments(src_dt)
+    npd = np.uint32 if src_dt == "f32" else np.uint16
+    src = np.zeros(src_len, dtype=npd)
+    rng = np.random.default_rng(9)
+    for k in range(4):
+        for r in range(int(o["nrows"][k])):
+            a = int(o["src_off"][k] + r * o["src_stride"][k])
+            src[a:a + int(o["row_len"][k])] = rng.integers(1, 1 << (8 * src.itemsize), size=int(o["row_len"][k])).astype(npd)
+    wire = segments.pack(o, [src], src_dt, "bf16")
+    want = np.zeros(LARGE_DST_LEN, dtype=np.uint16)
+    segments.unpack(o, wire, [want], "bf16")
+    plan = th.th_plan_create_from_segments(library_segments(th, o, src_dt, "bf16"), [src_len], [LARGE_DST_LEN],
+                                           1 << 20, HOST | th.TH_FLAG_PTRS_ALIGNED16)
+    assert {plan.tile(s_, i).kind for s_ in (0, 1) for i in range(plan.num_tiles(s_))} == {0, 1, 2}
+    src_u8 = src.view(np.uint8)
+    chunks = exec_runs_pack(plan, [src_u8], fill=0)
+    assert np.array_equal(np.concatenate(chunks)[:plan.wire_bytes], wire)
+    for what in ("runs", "tiles", "direct"):
+        dst = np.zeros(LARGE_DST_LEN, dtype=np.uint16)
+        if what == "runs":
+            exec_runs_unpack(plan, chunks, [dst.view(np.uint8)])
+        elif what == "tiles":
+            tchunks = [np.zeros(plan.chunk_bytes(c), dtype=np.uint8) for c in range(plan.num_chunks)]
+            exec_tiles(plan, 0, [src_u8], tchunks)
+            assert np.array_equal(np.concatenate(tchunks)[:plan.wire_bytes], wire)
+            exec_tiles(plan, 1, tchunks, [dst.view(np.uint8)])
+        else:
+            exec_tiles(plan, 2, [src_u8], [dst.view(np.uint8)])
+        # compared around every destination row (a whole-array comparison would fault in 10 GB of zero pages)
+        for k in range(4):
+            for r in range(int(o["nrows"][k])):
+                a = int(o["dst_off"][k] + r * o["dst_stride"][k])
+                lo, hi = max(0, a - 64), min(LARGE_DST_LEN, a + int(o["row_len"][k]) + 64)
+                assert np.array_equal(dst[lo:hi], want[lo:hi]), (what, k, r)
+        del dst
     plan.destroy()
 
 
