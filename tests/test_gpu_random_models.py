@@ -12,14 +12,14 @@ import paper_2604_09107_amd as th
 from paper_2604_09107_amd import device as dev
 from oracle import checksum, layouts, reshard
 from helpers import holder_tensors_cpu, tile_sizes
-from test_planner_property import cases
+from test_planner_property import FIXED_EXAMPLES, N_EXAMPLES, cases
 
 pytestmark = pytest.mark.gpu
 
 SENT16 = 0x5A5A
 
 
-@settings(max_examples=300, deadline=None, derandomize=True,
+@settings(max_examples=N_EXAMPLES, deadline=None, derandomize=FIXED_EXAMPLES,
           suppress_health_check=[HealthCheck.too_slow, HealthCheck.data_too_large])
 @given(cases())
 def test_random_model_plans_bit_exact(case):
