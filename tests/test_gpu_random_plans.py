@@ -152,3 +152,72 @@ def test_random_segment_plan(seed):
         assert np.array_equal(ps.cpu().numpy().view(np.uint64).reshape(-1, 2), want_sums), what + ": pack sums"
         assert np.array_equal(us.cpu().numpy().view(np.uint64).reshape(-1, 2), want_sums), what + ": unpack sums"
     plan.destroy()
+
+
+@pytest.mark.parametrize("seed", range(150))
+def test_random_segment_plan_with_progress_and_without_allocation(seed):
+    """The same generator through the launches that publish progress (every store written through, one
+    list in chunk order) and through th_pack_noalloc: wire and destination tensors bit for bit, the
+    caller's counter equal to the range's length after each call."""
+    rng = np.random.default_rng(500000 + seed)
+    p = draw_plan(rng)
+    segs, src_dt, dst_dt = p["segs"], p["src_dt"], p["dst_dt"]
+    if src_dt == "f32":
+        srcs = [synth.to_bits(synth.scatter_values(n, 77 * seed + i, special_rate=0.05))
+                for i, n in enumerate(p["src_len"])]
+    else:
+        srcs = [rng.integers(0, 1 << 16, size=n).astype(np.uint16) for n in p["src_len"]]
+    late = p["narrow_at_unpack"]
+    wire_dt = src_dt if late else dst_dt
+    wire = segments.pack(segs, srcs, src_dt, dst_dt, narrow_at="unpack" if late else "pack")
+    want = [np.full(n, SENT[dst_dt], dtype=NP[dst_dt]) for n in p["dst_len"]]
+    segments.unpack(segs, wire, want, dst_dt, wire_dtype=wire_dt)
+
+    csegs = np.zeros(len(segs["nrows"]), dtype=th.binding.SEGMENT_NP)
+    csegs["src_tensor"], csegs["dst_tensor"] = segs["src_tensor"], segs["dst_tensor"]
+    csegs["src_elem_off"], csegs["src_row_stride"] = segs["src_off"], segs["src_stride"]
+    csegs["dst_elem_off"], csegs["dst_row_stride"] = segs["dst_off"], segs["dst_stride"]
+    csegs["nrows"], csegs["row_len"] = segs["nrows"], segs["row_len"]
+    csegs["src_dtype"], csegs["dst_dtype"] = TH[src_dt], TH[dst_dt]
+    flags = (th.TH_FLAG_PROGRESS | (th.TH_FLAG_PTRS_ALIGNED16 if p["aligned"] else 0) |
+             (th.TH_FLAG_NARROW_AT_UNPACK if late else 0))
+    with tile_sizes(p["tile_bytes"]):
+        plan = th.th_plan_create_from_segments(csegs, p["src_len"], p["dst_len"], p["chunk_bytes"], flags)
+    assert plan.wire_bytes == len(wire)
+    es_s, es_d = NP[src_dt]().itemsize, NP[dst_dt]().itemsize
+    shift = (lambda es: 0) if p["aligned"] else (lambda es: int(rng.integers(0, 16 // es)))
+    src_keep, src_ptrs = zip(*[device_tensor(s, shift(es_s)) for s in srcs])
+    sent = [np.full(n, SENT[dst_dt], dtype=NP[dst_dt]) for n in p["dst_len"]]
+    dst_shift = [shift(es_d) for _ in sent]
+    dst_keep, dst_ptrs = zip(*[device_tensor(s, k) for s, k in zip(sent, dst_shift)])
+    src_ptrs, dst_ptrs = list(src_ptrs), list(dst_ptrs)
+    wire_dev, wptrs = dev.alloc_wire(plan, fill_byte=0xEE)
+    wire_na, wptrs_na = dev.alloc_wire(plan, fill_byte=0xEE)
+    stream = dev.current_stream()
+    n = plan.num_chunks
+    flag = torch.full((2,), -1, dtype=torch.int64, device="cuda")
+    what = "seed %d: %s" % (seed, {k: p[k] for k in ("src_dt", "dst_dt", "aligned", "chunk_bytes", "tile_bytes",
+                                                        "narrow_at_unpack")})
+    # pack in two ranges, each with a counter of its own
+    cut = int(rng.integers(0, n + 1))
+    th.th_pack_progress(plan, src_ptrs, wptrs[:cut], 0, cut, flag[0:].data_ptr(), stream)
+    th.th_pack_progress(plan, src_ptrs, wptrs[cut:], cut, n - cut, flag[1:].data_ptr(), stream)
+    for c in range(0, n, 4096):  # th_pack_noalloc takes at most 4096 chunks per call
+        k = min(4096, n - c)
+        th.th_pack_noalloc(plan, src_ptrs, wptrs_na[c:c + k], c, k, stream)
+    torch.cuda.synchronize()
+    assert flag.tolist() == [cut, n - cut], what
+    for name, w in (("th_pack_progress", wire_dev), ("th_pack_noalloc", wire_na)):
+        got = w.cpu().numpy()[:plan.wire_bytes]
+        bad = np.nonzero(got != wire)[0]
+        assert bad.size == 0, "%s: %s wire differs first at byte %d (%d differ)" % (what, name, bad[0], bad.size)
+    th.th_unpack_progress(plan, wptrs, 0, n, dst_ptrs, flag[0:].data_ptr(), stream)
+    torch.cuda.synchronize()
+    assert int(flag[0]) == n, what
+    for t, (g, w, k) in enumerate(zip(dst_keep, want, dst_shift)):
+        gb = synth.to_bits(g)
+        assert np.all(gb[:k] == 0), "%s: wrote before destination tensor %d" % (what, t)
+        bad = np.nonzero(gb[k:] != w)[0]
+        assert bad.size == 0, "%s: destination tensor %d differs first at element %d (%d differ)" % (
+            what, t, bad[0], bad.size)
+    plan.destroy()
