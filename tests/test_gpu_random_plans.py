@@ -23,28 +23,38 @@ TH = {"bf16": th.TH_BF16, "f32": th.TH_F32}
 SENT = {"bf16": 0x7777, "f32": 0x77777777}
 
 
-def draw_plan(rng):
+def draw_plan(rng, big=False):
+    """big: rows of up to 400,000 elements in tensors of up to 8M (rows longer than any tile, thousands of
+    rows per segment, chunks of up to 16 MiB) instead of rows of up to 3000 in tensors of up to 256K."""
     src_dt, dst_dt = [("f32", "bf16"), ("bf16", "bf16"), ("f32", "f32")][int(rng.integers(0, 3))]
     aligned = bool(rng.integers(0, 2))
     es_s, es_d = (4 if src_dt == "f32" else 2), (4 if dst_dt == "f32" else 2)
     # in the aligned regime every element count is a multiple of `q` (16 bytes on both sides)
     q = 16 // min(es_s, es_d) if aligned else 1
-    n_src = int(rng.integers(1, 6))
-    n_dst = int(rng.integers(1, 4))
-    src_len = [int(rng.integers(1 << 12, 1 << 18)) // 8 * 8 for _ in range(n_src)]
-    n_seg = int(rng.integers(1, 60))
+    n_src = int(rng.integers(1, 4 if big else 6))
+    n_dst = int(rng.integers(1, 3 if big else 4))
+    lo, hi = (1 << 18, 1 << 23) if big else (1 << 12, 1 << 18)
+    src_len = [int(rng.integers(lo, hi)) // 8 * 8 for _ in range(n_src)]
+    n_seg = int(rng.integers(1, 12 if big else 60))
     keys = ("src_tensor", "dst_tensor", "src_off", "src_stride", "dst_off", "dst_stride", "nrows", "row_len")
     segs = {k: np.zeros(n_seg, dtype=np.int64) for k in keys}
     dst_fill = [int(rng.integers(0, 5)) * q for _ in range(n_dst)]
     src_t = np.sort(rng.integers(0, n_src, size=n_seg)) if rng.integers(0, 2) else rng.integers(0, n_src, size=n_seg)
     for k in range(n_seg):
         t = int(src_t[k])
-        shape = int(rng.integers(0, 4))
-        row_len = [int(rng.integers(1, 9)), int(rng.integers(1, 200)), int(rng.integers(200, 3000)),
-                   int(rng.integers(1, 40))][shape]
-        nrows = [int(rng.integers(1, 400)), int(rng.integers(1, 60)), int(rng.integers(1, 12)), 1][shape]
+        if big:
+            shape = int(rng.integers(0, 5))
+            row_len = [int(rng.integers(1, 9)), int(rng.integers(1000, 9000)), int(rng.integers(9000, 200000)),
+                       int(rng.integers(1, 400000)), int(rng.integers(4000, 7000))][shape]
+            nrows = [int(rng.integers(1000, 40000)), int(rng.integers(1, 300)), int(rng.integers(1, 30)), 1,
+                     int(rng.integers(100, 700))][shape]
+        else:
+            shape = int(rng.integers(0, 4))
+            row_len = [int(rng.integers(1, 9)), int(rng.integers(1, 200)), int(rng.integers(200, 3000)),
+                       int(rng.integers(1, 40))][shape]
+            nrows = [int(rng.integers(1, 400)), int(rng.integers(1, 60)), int(rng.integers(1, 12)), 1][shape]
         row_len = max(q, row_len // q * q)
-        s_stride = row_len + int(rng.integers(0, 40)) // q * q
+        s_stride = row_len + int(rng.integers(0, 5000 if big else 40)) // q * q
         while (nrows - 1) * s_stride + row_len > src_len[t]:
             nrows = max(1, nrows // 2)
             if nrows == 1 and row_len > src_len[t]:
@@ -52,15 +62,16 @@ def draw_plan(rng):
         span = (nrows - 1) * s_stride + row_len
         s_off = int(rng.integers(0, src_len[t] - span + 1)) // q * q
         d = int(rng.integers(0, n_dst))
-        d_stride = row_len if rng.integers(0, 2) else row_len + int(rng.integers(1, 24)) // q * q + (0 if q > 1 else 0)
+        d_stride = row_len if rng.integers(0, 2) else row_len + int(rng.integers(1, 3000 if big else 24)) // q * q
         d_stride = max(d_stride, row_len)
         for key, v in (("src_tensor", t), ("dst_tensor", d), ("src_off", s_off), ("src_stride", s_stride),
                        ("dst_off", dst_fill[d]), ("dst_stride", d_stride), ("nrows", nrows), ("row_len", row_len)):
             segs[key][k] = v
         dst_fill[d] += (nrows - 1) * d_stride + row_len + int(rng.integers(0, 6)) * q
     dst_len = [max(8, f + 8) for f in dst_fill]
+    chunks = [4096, 65536, 1 << 20, 16 << 20] if big else [256, 4096, 65536, 1 << 20]
     return dict(src_dt=src_dt, dst_dt=dst_dt, aligned=aligned, segs=segs, src_len=src_len, dst_len=dst_len,
-                chunk_bytes=int([256, 4096, 65536, 1 << 20][int(rng.integers(0, 4))]),
+                chunk_bytes=int(chunks[int(rng.integers(0, 4))]),
                 tile_bytes=int([4096, 8192, 16384, 32768, 131072][int(rng.integers(0, 5))]),
                 checksum=bool(rng.integers(0, 2)),
                 narrow_at_unpack=bool(rng.integers(0, 2)) and src_dt != dst_dt)
@@ -72,10 +83,13 @@ def device_tensor(bits, shift_elems):
     return store, store.data_ptr() + shift_elems * bits.dtype.itemsize
 
 
-@pytest.mark.parametrize("seed", range(400))
+BIG = 1_000_000  # seeds from here on draw the larger shapes
+
+
+@pytest.mark.parametrize("seed", list(range(400)) + list(range(BIG, BIG + 40)))
 def test_random_segment_plan(seed):
     rng = np.random.default_rng(9000 + seed)
-    p = draw_plan(rng)
+    p = draw_plan(rng, big=seed >= BIG)
     segs, src_dt, dst_dt = p["segs"], p["src_dt"], p["dst_dt"]
     n_seg = len(segs["nrows"])
     if src_dt == "f32":
@@ -154,13 +168,13 @@ def test_random_segment_plan(seed):
     plan.destroy()
 
 
-@pytest.mark.parametrize("seed", range(150))
+@pytest.mark.parametrize("seed", list(range(150)) + list(range(BIG, BIG + 30)))
 def test_random_segment_plan_with_progress_and_without_allocation(seed):
     """The same generator through the launches that publish progress (every store written through, one
     list in chunk order) and through th_pack_noalloc: wire and destination tensors bit for bit, the
     caller's counter equal to the range's length after each call."""
     rng = np.random.default_rng(500000 + seed)
-    p = draw_plan(rng)
+    p = draw_plan(rng, big=seed >= BIG)
     segs, src_dt, dst_dt = p["segs"], p["src_dt"], p["dst_dt"]
     if src_dt == "f32":
         srcs = [synth.to_bits(synth.scatter_values(n, 77 * seed + i, special_rate=0.05))
