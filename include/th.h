@@ -80,10 +80,10 @@ enum {
                                            (default: th_pack narrows, the wire carries the reader's
                                            dtype: fewer bytes to transfer) */
     TH_FLAG_PROGRESS = 1u << 4,       /* the plan's launches can publish a progress counter
-                                         (th_pack_progress / th_unpack_progress): the work lists are kept
-                                         in prefix order, so that the chunks of one launch finish roughly
-                                         in order, and per-chunk arrival counters are allocated (4 KiB of
-                                         device memory per chunk and direction) */
+                                         (th_pack_progress / th_unpack_progress): each direction keeps one
+                                         work list in chunk order (no second launch per path class, whose
+                                         tiles would finish last), and per-chunk arrival counters are
+                                         allocated (4 KiB of device memory per chunk and direction) */
     TH_FLAG_CHECKSUM = 1u << 2        /* allocate what th_pack_checksum / th_unpack_checksum need
                                          (24 bytes of device memory per tile) and use the larger
                                          checksum tile size; plain th_pack / th_unpack on such a plan
@@ -194,8 +194,8 @@ int th_plan_create_from_segments(const th_segment* segs, size_t n,
  * A stream that has been used with a plan must not be destroyed before the plan.
  * Tensor pointers are checked (NULL, alignment) whenever a table is new; a table
  * equal to one seen before was checked then.
- * Graph capture: th_pack, th_unpack, their checksum variants, th_reshard and
- * th_signal may be called on a stream that is being captured (a per-chunk
+ * Graph capture: th_pack, th_unpack, their checksum and progress variants,
+ * th_reshard and th_signal may be called on a stream that is being captured (a per-chunk
  * pipeline replayed version after version, as tensors are registered once,
  * Sec. 4.2).  Such a call only records kernel launches.  It needs its pointer
  * tables on the device already: make the same call (same tensor pointers, and
@@ -253,7 +253,8 @@ uint32_t th_plan_tensors_complete(const th_plan* plan, uint32_t n_chunks_done);
 /* Progress counter advanced from inside one launch (Sec. 4.3.3: a worker that is still
  * receiving a version exposes how much of it has arrived, and a reader fetches that prefix instead
  * of waiting for the whole transfer).  Same as th_pack / th_unpack over chunks
- * [chunk_first, chunk_first + chunk_count), in one launch per path class, and while the launch runs
+ * [chunk_first, chunk_first + chunk_count), in one launch (such a plan keeps one work list per
+ * direction), and while the launch runs
  * *progress (device memory, or pinned host memory that the device can write; 8-byte aligned) holds
  * the number of leading chunks of the range whose every byte has been written and is visible to the
  * host, to other devices and to later work on any stream: it is set to 0 when the call's work
