@@ -346,8 +346,9 @@ int th_plan_get_run(const th_plan* plan, size_t i, th_run* out);
  * either kind (class 2: runs of at most TH_CFG_SHORT_TILE_SLOTS 16-byte vectors or destination
  * slots of 16 bytes, 8 when narrowing; each of their tiles runs on one wavefront, so that thousands of
  * small tensors batched into one launch keep every wavefront slot busy, which is what the paper's
- * Tiny-Tensor Optimization is after, Sec. 4.3.2), each sub-list ordered by chunk, so a chunk range
- * is at most three launches.  A tile is one workgroup's share of a
+ * Tiny-Tensor Optimization is after, Sec. 4.3.2; a list has this class only when at least one piece
+ * of its work in eight is such a run, else they stay in classes 0 and 1), each sub-list ordered by
+ * chunk, so a chunk range is at most three launches.  A tile is one workgroup's share of a
  * run, described as a copy from (src_buf, src_byte_off) to (dst_buf,
  * dst_byte_off).  For side 0 src_buf is a source tensor id and dst_buf a chunk
  * index; for side 1 src_buf is a chunk index and dst_buf a destination tensor
