@@ -160,7 +160,7 @@ def cpu_baseline(synth, w, jobs, budget_bytes=20e9):
 def build_scatter_inputs(th, dev, synth, w, torch):
     """The scattered sweep: fp32 pool (4-byte aligned tensors), explicit segments, dense bf16 arena."""
     import numpy as np
-    d = synth.scatter_description(w["n_tensors"], w["seed"])
+    d = synth.scatter_description(w["n_tensors"], w["seed"], **w["sizes"])
     pool = synth.scatter_values(d["pool_elems"] + 3, w["seed"], "cuda")[1:]
     # the arena itself starts where the allocator puts it (line-aligned); the slices inside it are only
     # 2-byte aligned

@@ -80,6 +80,10 @@ WORKLOADS = {
     # random wire order, narrowed to bf16 through 16 MiB chunks into a dense arena
     "cfg5_scatter_fp32_to_bf16": dict(kind="scatter", n_tensors=100_000, seed=5, chunk_bytes=16 * MiB),
     "small_scatter": dict(kind="scatter", n_tensors=2_000, seed=15, chunk_bytes=1 * MiB),
+    # thousands of tiny tensors in one launch: 400,000 fp32 tensors of 256 B to 4 KiB (log-uniform), the
+    # same strided sub-slices, wire order and dense bf16 arena as the scattered sweep
+    "tiny_tensors_fp32_to_bf16": dict(kind="scatter", n_tensors=400_000, seed=6, chunk_bytes=16 * MiB,
+                                      sizes=dict(min_bytes=256, max_bytes=4096, alpha=0.0)),
     # whole-model sweeps of the same three models: every reader rank the resident holders can feed
     # (parts = independent (holders -> reader) groups; holders named twice are resident once)
     "cfg2_8b_tp1_to_tp4_all_readers": dict(
@@ -147,4 +151,5 @@ def workload(name):
             w["holders"], w["reader"] = w["parts"][0]["holders"], w["parts"][0]["reader"]
     else:
         w["model_name"] = "scattered fp32 tensors"
+        w.setdefault("sizes", {})  # keyword arguments of scatter_description beyond (n_tensors, seed)
     return w

@@ -192,13 +192,16 @@ def for_every_scatter_segment(d, pool_dev, fn, batch_elems=1 << 29):
     backlog.drain()
 
 
-@pytest.mark.parametrize("arena_shift", [0, 1])
-def test_scattered_sweep_full_size(arena_shift):
-    """100,000 fp32 tensors (about 40 GB) narrowed into a dense bf16 arena through 16 MiB chunks.
+@pytest.mark.parametrize("name,arena_shift", [("cfg5_scatter_fp32_to_bf16", 0), ("cfg5_scatter_fp32_to_bf16", 1),
+                                              ("tiny_tensors_fp32_to_bf16", 0)])
+def test_scattered_sweep_full_size(name, arena_shift):
+    """100,000 fp32 tensors (about 40 GB) narrowed into a dense bf16 arena through 16 MiB chunks; and
+    400,000 tensors of 256 B to 4 KiB the same way (every run short: one wavefront each).
     arena_shift 0: the arena starts on a cache line, as in the benchmark (tiles that start on a line
     take the write-through stores); 1: it starts one element later, so nothing is aligned."""
-    n, seed, chunk = 100_000, 5, 16 << 20
-    d = synth.scatter_description(n, seed)
+    w = synth.workload(name)
+    n, seed, chunk = w["n_tensors"], w["seed"], w["chunk_bytes"]
+    d = synth.scatter_description(n, seed, **w["sizes"])
     log("pool %.1f GB, arena %.1f GB" % (d["pool_elems"] * 4 / 1e9, d["arena_elems"] * 2 / 1e9))
     pool_dev = synth.scatter_values(d["pool_elems"] + 3, seed, "cuda")[1:]   # 4-byte aligned only
     arena_dev = torch.empty(d["arena_elems"] + 9, dtype=torch.bfloat16, device="cuda")
